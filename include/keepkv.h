@@ -1,0 +1,150 @@
+/*
+ * keepkv.h -- C ABI of the KeepKV hot path for AMD MI355X (gfx950).
+ *
+ * KeepKV (arXiv 2504.09936) keeps a compressed per-layer KV cache in which every slot i
+ * carries an integer Electoral Votes count p_i (Sec. 3.3.1).  Decoding attends with the
+ * vote-weighted softmax of Eq. 6; every `period` steps the cache is compressed back to
+ * `budget` slots by scoring (Eq. 8), selecting, matching (Alg. 1 l.4-5) and ZIP-Merging
+ * (Eq. 7 / App. A.3).  This library exposes exactly those steps.
+ *
+ * Conventions common to all calls
+ *  - Every pointer marked DEVICE is GPU memory of the current HIP device; the library
+ *    allocates nothing and owns nothing.  Pointers must be 16-byte aligned.
+ *  - One cache holds one layer: for every (batch b, kv head h) `capacity` slots of which
+ *    the first len[b,h] are live.  Tensors are dense row-major in the order written.
+ *  - Calls enqueue work on `stream` (a hipStream_t passed as void*, NULL = default stream)
+ *    and return without waiting.  Calls on one stream execute in order.
+ *  - Arguments are validated on the host before anything is enqueued; on a non-OK status
+ *    nothing was launched and no output was touched.  KEEPKV_ERR_DEVICE reports a failed
+ *    launch (hipGetLastError).  No exception crosses this boundary; there is no global state.
+ *  - Storage dtype of Q, K, V, O is f32 or bf16; all accumulation is f32 (f64 where an
+ *    integer decision or a merge weight depends on it).
+ *  - Scores are natural logarithms: log_s holds ln S_i of Eq. 8 (uncorrected EMA of the
+ *    unnormalised score s_i = exp(q.k_i/sqrt(d)) of Eq. 3), -inf while n_obs == 0.
+ *    The bias-corrected score is ln s_hat_i = log_s_i - ln(1 - alpha^n_obs_i).
+ */
+#ifndef KEEPKV_H
+#define KEEPKV_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  KEEPKV_OK = 0,
+  KEEPKV_ERR_INVALID_ARG = 1,  /* null pointer, bad shape, bad parameter            */
+  KEEPKV_ERR_UNSUPPORTED = 2,  /* head_dim / group size / budget outside the built set */
+  KEEPKV_ERR_WORKSPACE = 3,    /* workspace missing or smaller than required         */
+  KEEPKV_ERR_DEVICE = 4        /* HIP reported a launch error                        */
+} keepkv_status;
+
+typedef enum { KEEPKV_F32 = 0, KEEPKV_BF16 = 1 } keepkv_dtype;
+
+/* Shape of one layer's attention; plain value struct, caller-owned (HOST memory). */
+typedef struct {
+  int32_t batch;        /* B  >= 1                                                    */
+  int32_t n_q_heads;    /* Hq, multiple of n_kv_heads; group G = Hq/Hkv in {1,2,4,8}    */
+  int32_t n_kv_heads;   /* Hkv >= 1                                                   */
+  int32_t head_dim;     /* D in {64, 128}                                             */
+  int32_t dtype;        /* keepkv_dtype: storage of Q, K, V, O                        */
+  float   scale;        /* logit scale 1/sqrt(head_dim) (Eq. 3)                       */
+} keepkv_layout;
+
+/* One layer's cache (HOST struct of DEVICE pointers, caller-owned). */
+typedef struct {
+  void    *k, *v;       /* [B, Hkv, capacity, D] storage dtype                        */
+  int32_t *votes;       /* [B, Hkv, capacity]  p_i >= 1 on live slots (Sec. 3.3.1)     */
+  float   *log_s;       /* [B, Hkv, capacity]  ln S_i (Eq. 8), -inf if never observed  */
+  int32_t *n_obs;       /* [B, Hkv, capacity]  observations folded into S_i           */
+  int32_t *len;         /* [B, Hkv]            live slots, 0 <= len <= capacity        */
+  int32_t  capacity;    /* slots allocated per (b, h); 1 <= capacity <= 2^20           */
+} keepkv_cache;
+
+/* Human-readable name of a status (static string). */
+const char *keepkv_strerror(keepkv_status st);
+
+/* Library version as an integer (major*10000 + minor*100 + patch). */
+int32_t keepkv_version(void);
+
+/* Bytes of DEVICE workspace sufficient for any call below on a cache of `capacity` slots
+ * compressed to `budget` slots (pure host function; 0 on invalid arguments).  The
+ * workspace is scratch: contents need not be preserved between calls, but it must not be
+ * shared by calls that may run concurrently. */
+size_t keepkv_workspace_bytes(const keepkv_layout *layout, int32_t capacity, int32_t budget);
+
+/* Append one token per (b, h): k_t, v_t [B, Hkv, D] DEVICE are written to slot len[b,h],
+ * with votes = 1, log_s = -inf, n_obs = 0, then len[b,h] += 1 (Sec. 3.1 cache update;
+ * votes initialised to 1, Sec. 3.3.1).  A head already at capacity is left unchanged and
+ * `overflow` (DEVICE int32, may be NULL) is set to 1. */
+keepkv_status keepkv_append(const keepkv_layout *layout, keepkv_cache *cache,
+                            const void *k_t, const void *v_t, int32_t *overflow, void *stream);
+
+/* Vote-weighted decode attention (Eq. 6): for every (b, query head h) with kv head
+ * h / G, over the live slots i of that kv head,
+ *     out[b,h,:] = sum_i p_i s_i v_i / sum_i p_i s_i,   s_i = exp(scale * q[b,h,:] . k_i)
+ * i.e. softmax over scale*q.k + ln p.  q, out: [B, Hq, D] DEVICE, storage dtype.
+ * logits_out (DEVICE f32 [B, Hkv, capacity], may be NULL): for each live slot the mean over
+ * the G query heads of the group of scale*q.k_i = ln s_i of the group-mean query (the
+ * score keepkv_score consumes).  lse_out (DEVICE f32 [B, Hq], may be NULL): ln sum_i p_i s_i.
+ * An empty cache (len == 0) gives out = 0 and lse = -inf.  Dead slots are never read.
+ * Needs workspace (split partial results). */
+keepkv_status keepkv_decode_attn(const keepkv_layout *layout, const keepkv_cache *cache,
+                                 const void *q, void *out, float *logits_out, float *lse_out,
+                                 void *workspace, size_t workspace_bytes, void *stream);
+
+/* EMA score update (Eq. 8, t > L branch; Alg. 1 line 6) on the live slots:
+ *     S_i <- alpha S_i + (1 - alpha) exp(logits[i]),  n_obs_i += 1
+ * held as log_s_i = ln S_i.  logits: DEVICE f32 [B, Hkv, capacity] as written by
+ * keepkv_decode_attn.  0 <= alpha < 1.  Running it w+1 times from the empty state over the
+ * prefill cache yields the t = L window sum of Eq. 8. */
+keepkv_status keepkv_score(const keepkv_layout *layout, keepkv_cache *cache,
+                           const float *logits, float alpha, void *stream);
+
+/* Token selection (Alg. 1 lines 2-3; fixed-budget policy with sink tokens, a recent
+ * window and heavy hitters, App. B.3).  Per (b, h) with len > budget: slots [0, n_sink)
+ * and [len - n_recent, len) are kept; of the others the budget - n_sink - n_recent with the
+ * largest ln p_i + ln s_hat_i are kept, equal values resolved in favour of the lower
+ * index.  keep_idx [B, Hkv, budget] and evict_idx [B, Hkv, capacity - budget] (DEVICE int32)
+ * receive the retained / to-be-evicted slot numbers in ascending order; n_evict [B, Hkv]
+ * receives len - budget.  With len <= budget nothing is evicted: n_evict = 0 and keep_idx
+ * = 0..len-1 followed by -1.  Requires n_sink + n_recent <= budget <= capacity. */
+keepkv_status keepkv_select(const keepkv_layout *layout, const keepkv_cache *cache,
+                            int32_t budget, int32_t n_sink, int32_t n_recent, float alpha,
+                            int32_t *keep_idx, int32_t *evict_idx, int32_t *n_evict,
+                            void *workspace, size_t workspace_bytes, void *stream);
+
+/* Merge-candidate matching (Alg. 1 lines 4-5): for every to-be-evicted slot e the
+ * retained slot of highest key cosine similarity U[e,c] = k_e.k_c/(|k_e||k_c|), lowest
+ * position winning ties; match[b,h,j] (DEVICE int32 [B, Hkv, capacity - budget]) is that
+ * position in keep_idx if U > threshold (strict) and -1 otherwise.  sim_out (DEVICE f32,
+ * same shape, may be NULL) receives the best similarity.  bf16 caches use bf16 MFMA with
+ * f32 accumulation; rows whose decision lies within rounding of a tie or of the threshold
+ * are re-evaluated in f64, so indices equal an f64 evaluation.  budget <= 4096. */
+keepkv_status keepkv_match(const keepkv_layout *layout, const keepkv_cache *cache,
+                           int32_t budget, const int32_t *keep_idx, const int32_t *evict_idx,
+                           const int32_t *n_evict, float threshold, int32_t *match,
+                           float *sim_out, void *workspace, size_t workspace_bytes, void *stream);
+
+/* Multi-way Zero Inference-Perturbation Merging with EMA scores (Eq. 7 in its App. A.3 /
+ * A.4 form; Alg. 1 lines 7-11).  For retained position r with group g = {keep_idx[r]} +
+ * {evict_idx[j] : match[j] = r}, w_i = p_i s_hat_i, W = sum w, P = sum p:
+ *     v_r = sum w_i v_i / W,   k_r = (sum w_i k_i / W) * ln(W/P) / (sum w_i ln s_hat_i / W),
+ *     p_r = P,   ln s_hat_r = ln(W/P),   n_r = max(n_obs of the retained slot, 1).
+ * When |sum w_i ln s_hat_i / W| < 1e-3 the key scale is taken as 1.  Unmatched evicted
+ * slots are dropped and their votes added to dropped_votes[b,h] (DEVICE int64, accumulated,
+ * may be NULL).  Results are written to dst slots 0..budget-1 in keep_idx order and
+ * dst.len = number of retained slots; heads with n_evict == 0 are copied.  src and dst must
+ * not overlap; dst.capacity >= budget. */
+keepkv_status keepkv_merge(const keepkv_layout *layout, const keepkv_cache *src,
+                           keepkv_cache *dst, int32_t budget, const int32_t *keep_idx,
+                           const int32_t *evict_idx, const int32_t *n_evict,
+                           const int32_t *match, float alpha, int64_t *dropped_votes,
+                           void *workspace, size_t workspace_bytes, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* KEEPKV_H */

@@ -1,0 +1,162 @@
+"""ctypes binding of libkeepkv.so: argument marshalling only.
+
+Every function has the name and meaning of the C entry point declared in include/keepkv.h;
+tensors are torch tensors on the GPU (used here purely as device memory), passed down as raw
+pointers together with the current torch stream.  There is no fallback: if the HIP library has
+not been built, importing this module raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libkeepkv.so")
+
+if not os.path.exists(LIB_PATH):
+    raise ImportError(
+        f"{LIB_PATH} not found: build the HIP library first (python -m paper_2504_09936_amd.build)")
+
+_lib = C.CDLL(LIB_PATH)
+
+F32, BF16 = 0, 1
+OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_DEVICE = range(5)
+
+
+class _Layout(C.Structure):
+    _fields_ = [("batch", C.c_int32), ("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32),
+                ("head_dim", C.c_int32), ("dtype", C.c_int32), ("scale", C.c_float)]
+
+
+class _Cache(C.Structure):
+    _fields_ = [("k", C.c_void_p), ("v", C.c_void_p), ("votes", C.c_void_p), ("log_s", C.c_void_p),
+                ("n_obs", C.c_void_p), ("len", C.c_void_p), ("capacity", C.c_int32)]
+
+
+_P = C.c_void_p
+_lib.keepkv_strerror.restype = C.c_char_p
+_lib.keepkv_strerror.argtypes = [C.c_int]
+_lib.keepkv_version.restype = C.c_int32
+_lib.keepkv_workspace_bytes.restype = C.c_size_t
+_lib.keepkv_workspace_bytes.argtypes = [C.POINTER(_Layout), C.c_int32, C.c_int32]
+_lib.keepkv_append.argtypes = [C.POINTER(_Layout), C.POINTER(_Cache), _P, _P, _P, _P]
+_lib.keepkv_decode_attn.argtypes = [C.POINTER(_Layout), C.POINTER(_Cache), _P, _P, _P, _P, _P, C.c_size_t, _P]
+_lib.keepkv_score.argtypes = [C.POINTER(_Layout), C.POINTER(_Cache), _P, C.c_float, _P]
+_lib.keepkv_select.argtypes = [C.POINTER(_Layout), C.POINTER(_Cache), C.c_int32, C.c_int32, C.c_int32,
+                               C.c_float, _P, _P, _P, _P, C.c_size_t, _P]
+_lib.keepkv_match.argtypes = [C.POINTER(_Layout), C.POINTER(_Cache), C.c_int32, _P, _P, _P, C.c_float,
+                              _P, _P, _P, C.c_size_t, _P]
+_lib.keepkv_merge.argtypes = [C.POINTER(_Layout), C.POINTER(_Cache), C.POINTER(_Cache), C.c_int32, _P, _P, _P,
+                              _P, C.c_float, _P, _P, C.c_size_t, _P]
+for _f in ("append", "decode_attn", "score", "select", "match", "merge"):
+    getattr(_lib, "keepkv_" + _f).restype = C.c_int
+
+EXPORTS = ["keepkv_strerror", "keepkv_version", "keepkv_workspace_bytes", "keepkv_append",
+           "keepkv_decode_attn", "keepkv_score", "keepkv_select", "keepkv_match", "keepkv_merge"]
+
+
+class KeepKVError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {_lib.keepkv_strerror(status).decode()} (status {status})")
+
+
+def _check(st: int, where: str) -> None:
+    if st != OK:
+        raise KeepKVError(st, where)
+
+
+def _ptr(t) -> int | None:
+    return None if t is None else t.data_ptr()
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+@dataclass
+class Layout:
+    batch: int
+    n_q_heads: int
+    n_kv_heads: int
+    head_dim: int
+    dtype: int
+    scale: float
+
+    def c(self) -> _Layout:
+        return _Layout(self.batch, self.n_q_heads, self.n_kv_heads, self.head_dim, self.dtype, self.scale)
+
+    @property
+    def torch_dtype(self):
+        return torch.bfloat16 if self.dtype == BF16 else torch.float32
+
+
+class Cache:
+    """One layer's cache as device tensors (plain storage; no arithmetic happens here)."""
+
+    def __init__(self, layout: Layout, capacity: int, device="cuda"):
+        B, H, D = layout.batch, layout.n_kv_heads, layout.head_dim
+        self.layout, self.capacity = layout, capacity
+        self.k = torch.zeros(B, H, capacity, D, dtype=layout.torch_dtype, device=device)
+        self.v = torch.zeros(B, H, capacity, D, dtype=layout.torch_dtype, device=device)
+        self.votes = torch.zeros(B, H, capacity, dtype=torch.int32, device=device)
+        self.log_s = torch.full((B, H, capacity), float("-inf"), dtype=torch.float32, device=device)
+        self.n_obs = torch.zeros(B, H, capacity, dtype=torch.int32, device=device)
+        self.len = torch.zeros(B, H, dtype=torch.int32, device=device)
+
+    def c(self) -> _Cache:
+        return _Cache(self.k.data_ptr(), self.v.data_ptr(), self.votes.data_ptr(), self.log_s.data_ptr(),
+                      self.n_obs.data_ptr(), self.len.data_ptr(), self.capacity)
+
+
+def version() -> int:
+    return int(_lib.keepkv_version())
+
+
+def workspace_bytes(layout: Layout, capacity: int, budget: int) -> int:
+    return int(_lib.keepkv_workspace_bytes(C.byref(layout.c()), capacity, budget))
+
+
+def append(layout: Layout, cache: Cache, k_t, v_t, overflow=None) -> None:
+    _check(_lib.keepkv_append(C.byref(layout.c()), C.byref(cache.c()), _ptr(k_t), _ptr(v_t), _ptr(overflow),
+                              _stream()), "keepkv_append")
+
+
+def decode_attn(layout: Layout, cache: Cache, q, out, logits_out, lse_out, workspace) -> None:
+    _check(_lib.keepkv_decode_attn(C.byref(layout.c()), C.byref(cache.c()), _ptr(q), _ptr(out), _ptr(logits_out),
+                                   _ptr(lse_out), _ptr(workspace),
+                                   0 if workspace is None else workspace.numel() * workspace.element_size(),
+                                   _stream()), "keepkv_decode_attn")
+
+
+def score(layout: Layout, cache: Cache, logits, alpha: float) -> None:
+    _check(_lib.keepkv_score(C.byref(layout.c()), C.byref(cache.c()), _ptr(logits), alpha, _stream()),
+           "keepkv_score")
+
+
+def select(layout: Layout, cache: Cache, budget: int, n_sink: int, n_recent: int, alpha: float,
+           keep_idx, evict_idx, n_evict, workspace) -> None:
+    _check(_lib.keepkv_select(C.byref(layout.c()), C.byref(cache.c()), budget, n_sink, n_recent, alpha,
+                              _ptr(keep_idx), _ptr(evict_idx), _ptr(n_evict), _ptr(workspace),
+                              0 if workspace is None else workspace.numel() * workspace.element_size(),
+                              _stream()), "keepkv_select")
+
+
+def match(layout: Layout, cache: Cache, budget: int, keep_idx, evict_idx, n_evict, threshold: float,
+          match_out, sim_out, workspace) -> None:
+    _check(_lib.keepkv_match(C.byref(layout.c()), C.byref(cache.c()), budget, _ptr(keep_idx), _ptr(evict_idx),
+                             _ptr(n_evict), threshold, _ptr(match_out), _ptr(sim_out), _ptr(workspace),
+                             0 if workspace is None else workspace.numel() * workspace.element_size(),
+                             _stream()), "keepkv_match")
+
+
+def merge(layout: Layout, src: Cache, dst: Cache, budget: int, keep_idx, evict_idx, n_evict, match_in,
+          alpha: float, dropped_votes, workspace) -> None:
+    _check(_lib.keepkv_merge(C.byref(layout.c()), C.byref(src.c()), C.byref(dst.c()), budget, _ptr(keep_idx),
+                             _ptr(evict_idx), _ptr(n_evict), _ptr(match_in), alpha, _ptr(dropped_votes),
+                             _ptr(workspace),
+                             0 if workspace is None else workspace.numel() * workspace.element_size(),
+                             _stream()), "keepkv_merge")

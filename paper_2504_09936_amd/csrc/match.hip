@@ -1,0 +1,424 @@
+// keepkv_match: nearest retained key by cosine similarity for every to-be-evicted key
+// (Alg. 1 lines 4-5), the one dense contraction of the method.
+//
+// bf16 caches: a workgroup of 4 wavefronts owns 256 evicted rows; each wavefront keeps its 64 rows
+// (two 32-row MFMA A operands over the whole head dimension) in registers for the entire kernel and
+// streams the retained keys through LDS in 128-column stages.  Every 32x32 f32 accumulator tile is
+// reduced on the spot: scale by 1/|k_c| of the lane's column, pack the column-block number into the
+// low mantissa bits, and fold into a per-lane running (best, second best) pair with max / med3 on
+// the integer image.  The similarity matrix is never written.  After the last stage the per-lane
+// pairs are transposed through LDS and each row is finished by one lane.
+//
+// Exactness: the f32 result decides a row only when the best value leads the second by more than
+// the rounding envelope and is away from the threshold by as much; all other rows (a fraction of a
+// percent) are queued and re-evaluated in f64, where products of bf16 or f32 values are exact and
+// the sum is taken in channel order.  f32 caches go through the f64 kernel entirely.
+#include "kk_common.hpp"
+
+namespace kk {
+namespace {
+
+constexpr int kRowsPerWave = 64;
+constexpr int kMWaves = 4;
+constexpr int kRowsPerBlock = kRowsPerWave * kMWaves;   // 256 evicted rows per workgroup
+constexpr int kStageCols = 128;                         // retained keys per LDS stage
+
+// ---------------------------------------------------------------------------------------------------
+// 1/|k_c| (f32) of every retained key; 0 for padding and for zero keys.
+template <typename T, int D>
+__global__ __launch_bounds__(256) void rnorm_kernel(const T* __restrict__ k, const int32_t* __restrict__ keep_idx,
+                                                    const int32_t* __restrict__ n_evict, float* __restrict__ rnorm,
+                                                    int capacity, int budget) {
+  constexpr int EPL = 16 / (int)sizeof(T), LPS = D / EPL;
+  const int unit = blockIdx.y;
+  if (n_evict[unit] <= 0) return;
+  const int r = blockIdx.x * (256 / LPS) + threadIdx.x / LPS;
+  const int sub = threadIdx.x % LPS;
+  const bool valid = r < budget;
+  const int slot = valid ? keep_idx[(size_t)unit * budget + r] : 0;
+  float ss = 0.f;
+  if (valid && slot >= 0) {
+    const uint4 x = reinterpret_cast<const uint4*>(k)[((size_t)unit * capacity + slot) * LPS + sub];
+    if constexpr (sizeof(T) == 2) {
+      const uint32_t w[4] = {x.x, x.y, x.z, x.w};
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const float a = bf16_lo(w[i]), b = bf16_hi(w[i]);
+        ss = fmaf(a, a, ss);
+        ss = fmaf(b, b, ss);
+      }
+    } else {
+      const float w[4] = {__builtin_bit_cast(float, x.x), __builtin_bit_cast(float, x.y),
+                          __builtin_bit_cast(float, x.z), __builtin_bit_cast(float, x.w)};
+#pragma unroll
+      for (int i = 0; i < 4; ++i) ss = fmaf(w[i], w[i], ss);
+    }
+  }
+  ss = group_sum<LPS>(ss);
+  if (valid && sub == 0) rnorm[(size_t)unit * budget + r] = (ss > 0.f && slot >= 0) ? 1.0f / sqrtf(ss) : 0.f;
+}
+
+// ---------------------------------------------------------------------------------------------------
+struct MatchParams {
+  const void* k;
+  const int32_t* keep_idx;
+  const int32_t* evict_idx;
+  const int32_t* n_evict;
+  const float* rnorm;
+  int32_t* match;
+  float* sim_out;
+  int32_t* flag_count;   // [1]
+  int32_t* flag_rows;    // [units * max_evict]: unit * max_evict + j
+  int capacity, budget, max_evict;
+  float threshold, delta;
+  int code_bits;
+};
+
+__device__ __forceinline__ int imax(int a, int b) { return a > b ? a : b; }
+__device__ __forceinline__ int imin(int a, int b) { return a < b ? a : b; }
+// median of three; the backend folds this into v_med3_i32
+__device__ __forceinline__ int imed3(int a, int b, int c) { return imax(imin(a, b), imin(imax(a, b), c)); }
+
+template <int D>
+__global__ __launch_bounds__(kMWaves* kWave) void match_mfma_kernel(MatchParams p) {
+  constexpr int KS = D / 16;                 // MFMA k-steps over the head dimension
+  constexpr int PITCH = D * 2 + 16;          // bytes per retained key in LDS (padded against bank conflicts)
+  constexpr int CHUNKS = D * 2 / 16;         // 16-byte chunks per key
+  constexpr int STAGE_BYTES = kStageCols * PITCH;
+  constexpr int EPI_BYTES = kMWaves * kRowsPerWave * 33 * 2 * 4;   // transposed (best, second) pairs
+  constexpr int REGION = 2 * STAGE_BYTES > EPI_BYTES ? 2 * STAGE_BYTES : EPI_BYTES;
+
+  extern __shared__ __align__(16) unsigned char smem[];
+  unsigned char* s_stage = smem;                                        // 2 * STAGE_BYTES
+  float* s_rn = reinterpret_cast<float*>(smem + REGION);                // [2][kStageCols]
+  float* s_rne = s_rn + 2 * kStageCols;                                 // [kMWaves][64]
+
+  const int unit = blockIdx.y;
+  const int n_ev = p.n_evict[unit];
+  const int row_blk = blockIdx.x * kRowsPerBlock;
+  if (row_blk >= n_ev) return;
+  const int n_keep = p.budget;               // n_evict > 0 implies the retained list is full
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int l32 = lane & 31, half = lane >> 5;
+
+  const unsigned char* kbytes = reinterpret_cast<const unsigned char*>(p.k) + (size_t)unit * p.capacity * (D * 2);
+  const int32_t* keep = p.keep_idx + (size_t)unit * p.budget;
+  const int32_t* evict = p.evict_idx + (size_t)unit * p.max_evict;
+  const float* rn_c = p.rnorm + (size_t)unit * p.budget;
+
+  // ---- A operands: this wavefront's 64 evicted rows, resident for the whole kernel -----------------
+  bf16x8_t a[2][KS];
+  float rn_e_part[2];
+#pragma unroll
+  for (int t = 0; t < 2; ++t) {
+    const int j = min(row_blk + wave * kRowsPerWave + t * 32 + l32, n_ev - 1);
+    const unsigned char* row = kbytes + (size_t)evict[j] * (D * 2);
+    float ss = 0.f;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      const uint4 x = *reinterpret_cast<const uint4*>(row + ks * 32 + half * 16);
+      a[t][ks] = __builtin_bit_cast(bf16x8_t, x);
+      const uint32_t w[4] = {x.x, x.y, x.z, x.w};
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const float lo = bf16_lo(w[i]), hi = bf16_hi(w[i]);
+        ss = fmaf(lo, lo, ss);
+        ss = fmaf(hi, hi, ss);
+      }
+    }
+    rn_e_part[t] = ss + __shfl_xor(ss, 32);
+  }
+
+  const int code_mask = (1 << p.code_bits) - 1;
+  const int val_mask = ~code_mask;
+  int b1[2][16], b2[2][16];
+#pragma unroll
+  for (int t = 0; t < 2; ++t)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) b1[t][i] = b2[t][i] = (int)0x80000000;
+
+  const int n_stage = (n_keep + kStageCols - 1) / kStageCols;
+
+  // ---- stage loader: 128 keys x CHUNKS 16-byte chunks, 256 threads ------------------------------------
+  constexpr int LOADS = kStageCols * CHUNKS / (kMWaves * kWave);
+  uint4 stage_reg[LOADS];
+  auto load_stage = [&](int s) {
+#pragma unroll
+    for (int i = 0; i < LOADS; ++i) {
+      const int c = tid + i * (kMWaves * kWave);
+      const int col = s * kStageCols + c / CHUNKS;
+      const int slot = keep[min(col, n_keep - 1)];
+      stage_reg[i] = *reinterpret_cast<const uint4*>(kbytes + (size_t)slot * (D * 2) + (c % CHUNKS) * 16);
+    }
+  };
+  auto store_stage = [&](int s) {
+    unsigned char* dst = s_stage + (s & 1) * STAGE_BYTES;
+#pragma unroll
+    for (int i = 0; i < LOADS; ++i) {
+      const int c = tid + i * (kMWaves * kWave);
+      *reinterpret_cast<uint4*>(dst + (c / CHUNKS) * PITCH + (c % CHUNKS) * 16) = stage_reg[i];
+    }
+    if (tid < kStageCols) {
+      const int col = s * kStageCols + tid;
+      s_rn[(s & 1) * kStageCols + tid] = (col < n_keep) ? rn_c[col] : 0.f;   // padding columns score 0
+    }
+  };
+
+  load_stage(0);
+  store_stage(0);
+  __syncthreads();
+
+  for (int s = 0; s < n_stage; ++s) {
+    if (s + 1 < n_stage) load_stage(s + 1);
+    const unsigned char* src = s_stage + (s & 1) * STAGE_BYTES;
+#pragma unroll
+    for (int cbl = 0; cbl < kStageCols / 32; ++cbl) {
+      const int cb = s * (kStageCols / 32) + cbl;           // global column block
+      if (cb * 32 < n_keep) {                                 // uniform over the workgroup
+        f32x16_t acc0 = {0}, acc1 = {0};
+        const unsigned char* bcol = src + (cbl * 32 + l32) * PITCH + half * 16;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+          const bf16x8_t bfrag = *reinterpret_cast<const bf16x8_t*>(bcol + ks * 32);
+          acc0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[0][ks], bfrag, acc0, 0, 0, 0);
+          acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[1][ks], bfrag, acc1, 0, 0, 0);
+        }
+        const float rn = s_rn[(s & 1) * kStageCols + cbl * 32 + l32];
+        const int code = code_mask - cb;                      // lower column block -> larger code
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+          const int k0 = (__builtin_bit_cast(int, acc0[i] * rn) & val_mask) | code;
+          b2[0][i] = imed3(b1[0][i], b2[0][i], k0);
+          b1[0][i] = imax(b1[0][i], k0);
+          const int k1 = (__builtin_bit_cast(int, acc1[i] * rn) & val_mask) | code;
+          b2[1][i] = imed3(b1[1][i], b2[1][i], k1);
+          b1[1][i] = imax(b1[1][i], k1);
+        }
+      }
+    }
+    if (s + 1 < n_stage) store_stage(s + 1);   // other buffer: nobody reads it during stage s
+    __syncthreads();
+  }
+
+  // ---- transpose the per-lane pairs through LDS: [wave][row 0..63][33] x {best, second} ---------------
+  int* s_b1 = reinterpret_cast<int*>(s_stage) + wave * (kRowsPerWave * 33 * 2);
+  int* s_b2 = s_b1 + kRowsPerWave * 33;
+#pragma unroll
+  for (int t = 0; t < 2; ++t)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      const int r = t * 32 + 8 * (i / 4) + 4 * half + (i % 4);   // accumulator register -> tile row
+      s_b1[r * 33 + l32] = b1[t][i];
+      s_b2[r * 33 + l32] = b2[t][i];
+    }
+  if (half == 0) {
+    s_rne[wave * 64 + l32] = rn_e_part[0];
+    s_rne[wave * 64 + 32 + l32] = rn_e_part[1];
+  }
+  __syncthreads();
+
+  // lane r finishes row r of this wavefront
+  const int j = row_blk + wave * kRowsPerWave + lane;
+  if (j >= n_ev) return;
+  int v1 = (int)0x80000000, v2 = (int)0x80000000, c1 = 0;
+  for (int q = 0; q < 32; ++q) {
+    const int k1 = s_b1[lane * 33 + q], k2 = s_b2[lane * 33 + q];
+    const int val = k1 & val_mask;
+    const int col = (code_mask - (k1 & code_mask)) * 32 + q;
+    const int val2 = k2 & val_mask;
+    if (val > v1 || (val == v1 && col < c1)) {
+      v2 = imax(v1, val2);
+      v1 = val;
+      c1 = col;
+    } else {
+      v2 = imax(v2, val);
+    }
+  }
+  const float ss = s_rne[wave * 64 + lane];
+  const float rn_e = 1.0f / sqrtf(ss);
+  const float y1 = __builtin_bit_cast(float, v1), y2 = (v2 > 0) ? __builtin_bit_cast(float, v2) : 0.f;
+  const float cos1 = y1 * rn_e;
+  const bool fragile = !(v1 > 0) || !(ss > 0.f) || !(rn_e < INFINITY) || (y1 - y2) * rn_e <= p.delta ||
+                       fabsf(cos1 - p.threshold) <= p.delta || c1 >= n_keep;
+  const size_t o = (size_t)unit * p.max_evict + j;
+  p.match[o] = (cos1 > p.threshold) ? c1 : -1;
+  if (p.sim_out != nullptr) p.sim_out[o] = cos1;
+  if (fragile) {
+    const int at = atomicAdd(p.flag_count, 1);
+    p.flag_rows[at] = (int)o;
+  }
+}
+
+// queue every live evicted row (f32 caches)
+__global__ void flag_all_kernel(const int32_t* __restrict__ n_evict, int32_t* flag_count, int32_t* flag_rows,
+                                int max_evict) {
+  const int unit = blockIdx.y;
+  const int n = n_evict[unit];
+  for (int j = blockIdx.x * blockDim.x + threadIdx.x; j < n; j += gridDim.x * blockDim.x) {
+    const int at = atomicAdd(flag_count, 1);
+    flag_rows[at] = unit * max_evict + j;
+  }
+}
+
+__global__ void zero_counter_kernel(int32_t* c) { *c = 0; }
+
+// ---------------------------------------------------------------------------------------------------
+// f64 evaluation of queued rows: one wavefront per row, lanes stride over the retained keys.
+template <typename T, int D>
+__global__ __launch_bounds__(256) void match_exact_kernel(MatchParams p) {
+  __shared__ double s_e[4][D];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int n_flag = *p.flag_count;
+  const int waves_total = gridDim.x * 4;
+  const T* kall = reinterpret_cast<const T*>(p.k);
+  for (int f = blockIdx.x * 4 + wave; f < n_flag; f += waves_total) {
+    const int o = p.flag_rows[f];
+    const int unit = o / p.max_evict, j = o % p.max_evict;
+    const T* kunit = kall + (size_t)unit * p.capacity * D;
+    const int32_t* keep = p.keep_idx + (size_t)unit * p.budget;
+    const int e = p.evict_idx[(size_t)unit * p.max_evict + j];
+    for (int d = lane; d < D; d += 64) {
+      if constexpr (sizeof(T) == 2) s_e[wave][d] = (double)bf16_to_f32(reinterpret_cast<const uint16_t*>(kunit)[(size_t)e * D + d]);
+      else s_e[wave][d] = (double)kunit[(size_t)e * D + d];
+    }
+    __builtin_amdgcn_wave_barrier();
+    __threadfence_block();
+    double ss_e = 0.0;
+    for (int d = 0; d < D; ++d) ss_e = fma(s_e[wave][d], s_e[wave][d], ss_e);
+    const double rn_e = 1.0 / sqrt(ss_e);
+    double best = -INFINITY;
+    int best_c = 0x7FFFFFFF;
+    for (int c = lane; c < p.budget; c += 64) {
+      const int slot = keep[c];
+      if (slot < 0) continue;
+      const T* kc = kunit + (size_t)slot * D;
+      double dot = 0.0, ss_c = 0.0;
+      for (int d0 = 0; d0 < D; d0 += 16 / (int)sizeof(T)) {
+        const uint4 x = *reinterpret_cast<const uint4*>(kc + d0);
+        if constexpr (sizeof(T) == 2) {
+          const uint32_t w[4] = {x.x, x.y, x.z, x.w};
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            const double lo = (double)bf16_lo(w[i]), hi = (double)bf16_hi(w[i]);
+            dot = fma(s_e[wave][d0 + 2 * i], lo, dot);
+            ss_c = fma(lo, lo, ss_c);
+            dot = fma(s_e[wave][d0 + 2 * i + 1], hi, dot);
+            ss_c = fma(hi, hi, ss_c);
+          }
+        } else {
+          const float w[4] = {__builtin_bit_cast(float, x.x), __builtin_bit_cast(float, x.y),
+                              __builtin_bit_cast(float, x.z), __builtin_bit_cast(float, x.w)};
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            dot = fma(s_e[wave][d0 + i], (double)w[i], dot);
+            ss_c = fma((double)w[i], (double)w[i], ss_c);
+          }
+        }
+      }
+      const double rn_c = 1.0 / sqrt(ss_c);
+      double u = (dot * rn_e) * rn_c;
+      if (!(fabs(u) <= 1.79e308)) u = -INFINITY;   // zero-norm keys (nan / inf) match nothing
+      if (u > best) {
+        best = u;
+        best_c = c;
+      }
+    }
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+      const double ob = __shfl_xor(best, off);
+      const int oc = __shfl_xor(best_c, off);
+      if (ob > best || (ob == best && oc < best_c)) {
+        best = ob;
+        best_c = oc;
+      }
+    }
+    if (lane == 0) {
+      p.match[o] = (best > (double)p.threshold) ? best_c : -1;
+      if (p.sim_out != nullptr) p.sim_out[o] = (float)best;
+    }
+    __builtin_amdgcn_wave_barrier();
+  }
+}
+
+template <int D>
+size_t mfma_smem_bytes() {
+  const size_t stage = 2 * (size_t)kStageCols * (D * 2 + 16), epi = (size_t)kMWaves * kRowsPerWave * 33 * 2 * 4;
+  return (stage > epi ? stage : epi) + 2 * kStageCols * sizeof(float) + kMWaves * 64 * sizeof(float);
+}
+
+}  // namespace
+
+MatchPlan plan_match(const keepkv_layout* L, int capacity, int budget) {
+  MatchPlan pl;
+  const size_t units = (size_t)L->batch * L->n_kv_heads;
+  pl.rnorm_off = 0;
+  pl.flag_off = align_up(units * budget * sizeof(float), 256);
+  pl.bytes = pl.flag_off + align_up((1 + units * (size_t)(capacity - budget)) * sizeof(int32_t) + 256, 256);
+  return pl;
+}
+
+}  // namespace kk
+
+extern "C" keepkv_status keepkv_match(const keepkv_layout* layout, const keepkv_cache* cache, int32_t budget,
+                                      const int32_t* keep_idx, const int32_t* evict_idx, const int32_t* n_evict,
+                                      float threshold, int32_t* match, float* sim_out, void* workspace,
+                                      size_t workspace_bytes, void* stream) {
+  using namespace kk;
+  if (!layout_ok(layout) || !cache_ok(cache) || !keep_idx || !n_evict) return KEEPKV_ERR_INVALID_ARG;
+  if (budget < 1 || budget > cache->capacity) return KEEPKV_ERR_INVALID_ARG;
+  const int max_evict = cache->capacity - budget;
+  if (max_evict == 0) return KEEPKV_OK;   // nothing can be evicted
+  if (!evict_idx || !match) return KEEPKV_ERR_INVALID_ARG;
+  if (!(threshold == threshold)) return KEEPKV_ERR_INVALID_ARG;
+  if (!aligned16(cache->k)) return KEEPKV_ERR_INVALID_ARG;
+  if (layout->head_dim != 64 && layout->head_dim != 128) return KEEPKV_ERR_UNSUPPORTED;
+  if (budget > 4096) return KEEPKV_ERR_UNSUPPORTED;
+  const size_t units = (size_t)layout->batch * layout->n_kv_heads;
+  if (units * (size_t)max_evict >= (size_t)1 << 31) return KEEPKV_ERR_UNSUPPORTED;
+  const MatchPlan pl = plan_match(layout, cache->capacity, budget);
+  if (!workspace || workspace_bytes < pl.bytes || !aligned16(workspace)) return KEEPKV_ERR_WORKSPACE;
+  hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+
+  MatchParams p;
+  p.k = cache->k; p.keep_idx = keep_idx; p.evict_idx = evict_idx; p.n_evict = n_evict;
+  p.rnorm = reinterpret_cast<float*>(reinterpret_cast<char*>(workspace) + pl.rnorm_off);
+  p.flag_count = reinterpret_cast<int32_t*>(reinterpret_cast<char*>(workspace) + pl.flag_off);
+  p.flag_rows = p.flag_count + 64;
+  p.match = match; p.sim_out = sim_out;
+  p.capacity = cache->capacity; p.budget = budget; p.max_evict = max_evict;
+  p.threshold = threshold;
+  int nblk = (budget + 31) / 32, bits = 1;
+  while ((1 << bits) < nblk) ++bits;
+  p.code_bits = bits;
+  p.delta = 1.0e-5f + 1.5f * ldexpf(1.0f, bits - 23);
+
+  zero_counter_kernel<<<1, 1, 0, st>>>(p.flag_count);
+  const int exact_blocks = 1024;
+  if (layout->dtype == KEEPKV_BF16) {
+    const dim3 grid((max_evict + kRowsPerBlock - 1) / kRowsPerBlock, (unsigned)units);
+    if (layout->head_dim == 128) {
+      rnorm_kernel<uint16_t, 128><<<dim3((budget + 15) / 16, (unsigned)units), 256, 0, st>>>(
+          (const uint16_t*)cache->k, keep_idx, n_evict, const_cast<float*>(p.rnorm), cache->capacity, budget);
+      static const hipError_t attr128 = hipFuncSetAttribute(
+          (const void*)match_mfma_kernel<128>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)mfma_smem_bytes<128>());
+      if (attr128 != hipSuccess) return KEEPKV_ERR_DEVICE;
+      match_mfma_kernel<128><<<grid, kMWaves * kWave, mfma_smem_bytes<128>(), st>>>(p);
+      match_exact_kernel<uint16_t, 128><<<exact_blocks, 256, 0, st>>>(p);
+    } else {
+      rnorm_kernel<uint16_t, 64><<<dim3((budget + 31) / 32, (unsigned)units), 256, 0, st>>>(
+          (const uint16_t*)cache->k, keep_idx, n_evict, const_cast<float*>(p.rnorm), cache->capacity, budget);
+      static const hipError_t attr64 = hipFuncSetAttribute(
+          (const void*)match_mfma_kernel<64>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)mfma_smem_bytes<64>());
+      if (attr64 != hipSuccess) return KEEPKV_ERR_DEVICE;
+      match_mfma_kernel<64><<<grid, kMWaves * kWave, mfma_smem_bytes<64>(), st>>>(p);
+      match_exact_kernel<uint16_t, 64><<<exact_blocks, 256, 0, st>>>(p);
+    }
+  } else {
+    int bx = (max_evict + 255) / 256;
+    if (bx > 64) bx = 64;
+    flag_all_kernel<<<dim3(bx, (unsigned)units), 256, 0, st>>>(n_evict, p.flag_count, p.flag_rows, max_evict);
+    if (layout->head_dim == 128) match_exact_kernel<float, 128><<<exact_blocks, 256, 0, st>>>(p);
+    else match_exact_kernel<float, 64><<<exact_blocks, 256, 0, st>>>(p);
+  }
+  return launch_status();
+}

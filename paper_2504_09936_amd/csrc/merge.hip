@@ -1,0 +1,322 @@
+// keepkv_merge: multi-way Zero Inference-Perturbation Merging (Eq. 7 in the many-to-one form of
+// App. A.3, with the EMA scores of App. A.4; Alg. 1 lines 7-11) and compaction into the
+// destination cache.
+//
+// Two kernels.  (1) Per head, the evicted slots are grouped by merge target into a CSR list: an LDS
+// histogram of match[], a block scan, and a fill in which the thread owning target r walks match[]
+// in order, so every group lists its members in ascending slot order (deterministic summation
+// order, no float atomics).  (2) One lane group (LPS lanes, 16 bytes of a row each) per retained
+// position gathers its group: the merge weights w_i = p_i s_hat_i are formed in f64 relative to
+// the group's largest ln s_hat, one member per lane, and broadcast; K and V rows are accumulated in
+// f32 and scaled once at the end.  Positions without members are copied bit for bit.
+#include "kk_common.hpp"
+
+namespace kk {
+namespace {
+
+constexpr int kGroupThreads = 1024;
+constexpr int kMaxBudget = 4096;
+constexpr double kEllGuard = 1.0e-3;
+
+__global__ __launch_bounds__(kGroupThreads) void merge_group_kernel(
+    const int32_t* __restrict__ match, const int32_t* __restrict__ evict_idx, const int32_t* __restrict__ n_evict,
+    const int32_t* __restrict__ votes, int32_t* __restrict__ start, int32_t* __restrict__ members,
+    int64_t* __restrict__ dropped_votes, int capacity, int budget, int max_evict) {
+  __shared__ int s_cnt[kMaxBudget + 1];
+  __shared__ int s_wave[kGroupThreads / 64];
+  __shared__ long long s_drop;
+  const int unit = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int n_ev = n_evict[unit];
+  const int32_t* mt = match + (size_t)unit * max_evict;
+  const int32_t* ev = evict_idx + (size_t)unit * max_evict;
+  int32_t* st = start + (size_t)unit * (budget + 1);
+  int32_t* mem = members + (size_t)unit * capacity;
+
+  for (int r = tid; r <= budget; r += kGroupThreads) s_cnt[r] = 0;
+  if (tid == 0) s_drop = 0;
+  __syncthreads();
+  long long drop = 0;
+  for (int j = tid; j < n_ev; j += kGroupThreads) {
+    const int t = mt[j];
+    if (t >= 0) atomicAdd(&s_cnt[t], 1);
+    else drop += votes[(size_t)unit * capacity + ev[j]];
+  }
+  if (drop != 0) atomicAdd((unsigned long long*)&s_drop, (unsigned long long)drop);
+  __syncthreads();
+
+  // exclusive scan of s_cnt[0..budget): thread t owns a contiguous run of positions
+  const int per = (budget + kGroupThreads - 1) / kGroupThreads;
+  const int r0 = min(budget, tid * per), r1 = min(budget, r0 + per);
+  int mine = 0;
+  for (int r = r0; r < r1; ++r) mine += s_cnt[r];
+  int incl = mine;
+#pragma unroll
+  for (int off = 1; off < 64; off <<= 1) {
+    const int u = __shfl_up(incl, off);
+    if (lane >= off) incl += u;
+  }
+  if (lane == 63) s_wave[wave] = incl;
+  __syncthreads();
+  int before = 0;
+  for (int w = 0; w < wave; ++w) before += s_wave[w];
+  int run = before + incl - mine;
+  __syncthreads();   // all counts read before they are replaced by starts
+  for (int r = r0; r < r1; ++r) {
+    const int c = s_cnt[r];
+    s_cnt[r] = run;
+    run += c;
+  }
+  if (tid == kGroupThreads - 1) s_cnt[budget] = run;
+  __syncthreads();
+  for (int r = tid; r <= budget; r += kGroupThreads) st[r] = s_cnt[r];
+  if (tid == 0 && dropped_votes != nullptr && s_drop != 0) dropped_votes[unit] += s_drop;
+
+  // ordered fill: the owner of position r walks match[] front to back
+  for (int rb = 0; rb < budget; rb += kGroupThreads) {
+    const int r = rb + tid;
+    int pos = 0, endp = 0;
+    if (r < budget) {
+      pos = s_cnt[r];
+      endp = s_cnt[r + 1];
+    }
+    if (__any(pos < endp)) {
+      for (int j = 0; j < n_ev && __any(pos < endp); ++j) {
+        if (mt[j] == r && r < budget) mem[pos++] = ev[j];
+      }
+    }
+  }
+}
+
+struct MergeParams {
+  const void *sk, *sv;
+  const int32_t* svotes;
+  const float* slog_s;
+  const int32_t* sn_obs;
+  const int32_t* slen;
+  void *dk, *dv;
+  int32_t* dvotes;
+  float* dlog_s;
+  int32_t* dn_obs;
+  int32_t* dlen;
+  const int32_t* keep_idx;
+  const int32_t* n_evict;
+  const int32_t* start;
+  const int32_t* members;
+  int scap, dcap, budget;
+  double ln_alpha;
+};
+
+// ln s_hat_i = ln S_i - ln(1 - alpha^n_i); -inf when never observed
+__device__ __forceinline__ double log_s_hat(float log_s, int n, double ln_alpha) {
+  if (n <= 0) return -INFINITY;
+  double e = (double)log_s;
+  if (ln_alpha > -INFINITY) e -= log(-expm1((double)n * ln_alpha));
+  return e;
+}
+
+template <int LPS>
+__device__ __forceinline__ double group_max_f64(double x) {
+#pragma unroll
+  for (int off = 1; off < LPS; off <<= 1) x = fmax(x, __shfl_xor(x, off));
+  return x;
+}
+template <int LPS>
+__device__ __forceinline__ double group_sum_f64(double x) {
+#pragma unroll
+  for (int off = 1; off < LPS; off <<= 1) x += __shfl_xor(x, off);
+  return x;
+}
+
+template <typename T, int D>
+__global__ __launch_bounds__(256) void merge_apply_kernel(MergeParams p) {
+  constexpr int EPL = 16 / (int)sizeof(T), LPS = D / EPL, GPB = 256 / LPS;
+  const int unit = blockIdx.y;
+  const int r = blockIdx.x * GPB + threadIdx.x / LPS;
+  const int sub = threadIdx.x % LPS;
+  const int lane = threadIdx.x & 63;
+  const int gbase = lane - sub;                 // first lane of this group within the wavefront
+  if (blockIdx.x == 0 && threadIdx.x == 0) {
+    const int n = p.slen[unit];
+    p.dlen[unit] = n < p.budget ? n : p.budget;
+  }
+  if (r >= p.budget) return;
+  const int c = p.keep_idx[(size_t)unit * p.budget + r];
+  if (c < 0) return;
+  const size_t sbase = (size_t)unit * p.scap, dbase = (size_t)unit * p.dcap;
+  const uint4* sk = reinterpret_cast<const uint4*>(p.sk);
+  const uint4* sv = reinterpret_cast<const uint4*>(p.sv);
+  uint4* dk = reinterpret_cast<uint4*>(p.dk);
+  uint4* dv = reinterpret_cast<uint4*>(p.dv);
+  const int m0 = p.start[(size_t)unit * (p.budget + 1) + r], m1 = p.start[(size_t)unit * (p.budget + 1) + r + 1];
+  const int nm = m1 - m0;                        // evicted members of this group
+  const uint4 kc = sk[(sbase + c) * LPS + sub], vc = sv[(sbase + c) * LPS + sub];
+
+  if (nm == 0) {                                  // nothing merged here: copy
+    dk[(dbase + r) * LPS + sub] = kc;
+    dv[(dbase + r) * LPS + sub] = vc;
+    if (sub == 0) {
+      p.dvotes[dbase + r] = p.svotes[sbase + c];
+      p.dlog_s[dbase + r] = p.slog_s[sbase + c];
+      p.dn_obs[dbase + r] = p.sn_obs[sbase + c];
+    }
+    return;
+  }
+
+  const int32_t* mem = p.members + sbase + m0;
+  const int n_c = p.sn_obs[sbase + c];
+  const int p_c = p.svotes[sbase + c];
+  const double E_c = log_s_hat(p.slog_s[sbase + c], n_c, p.ln_alpha);
+
+  // pass 1 over the scalars: largest ln s_hat and total votes of the group
+  double mx = E_c;
+  long long P = p_c;
+  for (int i0 = 0; i0 < nm; i0 += LPS) {
+    const int i = i0 + sub;
+    double E = -INFINITY;
+    int pv = 0;
+    if (i < nm) {
+      const int s = mem[i];
+      pv = p.svotes[sbase + s];
+      E = log_s_hat(p.slog_s[sbase + s], p.sn_obs[sbase + s], p.ln_alpha);
+    }
+    mx = fmax(mx, group_max_f64<LPS>(E));
+    P += (long long)group_sum_f64<LPS>((double)pv);
+  }
+  const bool none_seen = !(mx > -INFINITY);
+
+  // pass 2: weights, weighted sums of rows
+  float ak[EPL], av[EPL];
+  auto fma_row = [&](const uint4& x, float w, float* a) {
+    if constexpr (sizeof(T) == 2) {
+      const uint32_t u[4] = {x.x, x.y, x.z, x.w};
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        a[2 * q] = fmaf(w, bf16_lo(u[q]), a[2 * q]);
+        a[2 * q + 1] = fmaf(w, bf16_hi(u[q]), a[2 * q + 1]);
+      }
+    } else {
+      const uint32_t u[4] = {x.x, x.y, x.z, x.w};
+#pragma unroll
+      for (int q = 0; q < 4; ++q) a[q] = fmaf(w, __builtin_bit_cast(float, u[q]), a[q]);
+    }
+  };
+#pragma unroll
+  for (int e = 0; e < EPL; ++e) ak[e] = av[e] = 0.f;
+  const double w_c = none_seen ? (double)p_c : (E_c > -INFINITY ? (double)p_c * exp(E_c - mx) : 0.0);
+  double W = w_c, WE = (w_c > 0.0 && !none_seen) ? w_c * E_c : 0.0;
+  fma_row(kc, (float)w_c, ak);
+  fma_row(vc, (float)w_c, av);
+  for (int i0 = 0; i0 < nm; i0 += LPS) {
+    const int i = i0 + sub;
+    double w = 0.0, E = 0.0;
+    int s = c;
+    if (i < nm) {
+      s = mem[i];
+      const int pv = p.svotes[sbase + s];
+      E = log_s_hat(p.slog_s[sbase + s], p.sn_obs[sbase + s], p.ln_alpha);
+      w = none_seen ? (double)pv : (E > -INFINITY ? (double)pv * exp(E - mx) : 0.0);
+    }
+    W += group_sum_f64<LPS>(w);
+    WE += group_sum_f64<LPS>((w > 0.0 && !none_seen) ? w * E : 0.0);
+    const float wf = (float)w;
+    const int cnt = min(LPS, nm - i0);
+    for (int q = 0; q < cnt; ++q) {
+      const int sq = __shfl(s, gbase + q);
+      const float wq = __shfl(wf, gbase + q);
+      fma_row(sk[(sbase + sq) * LPS + sub], wq, ak);
+      fma_row(sv[(sbase + sq) * LPS + sub], wq, av);
+    }
+  }
+
+  double kscale, L = -INFINITY;
+  int n_r = 0;
+  float out_log_s = -INFINITY;
+  if (none_seen) {
+    kscale = 1.0 / W;                            // W = P: vote-weighted mean, stays unobserved
+  } else {
+    L = mx + log(W / (double)P);                 // ln(sum p s_hat / sum p)
+    const double ell_bar = WE / W;               // sum w ln s_hat / W
+    kscale = (fabs(ell_bar) < kEllGuard) ? 1.0 / W : (L / ell_bar) / W;
+    n_r = n_c > 1 ? n_c : 1;
+    double ls = L;
+    if (p.ln_alpha > -INFINITY) ls += log(-expm1((double)n_r * p.ln_alpha));
+    out_log_s = (float)ls;
+  }
+  const float fk = (float)kscale, fv = (float)(1.0 / W);
+  uint4 ok, ov;
+  if constexpr (sizeof(T) == 2) {
+    ok.x = pack_bf16x2(ak[0] * fk, ak[1] * fk); ok.y = pack_bf16x2(ak[2] * fk, ak[3] * fk);
+    ok.z = pack_bf16x2(ak[4] * fk, ak[5] * fk); ok.w = pack_bf16x2(ak[6] * fk, ak[7] * fk);
+    ov.x = pack_bf16x2(av[0] * fv, av[1] * fv); ov.y = pack_bf16x2(av[2] * fv, av[3] * fv);
+    ov.z = pack_bf16x2(av[4] * fv, av[5] * fv); ov.w = pack_bf16x2(av[6] * fv, av[7] * fv);
+  } else {
+    ok.x = __builtin_bit_cast(uint32_t, ak[0] * fk); ok.y = __builtin_bit_cast(uint32_t, ak[1] * fk);
+    ok.z = __builtin_bit_cast(uint32_t, ak[2] * fk); ok.w = __builtin_bit_cast(uint32_t, ak[3] * fk);
+    ov.x = __builtin_bit_cast(uint32_t, av[0] * fv); ov.y = __builtin_bit_cast(uint32_t, av[1] * fv);
+    ov.z = __builtin_bit_cast(uint32_t, av[2] * fv); ov.w = __builtin_bit_cast(uint32_t, av[3] * fv);
+  }
+  dk[(dbase + r) * LPS + sub] = ok;
+  dv[(dbase + r) * LPS + sub] = ov;
+  if (sub == 0) {
+    p.dvotes[dbase + r] = (int32_t)P;
+    p.dlog_s[dbase + r] = out_log_s;
+    p.dn_obs[dbase + r] = n_r;
+  }
+}
+
+}  // namespace
+
+MergePlan plan_merge(const keepkv_layout* L, int capacity, int budget) {
+  MergePlan pl;
+  const size_t units = (size_t)L->batch * L->n_kv_heads;
+  pl.start_off = 0;
+  pl.member_off = align_up(units * (budget + 1) * sizeof(int32_t), 256);
+  pl.bytes = pl.member_off + align_up(units * capacity * sizeof(int32_t), 256);
+  return pl;
+}
+
+}  // namespace kk
+
+extern "C" keepkv_status keepkv_merge(const keepkv_layout* layout, const keepkv_cache* src, keepkv_cache* dst,
+                                      int32_t budget, const int32_t* keep_idx, const int32_t* evict_idx,
+                                      const int32_t* n_evict, const int32_t* match, float alpha,
+                                      int64_t* dropped_votes, void* workspace, size_t workspace_bytes, void* stream) {
+  using namespace kk;
+  if (!layout_ok(layout) || !cache_ok(src) || !cache_ok(dst) || !keep_idx || !n_evict) return KEEPKV_ERR_INVALID_ARG;
+  if (budget < 1 || budget > src->capacity || dst->capacity < budget) return KEEPKV_ERR_INVALID_ARG;
+  const int max_evict = src->capacity - budget;
+  if (max_evict > 0 && (!evict_idx || !match)) return KEEPKV_ERR_INVALID_ARG;
+  if (!(alpha >= 0.f && alpha < 1.f)) return KEEPKV_ERR_INVALID_ARG;
+  if (src->k == dst->k || src->v == dst->v || src->votes == dst->votes || src->log_s == dst->log_s ||
+      src->n_obs == dst->n_obs)
+    return KEEPKV_ERR_INVALID_ARG;
+  if (!aligned16(src->k) || !aligned16(src->v) || !aligned16(dst->k) || !aligned16(dst->v)) return KEEPKV_ERR_INVALID_ARG;
+  if (layout->head_dim != 64 && layout->head_dim != 128) return KEEPKV_ERR_UNSUPPORTED;
+  if (budget > kMaxBudget) return KEEPKV_ERR_UNSUPPORTED;
+  const MergePlan pl = plan_merge(layout, src->capacity, budget);
+  if (!workspace || workspace_bytes < pl.bytes || !aligned16(workspace)) return KEEPKV_ERR_WORKSPACE;
+  const unsigned units = (unsigned)(layout->batch * layout->n_kv_heads);
+  hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+  int32_t* start = reinterpret_cast<int32_t*>(reinterpret_cast<char*>(workspace) + pl.start_off);
+  int32_t* members = reinterpret_cast<int32_t*>(reinterpret_cast<char*>(workspace) + pl.member_off);
+
+  merge_group_kernel<<<units, kGroupThreads, 0, st>>>(match, evict_idx, n_evict, src->votes, start, members,
+                                                      dropped_votes, src->capacity, budget, max_evict);
+  MergeParams p;
+  p.sk = src->k; p.sv = src->v; p.svotes = src->votes; p.slog_s = src->log_s; p.sn_obs = src->n_obs; p.slen = src->len;
+  p.dk = dst->k; p.dv = dst->v; p.dvotes = dst->votes; p.dlog_s = dst->log_s; p.dn_obs = dst->n_obs; p.dlen = dst->len;
+  p.keep_idx = keep_idx; p.n_evict = n_evict; p.start = start; p.members = members;
+  p.scap = src->capacity; p.dcap = dst->capacity; p.budget = budget;
+  p.ln_alpha = alpha > 0.f ? log((double)alpha) : -INFINITY;
+  const int esz = layout->dtype == KEEPKV_BF16 ? 2 : 4;
+  const int lps = layout->head_dim * esz / 16, gpb = 256 / lps;
+  const dim3 grid((budget + gpb - 1) / gpb, units);
+  if (layout->dtype == KEEPKV_BF16) {
+    if (layout->head_dim == 128) merge_apply_kernel<uint16_t, 128><<<grid, 256, 0, st>>>(p);
+    else merge_apply_kernel<uint16_t, 64><<<grid, 256, 0, st>>>(p);
+  } else {
+    if (layout->head_dim == 128) merge_apply_kernel<float, 128><<<grid, 256, 0, st>>>(p);
+    else merge_apply_kernel<float, 64><<<grid, 256, 0, st>>>(p);
+  }
+  return launch_status();
+}

@@ -1,0 +1,74 @@
+"""Plumbing shared by the GPU parity tests: host <-> device copies and oracle-side views."""
+import numpy as np
+import torch
+
+from oracle import keepkv_oracle as O
+from paper_2504_09936_amd import workloads as W
+
+
+def kk():
+    from paper_2504_09936_amd import binding
+    return binding
+
+
+def layout_of(w):
+    b = kk()
+    return b.Layout(w.batch, w.n_q_heads, w.n_kv_heads, w.head_dim, b.BF16 if w.dtype == "bf16" else b.F32, w.scale)
+
+
+def to_device(a, dtype):
+    a = np.ascontiguousarray(a, dtype=np.float32)
+    if dtype == "bf16":
+        return torch.from_numpy(W.to_bf16_bits(a).view(np.int16)).cuda().view(torch.bfloat16)
+    return torch.from_numpy(a).cuda()
+
+
+def to_host(t):
+    if t.dtype == torch.bfloat16:
+        return W.from_bf16_bits(t.view(torch.int16).cpu().numpy().view(np.uint16))
+    return t.cpu().numpy()
+
+
+def new_cache(w, capacity=None, K=None, V=None, votes=None, lens=None):
+    b = kk()
+    lay = layout_of(w)
+    c = b.Cache(lay, capacity or w.capacity)
+    if K is not None:
+        n = K.shape[2]
+        c.k[:, :, :n] = to_device(K, w.dtype)
+        c.v[:, :, :n] = to_device(V, w.dtype)
+        c.votes[:, :, :n] = 1 if votes is None else torch.from_numpy(np.asarray(votes, dtype=np.int32)).cuda()
+        c.len[:] = n if lens is None else torch.from_numpy(np.asarray(lens, dtype=np.int32)).cuda()
+    return lay, c
+
+
+def download(c):
+    """GPU cache -> oracle Cache holding the same values (float64 / int64)."""
+    B, H, cap, D = c.k.shape
+    o = O.Cache(B, H, cap, D)
+    o.k[:] = to_host(c.k)
+    o.v[:] = to_host(c.v)
+    o.votes[:] = c.votes.cpu().numpy()
+    o.log_S[:] = c.log_s.cpu().numpy().astype(np.float64)
+    o.n_obs[:] = c.n_obs.cpu().numpy()
+    o.len[:] = c.len.cpu().numpy()
+    return o
+
+
+def workspace(lay, capacity, budget):
+    n = kk().workspace_bytes(lay, capacity, budget)
+    assert n > 0
+    return torch.empty(n, dtype=torch.uint8, device="cuda")
+
+
+def rel_err_rows(got, ref):
+    """Per-vector ||got - ref||_2 / ||ref||_2 over the last axis (0 where both are 0)."""
+    got, ref = np.asarray(got, np.float64), np.asarray(ref, np.float64)
+    num = np.linalg.norm(got - ref, axis=-1)
+    den = np.linalg.norm(ref, axis=-1)
+    return np.where(den > 0, num / np.where(den > 0, den, 1), num)
+
+
+def f32(x):
+    """The float32 value of a Python float, as a Python float (what the C ABI receives)."""
+    return float(np.float32(x))

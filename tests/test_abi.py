@@ -1,0 +1,60 @@
+"""Host-side checks of the C ABI: the library loads, exports every symbol the header declares,
+sizes workspaces, and rejects bad arguments before touching the device."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+LIB = os.path.join(ROOT, "paper_2504_09936_amd", "libkeepkv.so")
+
+pytestmark = pytest.mark.skipif(not os.path.exists(LIB), reason="libkeepkv.so not built")
+
+
+def _declared():
+    text = open(os.path.join(ROOT, "include", "keepkv.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(keepkv_[a-z_]+)\s*\(", text)))
+
+
+def test_header_symbols_are_exported():
+    lib = C.CDLL(LIB)
+    names = _declared()
+    assert {"keepkv_decode_attn", "keepkv_score", "keepkv_select", "keepkv_match", "keepkv_merge",
+            "keepkv_append", "keepkv_workspace_bytes", "keepkv_strerror", "keepkv_version"} <= set(names)
+    for n in names:
+        assert hasattr(lib, n), n
+
+
+def test_binding_lists_the_same_entry_points():
+    from paper_2504_09936_amd import binding
+    assert sorted(binding.EXPORTS) == _declared()
+    assert binding.version() >= 100
+
+
+def test_workspace_and_argument_validation_without_device():
+    from paper_2504_09936_amd import binding as kk
+    lay = kk.Layout(8, 32, 8, 128, kk.BF16, 128 ** -0.5)
+    small = kk.workspace_bytes(lay, 884, 820)
+    big = kk.workspace_bytes(lay, 8192, 820)
+    assert 0 < small < big
+    assert big >= 8 * 8 * 8192 * 8                      # selection keys: one u64 per slot
+    assert kk.workspace_bytes(lay, 100, 200) == 0       # budget above capacity
+    bad = kk.Layout(8, 30, 8, 128, kk.BF16, 0.1)        # Hq not a multiple of Hkv
+    assert kk.workspace_bytes(bad, 884, 820) == 0
+    lib = kk._lib
+    assert lib.keepkv_strerror(0) == b"ok"
+    assert lib.keepkv_strerror(3) == b"workspace missing or too small"
+    # null pointers are rejected on the host; nothing is launched
+    assert lib.keepkv_score(None, None, None, C.c_float(0.9), None) == kk.ERR_INVALID_ARG
+    assert lib.keepkv_decode_attn(C.byref(lay.c()), None, None, None, None, None, None, 0, None) == kk.ERR_INVALID_ARG
+    cache = kk._Cache(16, 16, 16, 16, 16, 16, 884)      # non-null dummies; never dereferenced on these paths
+    assert lib.keepkv_score(C.byref(lay.c()), C.byref(cache), C.c_void_p(16), C.c_float(1.5), None) == kk.ERR_INVALID_ARG
+    lay3 = kk.Layout(8, 24, 8, 128, kk.BF16, 0.1)       # group size 3 is not built
+    assert lib.keepkv_decode_attn(C.byref(lay3.c()), C.byref(cache), C.c_void_p(16), C.c_void_p(16), None, None,
+                                  None, 0, None) == kk.ERR_UNSUPPORTED
+    assert lib.keepkv_decode_attn(C.byref(lay.c()), C.byref(cache), C.c_void_p(16), C.c_void_p(16), None, None,
+                                  None, 0, None) == kk.ERR_WORKSPACE
+    assert lib.keepkv_select(C.byref(lay.c()), C.byref(cache), 820, 500, 500, C.c_float(0.9), C.c_void_p(16),
+                             C.c_void_p(16), C.c_void_p(16), C.c_void_p(16), 1 << 30, None) == kk.ERR_INVALID_ARG

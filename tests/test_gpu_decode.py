@@ -1,0 +1,112 @@
+"""GPU parity: keepkv_decode_attn, keepkv_score, keepkv_append against the fp64 oracle."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import keepkv_oracle as O
+from paper_2504_09936_amd import workloads as W
+from tests import gpu_util as U
+
+pytestmark = pytest.mark.gpu
+
+TOL = 2e-3   # relative error of attention outputs (per output vector), as the task states
+
+
+def _case(name, **kw):
+    return W.CONFIGS[name].scaled(**kw)
+
+
+CASES = [
+    ("tiny_f32", _case("tiny")),
+    ("bf16_g4", _case("llama3_8b", batch=2, context=1000)),
+    ("bf16_g8", _case("llama3_70b", batch=2, context=700)),
+    ("bf16_d64_g2", _case("llama3_8b", batch=1, n_q_heads=8, n_kv_heads=4, head_dim=64, context=333)),
+    ("f32_d128_g1", _case("tiny", batch=2, n_q_heads=2, n_kv_heads=2, head_dim=128, context=257)),
+    ("bf16_mixture", _case("long_32k", batch=1, context=4100)),
+]
+
+
+@pytest.mark.parametrize("name,w", CASES, ids=[c[0] for c in CASES])
+def test_decode_attn_matches_oracle(name, w):
+    kk = U.kk()
+    K, V = W.make_cache(w, 0)
+    g = np.random.default_rng(1)
+    B, H, N = w.batch, w.n_kv_heads, w.context
+    votes = g.integers(1, 9, size=(B, H, N)).astype(np.int32)
+    lens = g.integers(1, N + 1, size=(B, H)).astype(np.int32)
+    lens.flat[0] = N                      # one full head
+    if lens.size > 1:
+        lens.flat[1] = 0                  # one empty head
+    if lens.size > 2:
+        lens.flat[2] = 1
+    lay, c = U.new_cache(w, capacity=N, K=K, V=V, votes=votes, lens=lens)
+    # poison dead slots: they must never be read
+    for b in range(B):
+        for h in range(H):
+            c.k[b, h, lens[b, h]:] = float("nan")
+            c.v[b, h, lens[b, h]:] = float("nan")
+    q = W.make_query(w, 0, 0)
+    qd = U.to_device(q, w.dtype)
+    out = torch.full_like(qd, 7.0)
+    logits = torch.full((B, H, N), -123.0, dtype=torch.float32, device="cuda")
+    lse = torch.zeros(B, w.n_q_heads, dtype=torch.float32, device="cuda")
+    ws = U.workspace(lay, N, max(1, N // 10))
+    kk.decode_attn(lay, c, qd, out, logits, lse, ws)
+    torch.cuda.synchronize()
+    oc = U.download(c)
+    o_ref, lse_ref, lg_ref = O.attend(oc, q.astype(np.float64), w.scale)
+    o_ref = W.round_storage(o_ref, w.dtype)
+    got = U.to_host(out)
+    err = U.rel_err_rows(got, o_ref)
+    assert err.max() <= TOL, (name, err.max())
+    lg = logits.cpu().numpy()
+    G = w.group
+    for b in range(B):
+        for h in range(H):
+            n = lens[b, h]
+            np.testing.assert_allclose(lg[b, h, :n], lg_ref[b, h, :n], rtol=2e-3, atol=2e-3)
+            assert (lg[b, h, n:] == -123.0).all()          # untouched beyond the live prefix
+            if n == 0:
+                assert (got[b, h * G:(h + 1) * G] == 0).all()
+                assert np.isneginf(lse.cpu().numpy()[b, h * G:(h + 1) * G]).all()
+    live = np.repeat(lens > 0, G, axis=1)
+    np.testing.assert_allclose(lse.cpu().numpy()[live], lse_ref[live], rtol=1e-4, atol=2e-3)
+
+
+@pytest.mark.parametrize("alpha", [0.0, 0.9])
+def test_score_and_append_match_oracle(alpha):
+    kk = U.kk()
+    w = _case("llama3_8b", batch=2, context=300)
+    alpha = U.f32(alpha)
+    K, V = W.make_cache(w, 2)
+    lay, c = U.new_cache(w, capacity=w.context + 8, K=K, V=V)
+    oc = U.download(c)
+    ws = U.workspace(lay, c.capacity, 64)
+    logits = torch.zeros(w.batch, w.n_kv_heads, c.capacity, dtype=torch.float32, device="cuda")
+    out = torch.zeros(w.batch, w.n_q_heads, w.head_dim, dtype=lay.torch_dtype, device="cuda")
+    overflow = torch.zeros(1, dtype=torch.int32, device="cuda")
+    for t in range(6):
+        k_t, v_t = W.make_token(w, 2, t)
+        kk.append(lay, c, U.to_device(k_t, w.dtype), U.to_device(v_t, w.dtype), overflow)
+        oc.append(k_t, v_t)
+        q = W.make_query(w, 2, t)
+        kk.decode_attn(lay, c, U.to_device(q, w.dtype), out, logits, None, ws)
+        kk.score(lay, c, logits, alpha)
+        torch.cuda.synchronize()
+        # stage-wise: the oracle consumes the GPU's logits, so only the EMA arithmetic is compared
+        O.observe(oc, logits.cpu().numpy().astype(np.float64), alpha)
+        n = w.context + t + 1
+        assert (c.len.cpu().numpy() == n).all() and (oc.len == n).all()
+        np.testing.assert_array_equal(c.n_obs.cpu().numpy()[:, :, :n], oc.n_obs[:, :, :n])
+        np.testing.assert_allclose(c.log_s.cpu().numpy()[:, :, :n], oc.log_S[:, :, :n], rtol=1e-5, atol=1e-5)
+        np.testing.assert_array_equal(U.to_host(c.k)[:, :, :n], oc.k[:, :, :n].astype(np.float32))
+        np.testing.assert_array_equal(c.votes.cpu().numpy()[:, :, :n], oc.votes[:, :, :n])
+        # keep the oracle's state on the GPU's f32 values for the next step
+        oc.log_S[:] = c.log_s.cpu().numpy()
+    assert overflow.item() == 0
+    for t in range(4):                                     # run into the capacity limit
+        kk.append(lay, c, U.to_device(k_t, w.dtype), U.to_device(v_t, w.dtype), overflow)
+    torch.cuda.synchronize()
+    assert overflow.item() == 1 and (c.len.cpu().numpy() == c.capacity).all()
