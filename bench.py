@@ -1,0 +1,325 @@
+#!/usr/bin/env python3
+"""Benchmark of the KeepKV hot path on one MI355X.
+
+A *step* is one pass of the whole hot path over one batch for one layer: append the new
+token's (k, v), vote-weighted decode attention, EMA score update and -- every `period`
+steps of that layer -- a compression event (select, match, merge into the layer's other
+buffer).  Steps rotate over `--layers` distinct layer caches so that the working set
+(layers x cache bytes) is far larger than the 256 MB Infinity Cache.  All inputs are
+synthetic (paper_2504_09936_amd.workloads) and resident in HBM before the timed region.
+The timed region is one HIP graph of exactly K steps.
+
+Prints ONE JSON line; `value` is decode tokens/s per layer for the whole hot path
+(batch x steps / time), with a `roofline` object for the decode-attention kernel and a
+`cpu_baseline` object (the numpy oracle on the host cores, bounded sample).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0      # MI355X HBM3E
+MFMA_BF16_PEAK_TFLOPS = 2500.0
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=4096)
+    ap.add_argument("--warmup", type=int, default=256)
+    ap.add_argument("--workload", default="llama3_8b")
+    ap.add_argument("--layers", type=int, default=32)
+    ap.add_argument("--threshold", type=float, default=None, help="merging threshold T (default: workload's, 0.8)")
+    ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying a HIP graph")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--unfused", action="store_true",
+                    help="use keepkv_append + keepkv_decode_attn + keepkv_score instead of keepkv_decode_step")
+    ap.add_argument("--window", type=int, default=None, help="observation passes before the first event")
+    return ap.parse_args()
+
+
+def main():
+    args = parse()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on one GPU only (every (batch, kv head) cache is independent; "
+              "see DESIGN.md for how the path would shard). Run with --gpus 1.", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+
+    from paper_2504_09936_amd import binding as kk
+    from paper_2504_09936_amd import workloads as W
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    dev = torch.device("cuda:0")
+    w = W.CONFIGS[args.workload]
+    if args.window is not None:
+        w = w.scaled(window=args.window)
+    R, K, Wm = args.layers, args.steps, args.warmup
+    B, Hq, H, D, P, Bud, N = w.batch, w.n_q_heads, w.n_kv_heads, w.head_dim, w.period, w.budget, w.context
+    alpha = float(np.float32(w.alpha))
+    T = float(np.float32(w.threshold if args.threshold is None else args.threshold))
+    bf16 = w.dtype == "bf16"
+    lay = kk.Layout(B, Hq, H, D, kk.BF16 if bf16 else kk.F32, w.scale)
+    esz = 2 if bf16 else 4
+    cap = Bud + P
+
+    def to_dev(a):
+        a = np.ascontiguousarray(a, dtype=np.float32)
+        if bf16:
+            return torch.from_numpy(W.to_bf16_bits(a).view(np.int16)).to(dev).view(torch.bfloat16)
+        return torch.from_numpy(a).to(dev)
+
+    # ------------------------------------------------------------------ buffers
+    big = kk.Cache(lay, N)
+    ws = kk.new_workspace(lay, N, Bud)
+    keep = torch.zeros(B, H, Bud, dtype=torch.int32, device=dev)
+    evict_big = torch.zeros(B, H, N - Bud, dtype=torch.int32, device=dev)
+    match_big = torch.zeros(B, H, N - Bud, dtype=torch.int32, device=dev)
+    evict_s = torch.zeros(B, H, cap - Bud, dtype=torch.int32, device=dev)
+    match_s = torch.zeros(B, H, cap - Bud, dtype=torch.int32, device=dev)
+    n_ev = torch.zeros(B, H, dtype=torch.int32, device=dev)
+    dropped = torch.zeros(R, B, H, dtype=torch.int64, device=dev)
+    logits = torch.zeros(B, H, N, dtype=torch.float32, device=dev)
+    out = torch.zeros(B, Hq, D, dtype=lay.torch_dtype, device=dev)
+    caches = [[kk.Cache(lay, cap), kk.Cache(lay, cap)] for _ in range(R)]
+    cur = [0] * R
+
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+
+    # ------------------------------------------------------------------ prefill: window passes + first event per layer
+    t0 = time.time()
+    K0, V0 = W.make_cache(w, 0)
+    K0d, V0d = to_dev(K0), to_dev(V0)
+    del K0, V0
+    first = {"select": [], "match": [], "merge": []}
+    for layer in range(R):
+        # layers are token/batch rotations of the seeded prefill tensors: same statistics, distinct bytes
+        big.k.copy_(torch.roll(K0d, shifts=(layer, 257 * layer), dims=(0, 2)))
+        big.v.copy_(torch.roll(V0d, shifts=(layer, 257 * layer), dims=(0, 2)))
+        if w.query_model == "mean":
+            big.k[:, :, 0] = K0d[:, :, 0]
+        big.votes.fill_(1); big.log_s.fill_(float("-inf")); big.n_obs.zero_(); big.len.fill_(N)
+        for t in range(w.window):
+            q = to_dev(W.make_query(w, layer, t - w.window))
+            kk.decode_attn(lay, big, q, out, logits, None, ws)
+            kk.score(lay, big, logits, alpha)
+        e = [ev() for _ in range(4)]
+        e[0].record()
+        kk.select(lay, big, Bud, w.n_sink, w.n_recent, alpha, keep, evict_big, n_ev, ws)
+        e[1].record()
+        kk.match(lay, big, Bud, keep, evict_big, n_ev, T, match_big, None, ws)
+        e[2].record()
+        kk.merge(lay, big, caches[layer][0], Bud, keep, evict_big, n_ev, match_big, alpha, dropped[layer], ws)
+        e[3].record()
+        torch.cuda.synchronize()
+        for i, name in enumerate(("select", "match", "merge")):
+            first[name].append(e[i].elapsed_time(e[i + 1]) * 1e3)
+    del K0d, V0d
+    t_prefill = time.time() - t0
+
+    # ------------------------------------------------------------------ per-step inputs, resident in HBM
+    total_steps = Wm + K
+    per_layer = (total_steps + R - 1) // R + 1
+    q_all = torch.empty(R, per_layer, B, Hq, D, dtype=lay.torch_dtype, device=dev)
+    k_all = torch.empty(R, per_layer, B, H, D, dtype=lay.torch_dtype, device=dev)
+    v_all = torch.empty(R, per_layer, B, H, D, dtype=lay.torch_dtype, device=dev)
+    for layer in range(R):
+        prev = None
+        qs, ks, vs = [], [], []
+        for t in range(per_layer):
+            qs.append(W.make_query(w, layer, t))
+            k_t, v_t = W.make_token(w, layer, t, prev=prev)
+            prev = (k_t, v_t) if w.key_model == "ar1" else None
+            ks.append(k_t); vs.append(v_t)
+        q_all[layer], k_all[layer], v_all[layer] = to_dev(np.stack(qs)), to_dev(np.stack(ks)), to_dev(np.stack(vs))
+
+    step_no = [0] * R          # decode steps done per layer
+    n_events = 0
+
+    def decode(c, layer, t):
+        if args.unfused:
+            kk.append(lay, c, k_all[layer, t], v_all[layer, t], None)
+            kk.decode_attn(lay, c, q_all[layer, t], out, logits, None, ws)
+            kk.score(lay, c, logits, alpha)
+        else:
+            kk.decode_step(lay, c, q_all[layer, t], k_all[layer, t], v_all[layer, t], out, None, alpha, None, ws)
+
+    def one_step(i):
+        nonlocal n_events
+        layer = i % R
+        t = step_no[layer]
+        c = caches[layer][cur[layer]]
+        decode(c, layer, t)
+        step_no[layer] = t + 1
+        if (t + 1) % P == 0:
+            d = caches[layer][1 - cur[layer]]
+            kk.select(lay, c, Bud, w.n_sink, w.n_recent, alpha, keep, evict_s, n_ev, ws)
+            kk.match(lay, c, Bud, keep, evict_s, n_ev, T, match_s, None, ws)
+            kk.merge(lay, c, d, Bud, keep, evict_s, n_ev, match_s, alpha, dropped[layer], ws)
+            cur[layer] = 1 - cur[layer]
+            n_events += 1
+
+    # ------------------------------------------------------------------ warm-up (eager), then the timed K steps
+    for i in range(Wm):
+        one_step(i)
+    torch.cuda.synchronize()
+    n_events = 0
+    stream = torch.cuda.Stream()
+    start, stop = ev(), ev()
+    if args.no_graph:
+        with torch.cuda.stream(stream):
+            torch.cuda.synchronize()
+            start.record()
+            for i in range(Wm, Wm + K):
+                one_step(i)
+            stop.record()
+        torch.cuda.synchronize()
+    else:
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=stream):
+            for i in range(Wm, Wm + K):
+                one_step(i)
+        torch.cuda.synchronize()
+        with torch.cuda.stream(stream):
+            start.record()
+            graph.replay()
+            stop.record()
+        torch.cuda.synchronize()
+    elapsed_ms = start.elapsed_time(stop)
+    timed_events = n_events
+    overflow_check = max(int(c[cu].len.max().item()) for c, cu in zip(caches, cur))
+    assert overflow_check <= cap
+
+    # ------------------------------------------------------------------ per-kernel durations (instrumented eager pass)
+    # HIP events on the launch stream (torch's current stream) around single calls, same rotation.
+    dec_ms, comp = [], {"select": [], "match": [], "merge": []}
+    live_slots = []
+    i0 = Wm + K
+    n_inst = min(8 * R, 512)
+    for i in range(i0, i0 + n_inst):
+        layer = i % R
+        t = step_no[layer]
+        c = caches[layer][cur[layer]]
+        a, b = ev(), ev()
+        a.record()
+        decode(c, layer, t % per_layer)
+        b.record()
+        torch.cuda.synchronize()
+        dec_ms.append(a.elapsed_time(b))
+        live_slots.append(int(c.len.sum().item()))
+        step_no[layer] = t + 1
+        if (t + 1) % P == 0:
+            d = caches[layer][1 - cur[layer]]
+            kk.select(lay, c, Bud, w.n_sink, w.n_recent, alpha, keep, evict_s, n_ev, ws)
+            kk.match(lay, c, Bud, keep, evict_s, n_ev, T, match_s, None, ws)
+            kk.merge(lay, c, d, Bud, keep, evict_s, n_ev, match_s, alpha, dropped[layer], ws)
+            cur[layer] = 1 - cur[layer]
+    # steady-state compression events: advance every layer to the end of its period, then time the event
+    for layer in range(R):
+        c = caches[layer][cur[layer]]
+        while step_no[layer] % P != 0:
+            decode(c, layer, step_no[layer] % per_layer)
+            step_no[layer] += 1
+        d = caches[layer][1 - cur[layer]]
+        e = [ev() for _ in range(4)]
+        e[0].record()
+        kk.select(lay, c, Bud, w.n_sink, w.n_recent, alpha, keep, evict_s, n_ev, ws)
+        e[1].record()
+        kk.match(lay, c, Bud, keep, evict_s, n_ev, T, match_s, None, ws)
+        e[2].record()
+        kk.merge(lay, c, d, Bud, keep, evict_s, n_ev, match_s, alpha, dropped[layer], ws)
+        e[3].record()
+        torch.cuda.synchronize()
+        for j, name in enumerate(("select", "match", "merge")):
+            comp[name].append(e[j].elapsed_time(e[j + 1]) * 1e3)
+        cur[layer] = 1 - cur[layer]
+
+    # algorithmic bytes of one decode_attn launch: K+V rows, votes, logit side output per live slot,
+    # plus Q in and O out
+    slots = float(np.mean(live_slots))
+    dec_bytes = slots * (2 * D * esz + 4 + 4) + 2 * B * Hq * D * esz
+    dec_us = float(np.mean(dec_ms)) * 1e3
+    achieved = dec_bytes / (dec_us * 1e-6) / 1e9
+    # (the fused step also reads and writes the EMA state: +16 B per slot, counted as algorithmic)
+    if not args.unfused:
+        dec_bytes += slots * 16
+    roofline = {"bound": "hbm", "kernel": "decode_attn_kernel", "achieved": round(achieved, 1),
+                "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
+                "traffic": None, "bytes_per_launch": int(dec_bytes), "avg_launch_us": round(dec_us, 2)}
+
+    M1 = N - Bud
+    match_first_us = float(np.median(first["match"]))
+    match_first_tflops = 2.0 * M1 * Bud * D * B * H / (match_first_us * 1e-6) / 1e12
+
+    # ------------------------------------------------------------------ CPU baseline: the oracle on one layer
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle import keepkv_oracle as O
+        try:
+            from threadpoolctl import threadpool_info
+            cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+        except Exception:
+            cores = 1
+        src = caches[0][cur[0]]
+        oc = O.Cache(B, H, cap, D)
+        f = (lambda t_: W.from_bf16_bits(t_.view(torch.int16).cpu().numpy().view(np.uint16))) if bf16 else (lambda t_: t_.cpu().numpy())
+        oc.k[:], oc.v[:] = f(src.k), f(src.v)
+        oc.votes[:], oc.n_obs[:], oc.len[:] = src.votes.cpu().numpy(), src.n_obs.cpu().numpy(), src.len.cpu().numpy()
+        oc.log_S[:] = src.log_s.cpu().numpy().astype(np.float64)
+        room = cap - int(oc.len.max())
+        n_cpu = 2 * P
+        tc = time.perf_counter()
+        done = 0
+        for t in range(n_cpu):
+            if int(oc.len.max()) == cap:
+                O.compress(oc, Bud, w.n_sink, w.n_recent, alpha, T, exact_any_order=bf16,
+                           storage_round=(W.round_bf16 if bf16 else None))
+            k_t, v_t = W.make_token(w, 0, t)
+            oc.append(k_t, v_t)
+            q = W.make_query(w, 0, t).astype(np.float64)
+            _, _, lg = O.attend(oc, q, w.scale)
+            O.observe(oc, lg, alpha)
+            done += 1
+            if time.perf_counter() - tc > 30.0:
+                break
+        dt = time.perf_counter() - tc
+        cpu = {"value": round(B * done / dt, 1), "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
+               "sample": f"one layer, {done} decode steps of the same workload (append, attention, score; "
+                         f"a compression event every {P} steps), numpy float64"}
+
+    tokens_per_s = B * K / (elapsed_ms * 1e-3)
+    res = {
+        "metric": "decode attn tokens/s + compress us/layer at 10% budget; % HBM/MFMA roofline",
+        "value": round(tokens_per_s, 1), "unit": "tokens/s", "n_gpus": 1, "steps": K, "warmup": Wm,
+        "ms_per_step": round(elapsed_ms / K, 6), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16" if bf16 else "f32", "data": "synthetic",
+        "config": {"workload": f"{w.name}: B={B} Hq={Hq} Hkv={H} D={D} {w.dtype}, context {N} -> budget {Bud} "
+                               f"({w.ratio:.0%}), period {P}, T={T:g}, alpha={alpha:g}",
+                   "layers_rotated": R, "graph": not args.no_graph, "fused_step": not args.unfused, "compress_events_timed": timed_events},
+        "roofline": roofline,
+        "cpu_baseline": cpu,
+        "kernels_us": {
+            "decode_step_event_bracketed": round(dec_us, 2),
+            "compress_steady": {k_: (round(float(np.median(v_)), 1) if v_ else None) for k_, v_ in comp.items()},
+            "compress_first": {k_: round(float(np.median(v_)), 1) for k_, v_ in first.items()},
+        },
+        "match_first_event": {"bound": "mfma", "achieved": round(match_first_tflops, 1), "peak": MFMA_BF16_PEAK_TFLOPS,
+                              "unit": "TFLOP/s", "frac": round(match_first_tflops / MFMA_BF16_PEAK_TFLOPS, 4)},
+        "prefill_s": round(t_prefill, 1),
+    }
+    print(json.dumps(res))
+
+
+if __name__ == "__main__":
+    main()

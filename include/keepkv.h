@@ -71,9 +71,14 @@ int32_t keepkv_version(void);
 
 /* Bytes of DEVICE workspace sufficient for any call below on a cache of `capacity` slots
  * compressed to `budget` slots (pure host function; 0 on invalid arguments).  The
- * workspace is scratch: contents need not be preserved between calls, but it must not be
- * shared by calls that may run concurrently. */
+ * workspace is scratch and must not be shared by calls that may run concurrently.  Its
+ * first 64 KiB hold control words that must be zero when a call starts: clear them once
+ * with keepkv_workspace_init after allocating; every call leaves them zero again. */
 size_t keepkv_workspace_bytes(const keepkv_layout *layout, int32_t capacity, int32_t budget);
+
+/* Clear the control words at the head of a freshly allocated DEVICE workspace (one small
+ * kernel on `stream`; no memset, so it may be captured in a HIP graph). */
+keepkv_status keepkv_workspace_init(void *workspace, size_t workspace_bytes, void *stream);
 
 /* Append one token per (b, h): k_t, v_t [B, Hkv, D] DEVICE are written to slot len[b,h],
  * with votes = 1, log_s = -inf, n_obs = 0, then len[b,h] += 1 (Sec. 3.1 cache update;
@@ -94,6 +99,17 @@ keepkv_status keepkv_append(const keepkv_layout *layout, keepkv_cache *cache,
 keepkv_status keepkv_decode_attn(const keepkv_layout *layout, const keepkv_cache *cache,
                                  const void *q, void *out, float *logits_out, float *lse_out,
                                  void *workspace, size_t workspace_bytes, void *stream);
+
+/* One whole decode step of one layer in a single kernel: keepkv_append of (k_t, v_t), then
+ * keepkv_decode_attn over the grown cache, then keepkv_score with the logits just computed
+ * (the order of App. C.2: the step attends over the cache including its own token, and the
+ * EMA of Eq. 8 observes that step).  Arguments as in those three calls; logits_out may be
+ * NULL.  A head already at capacity is attended and scored without its new token and
+ * `overflow` (DEVICE int32, may be NULL) is set to 1.  Results equal the three separate calls. */
+keepkv_status keepkv_decode_step(const keepkv_layout *layout, keepkv_cache *cache, const void *q,
+                                 const void *k_t, const void *v_t, void *out, float *logits_out,
+                                 float alpha, int32_t *overflow, void *workspace,
+                                 size_t workspace_bytes, void *stream);
 
 /* EMA score update (Eq. 8, t > L branch; Alg. 1 line 6) on the live slots:
  *     S_i <- alpha S_i + (1 - alpha) exp(logits[i]),  n_obs_i += 1
@@ -137,7 +153,7 @@ keepkv_status keepkv_match(const keepkv_layout *layout, const keepkv_cache *cach
  * slots are dropped and their votes added to dropped_votes[b,h] (DEVICE int64, accumulated,
  * may be NULL).  Results are written to dst slots 0..budget-1 in keep_idx order and
  * dst.len = number of retained slots; heads with n_evict == 0 are copied.  src and dst must
- * not overlap; dst.capacity >= budget. */
+ * not overlap; dst.capacity >= budget; budget <= 4096 and src.capacity - budget <= 32768. */
 keepkv_status keepkv_merge(const keepkv_layout *layout, const keepkv_cache *src,
                            keepkv_cache *dst, int32_t budget, const int32_t *keep_idx,
                            const int32_t *evict_idx, const int32_t *n_evict,

@@ -44,6 +44,9 @@ _lib.keepkv_workspace_bytes.restype = C.c_size_t
 _lib.keepkv_workspace_bytes.argtypes = [C.POINTER(_Layout), C.c_int32, C.c_int32]
 _lib.keepkv_append.argtypes = [C.POINTER(_Layout), C.POINTER(_Cache), _P, _P, _P, _P]
 _lib.keepkv_decode_attn.argtypes = [C.POINTER(_Layout), C.POINTER(_Cache), _P, _P, _P, _P, _P, C.c_size_t, _P]
+_lib.keepkv_workspace_init.argtypes = [_P, C.c_size_t, _P]
+_lib.keepkv_decode_step.argtypes = [C.POINTER(_Layout), C.POINTER(_Cache), _P, _P, _P, _P, _P, C.c_float, _P, _P,
+                                    C.c_size_t, _P]
 _lib.keepkv_score.argtypes = [C.POINTER(_Layout), C.POINTER(_Cache), _P, C.c_float, _P]
 _lib.keepkv_select.argtypes = [C.POINTER(_Layout), C.POINTER(_Cache), C.c_int32, C.c_int32, C.c_int32,
                                C.c_float, _P, _P, _P, _P, C.c_size_t, _P]
@@ -51,11 +54,11 @@ _lib.keepkv_match.argtypes = [C.POINTER(_Layout), C.POINTER(_Cache), C.c_int32, 
                               _P, _P, _P, C.c_size_t, _P]
 _lib.keepkv_merge.argtypes = [C.POINTER(_Layout), C.POINTER(_Cache), C.POINTER(_Cache), C.c_int32, _P, _P, _P,
                               _P, C.c_float, _P, _P, C.c_size_t, _P]
-for _f in ("append", "decode_attn", "score", "select", "match", "merge"):
+for _f in ("append", "decode_attn", "decode_step", "workspace_init", "score", "select", "match", "merge"):
     getattr(_lib, "keepkv_" + _f).restype = C.c_int
 
-EXPORTS = ["keepkv_strerror", "keepkv_version", "keepkv_workspace_bytes", "keepkv_append",
-           "keepkv_decode_attn", "keepkv_score", "keepkv_select", "keepkv_match", "keepkv_merge"]
+EXPORTS = ["keepkv_strerror", "keepkv_version", "keepkv_workspace_bytes", "keepkv_workspace_init",
+           "keepkv_append", "keepkv_decode_attn", "keepkv_decode_step", "keepkv_score", "keepkv_select", "keepkv_match", "keepkv_merge"]
 
 
 class KeepKVError(RuntimeError):
@@ -118,6 +121,27 @@ def version() -> int:
 
 def workspace_bytes(layout: Layout, capacity: int, budget: int) -> int:
     return int(_lib.keepkv_workspace_bytes(C.byref(layout.c()), capacity, budget))
+
+
+def _nbytes(t) -> int:
+    return 0 if t is None else t.numel() * t.element_size()
+
+
+def new_workspace(layout: Layout, capacity: int, budget: int, device="cuda"):
+    """Allocate a workspace tensor of the required size and clear its control words."""
+    ws = torch.empty(workspace_bytes(layout, capacity, budget), dtype=torch.uint8, device=device)
+    workspace_init(ws)
+    return ws
+
+
+def workspace_init(workspace) -> None:
+    _check(_lib.keepkv_workspace_init(_ptr(workspace), _nbytes(workspace), _stream()), "keepkv_workspace_init")
+
+
+def decode_step(layout: Layout, cache: Cache, q, k_t, v_t, out, logits_out, alpha: float, overflow, workspace) -> None:
+    _check(_lib.keepkv_decode_step(C.byref(layout.c()), C.byref(cache.c()), _ptr(q), _ptr(k_t), _ptr(v_t), _ptr(out),
+                                   _ptr(logits_out), alpha, _ptr(overflow), _ptr(workspace), _nbytes(workspace),
+                                   _stream()), "keepkv_decode_step")
 
 
 def append(layout: Layout, cache: Cache, k_t, v_t, overflow=None) -> None:

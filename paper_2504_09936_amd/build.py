@@ -13,6 +13,7 @@ LIB = os.path.join(HERE, "libkeepkv.so")
 SOURCES = ["api.hip", "decode_attn.hip", "score_append.hip", "select.hip", "match.hip", "merge.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=off",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+         "-mllvm", "-amdgpu-mfma-vgpr-form",   # MFMA results in VGPRs: the fused epilogue reads them directly
          "-I", os.path.join(ROOT, "include"), "-I", CSRC, "-Wall", "-Wno-unused-function"]
 
 

@@ -12,7 +12,23 @@ extern "C" const char* keepkv_strerror(keepkv_status st) {
   return "unknown status";
 }
 
-extern "C" int32_t keepkv_version(void) { return 100; }
+extern "C" int32_t keepkv_version(void) { return 101; }
+
+namespace {
+__global__ void clear_head_kernel(int32_t* w, int n) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) w[i] = 0;
+}
+}  // namespace
+
+extern "C" keepkv_status keepkv_workspace_init(void* workspace, size_t workspace_bytes, void* stream) {
+  using namespace kk;
+  if (!workspace || !aligned16(workspace) || workspace_bytes < kWorkspaceHead) return KEEPKV_ERR_WORKSPACE;
+  const int n = (int)(kWorkspaceHead / sizeof(int32_t));
+  clear_head_kernel<<<(n + 255) / 256, 256, 0, reinterpret_cast<hipStream_t>(stream)>>>(
+      reinterpret_cast<int32_t*>(workspace), n);
+  return launch_status();
+}
 
 extern "C" size_t keepkv_workspace_bytes(const keepkv_layout* layout, int32_t capacity, int32_t budget) {
   using namespace kk;

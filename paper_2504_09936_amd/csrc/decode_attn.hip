@@ -1,12 +1,17 @@
-// keepkv_decode_attn: vote-weighted flash-decode attention (Eq. 6) with split-K over slots.
+// keepkv_decode_attn / keepkv_decode_step: vote-weighted flash-decode attention (Eq. 6) with
+// split-K over slots, optionally fused with the cache append (Sec. 3.1) and the EMA score update
+// (Eq. 8) so that one decode step of one layer is a single kernel.
 //
 // One workgroup (4 wavefronts) handles one (batch, kv head, split).  A slot's row (D elements)
 // is spread over LPS consecutive lanes, 16 bytes per lane, so one wavefront load instruction
 // streams 64/LPS whole rows, fully coalesced.  Each lane group computes the G logits of its
 // slot with bf16 dot2 (or f32 fma) plus a DPP all-reduce inside the group, keeps its own
 // online-softmax state in the log2 domain with log2(votes) folded into the logit, and
-// accumulates p * v for its 16-byte slice of V.  Groups, wavefronts and splits are combined
-// at the end (LDS, then a small second kernel when nsplit > 1).
+// accumulates p * v for its 16-byte slice of V.  Lane groups and wavefronts are combined through
+// shuffles and LDS; splits are combined by the last workgroup of each head to finish (a ticket
+// counter in the workspace head), so no second kernel is launched.
+#include <stdlib.h>
+
 #include "kk_common.hpp"
 
 namespace kk {
@@ -15,54 +20,74 @@ namespace {
 
 struct DecodeParams {
   const void* q;
-  const void* k;
-  const void* v;
-  const int32_t* votes;
-  const int32_t* len;
+  void* k;            // written only in step mode (the appended row)
+  void* v;
+  int32_t* votes;
+  float* log_s;       // step mode / score fusion
+  int32_t* n_obs;
+  int32_t* len;
+  const void* k_t;    // step mode: [B, Hkv, D] new token, else null
+  const void* v_t;
+  int32_t* overflow;
   void* out;
   float* logits_out;
   float* lse_out;
-  float* partial;   // [B*Hq, nsplit, D + 2]
+  float* partial;     // [B*Hq, nsplit, D + 2]
+  int32_t* ticket;    // [B*Hkv] zero between launches
   int n_kv_heads;
   int capacity;
   int nsplit;
+  int per;          // slots per split
   float scale;
+  float ln_alpha, ln_1m_alpha;
 };
 
 constexpr int kWavesPerBlock = 4;
-constexpr int kUnroll = 4;  // slots per lane group per tile
 
-template <typename T>
-struct Vec16 {  // 16 bytes of a row as held by one lane
-  uint4 raw;
-};
 
-template <typename T, int D, int G>
+__device__ __forceinline__ void st_agent(float* p, float v) {
+  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ float ld_agent(const float* p) {
+  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// LPS lanes share one slot's row, each holding VPL 16-byte vectors of it (vector v of lane `sub` is
+// row vector v * LPS + sub, so the LPS lanes of a group read LPS * 16 contiguous bytes per load).
+// kUnroll slots per lane group are in flight per iteration.
+// STEP: append (k_t, v_t) as a new slot, attend over old + new, update the EMA scores, bump len.
+template <typename T, int D, int G, int LPS, int kUnroll, bool STEP>
 __global__ __launch_bounds__(kWavesPerBlock* kWave) void decode_attn_kernel(DecodeParams p) {
-  constexpr int EPL = 16 / (int)sizeof(T);   // elements per lane
-  constexpr int LPS = D / EPL;               // lanes per slot
-  constexpr int GPW = kWave / LPS;           // slots per load instruction
-  constexpr int TILE = GPW * kUnroll;        // slots per wavefront per iteration
+  constexpr int EPV = 16 / (int)sizeof(T);              // elements per 16-byte vector
+  constexpr int RV = D / EPV;                           // vectors per row
+  constexpr int VPL = RV / LPS;                         // vectors per lane
+  constexpr int EPL = EPV * VPL;                        // elements per lane
+  constexpr int GPW = kWave / LPS;                      // slots per load instruction
+  constexpr int TILE = GPW * kUnroll;                   // slots per wavefront per iteration
   constexpr bool kBf16 = sizeof(T) == 2;
+  static_assert(VPL >= 1 && RV % LPS == 0 && kUnroll <= LPS, "bad lane mapping");
+
+  extern __shared__ __align__(16) float smem[];
+  __shared__ int s_last;
 
   const int unit = blockIdx.x / p.nsplit;    // b * Hkv + h
   const int split = blockIdx.x % p.nsplit;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int grp = lane / LPS, sub = lane % LPS;
-  const int b = unit / p.n_kv_heads, h = unit % p.n_kv_heads;
-  const int len = p.len[unit];
-  const int per = (((len + p.nsplit - 1) / p.nsplit) + 63) & ~63;
-  const int start = split * per;
-  const int end = min(len, start + per);
+  const int len_old = p.len[unit];
+  // step mode: the new token becomes slot len_old (unless the head is full)
+  const bool grow = STEP && len_old < p.capacity;
+  const int len = grow ? len_old + 1 : len_old;
+  const int start = split * p.per;
+  const int end = min(len, start + p.per);
 
   // query slice of this lane for each head of the group
-  uint4 qv[G];
-  {
-    const size_t qrow = ((size_t)b * p.n_kv_heads + h) * G;
+  uint4 qv[G][VPL];
 #pragma unroll
-    for (int g = 0; g < G; ++g)
-      qv[g] = reinterpret_cast<const uint4*>(p.q)[(qrow + g) * LPS + sub];
-  }
+  for (int g = 0; g < G; ++g)
+#pragma unroll
+    for (int v = 0; v < VPL; ++v)
+      qv[g][v] = reinterpret_cast<const uint4*>(p.q)[((size_t)unit * G + g) * RV + v * LPS + sub];
 
   float m[G], l[G], acc[G][EPL];
 #pragma unroll
@@ -73,21 +98,42 @@ __global__ __launch_bounds__(kWavesPerBlock* kWave) void decode_attn_kernel(Deco
     for (int e = 0; e < EPL; ++e) acc[g][e] = 0.f;
   }
 
-  const uint4* kbase = reinterpret_cast<const uint4*>(p.k) + (size_t)unit * p.capacity * LPS;
-  const uint4* vbase = reinterpret_cast<const uint4*>(p.v) + (size_t)unit * p.capacity * LPS;
-  const int32_t* votes = p.votes + (size_t)unit * p.capacity;
+  const size_t ubase = (size_t)unit * p.capacity;
+  uint4* kbase = reinterpret_cast<uint4*>(p.k) + ubase * RV + sub;
+  uint4* vbase = reinterpret_cast<uint4*>(p.v) + ubase * RV + sub;
+  const uint4* knew = STEP ? reinterpret_cast<const uint4*>(p.k_t) + (size_t)unit * RV + sub : nullptr;
+  const uint4* vnew = STEP ? reinterpret_cast<const uint4*>(p.v_t) + (size_t)unit * RV + sub : nullptr;
   const float sl2 = p.scale * kLog2e;
 
   for (int base = start + wave * TILE; base < end; base += kWavesPerBlock * TILE) {
     const int s0 = base + grp * kUnroll;
-    uint4 kk_[kUnroll], vv_[kUnroll];
+    uint4 kk_[kUnroll][VPL], vv_[kUnroll][VPL];
     int pv[kUnroll];
 #pragma unroll
     for (int j = 0; j < kUnroll; ++j) {
       const int s = min(s0 + j, len - 1);      // clamp: dead slots are never read
-      kk_[j] = kbase[(size_t)s * LPS + sub];
-      vv_[j] = vbase[(size_t)s * LPS + sub];
-      pv[j] = votes[s];
+      const bool fresh = grow && s == len_old;
+      const uint4* ka = fresh ? knew : kbase + (size_t)s * RV;
+      const uint4* va = fresh ? vnew : vbase + (size_t)s * RV;
+#pragma unroll
+      for (int v = 0; v < VPL; ++v) {
+        kk_[j][v] = ka[v * LPS];
+        vv_[j][v] = va[v * LPS];
+      }
+      const int pj = p.votes[ubase + s];       // unconditional (in bounds); a branch here would
+      pv[j] = fresh ? 1 : pj;                  // serialise the row loads behind it
+    }
+    // EMA state of the slot this lane will update (lane `sub` < kUnroll owns slot s0 + sub)
+    const int s_mine = s0 + sub;
+    float ls_old = -INFINITY;
+    int no_old = 0;
+    if constexpr (STEP) {
+      const int sc = min(s_mine, len - 1);
+      const float lsv = p.log_s[ubase + sc];
+      const int nov = p.n_obs[ubase + sc];
+      const bool fresh_mine = grow && s_mine == len_old;
+      ls_old = fresh_mine ? -INFINITY : lsv;
+      no_old = fresh_mine ? 0 : nov;
     }
 
     float z[G][kUnroll];
@@ -99,17 +145,21 @@ __global__ __launch_bounds__(kWavesPerBlock* kWave) void decode_attn_kernel(Deco
       float sum = 0.f;
 #pragma unroll
       for (int g = 0; g < G; ++g) {
-        float d;
-        if constexpr (kBf16) {
-          d = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, kk_[j].x), __builtin_bit_cast(bf16x2_t, qv[g].x), 0.f, false);
-          d = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, kk_[j].y), __builtin_bit_cast(bf16x2_t, qv[g].y), d, false);
-          d = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, kk_[j].z), __builtin_bit_cast(bf16x2_t, qv[g].z), d, false);
-          d = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, kk_[j].w), __builtin_bit_cast(bf16x2_t, qv[g].w), d, false);
-        } else {
-          d = __builtin_bit_cast(float, kk_[j].x) * __builtin_bit_cast(float, qv[g].x);
-          d = fmaf(__builtin_bit_cast(float, kk_[j].y), __builtin_bit_cast(float, qv[g].y), d);
-          d = fmaf(__builtin_bit_cast(float, kk_[j].z), __builtin_bit_cast(float, qv[g].z), d);
-          d = fmaf(__builtin_bit_cast(float, kk_[j].w), __builtin_bit_cast(float, qv[g].w), d);
+        float d = 0.f;
+#pragma unroll
+        for (int v = 0; v < VPL; ++v) {
+          const uint4 a = kk_[j][v], b = qv[g][v];
+          if constexpr (kBf16) {
+            d = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, a.x), __builtin_bit_cast(bf16x2_t, b.x), d, false);
+            d = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, a.y), __builtin_bit_cast(bf16x2_t, b.y), d, false);
+            d = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, a.z), __builtin_bit_cast(bf16x2_t, b.z), d, false);
+            d = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, a.w), __builtin_bit_cast(bf16x2_t, b.w), d, false);
+          } else {
+            d = fmaf(__builtin_bit_cast(float, a.x), __builtin_bit_cast(float, b.x), d);
+            d = fmaf(__builtin_bit_cast(float, a.y), __builtin_bit_cast(float, b.y), d);
+            d = fmaf(__builtin_bit_cast(float, a.z), __builtin_bit_cast(float, b.z), d);
+            d = fmaf(__builtin_bit_cast(float, a.w), __builtin_bit_cast(float, b.w), d);
+          }
         }
         d = group_sum<LPS>(d);
         sum += d;
@@ -118,11 +168,37 @@ __global__ __launch_bounds__(kWavesPerBlock* kWave) void decode_attn_kernel(Deco
       mean_logit[j] = sum * (p.scale * (1.0f / G));
     }
 
-    if (p.logits_out != nullptr && sub < kUnroll) {
+    {
+      // every lane evaluates the update of slot s0 + (sub mod kUnroll); only lanes sub < kUnroll store
       float x = mean_logit[0];
 #pragma unroll
-      for (int j = 1; j < kUnroll; ++j) x = (sub == j) ? mean_logit[j] : x;
-      if (s0 + sub < end) p.logits_out[(size_t)unit * p.capacity + s0 + sub] = x;
+      for (int j = 1; j < kUnroll; ++j) x = ((sub & (kUnroll - 1)) == j) ? mean_logit[j] : x;
+      const bool mine = sub < kUnroll && s_mine < end;
+      if (p.logits_out != nullptr && mine) p.logits_out[ubase + s_mine] = x;
+      if constexpr (STEP) {
+        // log_s <- ln(alpha S + (1 - alpha) e^x), n_obs += 1  (Eq. 8)
+        const float a = p.ln_alpha + ls_old, b = p.ln_1m_alpha + x;
+        const float hi = fmaxf(a, b), lo = fminf(a, b);
+        const float r = (lo == -INFINITY) ? hi : hi + log1pf(expf(lo - hi));
+        if (mine) {
+          p.log_s[ubase + s_mine] = r;
+          p.n_obs[ubase + s_mine] = no_old + 1;
+        }
+      }
+    }
+    if constexpr (STEP) {
+      // the group that holds the new token stores it into the cache
+#pragma unroll
+      for (int j = 0; j < kUnroll; ++j) {
+        if (grow && s0 + j == len_old) {
+#pragma unroll
+          for (int v = 0; v < VPL; ++v) {
+            kbase[(size_t)len_old * RV + v * LPS] = kk_[j][v];
+            vbase[(size_t)len_old * RV + v * LPS] = vv_[j][v];
+          }
+          if (sub == 0) p.votes[ubase + len_old] = 1;
+        }
+      }
     }
 
     // online softmax update for this group's kUnroll slots
@@ -148,14 +224,18 @@ __global__ __launch_bounds__(kWavesPerBlock* kWave) void decode_attn_kernel(Deco
 #pragma unroll
     for (int j = 0; j < kUnroll; ++j) {
       float vf[EPL];
-      if constexpr (kBf16) {
-        vf[0] = bf16_lo(vv_[j].x); vf[1] = bf16_hi(vv_[j].x);
-        vf[2] = bf16_lo(vv_[j].y); vf[3] = bf16_hi(vv_[j].y);
-        vf[4] = bf16_lo(vv_[j].z); vf[5] = bf16_hi(vv_[j].z);
-        vf[6] = bf16_lo(vv_[j].w); vf[7] = bf16_hi(vv_[j].w);
-      } else {
-        vf[0] = __builtin_bit_cast(float, vv_[j].x); vf[1] = __builtin_bit_cast(float, vv_[j].y);
-        vf[2] = __builtin_bit_cast(float, vv_[j].z); vf[3] = __builtin_bit_cast(float, vv_[j].w);
+#pragma unroll
+      for (int v = 0; v < VPL; ++v) {
+        const uint4 x = vv_[j][v];
+        if constexpr (kBf16) {
+          vf[v * 8 + 0] = bf16_lo(x.x); vf[v * 8 + 1] = bf16_hi(x.x);
+          vf[v * 8 + 2] = bf16_lo(x.y); vf[v * 8 + 3] = bf16_hi(x.y);
+          vf[v * 8 + 4] = bf16_lo(x.z); vf[v * 8 + 5] = bf16_hi(x.z);
+          vf[v * 8 + 6] = bf16_lo(x.w); vf[v * 8 + 7] = bf16_hi(x.w);
+        } else {
+          vf[v * 4 + 0] = __builtin_bit_cast(float, x.x); vf[v * 4 + 1] = __builtin_bit_cast(float, x.y);
+          vf[v * 4 + 2] = __builtin_bit_cast(float, x.z); vf[v * 4 + 3] = __builtin_bit_cast(float, x.w);
+        }
       }
 #pragma unroll
       for (int g = 0; g < G; ++g)
@@ -164,128 +244,233 @@ __global__ __launch_bounds__(kWavesPerBlock* kWave) void decode_attn_kernel(Deco
     }
   }
 
-  // ---- combine the lane groups of this wavefront (lanes with equal `sub`) -----------------------
-#pragma unroll
-  for (int g = 0; g < G; ++g) {
-    float mw = m[g];
-#pragma unroll
-    for (int off = LPS; off < kWave; off <<= 1) mw = fmaxf(mw, __shfl_xor(mw, off));
-    const float c = (m[g] == -INFINITY) ? 0.f : fast_exp2(m[g] - mw);
-    float lw = l[g] * c;
-#pragma unroll
-    for (int off = LPS; off < kWave; off <<= 1) lw += __shfl_xor(lw, off);
-#pragma unroll
-    for (int e = 0; e < EPL; ++e) {
-      float a = acc[g][e] * c;
-#pragma unroll
-      for (int off = LPS; off < kWave; off <<= 1) a += __shfl_xor(a, off);
-      acc[g][e] = a;
-    }
-    m[g] = mw;
-    l[g] = lw;
-  }
-
-  // ---- combine the wavefronts through LDS ------------------------------------------------------
-  __shared__ float s_m[kWavesPerBlock][G];
-  __shared__ float s_l[kWavesPerBlock][G];
-  __shared__ float s_acc[kWavesPerBlock][G][D];
-  if (grp == 0) {
+  // ---- combine lane groups and wavefronts through LDS ----------------------------------------------
+  // With 8 lanes per slot the two groups of a 16-lane row are merged first with one DPP rotation;
+  // each row then deposits its (m, l, acc) and the workgroup reduces kParts partial states.
+  if constexpr (LPS == 8) {
 #pragma unroll
     for (int g = 0; g < G; ++g) {
-      if (sub == 0) {
-        s_m[wave][g] = m[g];
-        s_l[wave][g] = l[g];
-      }
+      const float mo = dpp_f32<0x128>(m[g]);        // row_ror:8 = the other group of this row
+      const float mw = fmaxf(m[g], mo);
+      const float c = (m[g] == -INFINITY) ? 0.f : fast_exp2(m[g] - mw);
+      const float lc = l[g] * c;
+      l[g] = lc + dpp_f32<0x128>(lc);
 #pragma unroll
-      for (int e = 0; e < EPL; ++e) s_acc[wave][g][sub * EPL + e] = acc[g][e];
+      for (int e = 0; e < EPL; ++e) {
+        const float a = acc[g][e] * c;
+        acc[g][e] = a + dpp_f32<0x128>(a);
+      }
+      m[g] = mw;
+    }
+  }
+  constexpr int LPR = LPS < 16 ? 16 : LPS;            // lanes per deposited part
+  constexpr int kParts = kWavesPerBlock * (kWave / LPR);
+  float* s_m = smem;                                  // [kParts][G]
+  float* s_l = s_m + kParts * G;                      // [kParts][G]
+  float* s_acc = s_l + kParts * G;                    // [kParts][G][D]
+  {
+    const int part = wave * (kWave / LPR) + lane / LPR;
+    if ((lane % LPR) < LPS) {
+#pragma unroll
+      for (int g = 0; g < G; ++g) {
+        if (sub == 0) {
+          s_m[part * G + g] = m[g];
+          s_l[part * G + g] = l[g];
+        }
+#pragma unroll
+        for (int v = 0; v < VPL; ++v) {
+          float4 t;
+          if constexpr (EPV == 8) {
+            t = make_float4(acc[g][v * 8 + 0], acc[g][v * 8 + 1], acc[g][v * 8 + 2], acc[g][v * 8 + 3]);
+            *reinterpret_cast<float4*>(&s_acc[(part * G + g) * D + (v * LPS + sub) * 8]) = t;
+            t = make_float4(acc[g][v * 8 + 4], acc[g][v * 8 + 5], acc[g][v * 8 + 6], acc[g][v * 8 + 7]);
+            *reinterpret_cast<float4*>(&s_acc[(part * G + g) * D + (v * LPS + sub) * 8 + 4]) = t;
+          } else {
+            t = make_float4(acc[g][v * 4 + 0], acc[g][v * 4 + 1], acc[g][v * 4 + 2], acc[g][v * 4 + 3]);
+            *reinterpret_cast<float4*>(&s_acc[(part * G + g) * D + (v * LPS + sub) * 4]) = t;
+          }
+        }
+      }
     }
   }
   __syncthreads();
 
+  auto finish = [&](size_t row, int d, float M, float L, float A) {
+    const float o = (L > 0.f) ? A / L : 0.f;
+    if constexpr (kBf16)
+      reinterpret_cast<uint16_t*>(p.out)[row * D + d] = (uint16_t)f32_to_bf16_bits(o);
+    else
+      reinterpret_cast<float*>(p.out)[row * D + d] = o;
+    if (d == 0 && p.lse_out != nullptr) p.lse_out[row] = (L > 0.f) ? (M + fast_log2(L)) * kLn2 : -INFINITY;
+  };
+
   for (int idx = threadIdx.x; idx < G * D; idx += kWavesPerBlock * kWave) {
     const int g = idx / D, d = idx % D;
-    float M = s_m[0][g];
+    float M = s_m[g];
 #pragma unroll
-    for (int w = 1; w < kWavesPerBlock; ++w) M = fmaxf(M, s_m[w][g]);
+    for (int w = 1; w < kParts; ++w) M = fmaxf(M, s_m[w * G + g]);
     float L = 0.f, A = 0.f;
 #pragma unroll
-    for (int w = 0; w < kWavesPerBlock; ++w) {
-      const float c = (s_m[w][g] == -INFINITY) ? 0.f : fast_exp2(s_m[w][g] - M);
-      L = fmaf(s_l[w][g], c, L);
-      A = fmaf(s_acc[w][g][d], c, A);
+    for (int w = 0; w < kParts; ++w) {
+      const float mw = s_m[w * G + g];
+      const float c = (mw == -INFINITY) ? 0.f : fast_exp2(mw - M);
+      L = fmaf(s_l[w * G + g], c, L);
+      A = fmaf(s_acc[(w * G + g) * D + d], c, A);
     }
     const size_t row = (size_t)unit * G + g;   // == b * Hq + h * G + g
     if (p.nsplit == 1) {
-      const float o = (L > 0.f) ? A / L : 0.f;
-      if constexpr (kBf16)
-        reinterpret_cast<uint16_t*>(p.out)[row * D + d] = (uint16_t)f32_to_bf16_bits(o);
-      else
-        reinterpret_cast<float*>(p.out)[row * D + d] = o;
-      if (d == 0 && p.lse_out != nullptr) p.lse_out[row] = (L > 0.f) ? (M + fast_log2(L)) * kLn2 : -INFINITY;
+      finish(row, d, M, L, A);
     } else {
+      // device-coherent (write-through) stores: the combining workgroup may run on another XCD
       float* dst = p.partial + (row * p.nsplit + split) * (D + 2);
-      dst[2 + d] = A;
+      st_agent(dst + 2 + d, A);
       if (d == 0) {
-        dst[0] = M;
-        dst[1] = L;
+        st_agent(dst, M);
+        st_agent(dst + 1, L);
       }
     }
   }
-}
 
-template <typename T, int D>
-__global__ __launch_bounds__(D) void decode_combine_kernel(const float* __restrict__ partial, void* out,
-                                                           float* lse_out, int nsplit) {
-  const size_t row = blockIdx.x;
-  const int d = threadIdx.x;
-  const float* src = partial + row * nsplit * (D + 2);
-  float M = -INFINITY;
-  for (int s = 0; s < nsplit; ++s) M = fmaxf(M, src[s * (D + 2)]);
-  float L = 0.f, A = 0.f;
-  for (int s = 0; s < nsplit; ++s) {
-    const float ms = src[s * (D + 2)];
-    const float c = (ms == -INFINITY) ? 0.f : fast_exp2(ms - M);
-    L = fmaf(src[s * (D + 2) + 1], c, L);
-    A = fmaf(src[s * (D + 2) + 2 + d], c, A);
+  if (p.nsplit == 1) {
+    if (STEP && threadIdx.x == 0 && grow) p.len[unit] = len;   // every wavefront read len before the barrier above
+    if (STEP && threadIdx.x == 0 && !grow && p.overflow != nullptr) *p.overflow = 1;
+    return;
   }
-  const float o = (L > 0.f) ? A / L : 0.f;
-  if constexpr (sizeof(T) == 2)
-    reinterpret_cast<uint16_t*>(out)[row * D + d] = (uint16_t)f32_to_bf16_bits(o);
-  else
-    reinterpret_cast<float*>(out)[row * D + d] = o;
-  if (d == 0 && lse_out != nullptr) lse_out[row] = (L > 0.f) ? (M + fast_log2(L)) * kLn2 : -INFINITY;
+
+  // ---- the last workgroup of this head to arrive combines the splits ------------------------------
+  // The partial results were stored write-through at device scope, so it is enough that every
+  // wavefront's stores have completed (workgroup-scope release = wait on the store counter) before
+  // the ticket is taken; a device-scope release fence here would write back the whole L2 per
+  // workgroup.  The combining workgroup reads the partials with device-scope loads.
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+  __syncthreads();
+  if (threadIdx.x == 0)
+    s_last = (__hip_atomic_fetch_add(&p.ticket[unit], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == p.nsplit - 1);
+  __syncthreads();
+  if (!s_last) return;
+  for (int idx = threadIdx.x; idx < G * D; idx += kWavesPerBlock * kWave) {
+    const int g = idx / D, d = idx % D;
+    const size_t row = (size_t)unit * G + g;
+    const float* src = p.partial + row * p.nsplit * (D + 2);
+    float M = -INFINITY, L = 0.f, A = 0.f;
+    constexpr int CH = 8;                       // splits fetched per round trip
+    for (int s0 = 0; s0 < p.nsplit; s0 += CH) {
+      float ms[CH], ls[CH], as[CH];
+#pragma unroll
+      for (int i = 0; i < CH; ++i) {
+        const int s = min(s0 + i, p.nsplit - 1);
+        ms[i] = ld_agent(src + s * (D + 2));
+        ls[i] = ld_agent(src + s * (D + 2) + 1);
+        as[i] = ld_agent(src + s * (D + 2) + 2 + d);
+      }
+      float mc = M;
+#pragma unroll
+      for (int i = 0; i < CH; ++i) mc = fmaxf(mc, ms[i]);
+      const float c0 = (M == -INFINITY) ? 0.f : fast_exp2(M - mc);
+      L *= c0;
+      A *= c0;
+#pragma unroll
+      for (int i = 0; i < CH; ++i) {
+        const float c = (s0 + i < p.nsplit && ms[i] != -INFINITY) ? fast_exp2(ms[i] - mc) : 0.f;
+        L = fmaf(ls[i], c, L);
+        A = fmaf(as[i], c, A);
+      }
+      M = mc;
+    }
+    finish(row, d, M, L, A);
+  }
+  if (threadIdx.x == 0) {
+    __hip_atomic_store(&p.ticket[unit], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // ready for the next launch
+    if (STEP && grow) p.len[unit] = len;
+    if (STEP && !grow && p.overflow != nullptr) *p.overflow = 1;
+  }
 }
 
 template <typename T, int D, int G>
-void launch_decode(const DecodeParams& p, int units, hipStream_t st) {
-  decode_attn_kernel<T, D, G><<<units * p.nsplit, kWavesPerBlock * kWave, 0, st>>>(p);
-  if (p.nsplit > 1)
-    decode_combine_kernel<T, D><<<units * G, D, 0, st>>>(p.partial, p.out, p.lse_out, p.nsplit);
+void launch_decode(const DecodeParams& p, int units, bool step, hipStream_t st) {
+  // 8 lanes per slot (16 channels each at D = 128 bf16) halves the cross-lane reduction work; the
+  // widest group keeps 16 lanes per slot so that its accumulators still fit two waves per SIMD.
+  constexpr int RV = D * (int)sizeof(T) / 16;                       // 16-byte vectors per row
+  constexpr int LPS = (G >= 8 && RV >= 16) ? RV / (RV >= 32 ? 2 : 1) : (RV >= 32 ? 16 : 8);
+  constexpr int U = 4;
+  const dim3 grid(units * p.nsplit), block(kWavesPerBlock * kWave);
+  constexpr int parts = kWavesPerBlock * (kWave / (LPS < 16 ? 16 : LPS));
+  constexpr size_t smem = (size_t)parts * G * (D + 2) * sizeof(float);
+  if constexpr (smem > 64 * 1024) {
+    static const hipError_t a1 = hipFuncSetAttribute((const void*)decode_attn_kernel<T, D, G, LPS, U, true>,
+                                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    static const hipError_t a2 = hipFuncSetAttribute((const void*)decode_attn_kernel<T, D, G, LPS, U, false>,
+                                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    (void)a1; (void)a2;
+  }
+  if (step) decode_attn_kernel<T, D, G, LPS, U, true><<<grid, block, smem, st>>>(p);
+  else decode_attn_kernel<T, D, G, LPS, U, false><<<grid, block, smem, st>>>(p);
 }
 
 template <typename T, int D>
-void dispatch_g(const DecodeParams& p, int units, int G, hipStream_t st) {
+void dispatch_g(const DecodeParams& p, int units, int G, bool step, hipStream_t st) {
   switch (G) {
-    case 1: launch_decode<T, D, 1>(p, units, st); break;
-    case 2: launch_decode<T, D, 2>(p, units, st); break;
-    case 4: launch_decode<T, D, 4>(p, units, st); break;
-    default: launch_decode<T, D, 8>(p, units, st); break;
+    case 1: launch_decode<T, D, 1>(p, units, step, st); break;
+    case 2: launch_decode<T, D, 2>(p, units, step, st); break;
+    case 4: launch_decode<T, D, 4>(p, units, step, st); break;
+    default: launch_decode<T, D, 8>(p, units, step, st); break;
   }
+}
+
+keepkv_status run_decode(const keepkv_layout* layout, const keepkv_cache* cache, const void* q, const void* k_t,
+                         const void* v_t, void* out, float* logits_out, float* lse_out, float alpha, int32_t* overflow,
+                         bool step, void* workspace, size_t workspace_bytes, void* stream) {
+  if (!layout_ok(layout) || !cache_ok(cache) || !q || !out) return KEEPKV_ERR_INVALID_ARG;
+  if (!aligned16(q) || !aligned16(out) || !aligned16(cache->k) || !aligned16(cache->v)) return KEEPKV_ERR_INVALID_ARG;
+  if (step && (!k_t || !v_t || !aligned16(k_t) || !aligned16(v_t) || !(alpha >= 0.f && alpha < 1.f)))
+    return KEEPKV_ERR_INVALID_ARG;
+  if (!layout_supported(layout)) return KEEPKV_ERR_UNSUPPORTED;
+  const int units = layout->batch * layout->n_kv_heads;
+  if (units > kMaxUnits) return KEEPKV_ERR_UNSUPPORTED;
+  const DecodePlan pl = plan_decode(layout, cache->capacity);
+  if (pl.nsplit > 1 && (!workspace || workspace_bytes < pl.bytes || !aligned16(workspace))) return KEEPKV_ERR_WORKSPACE;
+
+  DecodeParams p;
+  p.q = q; p.k = cache->k; p.v = cache->v; p.votes = cache->votes; p.log_s = cache->log_s; p.n_obs = cache->n_obs;
+  p.len = cache->len; p.k_t = k_t; p.v_t = v_t; p.overflow = overflow;
+  p.out = out; p.logits_out = logits_out; p.lse_out = lse_out;
+  p.partial = reinterpret_cast<float*>(reinterpret_cast<char*>(workspace) + pl.partial_off);
+  p.ticket = reinterpret_cast<int32_t*>(workspace);
+  p.n_kv_heads = layout->n_kv_heads; p.capacity = cache->capacity; p.nsplit = pl.nsplit; p.per = pl.per; p.scale = layout->scale;
+  p.ln_alpha = (step && alpha > 0.f) ? logf(alpha) : -INFINITY;
+  p.ln_1m_alpha = step ? log1pf(-alpha) : 0.f;
+
+  const int G = layout->n_q_heads / layout->n_kv_heads;
+  hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+  if (layout->dtype == KEEPKV_BF16) {
+    if (layout->head_dim == 128) dispatch_g<uint16_t, 128>(p, units, G, step, st);
+    else dispatch_g<uint16_t, 64>(p, units, G, step, st);
+  } else {
+    if (layout->head_dim == 128) dispatch_g<float, 128>(p, units, G, step, st);
+    else dispatch_g<float, 64>(p, units, G, step, st);
+  }
+  return launch_status();
 }
 
 }  // namespace
 
 DecodePlan plan_decode(const keepkv_layout* L, int capacity) {
+  // Slots per split: 128 (two 16-slot tiles per wavefront) unless that leaves the chip short of
+  // workgroups (then 64) or floods it (then enough slots per split for about 2048 workgroups).
   DecodePlan pl;
-  const int units = L->batch * L->n_kv_heads;
-  const int max_split = (capacity + 63) / 64;
-  int ns = (1024 + units - 1) / units;         // aim at ~4 workgroups per compute unit
-  ns = ns < 1 ? 1 : ns;
-  ns = ns > max_split ? max_split : ns;
-  ns = ns > 256 ? 256 : ns;
-  pl.nsplit = ns;
-  pl.partial_off = 0;
-  pl.bytes = align_up((size_t)L->batch * L->n_q_heads * ns * (L->head_dim + 2) * sizeof(float), 256);
+  const long units = (long)L->batch * L->n_kv_heads;
+  long per = 128;
+  const long spread = (units * capacity / 2048 + 63) / 64 * 64;
+  if (spread > per) per = spread;
+  if (units * ((capacity + per - 1) / per) < 256 && per > 64) per = 64;
+  static const long forced = [] { const char* e = getenv("KEEPKV_DECODE_CHUNK"); return e ? atol(e) : 0L; }();
+  if (forced >= 64) per = forced / 64 * 64;
+  long ns = (capacity + per - 1) / per;
+  if (ns > 1024) { ns = 1024; per = ((capacity + ns - 1) / ns + 63) / 64 * 64; ns = (capacity + per - 1) / per; }
+  pl.nsplit = (int)ns;
+  pl.per = (int)per;
+  pl.partial_off = kWorkspaceHead;
+  pl.bytes = kWorkspaceHead + align_up((size_t)L->batch * L->n_q_heads * ns * (L->head_dim + 2) * sizeof(float), 256);
   return pl;
 }
 
@@ -294,27 +479,14 @@ DecodePlan plan_decode(const keepkv_layout* L, int capacity) {
 extern "C" keepkv_status keepkv_decode_attn(const keepkv_layout* layout, const keepkv_cache* cache,
                                             const void* q, void* out, float* logits_out, float* lse_out,
                                             void* workspace, size_t workspace_bytes, void* stream) {
-  using namespace kk;
-  if (!layout_ok(layout) || !cache_ok(cache) || !q || !out) return KEEPKV_ERR_INVALID_ARG;
-  if (!aligned16(q) || !aligned16(out) || !aligned16(cache->k) || !aligned16(cache->v)) return KEEPKV_ERR_INVALID_ARG;
-  if (!layout_supported(layout)) return KEEPKV_ERR_UNSUPPORTED;
-  const DecodePlan pl = plan_decode(layout, cache->capacity);
-  if (pl.nsplit > 1 && (!workspace || workspace_bytes < pl.bytes || !aligned16(workspace))) return KEEPKV_ERR_WORKSPACE;
+  return kk::run_decode(layout, cache, q, nullptr, nullptr, out, logits_out, lse_out, 0.f, nullptr, false, workspace,
+                        workspace_bytes, stream);
+}
 
-  DecodeParams p;
-  p.q = q; p.k = cache->k; p.v = cache->v; p.votes = cache->votes; p.len = cache->len;
-  p.out = out; p.logits_out = logits_out; p.lse_out = lse_out;
-  p.partial = reinterpret_cast<float*>(reinterpret_cast<char*>(workspace) + pl.partial_off);
-  p.n_kv_heads = layout->n_kv_heads; p.capacity = cache->capacity; p.nsplit = pl.nsplit; p.scale = layout->scale;
-  const int units = layout->batch * layout->n_kv_heads;
-  const int G = layout->n_q_heads / layout->n_kv_heads;
-  hipStream_t st = reinterpret_cast<hipStream_t>(stream);
-  if (layout->dtype == KEEPKV_BF16) {
-    if (layout->head_dim == 128) dispatch_g<uint16_t, 128>(p, units, G, st);
-    else dispatch_g<uint16_t, 64>(p, units, G, st);
-  } else {
-    if (layout->head_dim == 128) dispatch_g<float, 128>(p, units, G, st);
-    else dispatch_g<float, 64>(p, units, G, st);
-  }
-  return launch_status();
+extern "C" keepkv_status keepkv_decode_step(const keepkv_layout* layout, keepkv_cache* cache, const void* q,
+                                            const void* k_t, const void* v_t, void* out, float* logits_out,
+                                            float alpha, int32_t* overflow, void* workspace, size_t workspace_bytes,
+                                            void* stream) {
+  return kk::run_decode(layout, cache, q, k_t, v_t, out, logits_out, nullptr, alpha, overflow, true, workspace,
+                        workspace_bytes, stream);
 }

@@ -82,8 +82,15 @@ inline keepkv_status launch_status() {
 }
 
 // ---- workspace carving (one definition, used by keepkv_workspace_bytes and by every call) ------
+// The first kWorkspaceHead bytes hold control words (split tickets) that must be zero between
+// calls; keepkv_workspace_init clears them and every kernel leaves them cleared.  Scratch areas of
+// all calls start behind the head.
+constexpr int kMaxUnits = 16384;                         // batch * n_kv_heads
+constexpr size_t kWorkspaceHead = kMaxUnits * sizeof(int32_t);
+
 struct DecodePlan {
   int nsplit;         // workgroups per (batch, kv head)
+  int per;            // slots per split (multiple of 64)
   size_t partial_off; // float [B*Hq, nsplit, D + 2]
   size_t bytes;
 };

@@ -28,12 +28,13 @@ constexpr int kStageCols = 128;                         // retained keys per LDS
 template <typename T, int D>
 __global__ __launch_bounds__(256) void rnorm_kernel(const T* __restrict__ k, const int32_t* __restrict__ keep_idx,
                                                     const int32_t* __restrict__ n_evict, float* __restrict__ rnorm,
-                                                    int capacity, int budget) {
+                                                    int capacity, int budget, int rn_pitch) {
   constexpr int EPL = 16 / (int)sizeof(T), LPS = D / EPL;
   const int unit = blockIdx.y;
   if (n_evict[unit] <= 0) return;
   const int r = blockIdx.x * (256 / LPS) + threadIdx.x / LPS;
   const int sub = threadIdx.x % LPS;
+  if (r >= rn_pitch) return;
   const bool valid = r < budget;
   const int slot = valid ? keep_idx[(size_t)unit * budget + r] : 0;
   float ss = 0.f;
@@ -55,7 +56,8 @@ __global__ __launch_bounds__(256) void rnorm_kernel(const T* __restrict__ k, con
     }
   }
   ss = group_sum<LPS>(ss);
-  if (valid && sub == 0) rnorm[(size_t)unit * budget + r] = (ss > 0.f && slot >= 0) ? 1.0f / sqrtf(ss) : 0.f;
+  // positions budget .. rn_pitch - 1 are padding: zero, so padded columns score 0
+  if (sub == 0) rnorm[(size_t)unit * rn_pitch + r] = (valid && ss > 0.f && slot >= 0) ? 1.0f / sqrtf(ss) : 0.f;
 }
 
 // ---------------------------------------------------------------------------------------------------
@@ -69,7 +71,7 @@ struct MatchParams {
   float* sim_out;
   int32_t* flag_count;   // [1]
   int32_t* flag_rows;    // [units * max_evict]: unit * max_evict + j
-  int capacity, budget, max_evict;
+  int capacity, budget, max_evict, rn_pitch;
   float threshold, delta;
   int code_bits;
 };
@@ -79,17 +81,74 @@ __device__ __forceinline__ int imin(int a, int b) { return a < b ? a : b; }
 // median of three; the backend folds this into v_med3_i32
 __device__ __forceinline__ int imed3(int a, int b, int c) { return imax(imin(a, b), imin(imax(a, b), c)); }
 
+// Row r of a wavefront's 64 rows is finished by lane r: reduce the 32 per-column-class pairs, then
+// decide from the f32 value or queue the row for the f64 kernel.
+__device__ __forceinline__ void reduce_pairs(const int* s_b1, const int* s_b2, int row, int val_mask, int code_mask,
+                                             int& v1, int& c1, int& v2) {
+  v1 = (int)0x80000000; v2 = (int)0x80000000; c1 = 0;
+  for (int q = 0; q < 32; ++q) {
+    const int k1 = s_b1[row * 33 + q], k2 = s_b2[row * 33 + q];
+    const int val = k1 & val_mask;
+    const int col = (code_mask - (k1 & code_mask)) * 32 + q;
+    const int val2 = k2 & val_mask;
+    if (val > v1 || (val == v1 && col < c1)) {
+      v2 = imax(v1, val2);
+      v1 = val;
+      c1 = col;
+    } else {
+      v2 = imax(v2, val);
+    }
+  }
+}
+
+__device__ __forceinline__ void decide_row(const MatchParams& p, int unit, int j, int v1, int c1, int v2, float ss) {
+  const float rn_e = 1.0f / sqrtf(ss);
+  const float y1 = __builtin_bit_cast(float, v1), y2 = (v2 > 0) ? __builtin_bit_cast(float, v2) : 0.f;
+  const float cos1 = y1 * rn_e;
+  const bool fragile = !(v1 > 0) || !(ss > 0.f) || !(rn_e < INFINITY) || (y1 - y2) * rn_e <= p.delta ||
+                       fabsf(cos1 - p.threshold) <= p.delta || c1 >= p.budget;
+  const size_t o = (size_t)unit * p.max_evict + j;
+  p.match[o] = (cos1 > p.threshold) ? c1 : -1;
+  if (p.sim_out != nullptr) p.sim_out[o] = cos1;
+  if (fragile) {
+    const int at = atomicAdd(p.flag_count, 1);
+    p.flag_rows[at] = (int)o;
+  }
+}
+
+// fold one scaled similarity into a running (best, second best) pair: 4 vector instructions
+__device__ __forceinline__ void fold_one(float c, float rn, int code, int val_mask, int& b1, int& b2) {
+  const int k = (__builtin_bit_cast(int, c * rn) & val_mask) | code;
+  b2 = imed3(b1, b2, k);
+  b1 = imax(b1, k);
+}
+
+// fold one pair of 32x32 accumulator tiles (rows of A tile 0 / 1, one column block) into the running pairs
+__device__ __forceinline__ void fold_tile(const f32x16_t& c0, const f32x16_t& c1, float rn, int code, int val_mask,
+                                          int (&b1)[2][16], int (&b2)[2][16]) {
+#pragma unroll
+  for (int i = 0; i < 16; ++i) {
+    const int k0 = (__builtin_bit_cast(int, c0[i] * rn) & val_mask) | code;
+    b2[0][i] = imed3(b1[0][i], b2[0][i], k0);
+    b1[0][i] = imax(b1[0][i], k0);
+    const int k1 = (__builtin_bit_cast(int, c1[i] * rn) & val_mask) | code;
+    b2[1][i] = imed3(b1[1][i], b2[1][i], k1);
+    b1[1][i] = imax(b1[1][i], k1);
+  }
+}
+
 template <int D>
 __global__ __launch_bounds__(kMWaves* kWave) void match_mfma_kernel(MatchParams p) {
   constexpr int KS = D / 16;                 // MFMA k-steps over the head dimension
-  constexpr int PITCH = D * 2 + 16;          // bytes per retained key in LDS (padded against bank conflicts)
-  constexpr int CHUNKS = D * 2 / 16;         // 16-byte chunks per key
-  constexpr int STAGE_BYTES = kStageCols * PITCH;
+  constexpr int ROWB = D * 2;                // bytes per key
+  constexpr int CHUNKS = ROWB / 16;          // 16-byte chunks per key
+  constexpr int STAGE_BYTES = kStageCols * ROWB;
   constexpr int EPI_BYTES = kMWaves * kRowsPerWave * 33 * 2 * 4;   // transposed (best, second) pairs
   constexpr int REGION = 2 * STAGE_BYTES > EPI_BYTES ? 2 * STAGE_BYTES : EPI_BYTES;
+  constexpr int LOADS = kStageCols * CHUNKS / (kMWaves * kWave);   // async 16-byte loads per lane per stage
 
   extern __shared__ __align__(16) unsigned char smem[];
-  unsigned char* s_stage = smem;                                        // 2 * STAGE_BYTES
+  unsigned char* s_stage = smem;                                        // 2 stages, swizzled rows
   float* s_rn = reinterpret_cast<float*>(smem + REGION);                // [2][kStageCols]
   float* s_rne = s_rn + 2 * kStageCols;                                 // [kMWaves][64]
 
@@ -98,13 +157,37 @@ __global__ __launch_bounds__(kMWaves* kWave) void match_mfma_kernel(MatchParams 
   const int row_blk = blockIdx.x * kRowsPerBlock;
   if (row_blk >= n_ev) return;
   const int n_keep = p.budget;               // n_evict > 0 implies the retained list is full
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int l32 = lane & 31, half = lane >> 5;
 
-  const unsigned char* kbytes = reinterpret_cast<const unsigned char*>(p.k) + (size_t)unit * p.capacity * (D * 2);
+  const unsigned char* kbytes = reinterpret_cast<const unsigned char*>(p.k) + (size_t)unit * p.capacity * ROWB;
   const int32_t* keep = p.keep_idx + (size_t)unit * p.budget;
   const int32_t* evict = p.evict_idx + (size_t)unit * p.max_evict;
-  const float* rn_c = p.rnorm + (size_t)unit * p.budget;
+  const float* rn_c = p.rnorm + (size_t)unit * p.rn_pitch;
+
+  // ---- stage loader: global -> LDS without passing through registers.  A wavefront instruction
+  // deposits 64 consecutive 16-byte chunks; chunk c of key `col` lives at position c ^ (col mod
+  // CHUNKS) of its row, which keeps the MFMA operand reads below free of bank conflicts.
+  auto issue_stage = [&](int s) {
+    unsigned char* dst = s_stage + (s & 1) * STAGE_BYTES;
+#pragma unroll
+    for (int i = 0; i < LOADS; ++i) {
+      const int q = tid + i * (kMWaves * kWave);
+      const int col_l = q / CHUNKS, phys = q % CHUNKS;
+      const int slot = keep[min(s * kStageCols + col_l, n_keep - 1)];
+      const unsigned char* src = kbytes + (size_t)slot * ROWB + ((phys ^ (col_l & (CHUNKS - 1))) * 16);
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
+                                       (__attribute__((address_space(3))) void*)(dst + (wave * 64 + i * (kMWaves * kWave)) * 16),
+                                       16, 0, 0);
+    }
+    if (wave < kStageCols / 64) {            // 1/|k_c| of the stage's keys (padded with zeros by rnorm_kernel)
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(rn_c + s * kStageCols + tid),
+                                       (__attribute__((address_space(3))) void*)(s_rn + (s & 1) * kStageCols + wave * 64),
+                                       4, 0, 0);
+    }
+  };
+  issue_stage(0);
 
   // ---- A operands: this wavefront's 64 evicted rows, resident for the whole kernel -----------------
   bf16x8_t a[2][KS];
@@ -112,7 +195,7 @@ __global__ __launch_bounds__(kMWaves* kWave) void match_mfma_kernel(MatchParams 
 #pragma unroll
   for (int t = 0; t < 2; ++t) {
     const int j = min(row_blk + wave * kRowsPerWave + t * 32 + l32, n_ev - 1);
-    const unsigned char* row = kbytes + (size_t)evict[j] * (D * 2);
+    const unsigned char* row = kbytes + (size_t)evict[j] * ROWB;
     float ss = 0.f;
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) {
@@ -130,7 +213,10 @@ __global__ __launch_bounds__(kMWaves* kWave) void match_mfma_kernel(MatchParams 
   }
 
   const int code_mask = (1 << p.code_bits) - 1;
-  const int val_mask = ~code_mask;
+  // the value mask lives in a vector register so that (x & mask) | code is one v_and_or_b32 (a VOP3
+  // instruction of this target may read only one scalar register, and the code is scalar)
+  int val_mask;
+  asm volatile("v_mov_b32 %0, %1" : "=v"(val_mask) : "s"(~code_mask));
   int b1[2][16], b2[2][16];
 #pragma unroll
   for (int t = 0; t < 2; ++t)
@@ -138,67 +224,56 @@ __global__ __launch_bounds__(kMWaves* kWave) void match_mfma_kernel(MatchParams 
     for (int i = 0; i < 16; ++i) b1[t][i] = b2[t][i] = (int)0x80000000;
 
   const int n_stage = (n_keep + kStageCols - 1) / kStageCols;
-
-  // ---- stage loader: 128 keys x CHUNKS 16-byte chunks, 256 threads ------------------------------------
-  constexpr int LOADS = kStageCols * CHUNKS / (kMWaves * kWave);
-  uint4 stage_reg[LOADS];
-  auto load_stage = [&](int s) {
-#pragma unroll
-    for (int i = 0; i < LOADS; ++i) {
-      const int c = tid + i * (kMWaves * kWave);
-      const int col = s * kStageCols + c / CHUNKS;
-      const int slot = keep[min(col, n_keep - 1)];
-      stage_reg[i] = *reinterpret_cast<const uint4*>(kbytes + (size_t)slot * (D * 2) + (c % CHUNKS) * 16);
-    }
-  };
-  auto store_stage = [&](int s) {
-    unsigned char* dst = s_stage + (s & 1) * STAGE_BYTES;
-#pragma unroll
-    for (int i = 0; i < LOADS; ++i) {
-      const int c = tid + i * (kMWaves * kWave);
-      *reinterpret_cast<uint4*>(dst + (c / CHUNKS) * PITCH + (c % CHUNKS) * 16) = stage_reg[i];
-    }
-    if (tid < kStageCols) {
-      const int col = s * kStageCols + tid;
-      s_rn[(s & 1) * kStageCols + tid] = (col < n_keep) ? rn_c[col] : 0.f;   // padding columns score 0
-    }
-  };
-
-  load_stage(0);
-  store_stage(0);
+  // software pipeline: the MFMAs of column block cb are issued together with the fold of block
+  // cb - 1, whose accumulators are carried in (p0, p1).  The first fold sees zeros and is harmless.
+  f32x16_t p0 = {0}, p1 = {0};
+  float prn = 0.f;
+  int pcode = 0;
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   __syncthreads();
 
+  constexpr int VPK = 16 / KS;               // accumulator values folded per k-step and tile
   for (int s = 0; s < n_stage; ++s) {
-    if (s + 1 < n_stage) load_stage(s + 1);
+    if (s + 1 < n_stage) issue_stage(s + 1);
     const unsigned char* src = s_stage + (s & 1) * STAGE_BYTES;
+    auto frag = [&](int cbl, int ks) {
+      return *reinterpret_cast<const bf16x8_t*>(src + (cbl * 32 + l32) * ROWB +
+                                               (((ks * 2 + half) ^ (l32 & (CHUNKS - 1))) * 16));
+    };
+    bf16x8_t bq = frag(0, 0);
 #pragma unroll
     for (int cbl = 0; cbl < kStageCols / 32; ++cbl) {
       const int cb = s * (kStageCols / 32) + cbl;           // global column block
       if (cb * 32 < n_keep) {                                 // uniform over the workgroup
-        f32x16_t acc0 = {0}, acc1 = {0};
-        const unsigned char* bcol = src + (cbl * 32 + l32) * PITCH + half * 16;
+        f32x16_t n0 = {0}, n1 = {0};
+        // Explicit interleave: each MFMA is followed by the fold of VPK values of the previous
+        // column block, and nothing may be scheduled across the fences, so the matrix pipe and the
+        // vector ALU of this wavefront run side by side.
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) {
-          const bf16x8_t bfrag = *reinterpret_cast<const bf16x8_t*>(bcol + ks * 32);
-          acc0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[0][ks], bfrag, acc0, 0, 0, 0);
-          acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[1][ks], bfrag, acc1, 0, 0, 0);
-        }
-        const float rn = s_rn[(s & 1) * kStageCols + cbl * 32 + l32];
-        const int code = code_mask - cb;                      // lower column block -> larger code
+          const bf16x8_t bnext = (ks + 1 < KS) ? frag(cbl, ks + 1) : frag((cbl + 1) % (kStageCols / 32), 0);
+          n0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[0][ks], bq, n0, 0, 0, 0);
+          __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (int i = 0; i < 16; ++i) {
-          const int k0 = (__builtin_bit_cast(int, acc0[i] * rn) & val_mask) | code;
-          b2[0][i] = imed3(b1[0][i], b2[0][i], k0);
-          b1[0][i] = imax(b1[0][i], k0);
-          const int k1 = (__builtin_bit_cast(int, acc1[i] * rn) & val_mask) | code;
-          b2[1][i] = imed3(b1[1][i], b2[1][i], k1);
-          b1[1][i] = imax(b1[1][i], k1);
+          for (int i = ks * VPK; i < (ks + 1) * VPK; ++i) fold_one(p0[i], prn, pcode, val_mask, b1[0][i], b2[0][i]);
+          __builtin_amdgcn_sched_barrier(0);
+          n1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[1][ks], bq, n1, 0, 0, 0);
+          __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+          for (int i = ks * VPK; i < (ks + 1) * VPK; ++i) fold_one(p1[i], prn, pcode, val_mask, b1[1][i], b2[1][i]);
+          __builtin_amdgcn_sched_barrier(0);
+          bq = bnext;
         }
+        p0 = n0;
+        p1 = n1;
+        prn = s_rn[(s & 1) * kStageCols + cbl * 32 + l32];
+        pcode = code_mask - cb;                               // lower column block -> larger code
       }
     }
-    if (s + 1 < n_stage) store_stage(s + 1);   // other buffer: nobody reads it during stage s
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
   }
+  fold_tile(p0, p1, prn, pcode, val_mask, b1, b2);
 
   // ---- transpose the per-lane pairs through LDS: [wave][row 0..63][33] x {best, second} ---------------
   int* s_b1 = reinterpret_cast<int*>(s_stage) + wave * (kRowsPerWave * 33 * 2);
@@ -217,15 +292,127 @@ __global__ __launch_bounds__(kMWaves* kWave) void match_mfma_kernel(MatchParams 
   }
   __syncthreads();
 
-  // lane r finishes row r of this wavefront
   const int j = row_blk + wave * kRowsPerWave + lane;
   if (j >= n_ev) return;
+  int v1, c1, v2;
+  reduce_pairs(s_b1, s_b2, lane, val_mask, code_mask, v1, c1, v2);
+  decide_row(p, unit, j, v1, c1, v2, s_rne[wave * 64 + lane]);
+}
+
+// Few evicted rows per head (the steady state: one period's worth).  One workgroup of 8 wavefronts
+// per 64-row block; every wavefront holds the same 64 rows and takes every 8th column block, reading
+// the retained keys straight from global memory, so the work of one head spreads over a whole
+// compute unit instead of a single wavefront.
+constexpr int kSmallWaves = 8;
+template <int D>
+__global__ __launch_bounds__(kSmallWaves* kWave) void match_small_kernel(MatchParams p) {
+  constexpr int KS = D / 16, ROWB = D * 2;
+  extern __shared__ __align__(16) unsigned char smem[];
+  int* s_pairs = reinterpret_cast<int*>(smem);                          // [kSmallWaves][2][64 * 33]
+  int* s_top = s_pairs + kSmallWaves * 2 * 64 * 33;                     // [kSmallWaves][64][3]
+  float* s_rne = reinterpret_cast<float*>(s_top + kSmallWaves * 64 * 3);  // [64]
+
+  const int unit = blockIdx.y;
+  const int n_ev = p.n_evict[unit];
+  const int row_blk = blockIdx.x * 64;
+  if (row_blk >= n_ev) return;
+  const int n_keep = p.budget;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int l32 = lane & 31, half = lane >> 5;
+  const unsigned char* kbytes = reinterpret_cast<const unsigned char*>(p.k) + (size_t)unit * p.capacity * ROWB;
+  const int32_t* keep = p.keep_idx + (size_t)unit * p.budget;
+  const int32_t* evict = p.evict_idx + (size_t)unit * p.max_evict;
+  const float* rn_c = p.rnorm + (size_t)unit * p.rn_pitch;
+
+  bf16x8_t a[2][KS];
+  float rn_e_part[2];
+#pragma unroll
+  for (int t = 0; t < 2; ++t) {
+    const int j = min(row_blk + t * 32 + l32, n_ev - 1);
+    const unsigned char* row = kbytes + (size_t)evict[j] * ROWB;
+    float ss = 0.f;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      const uint4 x = *reinterpret_cast<const uint4*>(row + ks * 32 + half * 16);
+      a[t][ks] = __builtin_bit_cast(bf16x8_t, x);
+      const uint32_t w[4] = {x.x, x.y, x.z, x.w};
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const float lo = bf16_lo(w[i]), hi = bf16_hi(w[i]);
+        ss = fmaf(lo, lo, ss);
+        ss = fmaf(hi, hi, ss);
+      }
+    }
+    rn_e_part[t] = ss + __shfl_xor(ss, 32);
+  }
+  const int code_mask = (1 << p.code_bits) - 1;
+  // the value mask lives in a vector register so that (x & mask) | code is one v_and_or_b32 (a VOP3
+  // instruction of this target may read only one scalar register, and the code is scalar)
+  int val_mask;
+  asm volatile("v_mov_b32 %0, %1" : "=v"(val_mask) : "s"(~code_mask));
+  int b1[2][16], b2[2][16];
+#pragma unroll
+  for (int t = 0; t < 2; ++t)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) b1[t][i] = b2[t][i] = (int)0x80000000;
+
+  const int ncb = (n_keep + 31) / 32;
+  auto load_b = [&](int cb, uint4 (&bf)[KS], float& rn) {
+    const int col = cb * 32 + l32;
+    const int slot = keep[min(col, n_keep - 1)];
+    const unsigned char* row = kbytes + (size_t)slot * ROWB + half * 16;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) bf[ks] = *reinterpret_cast<const uint4*>(row + ks * 32);
+    rn = rn_c[col];                          // zero beyond the retained keys
+  };
+  uint4 bcur[KS], bnext[KS];
+  float rcur = 0.f, rnext = 0.f;
+  if (wave < ncb) load_b(wave, bcur, rcur);
+  for (int cb = wave; cb < ncb; cb += kSmallWaves) {
+    if (cb + kSmallWaves < ncb) load_b(cb + kSmallWaves, bnext, rnext);
+    f32x16_t c0 = {0}, c1 = {0};
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      const bf16x8_t bfrag = __builtin_bit_cast(bf16x8_t, bcur[ks]);
+      c0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[0][ks], bfrag, c0, 0, 0, 0);
+      c1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[1][ks], bfrag, c1, 0, 0, 0);
+    }
+    fold_tile(c0, c1, rcur, code_mask - cb, val_mask, b1, b2);
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) bcur[ks] = bnext[ks];
+    rcur = rnext;
+  }
+
+  int* s_b1 = s_pairs + wave * (2 * 64 * 33);
+  int* s_b2 = s_b1 + 64 * 33;
+#pragma unroll
+  for (int t = 0; t < 2; ++t)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      const int r = t * 32 + 8 * (i / 4) + 4 * half + (i % 4);
+      s_b1[r * 33 + l32] = b1[t][i];
+      s_b2[r * 33 + l32] = b2[t][i];
+    }
+  if (wave == 0 && half == 0) {
+    s_rne[l32] = rn_e_part[0];
+    s_rne[32 + l32] = rn_e_part[1];
+  }
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+  __builtin_amdgcn_wave_barrier();
+  {
+    int v1, c1, v2;
+    reduce_pairs(s_b1, s_b2, lane, val_mask, code_mask, v1, c1, v2);   // this wavefront's column blocks
+    int* t3 = s_top + (wave * 64 + lane) * 3;
+    t3[0] = v1; t3[1] = c1; t3[2] = v2;
+  }
+  __syncthreads();
+  if (wave != 0) return;
+  const int j = row_blk + lane;
+  if (j >= n_ev) return;
   int v1 = (int)0x80000000, v2 = (int)0x80000000, c1 = 0;
-  for (int q = 0; q < 32; ++q) {
-    const int k1 = s_b1[lane * 33 + q], k2 = s_b2[lane * 33 + q];
-    const int val = k1 & val_mask;
-    const int col = (code_mask - (k1 & code_mask)) * 32 + q;
-    const int val2 = k2 & val_mask;
+  for (int w = 0; w < kSmallWaves; ++w) {
+    const int* t3 = s_top + (w * 64 + lane) * 3;
+    const int val = t3[0], col = t3[1], val2 = t3[2];
     if (val > v1 || (val == v1 && col < c1)) {
       v2 = imax(v1, val2);
       v1 = val;
@@ -234,19 +421,7 @@ __global__ __launch_bounds__(kMWaves* kWave) void match_mfma_kernel(MatchParams 
       v2 = imax(v2, val);
     }
   }
-  const float ss = s_rne[wave * 64 + lane];
-  const float rn_e = 1.0f / sqrtf(ss);
-  const float y1 = __builtin_bit_cast(float, v1), y2 = (v2 > 0) ? __builtin_bit_cast(float, v2) : 0.f;
-  const float cos1 = y1 * rn_e;
-  const bool fragile = !(v1 > 0) || !(ss > 0.f) || !(rn_e < INFINITY) || (y1 - y2) * rn_e <= p.delta ||
-                       fabsf(cos1 - p.threshold) <= p.delta || c1 >= n_keep;
-  const size_t o = (size_t)unit * p.max_evict + j;
-  p.match[o] = (cos1 > p.threshold) ? c1 : -1;
-  if (p.sim_out != nullptr) p.sim_out[o] = cos1;
-  if (fragile) {
-    const int at = atomicAdd(p.flag_count, 1);
-    p.flag_rows[at] = (int)o;
-  }
+  decide_row(p, unit, j, v1, c1, v2, s_rne[lane]);
 }
 
 // queue every live evicted row (f32 caches)
@@ -263,46 +438,54 @@ __global__ void flag_all_kernel(const int32_t* __restrict__ n_evict, int32_t* fl
 __global__ void zero_counter_kernel(int32_t* c) { *c = 0; }
 
 // ---------------------------------------------------------------------------------------------------
-// f64 evaluation of queued rows: one wavefront per row, lanes stride over the retained keys.
+// f64 evaluation of queued rows: one workgroup per row, threads stride over the retained keys (each
+// thread evaluates whole keys, channels in index order, so the sums match an index-order f64 sum).
 template <typename T, int D>
 __global__ __launch_bounds__(256) void match_exact_kernel(MatchParams p) {
-  __shared__ double s_e[4][D];
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  __shared__ double s_e[D];
+  __shared__ double s_best[4];
+  __shared__ int s_bestc[4];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int n_flag = *p.flag_count;
-  const int waves_total = gridDim.x * 4;
   const T* kall = reinterpret_cast<const T*>(p.k);
-  for (int f = blockIdx.x * 4 + wave; f < n_flag; f += waves_total) {
+  constexpr int EPV = 16 / (int)sizeof(T), NV = D / EPV;
+  for (int f = blockIdx.x; f < n_flag; f += gridDim.x) {
     const int o = p.flag_rows[f];
     const int unit = o / p.max_evict, j = o % p.max_evict;
     const T* kunit = kall + (size_t)unit * p.capacity * D;
     const int32_t* keep = p.keep_idx + (size_t)unit * p.budget;
     const int e = p.evict_idx[(size_t)unit * p.max_evict + j];
-    for (int d = lane; d < D; d += 64) {
-      if constexpr (sizeof(T) == 2) s_e[wave][d] = (double)bf16_to_f32(reinterpret_cast<const uint16_t*>(kunit)[(size_t)e * D + d]);
-      else s_e[wave][d] = (double)kunit[(size_t)e * D + d];
+    __syncthreads();                      // previous row's shared values are no longer read
+    for (int d = tid; d < D; d += 256) {
+      if constexpr (sizeof(T) == 2) s_e[d] = (double)bf16_to_f32(reinterpret_cast<const uint16_t*>(kunit)[(size_t)e * D + d]);
+      else s_e[d] = (double)kunit[(size_t)e * D + d];
     }
-    __builtin_amdgcn_wave_barrier();
-    __threadfence_block();
+    __syncthreads();
     double ss_e = 0.0;
-    for (int d = 0; d < D; ++d) ss_e = fma(s_e[wave][d], s_e[wave][d], ss_e);
+    for (int d = 0; d < D; ++d) ss_e = fma(s_e[d], s_e[d], ss_e);
     const double rn_e = 1.0 / sqrt(ss_e);
     double best = -INFINITY;
     int best_c = 0x7FFFFFFF;
-    for (int c = lane; c < p.budget; c += 64) {
+    for (int c = tid; c < p.budget; c += 256) {
       const int slot = keep[c];
       if (slot < 0) continue;
       const T* kc = kunit + (size_t)slot * D;
+      uint4 rowv[NV];
+#pragma unroll
+      for (int v = 0; v < NV; ++v) rowv[v] = reinterpret_cast<const uint4*>(kc)[v];   // one round trip per key
       double dot = 0.0, ss_c = 0.0;
-      for (int d0 = 0; d0 < D; d0 += 16 / (int)sizeof(T)) {
-        const uint4 x = *reinterpret_cast<const uint4*>(kc + d0);
+#pragma unroll
+      for (int v = 0; v < NV; ++v) {
+        const int d0 = v * EPV;
+        const uint4 x = rowv[v];
         if constexpr (sizeof(T) == 2) {
           const uint32_t w[4] = {x.x, x.y, x.z, x.w};
 #pragma unroll
           for (int i = 0; i < 4; ++i) {
             const double lo = (double)bf16_lo(w[i]), hi = (double)bf16_hi(w[i]);
-            dot = fma(s_e[wave][d0 + 2 * i], lo, dot);
+            dot = fma(s_e[d0 + 2 * i], lo, dot);
             ss_c = fma(lo, lo, ss_c);
-            dot = fma(s_e[wave][d0 + 2 * i + 1], hi, dot);
+            dot = fma(s_e[d0 + 2 * i + 1], hi, dot);
             ss_c = fma(hi, hi, ss_c);
           }
         } else {
@@ -310,7 +493,7 @@ __global__ __launch_bounds__(256) void match_exact_kernel(MatchParams p) {
                               __builtin_bit_cast(float, x.z), __builtin_bit_cast(float, x.w)};
 #pragma unroll
           for (int i = 0; i < 4; ++i) {
-            dot = fma(s_e[wave][d0 + i], (double)w[i], dot);
+            dot = fma(s_e[d0 + i], (double)w[i], dot);
             ss_c = fma((double)w[i], (double)w[i], ss_c);
           }
         }
@@ -333,17 +516,50 @@ __global__ __launch_bounds__(256) void match_exact_kernel(MatchParams p) {
       }
     }
     if (lane == 0) {
+      s_best[wave] = best;
+      s_bestc[wave] = best_c;
+    }
+    __syncthreads();
+    if (tid == 0) {
+      for (int w = 1; w < 4; ++w)
+        if (s_best[w] > best || (s_best[w] == best && s_bestc[w] < best_c)) {
+          best = s_best[w];
+          best_c = s_bestc[w];
+        }
       p.match[o] = (best > (double)p.threshold) ? best_c : -1;
       if (p.sim_out != nullptr) p.sim_out[o] = (float)best;
     }
-    __builtin_amdgcn_wave_barrier();
   }
 }
 
 template <int D>
-size_t mfma_smem_bytes() {
-  const size_t stage = 2 * (size_t)kStageCols * (D * 2 + 16), epi = (size_t)kMWaves * kRowsPerWave * 33 * 2 * 4;
+constexpr size_t mfma_smem_bytes() {
+  constexpr size_t stage = 2 * (size_t)kStageCols * (D * 2), epi = (size_t)kMWaves * kRowsPerWave * 33 * 2 * 4;
   return (stage > epi ? stage : epi) + 2 * kStageCols * sizeof(float) + kMWaves * 64 * sizeof(float);
+}
+constexpr size_t small_smem_bytes() {
+  return (size_t)kSmallWaves * 2 * 64 * 33 * 4 + (size_t)kSmallWaves * 64 * 3 * 4 + 64 * 4;
+}
+constexpr int kSmallMaxEvict = 256;   // up to this many evictable slots per head the column-split kernel is used
+
+inline int rn_pitch_of(int budget) { return (budget + kStageCols - 1) / kStageCols * kStageCols; }
+
+template <int D>
+keepkv_status launch_bf16(const MatchParams& p, const void* k, unsigned units, hipStream_t st) {
+  constexpr int rows_per_block = 256 / (D * 2 / 16);
+  rnorm_kernel<uint16_t, D><<<dim3((p.rn_pitch + rows_per_block - 1) / rows_per_block, units), 256, 0, st>>>(
+      (const uint16_t*)k, p.keep_idx, p.n_evict, const_cast<float*>(p.rnorm), p.capacity, p.budget, p.rn_pitch);
+  static const hipError_t a1 = hipFuncSetAttribute((const void*)match_mfma_kernel<D>,
+                                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)mfma_smem_bytes<D>());
+  static const hipError_t a2 = hipFuncSetAttribute((const void*)match_small_kernel<D>,
+                                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)small_smem_bytes());
+  if (a1 != hipSuccess || a2 != hipSuccess) return KEEPKV_ERR_DEVICE;
+  if (p.max_evict <= kSmallMaxEvict)
+    match_small_kernel<D><<<dim3((p.max_evict + 63) / 64, units), kSmallWaves * kWave, small_smem_bytes(), st>>>(p);
+  else
+    match_mfma_kernel<D><<<dim3((p.max_evict + kRowsPerBlock - 1) / kRowsPerBlock, units), kMWaves * kWave,
+                           mfma_smem_bytes<D>(), st>>>(p);
+  return KEEPKV_OK;
 }
 
 }  // namespace
@@ -351,8 +567,8 @@ size_t mfma_smem_bytes() {
 MatchPlan plan_match(const keepkv_layout* L, int capacity, int budget) {
   MatchPlan pl;
   const size_t units = (size_t)L->batch * L->n_kv_heads;
-  pl.rnorm_off = 0;
-  pl.flag_off = align_up(units * budget * sizeof(float), 256);
+  pl.rnorm_off = kWorkspaceHead;
+  pl.flag_off = kWorkspaceHead + align_up(units * rn_pitch_of(budget) * sizeof(float), 256);
   pl.bytes = pl.flag_off + align_up((1 + units * (size_t)(capacity - budget)) * sizeof(int32_t) + 256, 256);
   return pl;
 }
@@ -392,25 +608,19 @@ extern "C" keepkv_status keepkv_match(const keepkv_layout* layout, const keepkv_
   p.code_bits = bits;
   p.delta = 1.0e-5f + 1.5f * ldexpf(1.0f, bits - 23);
 
+  p.rn_pitch = rn_pitch_of(budget);
   zero_counter_kernel<<<1, 1, 0, st>>>(p.flag_count);
-  const int exact_blocks = 1024;
+  long eb = (long)units * max_evict / 16;      // queued rows are a small fraction of all rows
+  const int exact_blocks = (int)(eb < 64 ? 64 : (eb > 2048 ? 2048 : eb));
   if (layout->dtype == KEEPKV_BF16) {
-    const dim3 grid((max_evict + kRowsPerBlock - 1) / kRowsPerBlock, (unsigned)units);
+    keepkv_status rc;
     if (layout->head_dim == 128) {
-      rnorm_kernel<uint16_t, 128><<<dim3((budget + 15) / 16, (unsigned)units), 256, 0, st>>>(
-          (const uint16_t*)cache->k, keep_idx, n_evict, const_cast<float*>(p.rnorm), cache->capacity, budget);
-      static const hipError_t attr128 = hipFuncSetAttribute(
-          (const void*)match_mfma_kernel<128>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)mfma_smem_bytes<128>());
-      if (attr128 != hipSuccess) return KEEPKV_ERR_DEVICE;
-      match_mfma_kernel<128><<<grid, kMWaves * kWave, mfma_smem_bytes<128>(), st>>>(p);
+      rc = launch_bf16<128>(p, cache->k, (unsigned)units, st);
+      if (rc != KEEPKV_OK) return rc;
       match_exact_kernel<uint16_t, 128><<<exact_blocks, 256, 0, st>>>(p);
     } else {
-      rnorm_kernel<uint16_t, 64><<<dim3((budget + 31) / 32, (unsigned)units), 256, 0, st>>>(
-          (const uint16_t*)cache->k, keep_idx, n_evict, const_cast<float*>(p.rnorm), cache->capacity, budget);
-      static const hipError_t attr64 = hipFuncSetAttribute(
-          (const void*)match_mfma_kernel<64>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)mfma_smem_bytes<64>());
-      if (attr64 != hipSuccess) return KEEPKV_ERR_DEVICE;
-      match_mfma_kernel<64><<<grid, kMWaves * kWave, mfma_smem_bytes<64>(), st>>>(p);
+      rc = launch_bf16<64>(p, cache->k, (unsigned)units, st);
+      if (rc != KEEPKV_OK) return rc;
       match_exact_kernel<uint16_t, 64><<<exact_blocks, 256, 0, st>>>(p);
     }
   } else {

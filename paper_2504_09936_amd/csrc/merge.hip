@@ -3,8 +3,8 @@
 // destination cache.
 //
 // Two kernels.  (1) Per head, the evicted slots are grouped by merge target into a CSR list: an LDS
-// histogram of match[], a block scan, and a fill in which the thread owning target r walks match[]
-// in order, so every group lists its members in ascending slot order (deterministic summation
+// histogram of match[], a block scan for the row starts, and a bitonic sort of (target, position)
+// keys in LDS, so every group lists its members in ascending slot order (deterministic summation
 // order, no float atomics).  (2) One lane group (LPS lanes, 16 bytes of a row each) per retained
 // position gathers its group: the merge weights w_i = p_i s_hat_i are formed in f64 relative to
 // the group's largest ln s_hat, one member per lane, and broadcast; K and V rows are accumulated in
@@ -16,12 +16,17 @@ namespace {
 
 constexpr int kGroupThreads = 1024;
 constexpr int kMaxBudget = 4096;
+constexpr int kMaxEvict = 32768;          // sort keys are (target << 15) | position
 constexpr double kEllGuard = 1.0e-3;
 
+// Groups the evicted slots of one head by merge target.  Keys (target << 15 | position in the evict
+// list) are sorted with a bitonic network in LDS, so each group's members come out in ascending slot
+// order; CSR starts come from a histogram and a block scan.
 __global__ __launch_bounds__(kGroupThreads) void merge_group_kernel(
     const int32_t* __restrict__ match, const int32_t* __restrict__ evict_idx, const int32_t* __restrict__ n_evict,
     const int32_t* __restrict__ votes, int32_t* __restrict__ start, int32_t* __restrict__ members,
     int64_t* __restrict__ dropped_votes, int capacity, int budget, int max_evict) {
+  extern __shared__ unsigned int s_key[];          // pow2ceil(max_evict) sort keys
   __shared__ int s_cnt[kMaxBudget + 1];
   __shared__ int s_wave[kGroupThreads / 64];
   __shared__ long long s_drop;
@@ -32,14 +37,24 @@ __global__ __launch_bounds__(kGroupThreads) void merge_group_kernel(
   int32_t* st = start + (size_t)unit * (budget + 1);
   int32_t* mem = members + (size_t)unit * capacity;
 
+  int n2 = 1;
+  while (n2 < n_ev) n2 <<= 1;
   for (int r = tid; r <= budget; r += kGroupThreads) s_cnt[r] = 0;
   if (tid == 0) s_drop = 0;
   __syncthreads();
   long long drop = 0;
-  for (int j = tid; j < n_ev; j += kGroupThreads) {
-    const int t = mt[j];
-    if (t >= 0) atomicAdd(&s_cnt[t], 1);
-    else drop += votes[(size_t)unit * capacity + ev[j]];
+  for (int j = tid; j < n2; j += kGroupThreads) {
+    unsigned int key = 0xFFFFFFFFu;                 // padding and unmatched slots sort to the end
+    if (j < n_ev) {
+      const int t = mt[j];
+      if (t >= 0) {
+        atomicAdd(&s_cnt[t], 1);
+        key = ((unsigned int)t << 15) | (unsigned int)j;
+      } else {
+        drop += votes[(size_t)unit * capacity + ev[j]];
+      }
+    }
+    s_key[j] = key;
   }
   if (drop != 0) atomicAdd((unsigned long long*)&s_drop, (unsigned long long)drop);
   __syncthreads();
@@ -60,31 +75,33 @@ __global__ __launch_bounds__(kGroupThreads) void merge_group_kernel(
   int before = 0;
   for (int w = 0; w < wave; ++w) before += s_wave[w];
   int run = before + incl - mine;
-  __syncthreads();   // all counts read before they are replaced by starts
   for (int r = r0; r < r1; ++r) {
-    const int c = s_cnt[r];
-    s_cnt[r] = run;
-    run += c;
+    st[r] = run;
+    run += s_cnt[r];
   }
-  if (tid == kGroupThreads - 1) s_cnt[budget] = run;
-  __syncthreads();
-  for (int r = tid; r <= budget; r += kGroupThreads) st[r] = s_cnt[r];
+  if (tid == kGroupThreads - 1) st[budget] = run;
+  int n_matched = 0;
+  for (int w = 0; w < kGroupThreads / 64; ++w) n_matched += s_wave[w];
   if (tid == 0 && dropped_votes != nullptr && s_drop != 0) dropped_votes[unit] += s_drop;
+  if (n_matched == 0) return;                       // uniform over the block
 
-  // ordered fill: the owner of position r walks match[] front to back
-  for (int rb = 0; rb < budget; rb += kGroupThreads) {
-    const int r = rb + tid;
-    int pos = 0, endp = 0;
-    if (r < budget) {
-      pos = s_cnt[r];
-      endp = s_cnt[r + 1];
-    }
-    if (__any(pos < endp)) {
-      for (int j = 0; j < n_ev && __any(pos < endp); ++j) {
-        if (mt[j] == r && r < budget) mem[pos++] = ev[j];
+  // bitonic sort, ascending
+  for (int k = 2; k <= n2; k <<= 1) {
+    for (int j = k >> 1; j > 0; j >>= 1) {
+      for (int i = tid; i < (n2 >> 1); i += kGroupThreads) {
+        const int lo = ((i & ~(j - 1)) << 1) | (i & (j - 1));
+        const int hi = lo | j;
+        const unsigned int x = s_key[lo], y = s_key[hi];
+        const bool up = (lo & k) == 0;
+        if ((x > y) == up) {
+          s_key[lo] = y;
+          s_key[hi] = x;
+        }
       }
+      __syncthreads();
     }
   }
+  for (int i = tid; i < n_matched; i += kGroupThreads) mem[i] = ev[s_key[i] & 0x7FFFu];
 }
 
 struct MergeParams {
@@ -269,8 +286,8 @@ __global__ __launch_bounds__(256) void merge_apply_kernel(MergeParams p) {
 MergePlan plan_merge(const keepkv_layout* L, int capacity, int budget) {
   MergePlan pl;
   const size_t units = (size_t)L->batch * L->n_kv_heads;
-  pl.start_off = 0;
-  pl.member_off = align_up(units * (budget + 1) * sizeof(int32_t), 256);
+  pl.start_off = kWorkspaceHead;
+  pl.member_off = kWorkspaceHead + align_up(units * (budget + 1) * sizeof(int32_t), 256);
   pl.bytes = pl.member_off + align_up(units * capacity * sizeof(int32_t), 256);
   return pl;
 }
@@ -292,7 +309,7 @@ extern "C" keepkv_status keepkv_merge(const keepkv_layout* layout, const keepkv_
     return KEEPKV_ERR_INVALID_ARG;
   if (!aligned16(src->k) || !aligned16(src->v) || !aligned16(dst->k) || !aligned16(dst->v)) return KEEPKV_ERR_INVALID_ARG;
   if (layout->head_dim != 64 && layout->head_dim != 128) return KEEPKV_ERR_UNSUPPORTED;
-  if (budget > kMaxBudget) return KEEPKV_ERR_UNSUPPORTED;
+  if (budget > kMaxBudget || max_evict > kMaxEvict) return KEEPKV_ERR_UNSUPPORTED;
   const MergePlan pl = plan_merge(layout, src->capacity, budget);
   if (!workspace || workspace_bytes < pl.bytes || !aligned16(workspace)) return KEEPKV_ERR_WORKSPACE;
   const unsigned units = (unsigned)(layout->batch * layout->n_kv_heads);
@@ -300,8 +317,15 @@ extern "C" keepkv_status keepkv_merge(const keepkv_layout* layout, const keepkv_
   int32_t* start = reinterpret_cast<int32_t*>(reinterpret_cast<char*>(workspace) + pl.start_off);
   int32_t* members = reinterpret_cast<int32_t*>(reinterpret_cast<char*>(workspace) + pl.member_off);
 
-  merge_group_kernel<<<units, kGroupThreads, 0, st>>>(match, evict_idx, n_evict, src->votes, start, members,
-                                                      dropped_votes, src->capacity, budget, max_evict);
+  size_t key_bytes = 4;
+  while (key_bytes < (size_t)max_evict * 4) key_bytes <<= 1;
+  if (key_bytes > 64 * 1024) {
+    static const hipError_t attr = hipFuncSetAttribute((const void*)merge_group_kernel,
+                                                       hipFuncAttributeMaxDynamicSharedMemorySize, kMaxEvict * 4);
+    if (attr != hipSuccess) return KEEPKV_ERR_DEVICE;
+  }
+  merge_group_kernel<<<units, kGroupThreads, key_bytes, st>>>(match, evict_idx, n_evict, src->votes, start, members,
+                                                              dropped_votes, src->capacity, budget, max_evict);
   MergeParams p;
   p.sk = src->k; p.sv = src->v; p.svotes = src->votes; p.slog_s = src->log_s; p.sn_obs = src->n_obs; p.slen = src->len;
   p.dk = dst->k; p.dv = dst->v; p.dvotes = dst->votes; p.dlog_s = dst->log_s; p.dn_obs = dst->n_obs; p.dlen = dst->len;

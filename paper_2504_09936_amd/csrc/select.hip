@@ -164,8 +164,8 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(
 
 SelectPlan plan_select(const keepkv_layout* L, int capacity) {
   SelectPlan pl;
-  pl.keys_off = 0;
-  pl.bytes = align_up((size_t)L->batch * L->n_kv_heads * capacity * sizeof(uint64_t), 256);
+  pl.keys_off = kWorkspaceHead;
+  pl.bytes = kWorkspaceHead + align_up((size_t)L->batch * L->n_kv_heads * capacity * sizeof(uint64_t), 256);
   return pl;
 }
 

@@ -56,9 +56,8 @@ def download(c):
 
 
 def workspace(lay, capacity, budget):
-    n = kk().workspace_bytes(lay, capacity, budget)
-    assert n > 0
-    return torch.empty(n, dtype=torch.uint8, device="cuda")
+    assert kk().workspace_bytes(lay, capacity, budget) > 0
+    return kk().new_workspace(lay, capacity, budget)
 
 
 def rel_err_rows(got, ref):

@@ -110,3 +110,60 @@ def test_score_and_append_match_oracle(alpha):
         kk.append(lay, c, U.to_device(k_t, w.dtype), U.to_device(v_t, w.dtype), overflow)
     torch.cuda.synchronize()
     assert overflow.item() == 1 and (c.len.cpu().numpy() == c.capacity).all()
+
+
+@pytest.mark.parametrize("name,w", [CASES[0], CASES[1], CASES[2], CASES[3]], ids=[c[0] for c in CASES[:4]])
+def test_decode_step_equals_append_attend_score(name, w):
+    """The fused single-kernel step against the oracle's append -> attention -> EMA update."""
+    kk = U.kk()
+    alpha = U.f32(0.9)
+    K, V = W.make_cache(w, 5)
+    B, H, N = w.batch, w.n_kv_heads, w.context
+    g = np.random.default_rng(2)
+    lens = g.integers(1, N + 1, size=(B, H)).astype(np.int32)
+    lens.flat[0] = N + 6                       # will hit the capacity limit during the run
+    if lens.size > 1:
+        lens.flat[1] = 0                       # starts empty
+    cap = N + 8
+    Kp = np.concatenate([K, K[:, :, :8]], axis=2)
+    Vp = np.concatenate([V, V[:, :, :8]], axis=2)
+    votes = g.integers(1, 5, size=(B, H, cap)).astype(np.int32)
+    lay, c = U.new_cache(w, capacity=cap, K=Kp, V=Vp, votes=votes, lens=lens)
+    c.log_s[:] = torch.from_numpy(g.standard_normal((B, H, cap)).astype(np.float32)).cuda()
+    c.n_obs[:] = torch.from_numpy(g.integers(1, 9, size=(B, H, cap)).astype(np.int32)).cuda()
+    ws = U.workspace(lay, cap, max(1, N // 10))
+    out = torch.zeros(B, w.n_q_heads, w.head_dim, dtype=lay.torch_dtype, device="cuda")
+    logits = torch.zeros(B, H, cap, dtype=torch.float32, device="cuda")
+    overflow = torch.zeros(1, dtype=torch.int32, device="cuda")
+    oc = U.download(c)
+    for t in range(4):
+        k_t, v_t = W.make_token(w, 5, t)
+        q = W.make_query(w, 5, t)
+        kk.decode_step(lay, c, U.to_device(q, w.dtype), U.to_device(k_t, w.dtype), U.to_device(v_t, w.dtype), out,
+                       logits if t % 2 == 0 else None, alpha, overflow, ws)
+        torch.cuda.synchronize()
+        for b in range(B):                     # oracle: append where there is room
+            for h in range(H):
+                i = int(oc.len[b, h])
+                if i < cap:
+                    oc.k[b, h, i], oc.v[b, h, i] = k_t[b, h], v_t[b, h]
+                    oc.votes[b, h, i], oc.log_S[b, h, i], oc.n_obs[b, h, i] = 1, -np.inf, 0
+                    oc.len[b, h] = i + 1
+        o_ref, _, lg_ref = O.attend(oc, q.astype(np.float64), w.scale)
+        O.observe(oc, lg_ref, alpha)
+        np.testing.assert_array_equal(c.len.cpu().numpy(), oc.len)
+        err = U.rel_err_rows(U.to_host(out), W.round_storage(o_ref, w.dtype))
+        assert err.max() <= TOL, (name, t, err.max())
+        for b in range(B):
+            for h in range(H):
+                n = int(oc.len[b, h])
+                np.testing.assert_array_equal(c.n_obs[b, h, :n].cpu().numpy(), oc.n_obs[b, h, :n])
+                np.testing.assert_array_equal(c.votes[b, h, :n].cpu().numpy(), oc.votes[b, h, :n])
+                np.testing.assert_allclose(c.log_s[b, h, :n].cpu().numpy(), oc.log_S[b, h, :n], rtol=2e-3, atol=2e-3)
+                np.testing.assert_array_equal(U.to_host(c.k)[b, h, :n], oc.k[b, h, :n].astype(np.float32))
+                np.testing.assert_array_equal(U.to_host(c.v)[b, h, :n], oc.v[b, h, :n].astype(np.float32))
+                if t % 2 == 0:
+                    np.testing.assert_allclose(logits[b, h, :n].cpu().numpy(), lg_ref[b, h, :n], rtol=2e-3, atol=2e-3)
+        oc.log_S[:] = c.log_s.cpu().numpy()    # continue from the GPU's f32 state
+    assert overflow.item() == 1                # the head that started at N + 6 ran out of room
+    assert c.len.cpu().numpy().flat[0] == cap
