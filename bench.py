@@ -201,31 +201,10 @@ def main():
     overflow_check = max(int(c[cu].len.max().item()) for c, cu in zip(caches, cur))
     assert overflow_check <= cap
 
-    # ------------------------------------------------------------------ per-kernel durations (instrumented eager pass)
-    # HIP events on the launch stream (torch's current stream) around single calls, same rotation.
-    dec_ms, comp = [], {"select": [], "match": [], "merge": []}
-    live_slots = []
-    i0 = Wm + K
-    n_inst = min(8 * R, 512)
-    for i in range(i0, i0 + n_inst):
-        layer = i % R
-        t = step_no[layer]
-        c = caches[layer][cur[layer]]
-        a, b = ev(), ev()
-        a.record()
-        decode(c, layer, t % per_layer)
-        b.record()
-        torch.cuda.synchronize()
-        dec_ms.append(a.elapsed_time(b))
-        live_slots.append(int(c.len.sum().item()))
-        step_no[layer] = t + 1
-        if (t + 1) % P == 0:
-            d = caches[layer][1 - cur[layer]]
-            kk.select(lay, c, Bud, w.n_sink, w.n_recent, alpha, keep, evict_s, n_ev, ws)
-            kk.match(lay, c, Bud, keep, evict_s, n_ev, T, match_s, None, ws)
-            kk.merge(lay, c, d, Bud, keep, evict_s, n_ev, match_s, alpha, dropped[layer], ws)
-            cur[layer] = 1 - cur[layer]
-    # steady-state compression events: advance every layer to the end of its period, then time the event
+    # ------------------------------------------------------------------ per-kernel durations
+    # (1) steady-state compression events: advance every layer to the end of its period (eager),
+    #     then time select / match / merge with HIP events on the launch stream.
+    comp = {"select": [], "match": [], "merge": []}
     for layer in range(R):
         c = caches[layer][cur[layer]]
         while step_no[layer] % P != 0:
@@ -244,16 +223,35 @@ def main():
         for j, name in enumerate(("select", "match", "merge")):
             comp[name].append(e[j].elapsed_time(e[j + 1]) * 1e3)
         cur[layer] = 1 - cur[layer]
+    # (2) the decode kernel: a graph of decode steps only (every layer now sits at len = budget, so
+    #     P/2 steps per layer stay inside the period), HIP events around the replay on the stream the
+    #     kernels run on; average duration = elapsed / launches (back-to-back launches, no host gaps).
+    n_dec = R * (P // 2)
+    dgraph = torch.cuda.CUDAGraph()
+    base_step = list(step_no)
+    with torch.cuda.graph(dgraph, stream=stream):
+        for i in range(n_dec):
+            layer = i % R
+            decode(caches[layer][cur[layer]], layer, (base_step[layer] + i // R) % per_layer)
+    torch.cuda.synchronize()
+    d0, d1 = ev(), ev()
+    with torch.cuda.stream(stream):
+        d0.record()
+        dgraph.replay()
+        d1.record()
+    torch.cuda.synchronize()
+    dec_us = d0.elapsed_time(d1) * 1e3 / n_dec
+    live_mean = Bud + (P // 2 + 1) / 2.0          # slots per head attended, averaged over the replay
+    slots = B * H * live_mean
 
     # algorithmic bytes of one decode_attn launch: K+V rows, votes, logit side output per live slot,
     # plus Q in and O out
-    slots = float(np.mean(live_slots))
+    # per slot: K and V rows, votes (4 B) and the logit that feeds the EMA (4 B); plus Q in and O out
     dec_bytes = slots * (2 * D * esz + 4 + 4) + 2 * B * Hq * D * esz
-    dec_us = float(np.mean(dec_ms)) * 1e3
     achieved = dec_bytes / (dec_us * 1e-6) / 1e9
-    # (the fused step also reads and writes the EMA state: +16 B per slot, counted as algorithmic)
+    # (the fused step keeps the logit on chip but reads and writes the EMA state instead: 16 B per slot)
     if not args.unfused:
-        dec_bytes += slots * 16
+        dec_bytes += slots * (16 - 4)
     roofline = {"bound": "hbm", "kernel": "decode_attn_kernel", "achieved": round(achieved, 1),
                 "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
                 "traffic": None, "bytes_per_launch": int(dec_bytes), "avg_launch_us": round(dec_us, 2)}
@@ -310,7 +308,7 @@ def main():
         "roofline": roofline,
         "cpu_baseline": cpu,
         "kernels_us": {
-            "decode_step_event_bracketed": round(dec_us, 2),
+            "decode_step": round(dec_us, 2),
             "compress_steady": {k_: (round(float(np.median(v_)), 1) if v_ else None) for k_, v_ in comp.items()},
             "compress_first": {k_: round(float(np.median(v_)), 1) for k_, v_ in first.items()},
         },
