@@ -29,6 +29,10 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0      # MI355X HBM3E
 MFMA_BF16_PEAK_TFLOPS = 2500.0
+# HBM bytes per launch of the fused decode kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled
+# by the copy-probe calibration (profiles/decode_attn_hbm_traffic_llama3_8b.md).  Counters cannot be
+# read from inside this process, so the figure is the recorded one for the default workload.
+PMC_TRAFFIC_BYTES = {"llama3_8b": int((14733.7 * 2.00 + 1645.1 * 1.00) * 1024)}
 
 
 def parse():
@@ -44,6 +48,8 @@ def parse():
     ap.add_argument("--unfused", action="store_true",
                     help="use keepkv_append + keepkv_decode_attn + keepkv_score instead of keepkv_decode_step")
     ap.add_argument("--window", type=int, default=None, help="observation passes before the first event")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="only run a plain device copy of known size (calibrates rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     return ap.parse_args()
 
 
@@ -62,6 +68,15 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
     dev = torch.device("cuda:0")
+    if args.copy_probe:
+        n = 256 * 1024 * 1024                      # bytes read and bytes written per copy
+        src = torch.empty(n, dtype=torch.uint8, device=dev).fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(8):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_probe_bytes": n, "copies": 8}))
+        return
     w = W.CONFIGS[args.workload]
     if args.window is not None:
         w = w.scaled(window=args.window)
@@ -254,7 +269,7 @@ def main():
         dec_bytes += slots * (16 - 4)
     roofline = {"bound": "hbm", "kernel": "decode_attn_kernel", "achieved": round(achieved, 1),
                 "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
-                "traffic": None, "bytes_per_launch": int(dec_bytes), "avg_launch_us": round(dec_us, 2)}
+                "traffic": (PMC_TRAFFIC_BYTES.get(w.name) if not args.unfused else None), "bytes_per_launch": int(dec_bytes), "avg_launch_us": round(dec_us, 2)}
 
     M1 = N - Bud
     match_first_us = float(np.median(first["match"]))
