@@ -162,12 +162,14 @@ def main():
     step_no = [0] * R          # decode steps done per layer
     n_events = 0
 
-    def decode(c, layer, t):
+    def decode(c, layer, t, since):
+        """One decode step of `layer` with input set t; `since` = steps since its last compression."""
         if args.unfused:
             kk.append(lay, c, k_all[layer, t], v_all[layer, t], None)
             kk.decode_attn(lay, c, q_all[layer, t], out, logits, None, ws)
             kk.score(lay, c, logits, alpha)
         else:
+            c.len_hint = Bud + since          # host-known bound on len before this step's append
             kk.decode_step(lay, c, q_all[layer, t], k_all[layer, t], v_all[layer, t], out, None, alpha, None, ws)
 
     def one_step(i):
@@ -175,7 +177,7 @@ def main():
         layer = i % R
         t = step_no[layer]
         c = caches[layer][cur[layer]]
-        decode(c, layer, t)
+        decode(c, layer, t, t % P)
         step_no[layer] = t + 1
         if (t + 1) % P == 0:
             d = caches[layer][1 - cur[layer]]
@@ -223,7 +225,7 @@ def main():
     for layer in range(R):
         c = caches[layer][cur[layer]]
         while step_no[layer] % P != 0:
-            decode(c, layer, step_no[layer] % per_layer)
+            decode(c, layer, step_no[layer] % per_layer, step_no[layer] % P)
             step_no[layer] += 1
         d = caches[layer][1 - cur[layer]]
         e = [ev() for _ in range(4)]
@@ -247,7 +249,7 @@ def main():
     with torch.cuda.graph(dgraph, stream=stream):
         for i in range(n_dec):
             layer = i % R
-            decode(caches[layer][cur[layer]], layer, (base_step[layer] + i // R) % per_layer)
+            decode(caches[layer][cur[layer]], layer, (base_step[layer] + i // R) % per_layer, i // R)
     torch.cuda.synchronize()
     d0, d1 = ev(), ev()
     with torch.cuda.stream(stream):

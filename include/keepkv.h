@@ -61,6 +61,11 @@ typedef struct {
   int32_t *n_obs;       /* [B, Hkv, capacity]  observations folded into S_i           */
   int32_t *len;         /* [B, Hkv]            live slots, 0 <= len <= capacity        */
   int32_t  capacity;    /* slots allocated per (b, h); 1 <= capacity <= 2^20           */
+  int32_t  len_hint;    /* optional: an upper bound on every len[b,h] known to the host */
+                        /* (0 = unknown).  With a hint the decode kernels start fetching */
+                        /* rows without waiting for len; slots in [len, len_hint) may    */
+                        /* then be read but never influence a result.  A hint below some */
+                        /* len gives undefined (memory-safe) results.                    */
 } keepkv_cache;
 
 /* Human-readable name of a status (static string). */

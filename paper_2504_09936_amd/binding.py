@@ -14,7 +14,7 @@ from dataclasses import dataclass
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libkeepkv.so")
+LIB_PATH = os.environ.get("KEEPKV_LIB") or os.path.join(_HERE, "libkeepkv.so")
 
 if not os.path.exists(LIB_PATH):
     raise ImportError(
@@ -33,7 +33,7 @@ class _Layout(C.Structure):
 
 class _Cache(C.Structure):
     _fields_ = [("k", C.c_void_p), ("v", C.c_void_p), ("votes", C.c_void_p), ("log_s", C.c_void_p),
-                ("n_obs", C.c_void_p), ("len", C.c_void_p), ("capacity", C.c_int32)]
+                ("n_obs", C.c_void_p), ("len", C.c_void_p), ("capacity", C.c_int32), ("len_hint", C.c_int32)]
 
 
 _P = C.c_void_p
@@ -103,6 +103,7 @@ class Cache:
     def __init__(self, layout: Layout, capacity: int, device="cuda"):
         B, H, D = layout.batch, layout.n_kv_heads, layout.head_dim
         self.layout, self.capacity = layout, capacity
+        self.len_hint = 0     # host-side upper bound on len (0 = unknown); see keepkv_cache.len_hint
         self.k = torch.zeros(B, H, capacity, D, dtype=layout.torch_dtype, device=device)
         self.v = torch.zeros(B, H, capacity, D, dtype=layout.torch_dtype, device=device)
         self.votes = torch.zeros(B, H, capacity, dtype=torch.int32, device=device)
@@ -112,7 +113,7 @@ class Cache:
 
     def c(self) -> _Cache:
         return _Cache(self.k.data_ptr(), self.v.data_ptr(), self.votes.data_ptr(), self.log_s.data_ptr(),
-                      self.n_obs.data_ptr(), self.len.data_ptr(), self.capacity)
+                      self.n_obs.data_ptr(), self.len.data_ptr(), self.capacity, int(self.len_hint))
 
 
 def version() -> int:

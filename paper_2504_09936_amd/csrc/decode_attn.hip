@@ -16,6 +16,14 @@
 
 namespace kk {
 
+// Phase timestamps for kernel tuning; compiled in only with -DKEEPKV_TRACE (never in the product build).
+#ifdef KEEPKV_TRACE
+__device__ long long kk_trace[8 * 8192];
+#define KK_TS(i) do { if (threadIdx.x == 0 && blockIdx.x < 8192) kk_trace[blockIdx.x * 8 + (i)] = wall_clock64(); } while (0)
+#else
+#define KK_TS(i) do { } while (0)
+#endif
+
 namespace {
 
 struct DecodeParams {
@@ -38,6 +46,7 @@ struct DecodeParams {
   int capacity;
   int nsplit;
   int per;          // slots per split
+  int len_hint;     // caller's upper bound on len (0: none)
   float scale;
   float ln_alpha, ln_1m_alpha;
 };
@@ -69,17 +78,31 @@ __global__ __launch_bounds__(kWavesPerBlock* kWave) void decode_attn_kernel(Deco
 
   extern __shared__ __align__(16) float smem[];
   __shared__ int s_last;
+  __shared__ uint4 s_new[2 * RV];             // step mode: the appended token's K row, then its V row
 
   const int unit = blockIdx.x / p.nsplit;    // b * Hkv + h
   const int split = blockIdx.x % p.nsplit;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int grp = lane / LPS, sub = lane % LPS;
-  const int len_old = p.len[unit];
-  // step mode: the new token becomes slot len_old (unless the head is full)
-  const bool grow = STEP && len_old < p.capacity;
-  const int len = grow ? len_old + 1 : len_old;
+  KK_TS(0);
+  const int len_old = p.len[unit];          // needed only once the row loads are in flight (see `bound`)
+  // step mode: the new token becomes slot len_old (unless the head is full); it is attended as one
+  // extra slot after the cache slots, so the streaming loop below never depends on it
   const int start = split * p.per;
-  const int end = min(len, start + p.per);
+  // The wavefront that will attend the appended token copies it to LDS asynchronously (no registers,
+  // no wait), so that its extra slot costs no memory round trip after the streaming loop.
+  // (the last wavefront of the last split: its own share of the cache is the shortest)
+  const bool takes_new = STEP && split == p.nsplit - 1 && wave == kWavesPerBlock - 1;
+  if (takes_new && lane < 2 * RV) {
+    const uint4* src = (lane < RV ? reinterpret_cast<const uint4*>(p.k_t) : reinterpret_cast<const uint4*>(p.v_t)) +
+                       (size_t)unit * RV + (lane % RV);
+    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
+                                     (__attribute__((address_space(3))) void*)s_new, 16, 0, 0);
+  }
+  // Rows are fetched up to `bound`: the caller's upper bound on len if given, so that the loads do
+  // not wait for the len load; otherwise len itself.  Slots at or beyond len are masked out.
+  const int bound = p.len_hint > 0 ? min(p.len_hint, p.capacity) : len_old;
+  const int lim = min(bound, start + p.per);
 
   // query slice of this lane for each head of the group
   uint4 qv[G][VPL];
@@ -101,46 +124,64 @@ __global__ __launch_bounds__(kWavesPerBlock* kWave) void decode_attn_kernel(Deco
   const size_t ubase = (size_t)unit * p.capacity;
   uint4* kbase = reinterpret_cast<uint4*>(p.k) + ubase * RV + sub;
   uint4* vbase = reinterpret_cast<uint4*>(p.v) + ubase * RV + sub;
-  const uint4* knew = STEP ? reinterpret_cast<const uint4*>(p.k_t) + (size_t)unit * RV + sub : nullptr;
-  const uint4* vnew = STEP ? reinterpret_cast<const uint4*>(p.v_t) + (size_t)unit * RV + sub : nullptr;
   const float sl2 = p.scale * kLog2e;
 
-  for (int base = start + wave * TILE; base < end; base += kWavesPerBlock * TILE) {
-    const int s0 = base + grp * kUnroll;
+  // One tile: kUnroll slots per lane group.  `extra` is the appended token (step mode): lane group 0
+  // takes it from (k_t, v_t) as its slot 0, every other slot of the tile is masked.
+  auto tile = [&](int base, bool extra) {
+    const int s0 = extra ? len_old : base + grp * kUnroll;
     uint4 kk_[kUnroll][VPL], vv_[kUnroll][VPL];
     int pv[kUnroll];
+    bool live[kUnroll];
 #pragma unroll
     for (int j = 0; j < kUnroll; ++j) {
-      const int s = min(s0 + j, len - 1);      // clamp: dead slots are never read
-      const bool fresh = grow && s == len_old;
-      const uint4* ka = fresh ? knew : kbase + (size_t)s * RV;
-      const uint4* va = fresh ? vnew : vbase + (size_t)s * RV;
+      if (extra) {                               // only slot 0 is real; it comes from LDS
+        pv[j] = 1;
 #pragma unroll
-      for (int v = 0; v < VPL; ++v) {
-        kk_[j][v] = ka[v * LPS];
-        vv_[j][v] = va[v * LPS];
+        for (int v = 0; v < VPL; ++v) {
+          kk_[j][v] = (j == 0) ? s_new[v * LPS + sub] : make_uint4(0, 0, 0, 0);
+          vv_[j][v] = (j == 0) ? s_new[RV + v * LPS + sub] : make_uint4(0, 0, 0, 0);
+        }
+      } else {
+        const int s = min(s0 + j, bound - 1);   // clamp: slots at or beyond `bound` are never read
+        const uint4* ka = kbase + (size_t)s * RV;
+        const uint4* va = vbase + (size_t)s * RV;
+        pv[j] = p.votes[ubase + s];              // unconditional and in bounds: a branch behind a
+#pragma unroll                                   // load would serialise the row loads
+        for (int v = 0; v < VPL; ++v) {
+          kk_[j][v] = ka[v * LPS];
+          vv_[j][v] = va[v * LPS];
+        }
       }
-      const int pj = p.votes[ubase + s];       // unconditional (in bounds); a branch here would
-      pv[j] = fresh ? 1 : pj;                  // serialise the row loads behind it
     }
     // EMA state of the slot this lane will update (lane `sub` < kUnroll owns slot s0 + sub)
-    const int s_mine = s0 + sub;
+    const int s_mine = s0 + (extra ? 0 : sub);
     float ls_old = -INFINITY;
     int no_old = 0;
-    if constexpr (STEP) {
-      const int sc = min(s_mine, len - 1);
-      const float lsv = p.log_s[ubase + sc];
-      const int nov = p.n_obs[ubase + sc];
-      const bool fresh_mine = grow && s_mine == len_old;
-      ls_old = fresh_mine ? -INFINITY : lsv;
-      no_old = fresh_mine ? 0 : nov;
+    if (STEP && !extra) {
+      const int sc = min(s_mine, bound - 1);
+      ls_old = p.log_s[ubase + sc];
+      no_old = p.n_obs[ubase + sc];
+    }
+    // ---- first use of len: everything above was issued without waiting for it
+    const int live_end = min(len_old, start + p.per);
+#pragma unroll
+    for (int j = 0; j < kUnroll; ++j) live[j] = extra ? (grp == 0 && j == 0) : (s0 + j < live_end);
+    if (extra || base + TILE > live_end) {       // uniform over the wavefront: the tile holds masked slots;
+#pragma unroll                                   // zero their V so that 0 * garbage cannot make a NaN
+      for (int j = 0; j < kUnroll; ++j) {
+        const uint32_t keepmask = live[j] ? 0xFFFFFFFFu : 0u;
+#pragma unroll
+        for (int v = 0; v < VPL; ++v) {
+          vv_[j][v].x &= keepmask; vv_[j][v].y &= keepmask; vv_[j][v].z &= keepmask; vv_[j][v].w &= keepmask;
+        }
+      }
     }
 
     float z[G][kUnroll];
     float mean_logit[kUnroll];
 #pragma unroll
     for (int j = 0; j < kUnroll; ++j) {
-      const bool live = (s0 + j) < end;
       const float lp = fast_log2((float)pv[j]);
       float sum = 0.f;
 #pragma unroll
@@ -163,17 +204,19 @@ __global__ __launch_bounds__(kWavesPerBlock* kWave) void decode_attn_kernel(Deco
         }
         d = group_sum<LPS>(d);
         sum += d;
-        z[g][j] = live ? fmaf(d, sl2, lp) : -INFINITY;
+        z[g][j] = live[j] ? fmaf(d, sl2, lp) : -INFINITY;
       }
       mean_logit[j] = sum * (p.scale * (1.0f / G));
     }
 
     {
-      // every lane evaluates the update of slot s0 + (sub mod kUnroll); only lanes sub < kUnroll store
+      // every lane evaluates the update of slot s0 + (sub mod kUnroll); only the owning lanes store
       float x = mean_logit[0];
+      if (!extra) {
 #pragma unroll
-      for (int j = 1; j < kUnroll; ++j) x = ((sub & (kUnroll - 1)) == j) ? mean_logit[j] : x;
-      const bool mine = sub < kUnroll && s_mine < end;
+        for (int j = 1; j < kUnroll; ++j) x = ((sub & (kUnroll - 1)) == j) ? mean_logit[j] : x;
+      }
+      const bool mine = extra ? (grp == 0 && sub == 0) : (sub < kUnroll && s_mine < live_end);
       if (p.logits_out != nullptr && mine) p.logits_out[ubase + s_mine] = x;
       if constexpr (STEP) {
         // log_s <- ln(alpha S + (1 - alpha) e^x), n_obs += 1  (Eq. 8)
@@ -186,19 +229,14 @@ __global__ __launch_bounds__(kWavesPerBlock* kWave) void decode_attn_kernel(Deco
         }
       }
     }
-    if constexpr (STEP) {
-      // the group that holds the new token stores it into the cache
+    if (STEP && extra && grp == 0) {
+      // store the new token into the cache
 #pragma unroll
-      for (int j = 0; j < kUnroll; ++j) {
-        if (grow && s0 + j == len_old) {
-#pragma unroll
-          for (int v = 0; v < VPL; ++v) {
-            kbase[(size_t)len_old * RV + v * LPS] = kk_[j][v];
-            vbase[(size_t)len_old * RV + v * LPS] = vv_[j][v];
-          }
-          if (sub == 0) p.votes[ubase + len_old] = 1;
-        }
+      for (int v = 0; v < VPL; ++v) {
+        kbase[(size_t)len_old * RV + v * LPS] = kk_[0][v];
+        vbase[(size_t)len_old * RV + v * LPS] = vv_[0][v];
       }
+      if (sub == 0) p.votes[ubase + len_old] = 1;
     }
 
     // online softmax update for this group's kUnroll slots
@@ -242,6 +280,15 @@ __global__ __launch_bounds__(kWavesPerBlock* kWave) void decode_attn_kernel(Deco
 #pragma unroll
         for (int e = 0; e < EPL; ++e) acc[g][e] = fmaf(pw[g][j], vf[e], acc[g][e]);
     }
+  };
+
+  for (int base = start + wave * TILE; base < lim; base += kWavesPerBlock * TILE) tile(base, false);
+  KK_TS(1);
+  const bool grow = STEP && len_old < p.capacity;
+  const int len = grow ? len_old + 1 : len_old;
+  if (takes_new) {
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // the asynchronous copy of the new token has landed
+    if (grow) tile(0, true);
   }
 
   // ---- combine lane groups and wavefronts through LDS ----------------------------------------------
@@ -294,6 +341,7 @@ __global__ __launch_bounds__(kWavesPerBlock* kWave) void decode_attn_kernel(Deco
     }
   }
   __syncthreads();
+  KK_TS(2);
 
   auto finish = [&](size_t row, int d, float M, float L, float A) {
     const float o = (L > 0.f) ? A / L : 0.f;
@@ -337,6 +385,7 @@ __global__ __launch_bounds__(kWavesPerBlock* kWave) void decode_attn_kernel(Deco
     return;
   }
 
+  KK_TS(3);
   // ---- the last workgroup of this head to arrive combines the splits ------------------------------
   // The partial results were stored write-through at device scope, so it is enough that every
   // wavefront's stores have completed (workgroup-scope release = wait on the store counter) before
@@ -347,6 +396,7 @@ __global__ __launch_bounds__(kWavesPerBlock* kWave) void decode_attn_kernel(Deco
   if (threadIdx.x == 0)
     s_last = (__hip_atomic_fetch_add(&p.ticket[unit], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == p.nsplit - 1);
   __syncthreads();
+  KK_TS(4);
   if (!s_last) return;
   for (int idx = threadIdx.x; idx < G * D; idx += kWavesPerBlock * kWave) {
     const int g = idx / D, d = idx % D;
@@ -379,6 +429,7 @@ __global__ __launch_bounds__(kWavesPerBlock* kWave) void decode_attn_kernel(Deco
     }
     finish(row, d, M, L, A);
   }
+  KK_TS(5);
   if (threadIdx.x == 0) {
     __hip_atomic_store(&p.ticket[unit], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // ready for the next launch
     if (STEP && grow) p.len[unit] = len;
@@ -437,6 +488,7 @@ keepkv_status run_decode(const keepkv_layout* layout, const keepkv_cache* cache,
   p.partial = reinterpret_cast<float*>(reinterpret_cast<char*>(workspace) + pl.partial_off);
   p.ticket = reinterpret_cast<int32_t*>(workspace);
   p.n_kv_heads = layout->n_kv_heads; p.capacity = cache->capacity; p.nsplit = pl.nsplit; p.per = pl.per; p.scale = layout->scale;
+  p.len_hint = cache->len_hint > 0 ? cache->len_hint : 0;
   p.ln_alpha = (step && alpha > 0.f) ? logf(alpha) : -INFINITY;
   p.ln_1m_alpha = step ? log1pf(-alpha) : 0.f;
 
@@ -490,3 +542,9 @@ extern "C" keepkv_status keepkv_decode_step(const keepkv_layout* layout, keepkv_
   return kk::run_decode(layout, cache, q, k_t, v_t, out, logits_out, nullptr, alpha, overflow, true, workspace,
                         workspace_bytes, stream);
 }
+
+#ifdef KEEPKV_TRACE
+extern "C" int keepkv_trace_read(long long* host, int n) {
+  return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(kk::kk_trace), sizeof(long long) * n);
+}
+#endif

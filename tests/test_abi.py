@@ -49,7 +49,7 @@ def test_workspace_and_argument_validation_without_device():
     # null pointers are rejected on the host; nothing is launched
     assert lib.keepkv_score(None, None, None, C.c_float(0.9), None) == kk.ERR_INVALID_ARG
     assert lib.keepkv_decode_attn(C.byref(lay.c()), None, None, None, None, None, None, 0, None) == kk.ERR_INVALID_ARG
-    cache = kk._Cache(16, 16, 16, 16, 16, 16, 884)      # non-null dummies; never dereferenced on these paths
+    cache = kk._Cache(16, 16, 16, 16, 16, 16, 884, 0)     # non-null dummies; never dereferenced on these paths
     assert lib.keepkv_score(C.byref(lay.c()), C.byref(cache), C.c_void_p(16), C.c_float(1.5), None) == kk.ERR_INVALID_ARG
     lay3 = kk.Layout(8, 24, 8, 128, kk.BF16, 0.1)       # group size 3 is not built
     assert lib.keepkv_decode_attn(C.byref(lay3.c()), C.byref(cache), C.c_void_p(16), C.c_void_p(16), None, None,

@@ -28,8 +28,9 @@ CASES = [
 ]
 
 
+@pytest.mark.parametrize("hint", [False, True], ids=["wait_for_len", "len_hint"])
 @pytest.mark.parametrize("name,w", CASES, ids=[c[0] for c in CASES])
-def test_decode_attn_matches_oracle(name, w):
+def test_decode_attn_matches_oracle(name, w, hint):
     kk = U.kk()
     K, V = W.make_cache(w, 0)
     g = np.random.default_rng(1)
@@ -42,7 +43,9 @@ def test_decode_attn_matches_oracle(name, w):
     if lens.size > 2:
         lens.flat[2] = 1
     lay, c = U.new_cache(w, capacity=N, K=K, V=V, votes=votes, lens=lens)
-    # poison dead slots: they must never be read
+    if hint:
+        c.len_hint = int(lens.max())            # rows below the hint may be fetched but must not matter
+    # poison dead slots: they must never be read (or, below a hint, never influence a result)
     for b in range(B):
         for h in range(H):
             c.k[b, h, lens[b, h]:] = float("nan")
@@ -112,8 +115,9 @@ def test_score_and_append_match_oracle(alpha):
     assert overflow.item() == 1 and (c.len.cpu().numpy() == c.capacity).all()
 
 
+@pytest.mark.parametrize("hint", [False, True], ids=["wait_for_len", "len_hint"])
 @pytest.mark.parametrize("name,w", [CASES[0], CASES[1], CASES[2], CASES[3]], ids=[c[0] for c in CASES[:4]])
-def test_decode_step_equals_append_attend_score(name, w):
+def test_decode_step_equals_append_attend_score(name, w, hint):
     """The fused single-kernel step against the oracle's append -> attention -> EMA update."""
     kk = U.kk()
     alpha = U.f32(0.9)
@@ -136,7 +140,13 @@ def test_decode_step_equals_append_attend_score(name, w):
     logits = torch.zeros(B, H, cap, dtype=torch.float32, device="cuda")
     overflow = torch.zeros(1, dtype=torch.int32, device="cuda")
     oc = U.download(c)
+    for b in range(B):                         # dead slots hold garbage that must never matter
+        for h in range(H):
+            c.k[b, h, lens[b, h]:] = float("nan")
+            c.v[b, h, lens[b, h]:] = float("nan")
     for t in range(4):
+        if hint:
+            c.len_hint = int(min(cap, lens.max() + t))   # bound on len before this step's append
         k_t, v_t = W.make_token(w, 5, t)
         q = W.make_query(w, 5, t)
         kk.decode_step(lay, c, U.to_device(q, w.dtype), U.to_device(k_t, w.dtype), U.to_device(v_t, w.dtype), out,
