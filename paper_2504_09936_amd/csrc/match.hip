@@ -28,9 +28,10 @@ constexpr int kStageCols = 128;                         // retained keys per LDS
 template <typename T, int D>
 __global__ __launch_bounds__(256) void rnorm_kernel(const T* __restrict__ k, const int32_t* __restrict__ keep_idx,
                                                     const int32_t* __restrict__ n_evict, float* __restrict__ rnorm,
-                                                    int capacity, int budget, int rn_pitch) {
+                                                    int capacity, int budget, int rn_pitch, int32_t* flag_count) {
   constexpr int EPL = 16 / (int)sizeof(T), LPS = D / EPL;
   const int unit = blockIdx.y;
+  if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) *flag_count = 0;   // queue of fragile rows starts empty
   if (n_evict[unit] <= 0) return;
   const int r = blockIdx.x * (256 / LPS) + threadIdx.x / LPS;
   const int sub = threadIdx.x % LPS;
@@ -548,7 +549,8 @@ template <int D>
 keepkv_status launch_bf16(const MatchParams& p, const void* k, unsigned units, hipStream_t st) {
   constexpr int rows_per_block = 256 / (D * 2 / 16);
   rnorm_kernel<uint16_t, D><<<dim3((p.rn_pitch + rows_per_block - 1) / rows_per_block, units), 256, 0, st>>>(
-      (const uint16_t*)k, p.keep_idx, p.n_evict, const_cast<float*>(p.rnorm), p.capacity, p.budget, p.rn_pitch);
+      (const uint16_t*)k, p.keep_idx, p.n_evict, const_cast<float*>(p.rnorm), p.capacity, p.budget, p.rn_pitch,
+      p.flag_count);
   static const hipError_t a1 = hipFuncSetAttribute((const void*)match_mfma_kernel<D>,
                                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)mfma_smem_bytes<D>());
   static const hipError_t a2 = hipFuncSetAttribute((const void*)match_small_kernel<D>,
@@ -609,7 +611,7 @@ extern "C" keepkv_status keepkv_match(const keepkv_layout* layout, const keepkv_
   p.delta = 1.0e-5f + 1.5f * ldexpf(1.0f, bits - 23);
 
   p.rn_pitch = rn_pitch_of(budget);
-  zero_counter_kernel<<<1, 1, 0, st>>>(p.flag_count);
+  if (layout->dtype != KEEPKV_BF16) zero_counter_kernel<<<1, 1, 0, st>>>(p.flag_count);   // bf16: done by rnorm_kernel
   long eb = (long)units * max_evict / 16;      // queued rows are a small fraction of all rows
   const int exact_blocks = (int)(eb < 64 ? 64 : (eb > 2048 ? 2048 : eb));
   if (layout->dtype == KEEPKV_BF16) {

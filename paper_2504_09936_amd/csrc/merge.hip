@@ -12,6 +12,12 @@
 #include "kk_common.hpp"
 
 namespace kk {
+#ifdef KEEPKV_TRACE
+__device__ long long kk_trace_merge[8 * 1024];
+#define KM_TS(i) do { if (threadIdx.x == 0 && blockIdx.x < 1024) kk_trace_merge[blockIdx.x * 8 + (i)] = wall_clock64(); } while (0)
+#else
+#define KM_TS(i) do { } while (0)
+#endif
 namespace {
 
 constexpr int kGroupThreads = 1024;
@@ -30,6 +36,7 @@ __global__ __launch_bounds__(kGroupThreads) void merge_group_kernel(
   __shared__ int s_cnt[kMaxBudget + 1];
   __shared__ int s_wave[kGroupThreads / 64];
   __shared__ long long s_drop;
+  __shared__ int s_nm;
   const int unit = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int n_ev = n_evict[unit];
   const int32_t* mt = match + (size_t)unit * max_evict;
@@ -37,27 +44,47 @@ __global__ __launch_bounds__(kGroupThreads) void merge_group_kernel(
   int32_t* st = start + (size_t)unit * (budget + 1);
   int32_t* mem = members + (size_t)unit * capacity;
 
-  int n2 = 1;
-  while (n2 < n_ev) n2 <<= 1;
+  KM_TS(0);
   for (int r = tid; r <= budget; r += kGroupThreads) s_cnt[r] = 0;
-  if (tid == 0) s_drop = 0;
+  if (tid == 0) {
+    s_drop = 0;
+    s_nm = 0;
+  }
   __syncthreads();
+  // histogram of targets; matched slots append their key to the (unordered) sort buffer, unmatched
+  // slots give up their votes.  Loads of four slots are issued together.
   long long drop = 0;
-  for (int j = tid; j < n2; j += kGroupThreads) {
-    unsigned int key = 0xFFFFFFFFu;                 // padding and unmatched slots sort to the end
-    if (j < n_ev) {
-      const int t = mt[j];
-      if (t >= 0) {
-        atomicAdd(&s_cnt[t], 1);
-        key = ((unsigned int)t << 15) | (unsigned int)j;
-      } else {
-        drop += votes[(size_t)unit * capacity + ev[j]];
+  for (int j0 = tid; j0 < n_ev; j0 += 4 * kGroupThreads) {
+    int t[4], e[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int j = min(j0 + u * kGroupThreads, n_ev - 1);
+      t[u] = mt[j];
+      e[u] = ev[j];
+    }
+    int pv[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) pv[u] = votes[(size_t)unit * capacity + e[u]];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int j = j0 + u * kGroupThreads;
+      if (j < n_ev) {
+        if (t[u] >= 0) {
+          atomicAdd(&s_cnt[t[u]], 1);
+          s_key[atomicAdd(&s_nm, 1)] = ((unsigned int)t[u] << 15) | (unsigned int)j;
+        } else {
+          drop += pv[u];
+        }
       }
     }
-    s_key[j] = key;
   }
   if (drop != 0) atomicAdd((unsigned long long*)&s_drop, (unsigned long long)drop);
   __syncthreads();
+  KM_TS(1);
+  const int n_matched = s_nm;
+  int n2 = 1;
+  while (n2 < n_matched) n2 <<= 1;
+  for (int i = n_matched + tid; i < n2; i += kGroupThreads) s_key[i] = 0xFFFFFFFFu;   // padding sorts to the end
 
   // exclusive scan of s_cnt[0..budget): thread t owns a contiguous run of positions
   const int per = (budget + kGroupThreads - 1) / kGroupThreads;
@@ -80,28 +107,53 @@ __global__ __launch_bounds__(kGroupThreads) void merge_group_kernel(
     run += s_cnt[r];
   }
   if (tid == kGroupThreads - 1) st[budget] = run;
-  int n_matched = 0;
-  for (int w = 0; w < kGroupThreads / 64; ++w) n_matched += s_wave[w];
   if (tid == 0 && dropped_votes != nullptr && s_drop != 0) dropped_votes[unit] += s_drop;
+  KM_TS(2);
   if (n_matched == 0) return;                       // uniform over the block
 
-  // bitonic sort, ascending
-  for (int k = 2; k <= n2; k <<= 1) {
-    for (int j = k >> 1; j > 0; j >>= 1) {
-      for (int i = tid; i < (n2 >> 1); i += kGroupThreads) {
-        const int lo = ((i & ~(j - 1)) << 1) | (i & (j - 1));
-        const int hi = lo | j;
-        const unsigned int x = s_key[lo], y = s_key[hi];
-        const bool up = (lo & k) == 0;
-        if ((x > y) == up) {
-          s_key[lo] = y;
-          s_key[hi] = x;
+  // bitonic sort, ascending.  Thread i + 1024 m handles pair i of every stage; for strides j <= 64 both
+  // elements of all pairs of a wavefront lie in that wavefront's own 128-element blocks, so those stages
+  // need only a wavefront-level fence instead of a workgroup barrier.
+  auto stage = [&](int j, int k) {
+    // up to kMaxEvict / 2 / 1024 = 16 pairs per thread, four at a time so that the LDS reads overlap
+    for (int i0 = tid; i0 < (n2 >> 1); i0 += 4 * kGroupThreads) {
+      int lo[4], hi[4];
+      unsigned int x[4], y[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const int i = min(i0 + u * kGroupThreads, (n2 >> 1) - 1);
+        lo[u] = ((i & ~(j - 1)) << 1) | (i & (j - 1));
+        hi[u] = lo[u] | j;
+        x[u] = s_key[lo[u]];
+        y[u] = s_key[hi[u]];
+      }
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const bool act = i0 + u * kGroupThreads < (n2 >> 1);
+        const bool up = (lo[u] & k) == 0;
+        if (act && (x[u] > y[u]) == up) {
+          s_key[lo[u]] = y[u];
+          s_key[hi[u]] = x[u];
         }
       }
+    }
+  };
+  for (int k = 2; k <= n2; k <<= 1) {
+    int j = k >> 1;
+    for (; j > 64; j >>= 1) {
+      stage(j, k);
       __syncthreads();
     }
+    for (; j > 0; j >>= 1) {
+      stage(j, k);
+      __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
+      __builtin_amdgcn_wave_barrier();
+    }
+    __syncthreads();
   }
+  KM_TS(3);
   for (int i = tid; i < n_matched; i += kGroupThreads) mem[i] = ev[s_key[i] & 0x7FFFu];
+  KM_TS(4);
 }
 
 struct MergeParams {
@@ -344,3 +396,9 @@ extern "C" keepkv_status keepkv_merge(const keepkv_layout* layout, const keepkv_
   }
   return launch_status();
 }
+
+#ifdef KEEPKV_TRACE
+extern "C" int keepkv_trace_read_merge(long long* host, int n) {
+  return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(kk::kk_trace_merge), sizeof(long long) * n);
+}
+#endif

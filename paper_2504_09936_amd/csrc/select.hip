@@ -49,7 +49,7 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(
     int n_recent, double ln_alpha) {
   __shared__ int s_hist[256];
   __shared__ int s_wave[kSelThreads / 64];
-  __shared__ int s_digit, s_need;
+  __shared__ int s_digit, s_need, s_bucket;
 
   const int unit = blockIdx.x;
   const int tid = threadIdx.x;
@@ -68,16 +68,30 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(
   const int lo = n_sink, hi = n - n_recent;   // candidates are [lo, hi)
   const int n_heavy = budget - n_sink - n_recent;
 
-  for (int i = lo + tid; i < hi; i += kSelThreads) {
-    const int nn = n_obs[base + i];
-    double x;
-    if (nn <= 0) {
-      x = -INFINITY;
-    } else {
-      x = log((double)votes[base + i]) + (double)log_s[base + i];
-      if (ln_alpha > -INFINITY) x -= log(-expm1((double)nn * ln_alpha));
+  for (int i0 = lo + tid; i0 < hi; i0 += 4 * kSelThreads) {     // four slots per round trip
+    int nn[4], pv[4];
+    float ls[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int i = min(i0 + u * kSelThreads, hi - 1);
+      nn[u] = n_obs[base + i];
+      pv[u] = votes[base + i];
+      ls[u] = log_s[base + i];
     }
-    key[i] = sortable_u64(x);
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int i = i0 + u * kSelThreads;
+      if (i < hi) {
+        double x;
+        if (nn[u] <= 0) {
+          x = -INFINITY;
+        } else {
+          x = log((double)pv[u]) + (double)ls[u];
+          if (ln_alpha > -INFINITY) x -= log(-expm1((double)nn[u] * ln_alpha));
+        }
+        key[i] = sortable_u64(x);
+      }
+    }
   }
   __syncthreads();
 
@@ -89,10 +103,16 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(
       if (tid < 256) s_hist[tid] = 0;
       __syncthreads();
       const int shift = 8 * pass;
-      for (int i = lo + tid; i < hi; i += kSelThreads) {
-        const uint64_t k = key[i];
-        const bool in = (pass == 7) || ((k >> (shift + 8)) == prefix);
-        if (in) atomicAdd(&s_hist[(int)((k >> shift) & 255u)], 1);
+      for (int i0 = lo + tid; i0 < hi; i0 += 4 * kSelThreads) {   // four keys per round trip
+        uint64_t k4[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) k4[u] = key[min(i0 + u * kSelThreads, hi - 1)];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          const uint64_t k = k4[u];
+          const bool in = (i0 + u * kSelThreads < hi) && ((pass == 7) || ((k >> (shift + 8)) == prefix));
+          if (in) atomicAdd(&s_hist[(int)((k >> shift) & 255u)], 1);
+        }
       }
       __syncthreads();
       if (tid < 64) {
@@ -118,6 +138,7 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(
             if (run + c[j] >= need) {
               s_digit = 255 - 4 * tid - j;
               s_need = need - run;
+              s_bucket = c[j];
               break;
             }
             run += c[j];
@@ -127,7 +148,14 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(
       __syncthreads();
       prefix = (prefix << 8) | (uint64_t)s_digit;
       need = s_need;
+      const bool whole_bucket = (s_bucket == need);   // every key with this prefix is kept: stop refining
       __syncthreads();
+      if (whole_bucket && pass > 0 && prefix != 0) {
+        // keep exactly the keys >= prefix << shift, i.e. key > tau with no equal keys to count
+        prefix = (prefix << shift) - 1;                // prefix != 0 here: the candidates outnumber `need`
+        need = 0;
+        break;
+      }
     }
   }
   const uint64_t tau = prefix;
