@@ -137,6 +137,18 @@ keepkv_status keepkv_select(const keepkv_layout *layout, const keepkv_cache *cac
                             int32_t *keep_idx, int32_t *evict_idx, int32_t *n_evict,
                             void *workspace, size_t workspace_bytes, void *stream);
 
+/* Token selection under a caller-supplied ranking (the method places no constraint on the
+ * selection strategy, Sec. 3.3.2 last paragraph; combination with other eviction methods,
+ * Sec. 4.4): exactly keepkv_select with the ranking value of slot i read from rank[b,h,i]
+ * (DEVICE f32 [B, Hkv, capacity]; larger = more important, NaN ranks below every number)
+ * instead of ln p_i + ln s_hat_i.  A cumulative-attention heavy-hitter policy, for example,
+ * passes its accumulated scores.  Of `cache` only len and capacity are used. */
+keepkv_status keepkv_select_by_key(const keepkv_layout *layout, const keepkv_cache *cache,
+                                   const float *rank, int32_t budget, int32_t n_sink,
+                                   int32_t n_recent, int32_t *keep_idx, int32_t *evict_idx,
+                                   int32_t *n_evict, void *workspace, size_t workspace_bytes,
+                                   void *stream);
+
 /* Merge-candidate matching (Alg. 1 lines 4-5): for every to-be-evicted slot e the
  * retained slot of highest key cosine similarity U[e,c] = k_e.k_c/(|k_e||k_c|), lowest
  * position winning ties; match[b,h,j] (DEVICE int32 [B, Hkv, capacity - budget]) is that

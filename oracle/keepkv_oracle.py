@@ -105,29 +105,42 @@ def log_s_hat(log_S, n_obs, alpha):
 
 
 # --------------------------------------------------------------------------- selection (Alg. 1 l.2-3)
-def select(log_S, n_obs, votes, length, budget, n_sink, n_recent, alpha):
-    """Split the live slots into retained K_c and to-be-evicted K_e (Alg. 1 lines 2-3).
+def select_by_key(rank, length, budget, n_sink, n_recent):
+    """Split the live slots into retained and to-be-evicted sets under any ranking value.
 
-    Policy (fixed budget, sink tokens, recent window, heavy hitters -- App. B.3): slots
-    [0, n_sink) and [length - n_recent, length) are always kept; of the others the
-    budget - n_sink - n_recent with the largest vote-weighted EMA mass
-    ln p_i + ln s_hat_i are kept, equal masses resolved in favour of the lower index.
+    The method leaves the selection strategy open (Sec. 3.3.2, last paragraph; Sec. 4.4 combines
+    it with other eviction methods): slots [0, n_sink) and [length - n_recent, length) are
+    always kept; of the others the budget - n_sink - n_recent with the largest rank are kept,
+    equal ranks resolved in favour of the lower index, NaN below every number.
     Returns (keep_idx ascending, evict_idx ascending) as int64 arrays.
     """
     if length <= budget:
         return np.arange(length, dtype=np.int64), np.zeros(0, dtype=np.int64)
     if n_sink + n_recent > budget:
         raise ValueError("n_sink + n_recent exceeds the budget")
-    key = np.log(np.asarray(votes[:length], dtype=np.float64)) + log_s_hat(log_S[:length], n_obs[:length], alpha)
+    key = np.asarray(rank[:length], dtype=np.float64).copy()
+    key[np.isnan(key)] = -np.inf
     protected = np.zeros(length, dtype=bool)
     protected[:n_sink] = True
     protected[length - n_recent:] = True
     cand = np.flatnonzero(~protected)
     n_heavy = budget - int(protected.sum())
-    order = cand[np.lexsort((cand, -key[cand]))]                # mass descending, then index ascending
+    order = cand[np.lexsort((cand, -key[cand]))]                # rank descending, then index ascending
     keep = protected.copy()
     keep[order[:n_heavy]] = True
     return np.flatnonzero(keep).astype(np.int64), np.flatnonzero(~keep).astype(np.int64)
+
+
+def select(log_S, n_obs, votes, length, budget, n_sink, n_recent, alpha):
+    """Split the live slots into retained K_c and to-be-evicted K_e (Alg. 1 lines 2-3).
+
+    Policy (fixed budget, sink tokens, recent window, heavy hitters -- App. B.3) with the
+    vote-weighted EMA mass ln p_i + ln s_hat_i as the ranking value of select_by_key.
+    """
+    if length <= budget:
+        return np.arange(length, dtype=np.int64), np.zeros(0, dtype=np.int64)
+    key = np.log(np.asarray(votes[:length], dtype=np.float64)) + log_s_hat(log_S[:length], n_obs[:length], alpha)
+    return select_by_key(key, length, budget, n_sink, n_recent)
 
 
 # --------------------------------------------------------------------------- matching (Alg. 1 l.4-5)

@@ -50,15 +50,19 @@ _lib.keepkv_decode_step.argtypes = [C.POINTER(_Layout), C.POINTER(_Cache), _P, _
 _lib.keepkv_score.argtypes = [C.POINTER(_Layout), C.POINTER(_Cache), _P, C.c_float, _P]
 _lib.keepkv_select.argtypes = [C.POINTER(_Layout), C.POINTER(_Cache), C.c_int32, C.c_int32, C.c_int32,
                                C.c_float, _P, _P, _P, _P, C.c_size_t, _P]
+_lib.keepkv_select_by_key.argtypes = [C.POINTER(_Layout), C.POINTER(_Cache), _P, C.c_int32, C.c_int32, C.c_int32,
+                                      _P, _P, _P, _P, C.c_size_t, _P]
 _lib.keepkv_match.argtypes = [C.POINTER(_Layout), C.POINTER(_Cache), C.c_int32, _P, _P, _P, C.c_float,
                               _P, _P, _P, C.c_size_t, _P]
 _lib.keepkv_merge.argtypes = [C.POINTER(_Layout), C.POINTER(_Cache), C.POINTER(_Cache), C.c_int32, _P, _P, _P,
                               _P, C.c_float, _P, _P, C.c_size_t, _P]
-for _f in ("append", "decode_attn", "decode_step", "workspace_init", "score", "select", "match", "merge"):
+for _f in ("append", "decode_attn", "decode_step", "workspace_init", "score", "select", "select_by_key", "match",
+           "merge"):
     getattr(_lib, "keepkv_" + _f).restype = C.c_int
 
 EXPORTS = ["keepkv_strerror", "keepkv_version", "keepkv_workspace_bytes", "keepkv_workspace_init",
-           "keepkv_append", "keepkv_decode_attn", "keepkv_decode_step", "keepkv_score", "keepkv_select", "keepkv_match", "keepkv_merge"]
+           "keepkv_append", "keepkv_decode_attn", "keepkv_decode_step", "keepkv_score", "keepkv_select",
+           "keepkv_select_by_key", "keepkv_match", "keepkv_merge"]
 
 
 class KeepKVError(RuntimeError):
@@ -168,6 +172,13 @@ def select(layout: Layout, cache: Cache, budget: int, n_sink: int, n_recent: int
                               _ptr(keep_idx), _ptr(evict_idx), _ptr(n_evict), _ptr(workspace),
                               0 if workspace is None else workspace.numel() * workspace.element_size(),
                               _stream()), "keepkv_select")
+
+
+def select_by_key(layout: Layout, cache: Cache, rank, budget: int, n_sink: int, n_recent: int,
+                  keep_idx, evict_idx, n_evict, workspace) -> None:
+    _check(_lib.keepkv_select_by_key(C.byref(layout.c()), C.byref(cache.c()), _ptr(rank), budget, n_sink, n_recent,
+                                     _ptr(keep_idx), _ptr(evict_idx), _ptr(n_evict), _ptr(workspace),
+                                     _nbytes(workspace), _stream()), "keepkv_select_by_key")
 
 
 def match(layout: Layout, cache: Cache, budget: int, keep_idx, evict_idx, n_evict, threshold: float,

@@ -42,6 +42,9 @@ __device__ __forceinline__ int block_excl_scan(int v, int* s_wave, int& total) {
   return before + incl - v;
 }
 
+// EXT: the ranking value is read from a caller-supplied array (passed as log_s; n_obs and votes
+// unused) instead of being formed from the cache's votes and EMA scores.
+template <bool EXT>
 __global__ __launch_bounds__(kSelThreads) void select_kernel(
     const float* __restrict__ log_s, const int32_t* __restrict__ n_obs, const int32_t* __restrict__ votes,
     const int32_t* __restrict__ len, uint64_t* __restrict__ keys, int32_t* __restrict__ keep_idx,
@@ -74,8 +77,8 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
       const int i = min(i0 + u * kSelThreads, hi - 1);
-      nn[u] = n_obs[base + i];
-      pv[u] = votes[base + i];
+      nn[u] = EXT ? 1 : n_obs[base + i];
+      pv[u] = EXT ? 1 : votes[base + i];
       ls[u] = log_s[base + i];
     }
 #pragma unroll
@@ -83,7 +86,9 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(
       const int i = i0 + u * kSelThreads;
       if (i < hi) {
         double x;
-        if (nn[u] <= 0) {
+        if (EXT) {
+          x = (ls[u] == ls[u]) ? (double)ls[u] : -INFINITY;     // NaN ranks lowest
+        } else if (nn[u] <= 0) {
           x = -INFINITY;
         } else {
           x = log((double)pv[u]) + (double)ls[u];
@@ -213,9 +218,29 @@ extern "C" keepkv_status keepkv_select(const keepkv_layout* layout, const keepkv
   if (!workspace || workspace_bytes < pl.bytes || !aligned16(workspace)) return KEEPKV_ERR_WORKSPACE;
   const int units = layout->batch * layout->n_kv_heads;
   const double la = alpha > 0.f ? log((double)alpha) : -INFINITY;
-  select_kernel<<<units, kSelThreads, 0, reinterpret_cast<hipStream_t>(stream)>>>(
+  select_kernel<false><<<units, kSelThreads, 0, reinterpret_cast<hipStream_t>(stream)>>>(
       cache->log_s, cache->n_obs, cache->votes, cache->len,
       reinterpret_cast<uint64_t*>(reinterpret_cast<char*>(workspace) + pl.keys_off), keep_idx, evict_idx, n_evict,
       cache->capacity, budget, n_sink, n_recent, la);
+  return launch_status();
+}
+
+extern "C" keepkv_status keepkv_select_by_key(const keepkv_layout* layout, const keepkv_cache* cache,
+                                              const float* rank, int32_t budget, int32_t n_sink, int32_t n_recent,
+                                              int32_t* keep_idx, int32_t* evict_idx, int32_t* n_evict,
+                                              void* workspace, size_t workspace_bytes, void* stream) {
+  using namespace kk;
+  if (!layout_ok(layout) || !cache || !cache->len || !rank || !keep_idx || !n_evict) return KEEPKV_ERR_INVALID_ARG;
+  if (cache->capacity < 1 || cache->capacity > (1 << 20) || !aligned16(rank)) return KEEPKV_ERR_INVALID_ARG;
+  if (budget < 1 || budget > cache->capacity || n_sink < 0 || n_recent < 0 || n_sink + n_recent > budget)
+    return KEEPKV_ERR_INVALID_ARG;
+  if (budget < cache->capacity && !evict_idx) return KEEPKV_ERR_INVALID_ARG;
+  const SelectPlan pl = plan_select(layout, cache->capacity);
+  if (!workspace || workspace_bytes < pl.bytes || !aligned16(workspace)) return KEEPKV_ERR_WORKSPACE;
+  const int units = layout->batch * layout->n_kv_heads;
+  select_kernel<true><<<units, kSelThreads, 0, reinterpret_cast<hipStream_t>(stream)>>>(
+      rank, nullptr, nullptr, cache->len,
+      reinterpret_cast<uint64_t*>(reinterpret_cast<char*>(workspace) + pl.keys_off), keep_idx, evict_idx, n_evict,
+      cache->capacity, budget, n_sink, n_recent, 0.0);
   return launch_status();
 }

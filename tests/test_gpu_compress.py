@@ -155,3 +155,55 @@ def test_select_exact_ties_keep_lowest_index():
     c.n_obs[:] = 5
     c.votes[:] = torch.from_numpy(g.integers(1, 3, size=(1, 8, 900)).astype(np.int32)).cuda()
     _run_compress_stagewise(w, lay, c, ws, alpha, U.f32(0.8), check_merge=False)
+
+
+@pytest.mark.parametrize("context,budget_ratio", [(900, 0.1), (8192, 0.1), (2500, 0.5)])
+def test_select_by_key_matches_oracle_and_feeds_match_and_merge(context, budget_ratio):
+    """Caller-supplied ranking (an accumulated-attention heavy-hitter score here): index lists equal
+    the oracle's bit for bit, ragged lengths, exact ties, NaN and infinities included, and the lists
+    drive keepkv_match / keepkv_merge like those of keepkv_select."""
+    kk = U.kk()
+    w = W.CONFIGS["llama3_8b"].scaled(batch=2, context=context, ratio=budget_ratio)
+    alpha = U.f32(0.9)
+    lay, c, ws = _observed_cache(w, 5, 2, alpha)
+    B, H, cap = w.batch, w.n_kv_heads, c.capacity
+    g = np.random.default_rng(context)
+    lens = g.integers(w.budget + 1, context + 1, size=(B, H)).astype(np.int32)
+    lens[0, 0], lens[0, 1], lens[1, 2] = context, w.budget, 3          # full, exactly at budget, nearly empty
+    c.len[:] = torch.from_numpy(lens).cuda()
+    # accumulated attention probabilities of 6 synthetic steps, coarsened so that many ranks tie
+    rank = np.zeros((B, H, cap), dtype=np.float32)
+    for t in range(6):
+        x = g.standard_normal((B, H, cap)) * 3
+        p = np.exp(x - x.max(-1, keepdims=True))
+        rank += (p / p.sum(-1, keepdims=True)).astype(np.float32)
+    rank = np.round(rank * 2000).astype(np.float32) / 2000
+    rank[0, 3, g.integers(0, cap, 40)] = np.nan
+    rank[1, 0, g.integers(0, cap, 40)] = -np.inf
+    rank[1, 1, g.integers(0, cap, 5)] = np.inf
+    keep, evict, n_ev = _idx_buffers(w, cap)
+    kk.select_by_key(lay, c, torch.from_numpy(rank).cuda(), w.budget, w.n_sink, w.n_recent, keep, evict, n_ev, ws)
+    torch.cuda.synchronize()
+    keep_h, evict_h, n_ev_h = keep.cpu().numpy(), evict.cpu().numpy(), n_ev.cpu().numpy()
+    for b in range(B):
+        for h in range(H):
+            n = int(lens[b, h])
+            rk, re = O.select_by_key(rank[b, h], n, w.budget, w.n_sink, w.n_recent)
+            assert n_ev_h[b, h] == len(re), (b, h)
+            assert np.array_equal(keep_h[b, h, :len(rk)], rk), (b, h)
+            assert (keep_h[b, h, len(rk):] == -1).all()
+            assert np.array_equal(evict_h[b, h, :len(re)], re), (b, h)
+    # the lists are ordinary select output: match and merge accept them and conserve the votes
+    oc = U.download(c)
+    m = torch.full((B, H, cap - w.budget), -7, dtype=torch.int32, device="cuda")
+    kk.match(lay, c, w.budget, keep, evict, n_ev, U.f32(-2.0), m, None, ws)
+    _, dst = U.new_cache(w, capacity=w.capacity)
+    dropped = torch.zeros(B, H, dtype=torch.int64, device="cuda")
+    kk.merge(lay, c, dst, w.budget, keep, evict, n_ev, m, alpha, dropped, ws)
+    torch.cuda.synchronize()
+    od = U.download(dst)
+    for b in range(B):
+        for h in range(H):
+            n = int(lens[b, h])
+            assert od.len[b, h] == min(n, w.budget)
+            assert od.votes[b, h, :od.len[b, h]].sum() + int(dropped[b, h]) == oc.votes[b, h, :n].sum()

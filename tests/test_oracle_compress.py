@@ -69,6 +69,36 @@ def test_select_votes_weight_the_mass():
     assert keep.tolist() == [0, 1, 5, 8, 9]
 
 
+@pytest.mark.parametrize("seed", range(3))
+def test_select_by_key_brute_force_ties_nan_and_infinities(seed):
+    g = np.random.default_rng(100 + seed)
+    length, budget, n_sink, n_recent = 57, 19, 3, 7
+    rank = np.round(g.standard_normal(length), 1)
+    rank[g.integers(0, length, 6)] = np.nan
+    rank[g.integers(0, length, 3)] = -np.inf
+    rank[g.integers(0, length, 2)] = np.inf
+    keep, evict = O.select_by_key(rank, length, budget, n_sink, n_recent)
+    key = [(-math.inf if math.isnan(x) else x) for x in rank]
+    bk, be = _brute_select(key, length, budget, n_sink, n_recent)
+    assert keep.tolist() == bk and evict.tolist() == be
+
+
+def test_select_by_key_accumulated_attention_policy_differs_from_ema_mass():
+    # a cumulative-attention ranking (sum of past attention probabilities) and the EMA mass
+    # disagree on a slot that was heavy long ago: the accumulated sum keeps it, the EMA drops it
+    steps, length = 40, 12
+    probs = np.full((steps, length), 1.0 / length)
+    probs[:10, 5] = 0.9                                          # slot 5: heavy only in the first steps
+    probs[30:, 7] = 0.5                                          # slot 7: heavy recently
+    acc = probs.sum(0)
+    keep_acc, _ = O.select_by_key(acc, length, 5, 2, 2)
+    log_S, n_obs = np.full(length, -np.inf), np.zeros(length, dtype=np.int64)
+    for t in range(steps):
+        log_S, n_obs = O.score_update(log_S, n_obs, np.log(probs[t]), length, 0.5)
+    keep_ema, _ = O.select(log_S, n_obs, np.ones(length, dtype=int), length, 5, 2, 2, 0.5)
+    assert keep_acc.tolist() == [0, 1, 5, 10, 11] and keep_ema.tolist() == [0, 1, 7, 10, 11]
+
+
 # ----------------------------------------------------------------------------- match
 @pytest.mark.parametrize("exact", [False, True])
 def test_match_brute_force_cosine(exact):
