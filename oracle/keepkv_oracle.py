@@ -88,6 +88,43 @@ def score_update(log_S, n_obs, mean_logit, length, alpha):
     return log_S, n_obs
 
 
+def window_score(log_S, n_obs, q_win, k, length, scale, alpha, first_pos=-1):
+    """EMA scores from a window of W queries at once (Eq. 8, t = L branch, written as the sum).
+
+    q_win [W, G, d]: the window's queries of one kv head's group, oldest first; k [cap, d].
+    s_{j,i} = exp(mean over the group of scale * q_{j,g} . k_i).  With first_pos >= 0 query j
+    sits at sequence position first_pos + j and sees slot i only if i <= first_pos + j
+    (causal prefill); with first_pos < 0 every live slot is visible to every query.  For a slot
+    seen by the last n_i of the W queries,
+        S_i <- alpha^{n_i} S_i + sum_{j >= W - n_i} (1 - alpha) alpha^{W-1-j} s_{j,i},  n_obs_i += n_i
+    which from the empty state (S = 0, n = 0) is the window sum of Eq. 8.
+    Returns new (log_S, n_obs) copies.
+    """
+    log_S = np.array(log_S, dtype=np.float64)
+    n_obs = np.array(n_obs, dtype=np.int64)
+    q = np.asarray(q_win, dtype=np.float64)
+    W = q.shape[0]
+    kk = np.asarray(k[:length], dtype=np.float64)
+    x = scale * np.einsum("jgd,id->jgi", q, kk).mean(axis=1)                 # [W, length]  ln s_{j,i}
+    j = np.arange(W)[:, None]
+    i = np.arange(length)[None, :]
+    vis = np.ones((W, length), dtype=bool) if first_pos < 0 else (i <= first_pos + j)
+    n_vis = vis.sum(axis=0)
+    with np.errstate(divide="ignore", invalid="ignore"):
+        if alpha == 0.0:
+            coef = np.where(j == W - 1, 0.0, -np.inf)                        # only the last query counts
+            old = np.where(n_vis > 0, -np.inf, log_S[:length])
+        else:
+            coef = math.log1p(-alpha) + (W - 1 - j) * math.log(alpha)
+            old = log_S[:length] + n_vis * math.log(alpha)
+        terms = np.where(vis, x + coef, -np.inf)
+        new = np.logaddexp(old, np.logaddexp.reduce(terms, axis=0))
+    upd = n_vis > 0
+    log_S[:length][upd] = new[upd]
+    n_obs[:length] += n_vis
+    return log_S, n_obs
+
+
 def log_s_hat(log_S, n_obs, alpha):
     """ln s_hat = ln S - ln(1 - alpha^n): bias-corrected EMA score (Eq. 8), per-slot count n.
 

@@ -118,3 +118,54 @@ def test_ema_only_live_slots_and_unobserved_is_zero_score():
     sh = O.log_s_hat(log_S, n_obs, 0.9)
     np.testing.assert_allclose(sh[4:], 1.0, atol=1e-13)
     np.testing.assert_allclose(np.exp(sh[0]), (0.9 * 0.1 * 1 + 0.1 * math.e) / (1 - 0.81), rtol=1e-12)
+
+
+# ----------------------------------------------------------------------------- window form of Eq. 8
+def _window_case(seed, W=7, G=2, d=8, n=23, cap=30):
+    g = np.random.default_rng(seed)
+    return g.standard_normal((W, G, d)), g.standard_normal((cap, d)), n, cap, d ** -0.5
+
+
+@pytest.mark.parametrize("alpha", [0.0, 0.5, 0.9])
+@pytest.mark.parametrize("first_pos", [-1, 15, 22, 3])
+def test_window_score_equals_one_update_per_query(alpha, first_pos):
+    """The window sum of Eq. 8 (t = L) is what the per-step recursion (t > L) builds query by query,
+    also on top of an earlier state and with a causal window."""
+    q, k, n, cap, scale = _window_case(0)
+    W = q.shape[0]
+    g = np.random.default_rng(1)
+    for start in ("empty", "observed"):
+        if start == "empty":
+            log_S, n_obs = np.full(cap, -np.inf), np.zeros(cap, dtype=np.int64)
+        else:
+            log_S, n_obs = g.standard_normal(cap), g.integers(1, 5, cap)
+        want_S, want_n = log_S.copy(), n_obs.copy()
+        for j in range(W):
+            vis = n if first_pos < 0 else max(0, min(n, first_pos + j + 1))
+            logit = np.array([np.mean([scale * q[j, h] @ k[i] for h in range(q.shape[1])]) for i in range(n)])
+            want_S, want_n = O.score_update(want_S, want_n, logit, vis, alpha)
+        got_S, got_n = O.window_score(log_S, n_obs, q, k, n, scale, alpha, first_pos)
+        np.testing.assert_allclose(got_S, want_S, rtol=1e-12, atol=1e-12)
+        assert np.array_equal(got_n, want_n)
+        assert np.array_equal(got_S[n:], log_S[n:]) and np.array_equal(got_n[n:], n_obs[n:])
+
+
+def test_window_score_closed_forms():
+    q, k, n, cap, scale = _window_case(2)
+    W = q.shape[0]
+    # identical queries: every observation has the same score, so the corrected EMA returns it
+    q_same = np.repeat(q[:1], W, axis=0)
+    S, nn = O.window_score(np.full(cap, -np.inf), np.zeros(cap, dtype=np.int64), q_same, k, n, scale, 0.8)
+    x = scale * (q_same[0] @ k[:n].T).mean(0)
+    np.testing.assert_allclose(O.log_s_hat(S, nn, 0.8)[:n], x, rtol=1e-12, atol=1e-12)
+    assert (nn[:n] == W).all() and (nn[n:] == 0).all() and np.isinf(S[n:]).all()
+    # alpha = 0 keeps the last query's score only
+    S0, _ = O.window_score(np.full(cap, -np.inf), np.zeros(cap, dtype=np.int64), q, k, n, scale, 0.0)
+    np.testing.assert_allclose(S0[:n], scale * (q[-1] @ k[:n].T).mean(0), rtol=1e-12)
+    # causal window: slot i is seen by the queries at positions >= i; the weights are the stated powers
+    first = n - W
+    Sc, nc = O.window_score(np.full(cap, -np.inf), np.zeros(cap, dtype=np.int64), q, k, n, scale, 0.5, first)
+    assert nc[:n].tolist() == [W] * (first + 1) + list(range(W - 1, 0, -1))
+    i = n - 2                                                     # seen by the last two queries
+    s = [math.exp(np.mean([scale * q[j, h] @ k[i] for h in range(q.shape[1])])) for j in (W - 2, W - 1)]
+    assert math.exp(Sc[i]) == pytest.approx(0.5 * 0.5 * s[0] + 0.5 * s[1], rel=1e-12)
