@@ -124,6 +124,23 @@ keepkv_status keepkv_decode_step(const keepkv_layout *layout, keepkv_cache *cach
 keepkv_status keepkv_score(const keepkv_layout *layout, keepkv_cache *cache,
                            const float *logits, float alpha, void *stream);
 
+/* EMA scores from a window of queries in one pass over the keys (Eq. 8, t = L branch: after
+ * prefill the scores come from the last w + 1 queries).  q_win: DEVICE [B, Hq, window, D]
+ * storage dtype, oldest query first.  With s_{j,i} = exp of the group-mean logit of query j on
+ * slot i (as in keepkv_decode_attn), every live slot seen by the last n_i queries of the window
+ * gets
+ *     S_i <- alpha^{n_i} S_i + sum_{j >= window - n_i} (1 - alpha) alpha^{window-1-j} s_{j,i},
+ *     n_obs_i += n_i
+ * i.e. the result of `window` consecutive keepkv_score calls; on a fresh cache (log_s = -inf,
+ * n_obs = 0) this is the window sum of Eq. 8.  first_pos < 0: every query sees every live
+ * slot (n_i = window).  first_pos >= 0: query j sits at sequence position first_pos + j and
+ * sees only slots i <= first_pos + j (causal prefill; first_pos = len - window for the last
+ * `window` prompt tokens).  bf16 caches use bf16 MFMA with f32 accumulation.  Requires
+ * window * G <= 128 (longer windows: several calls, oldest queries first).  Needs no workspace. */
+keepkv_status keepkv_score_window(const keepkv_layout *layout, keepkv_cache *cache,
+                                  const void *q_win, int32_t window, float alpha,
+                                  int32_t first_pos, void *stream);
+
 /* Token selection (Alg. 1 lines 2-3; fixed-budget policy with sink tokens, a recent
  * window and heavy hitters, App. B.3).  Per (b, h) with len > budget: slots [0, n_sink)
  * and [len - n_recent, len) are kept; of the others the budget - n_sink - n_recent with the

@@ -48,6 +48,7 @@ _lib.keepkv_workspace_init.argtypes = [_P, C.c_size_t, _P]
 _lib.keepkv_decode_step.argtypes = [C.POINTER(_Layout), C.POINTER(_Cache), _P, _P, _P, _P, _P, C.c_float, _P, _P,
                                     C.c_size_t, _P]
 _lib.keepkv_score.argtypes = [C.POINTER(_Layout), C.POINTER(_Cache), _P, C.c_float, _P]
+_lib.keepkv_score_window.argtypes = [C.POINTER(_Layout), C.POINTER(_Cache), _P, C.c_int32, C.c_float, C.c_int32, _P]
 _lib.keepkv_select.argtypes = [C.POINTER(_Layout), C.POINTER(_Cache), C.c_int32, C.c_int32, C.c_int32,
                                C.c_float, _P, _P, _P, _P, C.c_size_t, _P]
 _lib.keepkv_select_by_key.argtypes = [C.POINTER(_Layout), C.POINTER(_Cache), _P, C.c_int32, C.c_int32, C.c_int32,
@@ -56,12 +57,13 @@ _lib.keepkv_match.argtypes = [C.POINTER(_Layout), C.POINTER(_Cache), C.c_int32, 
                               _P, _P, _P, C.c_size_t, _P]
 _lib.keepkv_merge.argtypes = [C.POINTER(_Layout), C.POINTER(_Cache), C.POINTER(_Cache), C.c_int32, _P, _P, _P,
                               _P, C.c_float, _P, _P, C.c_size_t, _P]
-for _f in ("append", "decode_attn", "decode_step", "workspace_init", "score", "select", "select_by_key", "match",
+for _f in ("append", "decode_attn", "decode_step", "workspace_init", "score", "score_window", "select",
+           "select_by_key", "match",
            "merge"):
     getattr(_lib, "keepkv_" + _f).restype = C.c_int
 
 EXPORTS = ["keepkv_strerror", "keepkv_version", "keepkv_workspace_bytes", "keepkv_workspace_init",
-           "keepkv_append", "keepkv_decode_attn", "keepkv_decode_step", "keepkv_score", "keepkv_select",
+           "keepkv_append", "keepkv_decode_attn", "keepkv_decode_step", "keepkv_score", "keepkv_score_window", "keepkv_select",
            "keepkv_select_by_key", "keepkv_match", "keepkv_merge"]
 
 
@@ -164,6 +166,11 @@ def decode_attn(layout: Layout, cache: Cache, q, out, logits_out, lse_out, works
 def score(layout: Layout, cache: Cache, logits, alpha: float) -> None:
     _check(_lib.keepkv_score(C.byref(layout.c()), C.byref(cache.c()), _ptr(logits), alpha, _stream()),
            "keepkv_score")
+
+
+def score_window(layout: Layout, cache: Cache, q_win, window: int, alpha: float, first_pos: int = -1) -> None:
+    _check(_lib.keepkv_score_window(C.byref(layout.c()), C.byref(cache.c()), _ptr(q_win), window, alpha, first_pos,
+                                    _stream()), "keepkv_score_window")
 
 
 def select(layout: Layout, cache: Cache, budget: int, n_sink: int, n_recent: int, alpha: float,

@@ -1,0 +1,116 @@
+"""GPU parity: keepkv_score_window (window form of Eq. 8) against the fp64 oracle, and against the
+library's own one-query-at-a-time path."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import keepkv_oracle as O
+from paper_2504_09936_amd import workloads as W
+from tests import gpu_util as U
+
+pytestmark = pytest.mark.gpu
+
+# ln S: the logits are f32 sums of exact bf16 products (|logit| up to ~1e2, f32 spacing ~1e-5 there)
+RTOL, ATOL = 1e-5, 2e-4
+
+
+def _window_queries(w, seed, window):
+    """[B, Hq, window, D], oldest first (the generator's steps -window .. -1)."""
+    return np.stack([W.round_storage(W.make_query(w, seed, t - window), w.dtype) for t in range(window)], axis=2)
+
+
+def _check(w, window, alpha, first_pos, lens=None, observed=False, seed=3):
+    kk = U.kk()
+    K, V = W.make_cache(w, seed)
+    lay, c = U.new_cache(w, capacity=w.context + 5, K=K, V=V, lens=lens)
+    if observed:                                   # start from an arbitrary earlier state
+        g = np.random.default_rng(seed)
+        c.log_s[:] = torch.from_numpy(g.standard_normal(tuple(c.log_s.shape)).astype(np.float32) * 3).cuda()
+        c.n_obs[:] = torch.from_numpy(g.integers(1, 9, size=tuple(c.n_obs.shape)).astype(np.int32)).cuda()
+    oc = U.download(c)
+    q = _window_queries(w, seed, window)
+    kk.score_window(lay, c, U.to_device(q, w.dtype), window, alpha, first_pos)
+    torch.cuda.synchronize()
+    got_S, got_n = c.log_s.cpu().numpy(), c.n_obs.cpu().numpy()
+    G = w.group
+    worst = 0.0
+    for b in range(w.batch):
+        for h in range(w.n_kv_heads):
+            n = int(oc.len[b, h])
+            qg = q[b, h * G:(h + 1) * G].transpose(1, 0, 2)             # [window, G, D]
+            ref_S, ref_n = O.window_score(oc.log_S[b, h], oc.n_obs[b, h], qg, oc.k[b, h], n, U.f32(w.scale),
+                                          alpha, first_pos)
+            assert np.array_equal(got_n[b, h], ref_n), (b, h)
+            np.testing.assert_allclose(got_S[b, h, :n], ref_S[:n], rtol=RTOL, atol=ATOL, err_msg=f"unit {(b, h)}")
+            assert np.array_equal(got_S[b, h, n:], oc.log_S[b, h, n:].astype(np.float32))   # dead slots untouched
+            fin = np.isfinite(ref_S[:n])
+            if fin.any():
+                worst = max(worst, float(np.abs(got_S[b, h, :n][fin] - ref_S[:n][fin]).max()))
+    return worst
+
+
+@pytest.mark.parametrize("alpha", [0.9, 0.0])
+@pytest.mark.parametrize("causal", [False, True])
+def test_llama_shape_window_32(alpha, causal):
+    w = W.CONFIGS["llama3_8b"].scaled(batch=2, context=1500)
+    _check(w, 32, U.f32(alpha), 1500 - 32 if causal else -1)
+
+
+def test_ragged_heads_and_observed_start():
+    w = W.CONFIGS["llama3_8b"].scaled(batch=1, context=1100)
+    lens = np.array([[1100, 1, 127, 128, 129, 0, 640, 1099]], dtype=np.int32)
+    _check(w, 32, U.f32(0.9), -1, lens=lens)
+    _check(w, 32, U.f32(0.9), -1, lens=lens, observed=True)
+    _check(w, 20, U.f32(0.5), 600, lens=lens, observed=True)           # window ends inside some heads
+
+
+@pytest.mark.parametrize("cfg,window,kw", [
+    ("tiny", 32, {}),                                                   # f32 storage, D = 64, G = 1
+    ("tiny", 5, {"n_q_heads": 8}),                                      # f32, G = 2
+    ("llama3_70b", 16, {"batch": 1, "context": 700}),                   # G = 8, 128 query rows
+    ("llama3_70b", 3, {"batch": 2, "context": 300}),                    # G = 8, partly filled tile
+    ("llama3_8b", 100, {"batch": 1, "context": 900, "n_q_heads": 8}),   # G = 1, 100 rows (ragged last tile)
+    ("llama3_8b", 33, {"batch": 1, "context": 900, "n_q_heads": 16}),   # G = 2
+    ("llama3_8b", 32, {"batch": 1, "context": 900, "head_dim": 64}),    # D = 64 bf16
+])
+def test_other_layouts(cfg, window, kw):
+    w = W.CONFIGS[cfg].scaled(**kw)
+    _check(w, window, U.f32(0.9), -1)
+    _check(w, window, U.f32(0.7), w.context - window)
+
+
+def test_equals_one_decode_and_score_pass_per_query():
+    kk = U.kk()
+    w = W.CONFIGS["llama3_8b"].scaled(batch=2, context=2000)
+    window, alpha, seed = 32, U.f32(0.9), 1
+    K, V = W.make_cache(w, seed)
+    lay, c1 = U.new_cache(w, capacity=w.context, K=K, V=V)
+    _, c2 = U.new_cache(w, capacity=w.context, K=K, V=V)
+    ws = U.workspace(lay, c1.capacity, w.budget)
+    q = _window_queries(w, seed, window)
+    logits = torch.zeros(w.batch, w.n_kv_heads, c1.capacity, dtype=torch.float32, device="cuda")
+    out = torch.zeros(w.batch, w.n_q_heads, w.head_dim, dtype=lay.torch_dtype, device="cuda")
+    for j in range(window):
+        kk.decode_attn(lay, c1, U.to_device(q[:, :, j], w.dtype), out, logits, None, ws)
+        kk.score(lay, c1, logits, alpha)
+    kk.score_window(lay, c2, U.to_device(q, w.dtype), window, alpha, -1)
+    torch.cuda.synchronize()
+    assert torch.equal(c1.n_obs, c2.n_obs)
+    np.testing.assert_allclose(c2.log_s.cpu().numpy(), c1.log_s.cpu().numpy(), rtol=1e-4, atol=1e-3)
+
+
+def test_window_argument_errors():
+    kk = U.kk()
+    w = W.CONFIGS["llama3_8b"].scaled(batch=1, context=300)
+    lay, c = U.new_cache(w, capacity=300, K=None)
+    q = torch.zeros(1, w.n_q_heads, 64, w.head_dim, dtype=torch.bfloat16, device="cuda")
+    before = c.log_s.clone()
+    for window, alpha, status in ((33, 0.9, kk.ERR_UNSUPPORTED), (0, 0.9, kk.ERR_INVALID_ARG),
+                                  (8, 1.0, kk.ERR_INVALID_ARG)):
+        with pytest.raises(kk.KeepKVError) as e:
+            kk.score_window(lay, c, q, window, alpha, -1)
+        assert e.value.status == status
+    with pytest.raises(kk.KeepKVError):
+        kk.score_window(lay, c, None, 8, 0.9, -1)
+    torch.cuda.synchronize()
+    assert torch.equal(before, c.log_s)
