@@ -134,3 +134,34 @@ def test_llama3_70b_group_of_8_reduced_batch():
 def test_stress_shape_reduced_batch():
     w = W.CONFIGS["stress"].scaled(batch=2)
     _run(w, 0, n_window=2, n_steps=w.period, threshold=-2.0, sample=[(0, 2), (1, 7)])
+
+
+@pytest.mark.parametrize("cfg,kw,window,causal", [
+    ("llama3_8b", {}, 32, False),
+    ("llama3_8b", {}, 32, True),
+    ("long_32k", {}, 32, True),
+    ("llama3_70b", {"batch": 16}, 16, False),
+])
+def test_window_scores_full_size(cfg, kw, window, causal):
+    """keepkv_score_window at the benchmark's sizes and launch configuration; sampled units against the oracle,
+    observation counts on every unit."""
+    kk = U.kk()
+    w = W.CONFIGS[cfg].scaled(**kw)
+    alpha, seed = U.f32(w.alpha), 2
+    B, H, G, N = w.batch, w.n_kv_heads, w.group, w.context
+    K, V = W.make_cache(w, seed)
+    lay, c = U.new_cache(w, capacity=N, K=K, V=V)
+    del K, V
+    q = np.stack([W.make_query(w, seed, t - window) for t in range(window)], axis=2)
+    first_pos = N - window if causal else -1
+    kk.score_window(lay, c, U.to_device(q, w.dtype), window, alpha, first_pos)
+    torch.cuda.synchronize()
+    n_obs = c.n_obs.cpu().numpy()
+    want_n = np.full(N, window) if not causal else window - np.maximum(0, np.arange(N) - first_pos)
+    assert (n_obs == want_n[None, None, :]).all()
+    empty_S, empty_n = np.full(N, -np.inf), np.zeros(N, dtype=np.int64)
+    for (b, h) in [(0, 0), (B - 1, H - 1), (B // 2, 3)]:
+        kh = U.to_host(c.k[b, h])
+        ref_S, _ = O.window_score(empty_S, empty_n, q[b, h * G:(h + 1) * G].transpose(1, 0, 2), kh, N,
+                                  U.f32(w.scale), alpha, first_pos)
+        np.testing.assert_allclose(c.log_s[b, h].cpu().numpy(), ref_S, rtol=1e-5, atol=2e-4, err_msg=f"unit {(b, h)}")
