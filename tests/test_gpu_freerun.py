@@ -1,0 +1,166 @@
+"""Free-running parity: the GPU path and the oracle each run the whole loop on their own state
+(window scores, first compression event, decode steps with an event every `period` steps) from
+the same seeded inputs; nothing is copied from one side to the other along the way.  Index lists
+must be identical at every event and the attention outputs within tolerance at every step."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import keepkv_oracle as O
+from paper_2504_09936_amd import workloads as W
+from tests import gpu_util as U
+
+pytestmark = pytest.mark.gpu
+
+# Stage-wise parity (same state on both sides) is held to 2e-3 elsewhere.  Here each side carries its own
+# state: merged K/V are rounded to bf16 on both sides from f32 resp. f64 arithmetic and so differ by an
+# ulp (2^-8 relative) in places, which moves later outputs by up to a few bf16 ulps.  f32 caches have no
+# such rounding and stay far inside the stage-wise bar.  In merge-all runs (T = -2) some merged keys are
+# ill-conditioned (the key scale ln(W/P) / (sum w ln s_hat / W) of App. A.3 has a denominator near zero and
+# amplifies the f32-versus-f64 difference of the weighted mean), so single heads drift by ~1e-2; the bar
+# there only catches gross errors, the identical index lists are the real check.
+TOL = {"bf16": 6e-3, "f32": 1e-4}
+TOL_MERGE_ALL = 5e-2
+# A merged key whose scale exceeds this (its denominator is within ~1e-2 of zero) is many times longer than
+# any original key; the slot's logit then amplifies the last-bit differences of the two sides' states, and the
+# outputs of that kv head are no longer comparable (they are still required to be finite).
+ILL_SCALE = 8.0
+
+
+def _oracle_event(oc, w, alpha, T, rnd, ill):
+    """The oracle's compression event, step by step, also reporting which units got an ill-conditioned key."""
+    trace = []
+    for b in range(oc.B):
+        for h in range(oc.H):
+            n = int(oc.len[b, h])
+            keep, ev = O.select(oc.log_S[b, h], oc.n_obs[b, h], oc.votes[b, h], n, w.budget, w.n_sink, w.n_recent, alpha)
+            tgt, _ = O.match(oc.k[b, h], keep, ev, T, w.dtype == "bf16")
+            r = O.merge(oc.k[b, h], oc.v[b, h], oc.votes[b, h], oc.log_S[b, h], oc.n_obs[b, h], keep, ev, tgt, alpha)
+            nk = len(keep)
+            merged = np.isfinite(r.ell_bar) & ~r.guarded
+            if merged.any():
+                scale = O.log_s_hat(r.log_S, r.n_obs, alpha)[merged] / r.ell_bar[merged]
+                if np.abs(scale).max() > ILL_SCALE:
+                    ill.add((b, h))
+            oc.k[b, h, :nk] = r.k if rnd is None else rnd(r.k)
+            oc.v[b, h, :nk] = r.v if rnd is None else rnd(r.v)
+            oc.votes[b, h, :nk], oc.log_S[b, h, :nk], oc.n_obs[b, h, :nk] = r.votes, r.log_S, r.n_obs
+            oc.len[b, h] = nk
+            oc.dropped[b, h] += r.dropped
+            trace.append((keep, ev, tgt))
+    return trace
+
+
+def _free_run(w, seed, threshold):
+    kk = U.kk()
+    alpha, T = U.f32(w.alpha), U.f32(threshold)
+    B, H, G, N, Bud, P = w.batch, w.n_kv_heads, w.group, w.context, w.budget, w.period
+    rnd = (lambda a: W.round_storage(a, w.dtype)) if w.dtype == "bf16" else None
+    K, V = W.make_cache(w, seed)
+
+    # ---------------- GPU side
+    lay, big = U.new_cache(w, capacity=N, K=K, V=V)
+    ws = U.workspace(lay, N, Bud)
+    small = [kk.Cache(lay, Bud + P), kk.Cache(lay, Bud + P)]
+    keep = torch.zeros(B, H, Bud, dtype=torch.int32, device="cuda")
+    evict = torch.zeros(B, H, N - Bud, dtype=torch.int32, device="cuda")
+    match = torch.zeros(B, H, N - Bud, dtype=torch.int32, device="cuda")
+    n_ev = torch.zeros(B, H, dtype=torch.int32, device="cuda")
+    dropped = torch.zeros(B, H, dtype=torch.int64, device="cuda")
+    out = torch.zeros(B, w.n_q_heads, w.head_dim, dtype=lay.torch_dtype, device="cuda")
+
+    # ---------------- oracle side
+    oc = O.Cache(B, H, max(N, Bud + P), w.head_dim)
+    oc.k[:, :, :N], oc.v[:, :, :N] = K, V
+    oc.votes[:, :, :N] = 1
+    oc.len[:] = N
+
+    def gpu_event(src, dst):
+        cap = src.capacity
+        ev = evict.view(-1)[: B * H * (cap - Bud)].view(B, H, cap - Bud)
+        mt = match.view(-1)[: B * H * (cap - Bud)].view(B, H, cap - Bud)
+        kk.select(lay, src, Bud, w.n_sink, w.n_recent, alpha, keep, ev, n_ev, ws)
+        kk.match(lay, src, Bud, keep, ev, n_ev, T, mt, None, ws)
+        kk.merge(lay, src, dst, Bud, keep, ev, n_ev, mt, alpha, dropped, ws)
+        torch.cuda.synchronize()
+        return keep.cpu().numpy(), ev.cpu().numpy(), mt.cpu().numpy()
+
+    def compare_event(tag, got, trace):
+        gk, ge, gm = got
+        u = 0
+        for b in range(B):
+            for h in range(H):
+                rk, re, tg = trace[u]
+                u += 1
+                assert np.array_equal(gk[b, h], rk), (tag, "keep", b, h)
+                assert np.array_equal(ge[b, h, :len(re)], re), (tag, "evict", b, h)
+                assert np.array_equal(gm[b, h, :len(re)], tg), (tag, "match", b, h)
+
+    # window scores (Eq. 8, t = L)
+    q_win = np.stack([W.make_query(w, seed, t - w.window) for t in range(w.window)], axis=2)   # [B, Hq, W, D]
+    chunk = max(1, 128 // G)
+    for j0 in range(0, w.window, chunk):
+        qc = np.ascontiguousarray(q_win[:, :, j0:j0 + chunk])
+        kk.score_window(lay, big, U.to_device(qc, w.dtype), qc.shape[2], alpha, -1)
+    for b in range(B):
+        for h in range(H):
+            oc.log_S[b, h], oc.n_obs[b, h] = O.window_score(
+                oc.log_S[b, h], oc.n_obs[b, h], q_win[b, h * G:(h + 1) * G].transpose(1, 0, 2), oc.k[b, h], N,
+                U.f32(w.scale), alpha)
+
+    ill = set()
+    compare_event("first event", gpu_event(big, small[0]), _oracle_event(oc, w, alpha, T, rnd, ill))
+    cur, worst, prev = 0, 0.0, None
+    for t in range(w.steps):
+        k_t, v_t = W.make_token(w, seed, t, prev=prev)
+        prev = (k_t, v_t) if w.key_model == "ar1" else None
+        q = W.make_query(w, seed, t)
+        kk.decode_step(lay, small[cur], U.to_device(q, w.dtype), U.to_device(k_t, w.dtype), U.to_device(v_t, w.dtype),
+                       out, None, alpha, None, ws)
+        oc.append(k_t.astype(np.float64), v_t.astype(np.float64))
+        o_ref, _, lg = O.attend(oc, q.astype(np.float64), w.scale)
+        O.observe(oc, lg, alpha)
+        torch.cuda.synchronize()
+        got = U.to_host(out)
+        assert np.isfinite(got).all()
+        err = U.rel_err_rows(got, W.round_storage(o_ref, w.dtype))
+        for (b, h) in ill:
+            err[b, h * G:(h + 1) * G] = 0.0
+        worst = max(worst, float(err.max()))
+        bar = TOL_MERGE_ALL if (threshold < -1 and w.dtype == "bf16") else TOL[w.dtype]
+        assert err.max() <= bar, ("step", t, float(err.max()))
+        if (t + 1) % P == 0:
+            compare_event(f"event after step {t}", gpu_event(small[cur], small[1 - cur]),
+                          _oracle_event(oc, w, alpha, T, rnd, ill))
+            cur = 1 - cur
+    c = small[cur]
+    torch.cuda.synchronize()
+    n = int(oc.len[0, 0])
+    assert np.array_equal(c.len.cpu().numpy(), oc.len)
+    assert np.array_equal(c.votes[:, :, :n].cpu().numpy(), oc.votes[:, :, :n])
+    assert np.array_equal(c.n_obs[:, :, :n].cpu().numpy(), oc.n_obs[:, :, :n])
+    assert np.array_equal(dropped.cpu().numpy(), oc.dropped)
+    ok = np.ones((B, H), dtype=bool)
+    for u in ill:
+        ok[u] = False
+    np.testing.assert_allclose(c.log_s[:, :, :n].cpu().numpy()[ok], oc.log_S[:, :, :n][ok], rtol=1e-4,
+                               atol=TOL_MERGE_ALL if threshold < -1 else 5e-3)
+    print(f"free run {w.name} T={threshold}: worst output error {worst:.2e}, "
+          f"{len(ill)} of {B * H} units with an ill-conditioned merged key")
+    return worst
+
+
+@pytest.mark.parametrize("threshold", [0.8, -2.0])
+def test_tiny_f32_whole_run_is_index_identical(threshold):
+    """512 tokens -> 52 slots, 32 window queries, 64 decode steps, an event every 32 steps."""
+    _free_run(W.CONFIGS["tiny"], 0, threshold)
+
+
+@pytest.mark.parametrize("cfg,kw,threshold", [
+    ("llama3_8b", {"batch": 1, "context": 1536, "steps": 128, "period": 32}, 0.8),
+    ("llama3_8b", {"batch": 1, "context": 1536, "steps": 96, "period": 32}, -2.0),
+    ("long_32k", {"context": 2048, "steps": 64, "period": 32}, 0.8),
+    ("stress", {"batch": 1, "context": 1280, "steps": 64, "period": 16}, 0.8),
+])
+def test_bf16_whole_run(cfg, kw, threshold):
+    _free_run(W.CONFIGS[cfg].scaled(**kw), 1, threshold)
