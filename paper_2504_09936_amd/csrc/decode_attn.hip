@@ -507,14 +507,37 @@ keepkv_status run_decode(const keepkv_layout* layout, const keepkv_cache* cache,
 }  // namespace
 
 DecodePlan plan_decode(const keepkv_layout* L, int capacity) {
-  // Slots per split: 128 (two 16-slot tiles per wavefront) unless that leaves the chip short of
-  // workgroups (then 64) or floods it (then enough slots per split for about 2048 workgroups).
+  // Slots per split (a multiple of 64) from a small cost model fitted to measurements on MI355X
+  // (batch 1..128, 850..32768 slots): about 512 workgroups are resident at once; a workgroup streams at
+  // no more than ~17 GB/s (its rows in flight over the memory latency) and all of them together at
+  // ~5 TB/s; every round of workgroups costs ~3 us of start-up; the last workgroup of a head combines
+  // the splits eight at a time, ~2.3 us per round trip of device-scope loads.  Few long splits starve the chip, many short
+  // ones pay for rounds and for the combine.
   DecodePlan pl;
-  const long units = (long)L->batch * L->n_kv_heads;
+  const double units = (double)L->batch * L->n_kv_heads;
+  const double slot_bytes = 2.0 * L->head_dim * (L->dtype == KEEPKV_BF16 ? 2 : 4) + 24.0;
+  // slots a workgroup consumes per loop iteration (4 wavefronts x 4 slots per lane group; see launch_decode)
+  const int rv = L->head_dim * (L->dtype == KEEPKV_BF16 ? 2 : 4) / 16;
+  const long granule = (rv >= 32 || (L->n_q_heads / L->n_kv_heads >= 8 && rv >= 16)) ? 64 : 128;
   long per = 128;
-  const long spread = (units * capacity / 2048 + 63) / 64 * 64;
-  if (spread > per) per = spread;
-  if (units * ((capacity + per - 1) / per) < 256 && per > 64) per = 64;
+  double best = 1e300;
+  const long max_ns = (capacity + 63) / 64 < 1024 ? (capacity + 63) / 64 : 1024;
+  for (long ns = 1; ns <= max_ns; ++ns) {
+    const long cand = ((capacity + ns - 1) / ns + 63) / 64 * 64;
+    const double n_split = (double)((capacity + cand - 1) / cand);
+    const double wgs = units * n_split;
+    const double resident = wgs < 512.0 ? wgs : 512.0;
+    const double rounds = (double)(long)((wgs + 511.0) / 512.0);
+    double bw = 5000.0 / resident;                       // GB/s per workgroup
+    if (bw > 17.0) bw = 17.0;
+    const double streamed = (double)((cand + granule - 1) / granule * granule);          // whole iterations
+    const double t_stream = rounds * (3.0 + streamed * slot_bytes / (bw * 1e3));       // us
+    const double t_combine = n_split > 1.0 ? 1.0 + 2.3 * (double)(long)((n_split + 7.0) / 8.0) : 0.0;
+    if (t_stream + t_combine < best) {
+      best = t_stream + t_combine;
+      per = cand;
+    }
+  }
   static const long forced = [] { const char* e = getenv("KEEPKV_DECODE_CHUNK"); return e ? atol(e) : 0L; }();
   if (forced >= 64) per = forced / 64 * 64;
   long ns = (capacity + per - 1) / per;
