@@ -282,17 +282,51 @@ def main():
     live_mean = Bud + (P // 2 + 1) / 2.0          # slots per head attended, averaged over the replay
     slots = B * H * live_mean
 
-    # algorithmic bytes of one decode_attn launch: K+V rows, votes, logit side output per live slot,
-    # plus Q in and O out
-    # per slot: K and V rows, votes (4 B) and the logit that feeds the EMA (4 B); plus Q in and O out
-    dec_bytes = slots * (2 * D * esz + 4 + 4) + 2 * B * Hq * D * esz
+    # algorithmic bytes of one launch.  Per live slot: K and V rows and votes (4 B); the unfused attention
+    # call also writes the logit that feeds the EMA (4 B), the fused step instead reads and writes the EMA
+    # state in place (ln S and n: 16 B) and keeps the logit on chip.  Plus Q in and O out.
+    dec_bytes = slots * (2 * D * esz + 4 + (4 if args.unfused else 16)) + 2 * B * Hq * D * esz
     achieved = dec_bytes / (dec_us * 1e-6) / 1e9
-    # (the fused step keeps the logit on chip but reads and writes the EMA state instead: 16 B per slot)
-    if not args.unfused:
-        dec_bytes += slots * (16 - 4)
+
+    # what the GPU sustains on plain work of the same size (one launch reading a buffer as large as the decode
+    # working set, 32 distinct buffers in rotation, same number of workgroups), on a large stream, and on
+    # back-to-back bf16 MFMAs -- context for the fractions of the published peaks
+    def graph_time(fn, n_launch, reps=4):
+        fn()
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=stream):
+            fn()
+        torch.cuda.synchronize()
+        t0_, t1_ = ev(), ev()
+        with torch.cuda.stream(stream):
+            g.replay()
+            t0_.record()
+            for _ in range(reps):
+                g.replay()
+            t1_.record()
+        torch.cuda.synchronize()
+        return t0_.elapsed_time(t1_) * 1e3 / (reps * n_launch)
+
+    sink = torch.zeros(4, dtype=torch.float32, device=dev)
+    ws_bytes = int(dec_bytes) // 16 * 16
+    bufs = [torch.randint(0, 255, (ws_bytes,), dtype=torch.uint8, device=dev) for _ in range(R)]
+    n_wg = B * H * ((cap + 127) // 128)
+    small_us = graph_time(lambda: [kk.probe_read(b_, n_wg, sink) for b_ in bufs], R)
+    del bufs
+    big_buf = torch.randint(0, 255, (1 << 30,), dtype=torch.uint8, device=dev)
+    big_us = graph_time(lambda: [kk.probe_read(big_buf, 4096, sink) for _ in range(2)], 2)
+    del big_buf
+    flops_box = []
+    mfma_us = graph_time(lambda: flops_box.append(kk.probe_mfma(2048, 2000, sink)), 1)
+    measured = {"read_decode_working_set_GBps": round(ws_bytes / small_us / 1e3, 1),
+                "read_1GiB_GBps": round((1 << 30) / big_us / 1e3, 1),
+                "mfma_bf16_TFLOPs": round(flops_box[-1] / mfma_us / 1e6, 1)}
     roofline = {"bound": "hbm", "kernel": "decode_attn_kernel", "achieved": round(achieved, 1),
                 "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
-                "traffic": (PMC_TRAFFIC_BYTES.get(w.name) if not args.unfused else None), "bytes_per_launch": int(dec_bytes), "avg_launch_us": round(dec_us, 2)}
+                "traffic": (PMC_TRAFFIC_BYTES.get(w.name) if not args.unfused else None), "bytes_per_launch": int(dec_bytes),
+                "avg_launch_us": round(dec_us, 2),
+                "frac_of_measured_read": round(achieved / measured["read_decode_working_set_GBps"], 4)}
 
     M1 = N - Bud
     match_first_us = float(np.median(first["match"]))
@@ -354,7 +388,9 @@ def main():
             "compress_first": {k_: round(float(np.median(v_)), 1) for k_, v_ in first.items()},
         },
         "match_first_event": {"bound": "mfma", "achieved": round(match_first_tflops, 1), "peak": MFMA_BF16_PEAK_TFLOPS,
-                              "unit": "TFLOP/s", "frac": round(match_first_tflops / MFMA_BF16_PEAK_TFLOPS, 4)},
+                              "unit": "TFLOP/s", "frac": round(match_first_tflops / MFMA_BF16_PEAK_TFLOPS, 4),
+                              "frac_of_measured_mfma": round(match_first_tflops / measured["mfma_bf16_TFLOPs"], 4)},
+        "measured_rates": measured,
         "score_window_prefill": {"bound": "hbm", "achieved": round(win_gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                                  "frac": round(win_gbs / HBM_PEAK_GBS, 4)},
         "prefill_s": round(t_prefill, 1),

@@ -194,6 +194,17 @@ keepkv_status keepkv_merge(const keepkv_layout *layout, const keepkv_cache *src,
                            const int32_t *match, float alpha, int64_t *dropped_votes,
                            void *workspace, size_t workspace_bytes, void *stream);
 
+/* Measurement probes (not part of the method): what the GPU sustains, to set next to the
+ * published peaks.  keepkv_probe_read: `n_workgroups` workgroups stream `bytes` (a multiple of
+ * 16) of DEVICE memory at `src` once with coalesced 16-byte loads; nothing is written except
+ * possibly the DEVICE float `sink`.  keepkv_probe_mfma: every wavefront of `n_workgroups`
+ * workgroups (4 wavefronts each) issues 4 * iters independent 32x32x16 bf16 MFMAs; *flops (HOST,
+ * may be NULL) receives the floating-point operations of the launch.  Time them with events. */
+keepkv_status keepkv_probe_read(const void *src, size_t bytes, int32_t n_workgroups, float *sink,
+                                void *stream);
+keepkv_status keepkv_probe_mfma(int32_t n_workgroups, int32_t iters, float *sink, double *flops,
+                                void *stream);
+
 #ifdef __cplusplus
 }
 #endif

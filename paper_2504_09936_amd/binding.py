@@ -57,14 +57,16 @@ _lib.keepkv_match.argtypes = [C.POINTER(_Layout), C.POINTER(_Cache), C.c_int32, 
                               _P, _P, _P, C.c_size_t, _P]
 _lib.keepkv_merge.argtypes = [C.POINTER(_Layout), C.POINTER(_Cache), C.POINTER(_Cache), C.c_int32, _P, _P, _P,
                               _P, C.c_float, _P, _P, C.c_size_t, _P]
-for _f in ("append", "decode_attn", "decode_step", "workspace_init", "score", "score_window", "select",
+_lib.keepkv_probe_read.argtypes = [_P, C.c_size_t, C.c_int32, _P, _P]
+_lib.keepkv_probe_mfma.argtypes = [C.c_int32, C.c_int32, _P, C.POINTER(C.c_double), _P]
+for _f in ("probe_read", "probe_mfma", "append", "decode_attn", "decode_step", "workspace_init", "score", "score_window", "select",
            "select_by_key", "match",
            "merge"):
     getattr(_lib, "keepkv_" + _f).restype = C.c_int
 
 EXPORTS = ["keepkv_strerror", "keepkv_version", "keepkv_workspace_bytes", "keepkv_workspace_init",
            "keepkv_append", "keepkv_decode_attn", "keepkv_decode_step", "keepkv_score", "keepkv_score_window", "keepkv_select",
-           "keepkv_select_by_key", "keepkv_match", "keepkv_merge"]
+           "keepkv_select_by_key", "keepkv_match", "keepkv_merge", "keepkv_probe_read", "keepkv_probe_mfma"]
 
 
 class KeepKVError(RuntimeError):
@@ -186,6 +188,16 @@ def select_by_key(layout: Layout, cache: Cache, rank, budget: int, n_sink: int, 
     _check(_lib.keepkv_select_by_key(C.byref(layout.c()), C.byref(cache.c()), _ptr(rank), budget, n_sink, n_recent,
                                      _ptr(keep_idx), _ptr(evict_idx), _ptr(n_evict), _ptr(workspace),
                                      _nbytes(workspace), _stream()), "keepkv_select_by_key")
+
+
+def probe_read(src, n_workgroups: int, sink) -> None:
+    _check(_lib.keepkv_probe_read(_ptr(src), _nbytes(src), n_workgroups, _ptr(sink), _stream()), "keepkv_probe_read")
+
+
+def probe_mfma(n_workgroups: int, iters: int, sink) -> float:
+    flops = C.c_double(0.0)
+    _check(_lib.keepkv_probe_mfma(n_workgroups, iters, _ptr(sink), C.byref(flops), _stream()), "keepkv_probe_mfma")
+    return flops.value
 
 
 def match(layout: Layout, cache: Cache, budget: int, keep_idx, evict_idx, n_evict, threshold: float,

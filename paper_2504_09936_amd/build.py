@@ -10,7 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libkeepkv.so")
-SOURCES = ["api.hip", "decode_attn.hip", "score_append.hip", "score_window.hip", "select.hip", "match.hip", "merge.hip"]
+SOURCES = ["api.hip", "decode_attn.hip", "score_append.hip", "score_window.hip", "select.hip", "match.hip", "merge.hip", "probe.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=off",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-mllvm", "-amdgpu-mfma-vgpr-form",   # MFMA results in VGPRs: the fused epilogue reads them directly
