@@ -61,6 +61,110 @@ __device__ __forceinline__ float ld_agent(const float* p) {
   return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
+// Everything after the workgroup's kParts partial softmax states (m, l, acc[D] per head) have been
+// deposited in LDS and a barrier has passed: reduce them; a single split finishes the head, otherwise the
+// partial result goes to the workspace and the last workgroup of the head to arrive combines the splits,
+// resets the ticket and (step mode) publishes the new len.
+template <typename T, int D, int G, int kParts, bool STEP>
+__device__ __forceinline__ void combine_and_finish(const DecodeParams& p, const float* s_m, const float* s_l,
+                                                   const float* s_acc, int* s_last_p, int unit, int split, bool grow,
+                                                   int len) {
+  constexpr bool kBf16 = sizeof(T) == 2;
+  int& s_last = *s_last_p;
+  auto finish = [&](size_t row, int d, float M, float L, float A) {
+    const float o = (L > 0.f) ? A / L : 0.f;
+    if constexpr (kBf16)
+      reinterpret_cast<uint16_t*>(p.out)[row * D + d] = (uint16_t)f32_to_bf16_bits(o);
+    else
+      reinterpret_cast<float*>(p.out)[row * D + d] = o;
+    if (d == 0 && p.lse_out != nullptr) p.lse_out[row] = (L > 0.f) ? (M + fast_log2(L)) * kLn2 : -INFINITY;
+  };
+
+  for (int idx = threadIdx.x; idx < G * D; idx += kWavesPerBlock * kWave) {
+    const int g = idx / D, d = idx % D;
+    float M = s_m[g];
+#pragma unroll
+    for (int w = 1; w < kParts; ++w) M = fmaxf(M, s_m[w * G + g]);
+    float L = 0.f, A = 0.f;
+#pragma unroll
+    for (int w = 0; w < kParts; ++w) {
+      const float mw = s_m[w * G + g];
+      const float c = (mw == -INFINITY) ? 0.f : fast_exp2(mw - M);
+      L = fmaf(s_l[w * G + g], c, L);
+      A = fmaf(s_acc[(w * G + g) * D + d], c, A);
+    }
+    const size_t row = (size_t)unit * G + g;   // == b * Hq + h * G + g
+    if (p.nsplit == 1) {
+      finish(row, d, M, L, A);
+    } else {
+      // device-coherent (write-through) stores: the combining workgroup may run on another XCD
+      float* dst = p.partial + (row * p.nsplit + split) * (D + 2);
+      st_agent(dst + 2 + d, A);
+      if (d == 0) {
+        st_agent(dst, M);
+        st_agent(dst + 1, L);
+      }
+    }
+  }
+
+  if (p.nsplit == 1) {
+    if (STEP && threadIdx.x == 0 && grow) p.len[unit] = len;   // every wavefront read len before the barrier above
+    if (STEP && threadIdx.x == 0 && !grow && p.overflow != nullptr) *p.overflow = 1;
+    return;
+  }
+
+  KK_TS(3);
+  // ---- the last workgroup of this head to arrive combines the splits ------------------------------
+  // The partial results were stored write-through at device scope, so it is enough that every
+  // wavefront's stores have completed (workgroup-scope release = wait on the store counter) before
+  // the ticket is taken; a device-scope release fence here would write back the whole L2 per
+  // workgroup.  The combining workgroup reads the partials with device-scope loads.
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+  __syncthreads();
+  if (threadIdx.x == 0)
+    s_last = (__hip_atomic_fetch_add(&p.ticket[unit], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == p.nsplit - 1);
+  __syncthreads();
+  KK_TS(4);
+  if (!s_last) return;
+  for (int idx = threadIdx.x; idx < G * D; idx += kWavesPerBlock * kWave) {
+    const int g = idx / D, d = idx % D;
+    const size_t row = (size_t)unit * G + g;
+    const float* src = p.partial + row * p.nsplit * (D + 2);
+    float M = -INFINITY, L = 0.f, A = 0.f;
+    constexpr int CH = 8;                       // splits fetched per round trip
+    for (int s0 = 0; s0 < p.nsplit; s0 += CH) {
+      float ms[CH], ls[CH], as[CH];
+#pragma unroll
+      for (int i = 0; i < CH; ++i) {
+        const int s = min(s0 + i, p.nsplit - 1);
+        ms[i] = ld_agent(src + s * (D + 2));
+        ls[i] = ld_agent(src + s * (D + 2) + 1);
+        as[i] = ld_agent(src + s * (D + 2) + 2 + d);
+      }
+      float mc = M;
+#pragma unroll
+      for (int i = 0; i < CH; ++i) mc = fmaxf(mc, ms[i]);
+      const float c0 = (M == -INFINITY) ? 0.f : fast_exp2(M - mc);
+      L *= c0;
+      A *= c0;
+#pragma unroll
+      for (int i = 0; i < CH; ++i) {
+        const float c = (s0 + i < p.nsplit && ms[i] != -INFINITY) ? fast_exp2(ms[i] - mc) : 0.f;
+        L = fmaf(ls[i], c, L);
+        A = fmaf(as[i], c, A);
+      }
+      M = mc;
+    }
+    finish(row, d, M, L, A);
+  }
+  KK_TS(5);
+  if (threadIdx.x == 0) {
+    __hip_atomic_store(&p.ticket[unit], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // ready for the next launch
+    if (STEP && grow) p.len[unit] = len;
+    if (STEP && !grow && p.overflow != nullptr) *p.overflow = 1;
+  }
+}
+
 // LPS lanes share one slot's row, each holding VPL 16-byte vectors of it (vector v of lane `sub` is
 // row vector v * LPS + sub, so the LPS lanes of a group read LPS * 16 contiguous bytes per load).
 // kUnroll slots per lane group are in flight per iteration.
@@ -343,98 +447,267 @@ __global__ __launch_bounds__(kWavesPerBlock* kWave) void decode_attn_kernel(Deco
   __syncthreads();
   KK_TS(2);
 
-  auto finish = [&](size_t row, int d, float M, float L, float A) {
-    const float o = (L > 0.f) ? A / L : 0.f;
-    if constexpr (kBf16)
-      reinterpret_cast<uint16_t*>(p.out)[row * D + d] = (uint16_t)f32_to_bf16_bits(o);
-    else
-      reinterpret_cast<float*>(p.out)[row * D + d] = o;
-    if (d == 0 && p.lse_out != nullptr) p.lse_out[row] = (L > 0.f) ? (M + fast_log2(L)) * kLn2 : -INFINITY;
+  combine_and_finish<T, D, G, kParts, STEP>(p, s_m, s_l, s_acc, &s_last, unit, split, grow, len);
+}
+
+// ---------------------------------------------------------------------------------------------------
+// bf16 caches: the same decode step with both contractions on the matrix cores (16x16x32 bf16 MFMA).
+//
+// A wavefront owns 32-slot tiles.  Their K and V rows go global -> LDS without passing through
+// registers (rows XOR-swizzled in 16-byte chunks).  Scores are formed transposed, S^T = K Q^T: the A
+// operand is the K tile (row = slot), the B operand the query heads (column = head, heads repeated
+// to fill 16 columns), so lane (column c, quarter q) receives the logits of head c mod G for the
+// slots 16 st + 4 q + i (st = 0, 1; i = 0..3).  That is already the layout of an A operand whose row
+// is the head and whose contraction index runs over those 8 slots, so the probabilities feed the
+// second product O = P V without leaving their lanes; its B operand, 8 slots of one channel per
+// lane, is what the LDS transpose read (ds_read_b64_tr_b16) returns from the row-major V tile.
+// P is split into two bf16 terms (hi + lo, 16 significant bits), V is bf16 already, accumulation f32.
+// Output rows are heads again (row r = head r mod G), 16 channels per MFMA.
+constexpr int kMTile = 32;
+
+typedef __attribute__((ext_vector_type(4))) short v4i16_t;
+
+template <int G>
+__device__ __forceinline__ float head_sum(float x) {   // sum over the G heads held by G consecutive lanes
+  if constexpr (G >= 2) x += dpp_f32<0xB1>(x);          // quad_perm [1,0,3,2]
+  if constexpr (G >= 4) x += dpp_f32<0x4E>(x);          // quad_perm [2,3,0,1]
+  if constexpr (G >= 8) x += dpp_f32<0x141>(x);         // row_half_mirror
+  return x;
+}
+
+__device__ __forceinline__ uint32_t pack_hi16(float lo_elem, float hi_elem) {   // {bf16 trunc(lo_elem), bf16 trunc(hi_elem)}
+  return (__builtin_bit_cast(uint32_t, lo_elem) >> 16) | (__builtin_bit_cast(uint32_t, hi_elem) & 0xFFFF0000u);
+}
+
+template <int D, int G, bool STEP>
+__global__ __launch_bounds__(kWavesPerBlock* kWave, 2) void decode_mfma_kernel(DecodeParams p) {
+  using T = uint16_t;
+  constexpr int ROWB = D * 2, CHUNKS = ROWB / 16, KS = D / 32, NTILE = D / 16;
+  constexpr int TILE_BYTES = kMTile * ROWB;
+  constexpr int LOADS = TILE_BYTES / (kWave * 16);
+  constexpr int kParts = kWavesPerBlock;
+  extern __shared__ __align__(16) unsigned char smem_raw[];     // [wave][K tile | V tile]; later the deposit
+  __shared__ int s_last;
+  __shared__ __align__(16) unsigned char s_new[2 * ROWB];       // step mode: the appended token's K row, V row
+
+  const int unit = blockIdx.x / p.nsplit, split = blockIdx.x % p.nsplit;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int l16 = lane & 15, q = lane >> 4;
+  const int len_old = p.len[unit];
+  const int start = split * p.per;
+  const bool takes_new = STEP && split == p.nsplit - 1 && wave == kWavesPerBlock - 1;
+  if (takes_new && lane < 2 * CHUNKS) {        // asynchronous copy of (k_t, v_t) into LDS, awaited after the loop
+    const unsigned char* src = reinterpret_cast<const unsigned char*>(lane < CHUNKS ? p.k_t : p.v_t) +
+                               (size_t)unit * ROWB + (lane % CHUNKS) * 16;
+    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
+                                     (__attribute__((address_space(3))) void*)s_new, 16, 0, 0);
+  }
+  const int bound = p.len_hint > 0 ? min(p.len_hint, p.capacity) : len_old;
+  const int lim = min(bound, start + p.per);
+  const size_t ubase = (size_t)unit * p.capacity;
+  const unsigned char* kbytes = reinterpret_cast<const unsigned char*>(p.k) + ubase * ROWB;
+  const unsigned char* vbytes = reinterpret_cast<const unsigned char*>(p.v) + ubase * ROWB;
+  unsigned char* Kb = smem_raw + wave * (2 * TILE_BYTES);
+  unsigned char* Vb = Kb + TILE_BYTES;
+
+  // chunk c of row r of a tile sits at position c ^ (r mod CHUNKS); rows at or beyond `bound` are never read
+  auto issue_tile = [&](int base) {
+#pragma unroll
+    for (int i = 0; i < LOADS; ++i) {
+      const int c = lane + i * kWave;
+      const int row = c / CHUNKS, phys = c % CHUNKS;
+      const size_t off = (size_t)min(base + row, bound - 1) * ROWB + ((phys ^ (row & (CHUNKS - 1))) * 16);
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(kbytes + off),
+                                       (__attribute__((address_space(3))) void*)(Kb + i * (kWave * 16)), 16, 0, 0);
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(vbytes + off),
+                                       (__attribute__((address_space(3))) void*)(Vb + i * (kWave * 16)), 16, 0, 0);
+    }
+  };
+  int base = start + wave * kMTile;
+  if (base < lim) issue_tile(base);
+
+  // B operand of the score product: column l16 is head l16 mod G, this lane's 8 channels of every k-step
+  bf16x8_t qb[KS];
+  {
+    const unsigned char* qrow = reinterpret_cast<const unsigned char*>(p.q) + ((size_t)unit * G + (l16 % G)) * ROWB;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) qb[ks] = *reinterpret_cast<const bf16x8_t*>(qrow + ks * 64 + q * 16);
+  }
+
+  const float sl2 = p.scale * kLog2e;
+  float m_run = -INFINITY, l_run = 0.f;
+  f32x4_t O[NTILE];
+#pragma unroll
+  for (int nt = 0; nt < NTILE; ++nt) O[nt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+  bool first = true;
+  const int live_end = min(len_old, start + p.per);
+
+  // One tile.  `extra`: the appended token alone (row 0 of the tile, copied from s_new).
+  auto compute = [&](int tbase, bool extra, const int (&pv)[2][4], float ls_old, int no_old) {
+    const int n_live = extra ? 1 : max(0, min(kMTile, live_end - tbase));
+    if (n_live < kMTile) {                       // uniform: clear the V rows of masked slots (0 * garbage could be NaN)
+      for (int c = n_live * CHUNKS + lane; c < kMTile * CHUNKS; c += kWave)
+        *reinterpret_cast<uint4*>(Vb + c * 16) = make_uint4(0, 0, 0, 0);
+      __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
+      __builtin_amdgcn_wave_barrier();
+    }
+    // ---- S^T = K Q^T
+    f32x4_t s[2] = {f32x4_t{0.f, 0.f, 0.f, 0.f}, f32x4_t{0.f, 0.f, 0.f, 0.f}};
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      const int off = l16 * ROWB + (((4 * ks + q) ^ (l16 & (CHUNKS - 1))) * 16);
+      const bf16x8_t a0 = *reinterpret_cast<const bf16x8_t*>(Kb + off);
+      const bf16x8_t a1 = *reinterpret_cast<const bf16x8_t*>(Kb + off + 16 * ROWB);
+      s[0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a0, qb[ks], s[0], 0, 0, 0);
+      s[1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a1, qb[ks], s[1], 0, 0, 0);
+    }
+    // ---- logits (log2 domain, log2(votes) folded in), group-mean logit for the EMA
+    float z[2][4], xm[2][4];
+    float tm = -INFINITY;
+#pragma unroll
+    for (int st = 0; st < 2; ++st)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const bool live = (16 * st + 4 * q + i) < n_live;
+        z[st][i] = live ? fmaf(s[st][i], sl2, fast_log2((float)pv[st][i])) : -INFINITY;
+        tm = fmaxf(tm, z[st][i]);
+        xm[st][i] = head_sum<G>(s[st][i]) * (p.scale * (1.0f / G));
+      }
+    tm = fmaxf(tm, __shfl_xor(tm, 16));
+    tm = fmaxf(tm, __shfl_xor(tm, 32));
+    const float mn = fmaxf(m_run, tm);
+    const float c = (m_run == -INFINITY) ? 0.f : fast_exp2(m_run - mn);
+    float pr[2][4], ps = 0.f;
+#pragma unroll
+    for (int st = 0; st < 2; ++st)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        pr[st][i] = (mn == -INFINITY) ? 0.f : fast_exp2(z[st][i] - mn);
+        ps += pr[st][i];
+      }
+    l_run = fmaf(l_run, c, ps);
+    m_run = mn;
+    if (!first) {                                // uniform: rescale the accumulators, row r = head r mod G
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const float ci = __shfl(c, (lane & 48) | ((4 * q + i) % G));
+#pragma unroll
+        for (int nt = 0; nt < NTILE; ++nt) O[nt][i] *= ci;
+      }
+    }
+    first = false;
+    // ---- EMA update (Eq. 8) and optional logit output: lane (l16 < 8, q) owns slot 16 (l16 / 4) + 4 q + l16 % 4
+    {
+      float x = xm[0][0];
+#pragma unroll
+      for (int st = 0; st < 2; ++st)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) x = (l16 == 4 * st + i) ? xm[st][i] : x;
+      const int row_mine = 16 * (l16 >> 2) + 4 * q + (l16 & 3);
+      const bool mine = l16 < 8 && row_mine < n_live;
+      const size_t at = ubase + (extra ? len_old : tbase + row_mine);
+      if (p.logits_out != nullptr && mine) p.logits_out[at] = x;
+      if constexpr (STEP) {
+        const float a = p.ln_alpha + ls_old, b = p.ln_1m_alpha + x;
+        const float hi = fmaxf(a, b), lo = fminf(a, b);
+        const float r = (lo == -INFINITY) ? hi : hi + log1pf(expf(lo - hi));
+        if (mine) {
+          p.log_s[at] = r;
+          p.n_obs[at] = no_old + 1;
+        }
+      }
+    }
+    // ---- O += P V with P = hi + lo in bf16
+    uint4 ah, al;
+    {
+      float lo_[2][4];
+#pragma unroll
+      for (int st = 0; st < 2; ++st)
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+          lo_[st][i] = pr[st][i] - __builtin_bit_cast(float, __builtin_bit_cast(uint32_t, pr[st][i]) & 0xFFFF0000u);
+      ah = make_uint4(pack_hi16(pr[0][0], pr[0][1]), pack_hi16(pr[0][2], pr[0][3]), pack_hi16(pr[1][0], pr[1][1]),
+                      pack_hi16(pr[1][2], pr[1][3]));
+      al = make_uint4(pack_hi16(lo_[0][0], lo_[0][1]), pack_hi16(lo_[0][2], lo_[0][3]), pack_hi16(lo_[1][0], lo_[1][1]),
+                      pack_hi16(lo_[1][2], lo_[1][3]));
+    }
+    const bf16x8_t a_hi = __builtin_bit_cast(bf16x8_t, ah), a_lo = __builtin_bit_cast(bf16x8_t, al);
+    // transpose read: lane s of a 16-lane block supplies the address of row s / 4, columns 4 (s mod 4) .. + 3, and
+    // receives column s of the block's four rows
+    const int vrow = 4 * q + (l16 >> 2);
+#pragma unroll
+    for (int nt = 0; nt < NTILE; ++nt) {
+      const int chunk = 2 * nt + ((l16 & 3) >> 1);
+      const unsigned char* va = Vb + vrow * ROWB + ((chunk ^ (vrow & (CHUNKS - 1))) * 16) + (l16 & 1) * 8;
+      const v4i16_t b0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) v4i16_t*)va);
+      const v4i16_t b1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) v4i16_t*)(va + 16 * ROWB));
+      const uint4 bw = make_uint4(__builtin_bit_cast(uint2, b0).x, __builtin_bit_cast(uint2, b0).y,
+                                  __builtin_bit_cast(uint2, b1).x, __builtin_bit_cast(uint2, b1).y);
+      const bf16x8_t b = __builtin_bit_cast(bf16x8_t, bw);
+      O[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a_hi, b, O[nt], 0, 0, 0);
+      O[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a_lo, b, O[nt], 0, 0, 0);
+    }
   };
 
-  for (int idx = threadIdx.x; idx < G * D; idx += kWavesPerBlock * kWave) {
-    const int g = idx / D, d = idx % D;
-    float M = s_m[g];
+  while (base < lim) {
+    int pv[2][4];
 #pragma unroll
-    for (int w = 1; w < kParts; ++w) M = fmaxf(M, s_m[w * G + g]);
-    float L = 0.f, A = 0.f;
+    for (int st = 0; st < 2; ++st)
 #pragma unroll
-    for (int w = 0; w < kParts; ++w) {
-      const float mw = s_m[w * G + g];
-      const float c = (mw == -INFINITY) ? 0.f : fast_exp2(mw - M);
-      L = fmaf(s_l[w * G + g], c, L);
-      A = fmaf(s_acc[(w * G + g) * D + d], c, A);
+      for (int i = 0; i < 4; ++i) pv[st][i] = p.votes[ubase + min(base + 16 * st + 4 * q + i, bound - 1)];
+    float ls_old = -INFINITY;
+    int no_old = 0;
+    if constexpr (STEP) {
+      const size_t at = ubase + min(base + 16 * (l16 >> 2) + 4 * q + (l16 & 3), bound - 1);
+      ls_old = p.log_s[at];
+      no_old = p.n_obs[at];
     }
-    const size_t row = (size_t)unit * G + g;   // == b * Hq + h * G + g
-    if (p.nsplit == 1) {
-      finish(row, d, M, L, A);
-    } else {
-      // device-coherent (write-through) stores: the combining workgroup may run on another XCD
-      float* dst = p.partial + (row * p.nsplit + split) * (D + 2);
-      st_agent(dst + 2 + d, A);
-      if (d == 0) {
-        st_agent(dst, M);
-        st_agent(dst + 1, L);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");       // the tile (and the scalars above) have landed
+    compute(base, false, pv, ls_old, no_old);
+    base += kWavesPerBlock * kMTile;
+    if (base < lim) issue_tile(base);                        // the buffers are free again
+  }
+  const bool grow = STEP && len_old < p.capacity;
+  const int len = grow ? len_old + 1 : len_old;
+  if (takes_new) {
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");       // the copy of the new token has landed
+    if (grow) {
+      if (lane < 2 * CHUNKS) {
+        const uint4 x = *reinterpret_cast<const uint4*>(s_new + lane * 16);
+        // row 0 of the tile (its swizzle is the identity) and the cache row of the new slot
+        *reinterpret_cast<uint4*>((lane < CHUNKS ? Kb : Vb) + (lane % CHUNKS) * 16) = x;
+        unsigned char* dst = reinterpret_cast<unsigned char*>(lane < CHUNKS ? p.k : p.v) + (ubase + len_old) * ROWB;
+        *reinterpret_cast<uint4*>(dst + (lane % CHUNKS) * 16) = x;
       }
+      if (lane == 0) p.votes[ubase + len_old] = 1;
+      __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
+      __builtin_amdgcn_wave_barrier();
+      const int one[2][4] = {{1, 1, 1, 1}, {1, 1, 1, 1}};
+      compute(0, true, one, -INFINITY, 0);
     }
   }
 
-  if (p.nsplit == 1) {
-    if (STEP && threadIdx.x == 0 && grow) p.len[unit] = len;   // every wavefront read len before the barrier above
-    if (STEP && threadIdx.x == 0 && !grow && p.overflow != nullptr) *p.overflow = 1;
-    return;
+  // ---- deposit this wavefront's state; the workgroup reduces kParts of them -------------------------
+  float l_tot = l_run + __shfl_xor(l_run, 16);
+  l_tot += __shfl_xor(l_tot, 32);
+  __syncthreads();                               // every wavefront is done with its tile buffers
+  float* s_m = reinterpret_cast<float*>(smem_raw);     // [kParts][G]
+  float* s_l = s_m + kParts * G;                       // [kParts][G]
+  float* s_acc = s_l + kParts * G;                     // [kParts][G][D]
+  if (q == 0 && l16 < G) {
+    s_m[wave * G + l16] = m_run;
+    s_l[wave * G + l16] = l_tot;
   }
-
-  KK_TS(3);
-  // ---- the last workgroup of this head to arrive combines the splits ------------------------------
-  // The partial results were stored write-through at device scope, so it is enough that every
-  // wavefront's stores have completed (workgroup-scope release = wait on the store counter) before
-  // the ticket is taken; a device-scope release fence here would write back the whole L2 per
-  // workgroup.  The combining workgroup reads the partials with device-scope loads.
-  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
-  __syncthreads();
-  if (threadIdx.x == 0)
-    s_last = (__hip_atomic_fetch_add(&p.ticket[unit], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == p.nsplit - 1);
-  __syncthreads();
-  KK_TS(4);
-  if (!s_last) return;
-  for (int idx = threadIdx.x; idx < G * D; idx += kWavesPerBlock * kWave) {
-    const int g = idx / D, d = idx % D;
-    const size_t row = (size_t)unit * G + g;
-    const float* src = p.partial + row * p.nsplit * (D + 2);
-    float M = -INFINITY, L = 0.f, A = 0.f;
-    constexpr int CH = 8;                       // splits fetched per round trip
-    for (int s0 = 0; s0 < p.nsplit; s0 += CH) {
-      float ms[CH], ls[CH], as[CH];
 #pragma unroll
-      for (int i = 0; i < CH; ++i) {
-        const int s = min(s0 + i, p.nsplit - 1);
-        ms[i] = ld_agent(src + s * (D + 2));
-        ls[i] = ld_agent(src + s * (D + 2) + 1);
-        as[i] = ld_agent(src + s * (D + 2) + 2 + d);
-      }
-      float mc = M;
+  for (int i = 0; i < 4; ++i) {
+    const int head = 4 * q + i;                  // output row; rows >= G repeat heads
+    if (head < G) {
 #pragma unroll
-      for (int i = 0; i < CH; ++i) mc = fmaxf(mc, ms[i]);
-      const float c0 = (M == -INFINITY) ? 0.f : fast_exp2(M - mc);
-      L *= c0;
-      A *= c0;
-#pragma unroll
-      for (int i = 0; i < CH; ++i) {
-        const float c = (s0 + i < p.nsplit && ms[i] != -INFINITY) ? fast_exp2(ms[i] - mc) : 0.f;
-        L = fmaf(ls[i], c, L);
-        A = fmaf(as[i], c, A);
-      }
-      M = mc;
+      for (int nt = 0; nt < NTILE; ++nt) s_acc[(wave * G + head) * D + 16 * nt + l16] = O[nt][i];
     }
-    finish(row, d, M, L, A);
   }
-  KK_TS(5);
-  if (threadIdx.x == 0) {
-    __hip_atomic_store(&p.ticket[unit], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // ready for the next launch
-    if (STEP && grow) p.len[unit] = len;
-    if (STEP && !grow && p.overflow != nullptr) *p.overflow = 1;
-  }
+  __syncthreads();
+  combine_and_finish<T, D, G, kParts, STEP>(p, s_m, s_l, s_acc, &s_last, unit, split, grow, len);
 }
 
 template <typename T, int D, int G>
@@ -445,6 +718,15 @@ void launch_decode(const DecodeParams& p, int units, bool step, hipStream_t st) 
   constexpr int LPS = (G >= 8 && RV >= 16) ? RV / (RV >= 32 ? 2 : 1) : (RV >= 32 ? 16 : 8);
   constexpr int U = 4;
   const dim3 grid(units * p.nsplit), block(kWavesPerBlock * kWave);
+  if constexpr (sizeof(T) == 2) {
+    static const bool valu = getenv("KEEPKV_DECODE_VALU") != nullptr;     // tuning aid: the vector-ALU kernel
+    if (!valu) {
+      constexpr size_t tiles = (size_t)kWavesPerBlock * 2 * kMTile * D * 2;
+      if (step) decode_mfma_kernel<D, G, true><<<grid, block, tiles, st>>>(p);
+      else decode_mfma_kernel<D, G, false><<<grid, block, tiles, st>>>(p);
+      return;
+    }
+  }
   constexpr int parts = kWavesPerBlock * (kWave / (LPS < 16 ? 16 : LPS));
   constexpr size_t smem = (size_t)parts * G * (D + 2) * sizeof(float);
   if constexpr (smem > 64 * 1024) {
@@ -516,9 +798,10 @@ DecodePlan plan_decode(const keepkv_layout* L, int capacity) {
   DecodePlan pl;
   const double units = (double)L->batch * L->n_kv_heads;
   const double slot_bytes = 2.0 * L->head_dim * (L->dtype == KEEPKV_BF16 ? 2 : 4) + 24.0;
-  // slots a workgroup consumes per loop iteration (4 wavefronts x 4 slots per lane group; see launch_decode)
+  // slots a workgroup consumes per loop iteration: 4 wavefronts x 32-slot tiles (bf16, matrix-core kernel);
+  // the f32 kernel's lane groups cover 64 or 128 (see launch_decode)
   const int rv = L->head_dim * (L->dtype == KEEPKV_BF16 ? 2 : 4) / 16;
-  const long granule = (rv >= 32 || (L->n_q_heads / L->n_kv_heads >= 8 && rv >= 16)) ? 64 : 128;
+  const long granule = L->dtype == KEEPKV_BF16 ? 128 : (rv >= 32 ? 64 : 128);
   long per = 128;
   double best = 1e300;
   const long max_ns = (capacity + 63) / 64 < 1024 ? (capacity + 63) / 64 : 1024;
