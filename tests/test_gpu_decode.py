@@ -25,6 +25,8 @@ CASES = [
     ("bf16_d64_g2", _case("llama3_8b", batch=1, n_q_heads=8, n_kv_heads=4, head_dim=64, context=333)),
     ("f32_d128_g1", _case("tiny", batch=2, n_q_heads=2, n_kv_heads=2, head_dim=128, context=257)),
     ("bf16_mixture", _case("long_32k", batch=1, context=4100)),
+    ("bf16_g1", _case("llama3_8b", batch=1, n_q_heads=8, n_kv_heads=8, context=555)),
+    ("bf16_d64_g8", _case("llama3_8b", batch=2, n_q_heads=32, n_kv_heads=4, head_dim=64, context=300)),
 ]
 
 
@@ -116,7 +118,8 @@ def test_score_and_append_match_oracle(alpha):
 
 
 @pytest.mark.parametrize("hint", [False, True], ids=["wait_for_len", "len_hint"])
-@pytest.mark.parametrize("name,w", [CASES[0], CASES[1], CASES[2], CASES[3]], ids=[c[0] for c in CASES[:4]])
+@pytest.mark.parametrize("name,w", [CASES[0], CASES[1], CASES[2], CASES[3], CASES[6], CASES[7]],
+                         ids=[CASES[i][0] for i in (0, 1, 2, 3, 6, 7)])
 def test_decode_step_equals_append_attend_score(name, w, hint):
     """The fused single-kernel step against the oracle's append -> attention -> EMA update."""
     kk = U.kk()
