@@ -30,9 +30,9 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0      # MI355X HBM3E
 MFMA_BF16_PEAK_TFLOPS = 2500.0
 # HBM bytes per launch of the fused decode kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled
-# by the copy-probe calibration (profiles/decode_attn_hbm_traffic_llama3_8b.md).  Counters cannot be
+# by the copy-probe calibration (profiles/decode_hbm_traffic_llama3_8b.md).  Counters cannot be
 # read from inside this process, so the figure is the recorded one for the default workload.
-PMC_TRAFFIC_BYTES = {"llama3_8b": int((14756.8 * 2.00 + 1645.7 * 1.00) * 1024)}
+PMC_TRAFFIC_BYTES = {"llama3_8b": int((14762.5 * 2.00 + 1645.5 * 1.00) * 1024)}
 
 
 def parse():
@@ -322,7 +322,7 @@ def main():
     measured = {"read_decode_working_set_GBps": round(ws_bytes / small_us / 1e3, 1),
                 "read_1GiB_GBps": round((1 << 30) / big_us / 1e3, 1),
                 "mfma_bf16_TFLOPs": round(flops_box[-1] / mfma_us / 1e6, 1)}
-    roofline = {"bound": "hbm", "kernel": "decode_attn_kernel", "achieved": round(achieved, 1),
+    roofline = {"bound": "hbm", "kernel": "decode_mfma_kernel" if bf16 else "decode_attn_kernel", "achieved": round(achieved, 1),
                 "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
                 "traffic": (PMC_TRAFFIC_BYTES.get(w.name) if not args.unfused else None), "bytes_per_launch": int(dec_bytes),
                 "avg_launch_us": round(dec_us, 2),
