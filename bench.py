@@ -45,6 +45,8 @@ def parse():
     ap.add_argument("--threshold", type=float, default=None, help="merging threshold T (default: workload's, 0.8)")
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying a HIP graph")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-overlap", action="store_true",
+                    help="compress on the decode stream, all layers in the same round (no staggering, no second stream)")
     ap.add_argument("--unfused", action="store_true",
                     help="use keepkv_append + keepkv_decode_attn + keepkv_score instead of keepkv_decode_step")
     ap.add_argument("--window", type=int, default=None, help="observation passes before the first event")
@@ -182,6 +184,14 @@ def main():
 
     step_no = [0] * R          # decode steps done per layer
     n_events = 0
+    # Compression phases are staggered over the layers (layer L's first period is shorter by L*P/R steps), so
+    # that the events are spread evenly over the steps instead of all layers compressing in the same round;
+    # each event then runs on a second stream next to the decode steps of the other layers.  A layer's next
+    # decode step waits for its own event only.
+    since = [0 if args.no_overlap else (layer * P) // R for layer in range(R)]   # steps since the layer's last event
+    side = torch.cuda.Stream()
+    ws_side = kk.new_workspace(lay, N, Bud)
+    pending = [None] * R
 
     def decode(c, layer, t, since):
         """One decode step of `layer` with input set t; `since` = steps since its last compression."""
@@ -193,24 +203,47 @@ def main():
             c.len_hint = Bud + since          # host-known bound on len before this step's append
             kk.decode_step(lay, c, q_all[layer, t], k_all[layer, t], v_all[layer, t], out, None, alpha, None, ws)
 
+    def compress(c, d, layer, wsp):
+        kk.select(lay, c, Bud, w.n_sink, w.n_recent, alpha, keep, evict_s, n_ev, wsp)
+        kk.match(lay, c, Bud, keep, evict_s, n_ev, T, match_s, None, wsp)
+        kk.merge(lay, c, d, Bud, keep, evict_s, n_ev, match_s, alpha, dropped[layer], wsp)
+
     def one_step(i):
         nonlocal n_events
         layer = i % R
         t = step_no[layer]
         c = caches[layer][cur[layer]]
-        decode(c, layer, t, t % P)
+        main = torch.cuda.current_stream()
+        if pending[layer] is not None:           # the layer's last compression event ran on the side stream
+            main.wait_event(pending[layer])
+            pending[layer] = None
+        decode(c, layer, t % per_layer, since[layer])
         step_no[layer] = t + 1
-        if (t + 1) % P == 0:
+        since[layer] += 1
+        if since[layer] == P:
             d = caches[layer][1 - cur[layer]]
-            kk.select(lay, c, Bud, w.n_sink, w.n_recent, alpha, keep, evict_s, n_ev, ws)
-            kk.match(lay, c, Bud, keep, evict_s, n_ev, T, match_s, None, ws)
-            kk.merge(lay, c, d, Bud, keep, evict_s, n_ev, match_s, alpha, dropped[layer], ws)
+            if args.no_overlap:
+                compress(c, d, layer, ws)
+            else:
+                side.wait_stream(main)
+                with torch.cuda.stream(side):
+                    compress(c, d, layer, ws_side)
+                    pending[layer] = torch.cuda.Event()
+                    pending[layer].record()
             cur[layer] = 1 - cur[layer]
+            since[layer] = 0
             n_events += 1
+
+    def join_side():
+        if not args.no_overlap:
+            torch.cuda.current_stream().wait_stream(side)
+            for layer in range(R):
+                pending[layer] = None
 
     # ------------------------------------------------------------------ warm-up (eager), then the timed K steps
     for i in range(Wm):
         one_step(i)
+    join_side()
     torch.cuda.synchronize()
     n_events = 0
     stream = torch.cuda.Stream()
@@ -221,6 +254,7 @@ def main():
             start.record()
             for i in range(Wm, Wm + K):
                 one_step(i)
+            join_side()
             stop.record()
         torch.cuda.synchronize()
     else:
@@ -228,6 +262,7 @@ def main():
         with torch.cuda.graph(graph, stream=stream):
             for i in range(Wm, Wm + K):
                 one_step(i)
+            join_side()
         torch.cuda.synchronize()
         with torch.cuda.stream(stream):
             start.record()
@@ -245,9 +280,11 @@ def main():
     comp = {"select": [], "match": [], "merge": []}
     for layer in range(R):
         c = caches[layer][cur[layer]]
-        while step_no[layer] % P != 0:
-            decode(c, layer, step_no[layer] % per_layer, step_no[layer] % P)
+        while since[layer] != P:
+            decode(c, layer, step_no[layer] % per_layer, since[layer])
             step_no[layer] += 1
+            since[layer] += 1
+        since[layer] = 0
         d = caches[layer][1 - cur[layer]]
         e = [ev() for _ in range(4)]
         e[0].record()
@@ -379,7 +416,8 @@ def main():
         "vs_baseline": None, "dtype": "bf16" if bf16 else "f32", "data": "synthetic",
         "config": {"workload": f"{w.name}: B={B} Hq={Hq} Hkv={H} D={D} {w.dtype}, context {N} -> budget {Bud} "
                                f"({w.ratio:.0%}), period {P}, T={T:g}, alpha={alpha:g}",
-                   "layers_rotated": R, "graph": not args.no_graph, "fused_step": not args.unfused, "compress_events_timed": timed_events},
+                   "layers_rotated": R, "graph": not args.no_graph, "fused_step": not args.unfused, "compress_events_timed": timed_events,
+                   "compress_overlapped": not args.no_overlap},
         "roofline": roofline,
         "cpu_baseline": cpu,
         "kernels_us": {
