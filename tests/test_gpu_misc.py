@@ -145,3 +145,21 @@ def test_error_statuses_on_device_buffers():
     assert lib.keepkv_decode_attn(C.byref(lay.c()), C.byref(cs), C.c_void_p(q.data_ptr() + 2), P(out), None, None, P(ws),
                                   ws.numel(), None) == kk.ERR_INVALID_ARG
     torch.cuda.synchronize()
+
+
+def test_measurement_probes_run_and_validate_arguments():
+    kk = U.kk()
+    sink = torch.zeros(4, dtype=torch.float32, device="cuda")
+    buf = torch.randint(0, 255, (1 << 20,), dtype=torch.uint8, device="cuda")
+    kk.probe_read(buf, 64, sink)
+    kk.probe_read(buf[: 16 * 1000 + 16], 7, sink)            # ragged share per workgroup
+    flops = kk.probe_mfma(8, 10, sink)
+    torch.cuda.synchronize()
+    assert flops == 8 * 4 * 10 * 4 * 2 * 32 * 32 * 16
+    assert sink.sum().item() == 0.0                          # the sinks are never written in practice
+    for bad in (lambda: kk.probe_read(buf[:24], 4, sink), lambda: kk.probe_read(buf, 0, sink),
+                lambda: kk.probe_read(None, 4, sink), lambda: kk.probe_mfma(0, 10, sink),
+                lambda: kk.probe_mfma(4, 0, sink)):
+        with pytest.raises(kk.KeepKVError) as e:
+            bad()
+        assert e.value.status == kk.ERR_INVALID_ARG
