@@ -226,14 +226,18 @@ __global__ __launch_bounds__(kMWaves* kWave) void match_mfma_kernel(MatchParams 
 
   const int n_stage = (n_keep + kStageCols - 1) / kStageCols;
   // software pipeline: the MFMAs of column block cb are issued together with the fold of block
-  // cb - 1, whose accumulators are carried in (p0, p1).  The first fold sees zeros and is harmless.
-  f32x16_t p0 = {0}, p1 = {0};
-  float prn = 0.f;
-  int pcode = 0;
+  // cb - 1.  Two accumulator sets alternate (even blocks write A and fold B, odd blocks the reverse), so
+  // no accumulator is ever copied.  The first fold sees zeros and is harmless.
+  f32x16_t accA0 = {0}, accA1 = {0}, accB0 = {0}, accB1 = {0};
+  float rnA = 0.f, rnB = 0.f;
+  int codeA = 0, codeB = 0;
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   __syncthreads();
 
   constexpr int VPK = 16 / KS;               // accumulator values folded per k-step and tile
+  constexpr int BPS = kStageCols / 32;       // column blocks per stage (even)
+  static_assert(BPS % 2 == 0, "the accumulator sets alternate by column block");
+  const int n_blk = (n_keep + 31) / 32;
   for (int s = 0; s < n_stage; ++s) {
     if (s + 1 < n_stage) issue_stage(s + 1);
     const unsigned char* src = s_stage + (s & 1) * STAGE_BYTES;
@@ -242,39 +246,49 @@ __global__ __launch_bounds__(kMWaves* kWave) void match_mfma_kernel(MatchParams 
                                                (((ks * 2 + half) ^ (l32 & (CHUNKS - 1))) * 16));
     };
     bf16x8_t bq = frag(0, 0);
+    // Explicit interleave: each MFMA is followed by the fold of VPK values of the previous column
+    // block, and nothing may be scheduled across the fences, so the matrix pipe and the vector ALU of
+    // this wavefront run side by side.
+    auto block = [&](int cbl, f32x16_t& nw0, f32x16_t& nw1, const f32x16_t& od0, const f32x16_t& od1, float orn,
+                     int ocode) {
+      const f32x16_t zero = {0};
 #pragma unroll
-    for (int cbl = 0; cbl < kStageCols / 32; ++cbl) {
-      const int cb = s * (kStageCols / 32) + cbl;           // global column block
-      if (cb * 32 < n_keep) {                                 // uniform over the workgroup
-        f32x16_t n0 = {0}, n1 = {0};
-        // Explicit interleave: each MFMA is followed by the fold of VPK values of the previous
-        // column block, and nothing may be scheduled across the fences, so the matrix pipe and the
-        // vector ALU of this wavefront run side by side.
+      for (int ks = 0; ks < KS; ++ks) {
+        const bf16x8_t bnext = (ks + 1 < KS) ? frag(cbl, ks + 1) : frag((cbl + 1) % BPS, 0);
+        nw0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[0][ks], bq, ks == 0 ? zero : nw0, 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks) {
-          const bf16x8_t bnext = (ks + 1 < KS) ? frag(cbl, ks + 1) : frag((cbl + 1) % (kStageCols / 32), 0);
-          n0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[0][ks], bq, n0, 0, 0, 0);
-          __builtin_amdgcn_sched_barrier(0);
+        for (int i = ks * VPK; i < (ks + 1) * VPK; ++i) fold_one(od0[i], orn, ocode, val_mask, b1[0][i], b2[0][i]);
+        __builtin_amdgcn_sched_barrier(0);
+        nw1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[1][ks], bq, ks == 0 ? zero : nw1, 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-          for (int i = ks * VPK; i < (ks + 1) * VPK; ++i) fold_one(p0[i], prn, pcode, val_mask, b1[0][i], b2[0][i]);
-          __builtin_amdgcn_sched_barrier(0);
-          n1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[1][ks], bq, n1, 0, 0, 0);
-          __builtin_amdgcn_sched_barrier(0);
+        for (int i = ks * VPK; i < (ks + 1) * VPK; ++i) fold_one(od1[i], orn, ocode, val_mask, b1[1][i], b2[1][i]);
+        __builtin_amdgcn_sched_barrier(0);
+        bq = bnext;
+      }
+    };
 #pragma unroll
-          for (int i = ks * VPK; i < (ks + 1) * VPK; ++i) fold_one(p1[i], prn, pcode, val_mask, b1[1][i], b2[1][i]);
-          __builtin_amdgcn_sched_barrier(0);
-          bq = bnext;
+    for (int cbl = 0; cbl < BPS; ++cbl) {
+      const int cb = s * BPS + cbl;                           // global column block
+      if (cb < n_blk) {                                       // uniform over the workgroup
+        const float rn_new = s_rn[(s & 1) * kStageCols + cbl * 32 + l32];
+        if (cbl % 2 == 0) {
+          block(cbl, accA0, accA1, accB0, accB1, rnB, codeB);
+          rnA = rn_new;
+          codeA = code_mask - cb;                             // lower column block -> larger code
+        } else {
+          block(cbl, accB0, accB1, accA0, accA1, rnA, codeA);
+          rnB = rn_new;
+          codeB = code_mask - cb;
         }
-        p0 = n0;
-        p1 = n1;
-        prn = s_rn[(s & 1) * kStageCols + cbl * 32 + l32];
-        pcode = code_mask - cb;                               // lower column block -> larger code
       }
     }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
   }
-  fold_tile(p0, p1, prn, pcode, val_mask, b1, b2);
+  if (n_blk & 1) fold_tile(accA0, accA1, rnA, codeA, val_mask, b1, b2);   // the last block was an even one
+  else fold_tile(accB0, accB1, rnB, codeB, val_mask, b1, b2);
 
   // ---- transpose the per-lane pairs through LDS: [wave][row 0..63][33] x {best, second} ---------------
   int* s_b1 = reinterpret_cast<int*>(s_stage) + wave * (kRowsPerWave * 33 * 2);
