@@ -87,6 +87,7 @@ __device__ __forceinline__ int imed3(int a, int b, int c) { return imax(imin(a, 
 __device__ __forceinline__ void reduce_pairs(const int* s_b1, const int* s_b2, int row, int val_mask, int code_mask,
                                              int& v1, int& c1, int& v2) {
   v1 = (int)0x80000000; v2 = (int)0x80000000; c1 = 0;
+#pragma unroll 8
   for (int q = 0; q < 32; ++q) {
     const int k1 = s_b1[row * 33 + q], k2 = s_b2[row * 33 + q];
     const int val = k1 & val_mask;
