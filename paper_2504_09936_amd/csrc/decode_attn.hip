@@ -726,6 +726,12 @@ void launch_decode(const DecodeParams& p, int units, bool step, hipStream_t st) 
     static const bool valu = getenv("KEEPKV_DECODE_VALU") != nullptr;     // tuning aid: the vector-ALU kernel
     if (!valu) {
       constexpr size_t tiles = (size_t)kWavesPerBlock * 2 * kMTile * D * 2;
+      // 64 KB of tile buffers at D = 128, plus the kernel's static LDS: allow it explicitly
+      static const hipError_t a1 = hipFuncSetAttribute((const void*)decode_mfma_kernel<D, G, true>,
+                                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)tiles);
+      static const hipError_t a2 = hipFuncSetAttribute((const void*)decode_mfma_kernel<D, G, false>,
+                                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)tiles);
+      (void)a1; (void)a2;                      // a refusal shows up as a launch error below
       if (step) decode_mfma_kernel<D, G, true><<<grid, block, tiles, st>>>(p);
       else decode_mfma_kernel<D, G, false><<<grid, block, tiles, st>>>(p);
       return;
