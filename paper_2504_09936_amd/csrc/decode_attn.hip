@@ -512,20 +512,21 @@ __global__ __launch_bounds__(kWavesPerBlock* kWave, 2) void decode_mfma_kernel(D
   unsigned char* Vb = Kb + TILE_BYTES;
 
   // chunk c of row r of a tile sits at position c ^ (r mod CHUNKS); rows at or beyond `bound` are never read
-  auto issue_tile = [&](int base) {
+  auto issue_rows = [&](const unsigned char* rows, unsigned char* buf, int tbase) {
 #pragma unroll
     for (int i = 0; i < LOADS; ++i) {
       const int c = lane + i * kWave;
       const int row = c / CHUNKS, phys = c % CHUNKS;
-      const size_t off = (size_t)min(base + row, bound - 1) * ROWB + ((phys ^ (row & (CHUNKS - 1))) * 16);
-      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(kbytes + off),
-                                       (__attribute__((address_space(3))) void*)(Kb + i * (kWave * 16)), 16, 0, 0);
-      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(vbytes + off),
-                                       (__attribute__((address_space(3))) void*)(Vb + i * (kWave * 16)), 16, 0, 0);
+      const size_t off = (size_t)min(tbase + row, bound - 1) * ROWB + ((phys ^ (row & (CHUNKS - 1))) * 16);
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(rows + off),
+                                       (__attribute__((address_space(3))) void*)(buf + i * (kWave * 16)), 16, 0, 0);
     }
   };
   int base = start + wave * kMTile;
-  if (base < lim) issue_tile(base);
+  if (base < lim) {
+    issue_rows(kbytes, Kb, base);
+    issue_rows(vbytes, Vb, base);
+  }
 
   // B operand of the score product: column l16 is head l16 mod G, this lane's 8 channels of every k-step
   bf16x8_t qb[KS];
@@ -544,7 +545,9 @@ __global__ __launch_bounds__(kWavesPerBlock* kWave, 2) void decode_mfma_kernel(D
   const int live_end = min(len_old, start + p.per);
 
   // One tile.  `extra`: the appended token alone (row 0 of the tile, copied from s_new).
-  auto compute = [&](int tbase, bool extra, const int (&pv)[2][4], float ls_old, int no_old) {
+  // `next`: the wavefront's next tile (or -1); its K rows are requested as soon as the score product has
+  // consumed the K buffer, its V rows after the second product, so both travel during the arithmetic.
+  auto compute = [&](int tbase, bool extra, int next, const int (&pv)[2][4], float ls_old, int no_old) {
     const int n_live = extra ? 1 : max(0, min(kMTile, live_end - tbase));
     if (n_live < kMTile) {                       // uniform: clear the V rows of masked slots (0 * garbage could be NaN)
       for (int c = n_live * CHUNKS + lane; c < kMTile * CHUNKS; c += kWave)
@@ -562,6 +565,7 @@ __global__ __launch_bounds__(kWavesPerBlock* kWave, 2) void decode_mfma_kernel(D
       s[0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a0, qb[ks], s[0], 0, 0, 0);
       s[1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a1, qb[ks], s[1], 0, 0, 0);
     }
+    if (next >= 0) issue_rows(kbytes, Kb, next);
     // ---- logits (log2 domain, log2(votes) folded in), group-mean logit for the EMA
     float z[2][4], xm[2][4];
     float tm = -INFINITY;
@@ -649,6 +653,7 @@ __global__ __launch_bounds__(kWavesPerBlock* kWave, 2) void decode_mfma_kernel(D
       O[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a_hi, b, O[nt], 0, 0, 0);
       O[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a_lo, b, O[nt], 0, 0, 0);
     }
+    if (next >= 0) issue_rows(vbytes, Vb, next);
   };
 
   while (base < lim) {
@@ -665,9 +670,9 @@ __global__ __launch_bounds__(kWavesPerBlock* kWave, 2) void decode_mfma_kernel(D
       no_old = p.n_obs[at];
     }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");       // the tile (and the scalars above) have landed
-    compute(base, false, pv, ls_old, no_old);
-    base += kWavesPerBlock * kMTile;
-    if (base < lim) issue_tile(base);                        // the buffers are free again
+    const int next = base + kWavesPerBlock * kMTile;
+    compute(base, false, next < lim ? next : -1, pv, ls_old, no_old);
+    base = next;
   }
   KK_TS(1);
   const bool grow = STEP && len_old < p.capacity;
@@ -686,7 +691,7 @@ __global__ __launch_bounds__(kWavesPerBlock* kWave, 2) void decode_mfma_kernel(D
       __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
       __builtin_amdgcn_wave_barrier();
       const int one[2][4] = {{1, 1, 1, 1}, {1, 1, 1, 1}};
-      compute(0, true, one, -INFINITY, 0);
+      compute(0, true, -1, one, -INFINITY, 0);
     }
   }
 
