@@ -44,7 +44,8 @@ def test_select_brute_force_with_ties(seed):
     votes = g.integers(1, 4, size=length)
     log_S = np.round(g.standard_normal(length) * 2, 1)           # coarse values -> many exact ties
     n_obs[10:30], votes[10:30] = 3, 1
-    keep, evict = O.select(log_S, n_obs, votes, length, budget, n_sink, n_recent, alpha)
+    log_S[10:30:2] = log_S.max() + 1.0                           # ten exactly tied top candidates, seven places left:
+    keep, evict = O.select(log_S, n_obs, votes, length, budget, n_sink, n_recent, alpha)   # the boundary cuts the tie
     key = [math.log(votes[i]) + log_S[i] - math.log(1 - alpha ** n_obs[i]) for i in range(length)]
     bk, be = _brute_select(key, length, budget, n_sink, n_recent)
     assert keep.tolist() == bk and evict.tolist() == be
