@@ -59,7 +59,7 @@ def main():
     args = parse()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on one GPU only (every (batch, kv head) cache is independent; "
-              "see DESIGN.md for how the path would shard). Run with --gpus 1.", file=sys.stderr)
+              "kv heads or batch would shard across GPUs with no exchange). Run with --gpus 1.", file=sys.stderr)
         sys.exit(2)
 
     import torch
