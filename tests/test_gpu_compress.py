@@ -207,3 +207,32 @@ def test_select_by_key_matches_oracle_and_feeds_match_and_merge(context, budget_
             n = int(lens[b, h])
             assert od.len[b, h] == min(n, w.budget)
             assert od.votes[b, h, :od.len[b, h]].sum() + int(dropped[b, h]) == oc.votes[b, h, :n].sum()
+
+
+def test_maximum_sizes_and_limits():
+    """The largest sizes match / merge accept: 4096 retained slots and 32768 evictable slots in one head."""
+    kk = U.kk()
+    N, Bud = 4096 + 32768, 4096
+    w = W.CONFIGS["llama3_8b"].scaled(batch=1, n_q_heads=1, n_kv_heads=1, head_dim=64, context=N,
+                                      ratio=(Bud - 0.5) / N, period=16)
+    assert w.budget == Bud and w.context - w.budget == 32768
+    alpha = U.f32(w.alpha)
+    lay, c, ws = _observed_cache(w, 7, 2, alpha)
+    n = _run_compress_stagewise(w, lay, c, ws, alpha, U.f32(0.3))
+    assert n > 100                                             # plenty of merges at this threshold
+    # one past either limit is refused before anything is launched
+    keep = torch.zeros(1, 1, Bud + 1, dtype=torch.int32, device="cuda")
+    evict = torch.zeros(1, 1, 40000, dtype=torch.int32, device="cuda")
+    n_ev = torch.zeros(1, 1, dtype=torch.int32, device="cuda")
+    m = torch.zeros_like(evict)
+    lay2, big = U.new_cache(w, capacity=Bud + 1 + 32768)
+    ws2 = U.workspace(lay2, big.capacity, Bud + 1)
+    with pytest.raises(kk.KeepKVError) as e:
+        kk.match(lay2, big, Bud + 1, keep, evict, n_ev, 0.5, m, None, ws2)
+    assert e.value.status == kk.ERR_UNSUPPORTED
+    lay3, big3 = U.new_cache(w, capacity=Bud + 32769)
+    _, dst = U.new_cache(w, capacity=Bud + 16)
+    ws3 = U.workspace(lay3, big3.capacity, Bud)
+    with pytest.raises(kk.KeepKVError) as e:
+        kk.merge(lay3, big3, dst, Bud, keep, evict, n_ev, m, alpha, None, ws3)
+    assert e.value.status == kk.ERR_UNSUPPORTED
