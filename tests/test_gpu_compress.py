@@ -106,8 +106,10 @@ def _run_compress_stagewise(w, lay, c, ws, alpha, threshold, check_merge=True):
             assert ev.max(initial=0) <= TOL, ("v", b, h, ev.max())
             assert ek[well].max(initial=0) <= TOL, ("k", b, h, ek[well].max())
             worst = max(worst, ek[well].max(initial=0), ev.max(initial=0))
-            merged = np.flatnonzero(~np.isnan(res.ell_bar))
-            untouched = np.setdiff1d(np.arange(nk), merged)
+            tg = match_h[b, h, :len(re)]
+            has_members = np.zeros(nk, dtype=bool)
+            has_members[tg[tg >= 0]] = True
+            untouched = np.flatnonzero(~has_members)
             # slots that absorbed nothing are bit-exact copies
             np.testing.assert_array_equal(dk[b, h, untouched], oc.k[b, h, rk[untouched]].astype(np.float32))
     return n_matched
@@ -236,3 +238,27 @@ def test_maximum_sizes_and_limits():
     with pytest.raises(kk.KeepKVError) as e:
         kk.merge(lay3, big3, dst, Bud, keep, evict, n_ev, m, alpha, None, ws3)
     assert e.value.status == kk.ERR_UNSUPPORTED
+
+
+@pytest.mark.parametrize("alpha", [0.9, 0.0])
+def test_degenerate_inputs(alpha):
+    """Zero-norm keys (match nothing, are matched by nothing), never-observed slots (weight 0; groups with no
+    observed member), log-scores at zero (the key-scale guard of the merge), identical keys (Lemma 4)."""
+    w = W.CONFIGS["llama3_8b"].scaled(batch=1, context=700, ratio=0.2)
+    alpha = U.f32(alpha)
+    lay, c, ws = _observed_cache(w, 11, 2, alpha if alpha > 0 else U.f32(0.5))
+    g = np.random.default_rng(3)
+    N = w.context
+    zero = g.choice(N, 60, replace=False)
+    c.k[:, :, zero] = 0                                        # zero-norm keys on retained and evicted slots
+    unobs = g.choice(N, 120, replace=False)
+    c.log_s[:, :, unobs] = float("-inf")
+    c.n_obs[:, :, unobs] = 0
+    c.log_s[0, 0] = torch.from_numpy((g.standard_normal(N) * 1e-3).astype(np.float32)).cuda()   # ln s_hat ~ 0: guarded
+    c.n_obs[0, 0] = 50
+    c.log_s[0, 1, :] = float("-inf")                           # a head in which nothing was ever observed
+    c.n_obs[0, 1, :] = 0
+    c.k[0, 2, 100:400] = c.k[0, 2, 100:101]                    # a run of identical keys
+    c.votes[0, 3] = torch.from_numpy(g.integers(1, 1000, N).astype(np.int32)).cuda()
+    _run_compress_stagewise(w, lay, c, ws, alpha, U.f32(-2.0))
+    _run_compress_stagewise(w, lay, c, ws, alpha, U.f32(0.8))
