@@ -180,3 +180,34 @@ def test_decode_step_equals_append_attend_score(name, w, hint):
         oc.log_S[:] = c.log_s.cpu().numpy()    # continue from the GPU's f32 state
     assert overflow.item() == 1                # the head that started at N + 6 ran out of room
     assert c.len.cpu().numpy().flat[0] == cap
+
+
+@pytest.mark.parametrize("name,w", [CASES[1], CASES[2], CASES[0]], ids=[CASES[i][0] for i in (1, 2, 0)])
+def test_decode_extreme_values(name, w):
+    """Logits of magnitude ~1e2..1e3 (no overflow: the running maximum carries them), votes up to a million,
+    one slot dominating a head, a head whose slots all tie."""
+    kk = U.kk()
+    K, V = W.make_cache(w, 4)
+    g = np.random.default_rng(9)
+    B, H, N, G = w.batch, w.n_kv_heads, w.context, w.group
+    votes = g.integers(1, 1_000_000, size=(B, H, N)).astype(np.int32)
+    votes[0, 0] = 1
+    K[0, 0] = K[0, 0, :1]                                   # identical keys: every slot ties
+    q = W.round_storage(W.make_query(w, 4, 0) * 40.0, w.dtype)
+    lay, c = U.new_cache(w, capacity=N, K=K, V=V, votes=votes)
+    qd = U.to_device(q, w.dtype)
+    out = torch.zeros_like(qd)
+    logits = torch.zeros(B, H, N, dtype=torch.float32, device="cuda")
+    lse = torch.zeros(B, w.n_q_heads, dtype=torch.float32, device="cuda")
+    ws = U.workspace(lay, N, max(1, N // 10))
+    kk.decode_attn(lay, c, qd, out, logits, lse, ws)
+    torch.cuda.synchronize()
+    oc = U.download(c)
+    o_ref, lse_ref, lg_ref = O.attend(oc, q.astype(np.float64), w.scale)
+    assert np.abs(lg_ref).max() > 100.0
+    got = U.to_host(out)
+    assert np.isfinite(got).all()
+    err = U.rel_err_rows(got, W.round_storage(o_ref, w.dtype))
+    assert err.max() <= TOL, (name, err.max())
+    np.testing.assert_allclose(logits.cpu().numpy(), lg_ref, rtol=2e-3, atol=2e-3)
+    np.testing.assert_allclose(lse.cpu().numpy(), lse_ref, rtol=1e-4, atol=2e-3)
