@@ -209,32 +209,34 @@ __global__ __launch_bounds__(256) void merge_apply_kernel(MergeParams p) {
     p.dlen[unit] = n < p.budget ? n : p.budget;
   }
   if (r >= p.budget) return;
+  // two dependent round trips per row: (slot number, member range), then (rows, scalars)
   const int c = p.keep_idx[(size_t)unit * p.budget + r];
+  const int m0 = p.start[(size_t)unit * (p.budget + 1) + r], m1 = p.start[(size_t)unit * (p.budget + 1) + r + 1];
   if (c < 0) return;
   const size_t sbase = (size_t)unit * p.scap, dbase = (size_t)unit * p.dcap;
   const uint4* sk = reinterpret_cast<const uint4*>(p.sk);
   const uint4* sv = reinterpret_cast<const uint4*>(p.sv);
   uint4* dk = reinterpret_cast<uint4*>(p.dk);
   uint4* dv = reinterpret_cast<uint4*>(p.dv);
-  const int m0 = p.start[(size_t)unit * (p.budget + 1) + r], m1 = p.start[(size_t)unit * (p.budget + 1) + r + 1];
   const int nm = m1 - m0;                        // evicted members of this group
   const uint4 kc = sk[(sbase + c) * LPS + sub], vc = sv[(sbase + c) * LPS + sub];
+  const int p_c = p.svotes[sbase + c];
+  const float ls_c = p.slog_s[sbase + c];
+  const int n_c = p.sn_obs[sbase + c];
 
   if (nm == 0) {                                  // nothing merged here: copy
     dk[(dbase + r) * LPS + sub] = kc;
     dv[(dbase + r) * LPS + sub] = vc;
     if (sub == 0) {
-      p.dvotes[dbase + r] = p.svotes[sbase + c];
-      p.dlog_s[dbase + r] = p.slog_s[sbase + c];
-      p.dn_obs[dbase + r] = p.sn_obs[sbase + c];
+      p.dvotes[dbase + r] = p_c;
+      p.dlog_s[dbase + r] = ls_c;
+      p.dn_obs[dbase + r] = n_c;
     }
     return;
   }
 
   const int32_t* mem = p.members + sbase + m0;
-  const int n_c = p.sn_obs[sbase + c];
-  const int p_c = p.svotes[sbase + c];
-  const double E_c = log_s_hat(p.slog_s[sbase + c], n_c, p.ln_alpha);
+  const double E_c = log_s_hat(ls_c, n_c, p.ln_alpha);
 
   // pass 1 over the scalars: largest ln s_hat and total votes of the group
   double mx = E_c;
