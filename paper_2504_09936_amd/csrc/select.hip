@@ -44,7 +44,9 @@ __device__ __forceinline__ int block_excl_scan(int v, int* s_wave, int& total) {
 
 // EXT: the ranking value is read from a caller-supplied array (passed as log_s; n_obs and votes
 // unused) instead of being formed from the cache's votes and EMA scores.
-template <bool EXT>
+// LDSKEYS: the sortable keys of the head live in LDS (capacity * 8 bytes fit) instead of the workspace, so
+// the radix passes and the compaction never leave the CU.
+template <bool EXT, bool LDSKEYS>
 __global__ __launch_bounds__(kSelThreads) void select_kernel(
     const float* __restrict__ log_s, const int32_t* __restrict__ n_obs, const int32_t* __restrict__ votes,
     const int32_t* __restrict__ len, uint64_t* __restrict__ keys, int32_t* __restrict__ keep_idx,
@@ -53,6 +55,7 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(
   __shared__ int s_hist[256];
   __shared__ int s_wave[kSelThreads / 64];
   __shared__ int s_digit, s_need, s_bucket;
+  extern __shared__ __align__(16) uint64_t s_keys[];
 
   const int unit = blockIdx.x;
   const int tid = threadIdx.x;
@@ -67,7 +70,11 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(
   }
 
   const size_t base = (size_t)unit * capacity;
-  uint64_t* key = keys + base;
+  uint64_t* key_g = keys + base;
+  auto key = [&](int i) -> uint64_t& {
+    if constexpr (LDSKEYS) return s_keys[i];
+    else return key_g[i];
+  };
   const int lo = n_sink, hi = n - n_recent;   // candidates are [lo, hi)
   const int n_heavy = budget - n_sink - n_recent;
 
@@ -94,7 +101,7 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(
           x = log((double)pv[u]) + (double)ls[u];
           if (ln_alpha > -INFINITY) x -= log(-expm1((double)nn[u] * ln_alpha));
         }
-        key[i] = sortable_u64(x);
+        key(i) = sortable_u64(x);
       }
     }
   }
@@ -111,7 +118,7 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(
       for (int i0 = lo + tid; i0 < hi; i0 += 4 * kSelThreads) {   // four keys per round trip
         uint64_t k4[4];
 #pragma unroll
-        for (int u = 0; u < 4; ++u) k4[u] = key[min(i0 + u * kSelThreads, hi - 1)];
+        for (int u = 0; u < 4; ++u) k4[u] = key(min(i0 + u * kSelThreads, hi - 1));
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
           const uint64_t k = k4[u];
@@ -171,13 +178,13 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(
   const int i0 = min(n, tid * ipt), i1 = min(n, i0 + ipt);
   int eq = 0;
   if (n_heavy > 0)
-    for (int i = max(i0, lo); i < min(i1, hi); ++i) eq += (key[i] == tau);
+    for (int i = max(i0, lo); i < min(i1, hi); ++i) eq += (key(i) == tau);
   int total;
   const int eq_start = block_excl_scan(eq, s_wave, total);   // equal keys at lower indices
   auto kept = [&](int i, int& er) -> bool {
     if (i < lo || i >= hi) return true;
     if (n_heavy <= 0) return false;
-    const uint64_t k = key[i];
+    const uint64_t k = key(i);
     if (k > tau) return true;
     if (k == tau) return er++ < need_eq;
     return false;
@@ -194,6 +201,24 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(
 }
 
 }  // namespace
+
+constexpr int kSelLdsKeys = 16384;     // up to this capacity the keys of a head are kept in LDS (128 KB)
+
+template <bool EXT>
+void launch_select(int units, hipStream_t st, const float* log_s, const int32_t* n_obs, const int32_t* votes,
+                   const int32_t* len, uint64_t* keys, int32_t* keep_idx, int32_t* evict_idx, int32_t* n_evict,
+                   int capacity, int budget, int n_sink, int n_recent, double ln_alpha) {
+  if (capacity <= kSelLdsKeys) {
+    static const hipError_t attr = hipFuncSetAttribute((const void*)select_kernel<EXT, true>,
+                                                       hipFuncAttributeMaxDynamicSharedMemorySize, kSelLdsKeys * 8);
+    (void)attr;                              // a refusal shows up as a launch error
+    select_kernel<EXT, true><<<units, kSelThreads, (size_t)capacity * 8, st>>>(
+        log_s, n_obs, votes, len, keys, keep_idx, evict_idx, n_evict, capacity, budget, n_sink, n_recent, ln_alpha);
+  } else {
+    select_kernel<EXT, false><<<units, kSelThreads, 0, st>>>(
+        log_s, n_obs, votes, len, keys, keep_idx, evict_idx, n_evict, capacity, budget, n_sink, n_recent, ln_alpha);
+  }
+}
 
 SelectPlan plan_select(const keepkv_layout* L, int capacity) {
   SelectPlan pl;
@@ -218,7 +243,7 @@ extern "C" keepkv_status keepkv_select(const keepkv_layout* layout, const keepkv
   if (!workspace || workspace_bytes < pl.bytes || !aligned16(workspace)) return KEEPKV_ERR_WORKSPACE;
   const int units = layout->batch * layout->n_kv_heads;
   const double la = alpha > 0.f ? log((double)alpha) : -INFINITY;
-  select_kernel<false><<<units, kSelThreads, 0, reinterpret_cast<hipStream_t>(stream)>>>(
+  launch_select<false>(units, reinterpret_cast<hipStream_t>(stream),
       cache->log_s, cache->n_obs, cache->votes, cache->len,
       reinterpret_cast<uint64_t*>(reinterpret_cast<char*>(workspace) + pl.keys_off), keep_idx, evict_idx, n_evict,
       cache->capacity, budget, n_sink, n_recent, la);
@@ -238,7 +263,7 @@ extern "C" keepkv_status keepkv_select_by_key(const keepkv_layout* layout, const
   const SelectPlan pl = plan_select(layout, cache->capacity);
   if (!workspace || workspace_bytes < pl.bytes || !aligned16(workspace)) return KEEPKV_ERR_WORKSPACE;
   const int units = layout->batch * layout->n_kv_heads;
-  select_kernel<true><<<units, kSelThreads, 0, reinterpret_cast<hipStream_t>(stream)>>>(
+  launch_select<true>(units, reinterpret_cast<hipStream_t>(stream),
       rank, nullptr, nullptr, cache->len,
       reinterpret_cast<uint64_t*>(reinterpret_cast<char*>(workspace) + pl.keys_off), keep_idx, evict_idx, n_evict,
       cache->capacity, budget, n_sink, n_recent, 0.0);
