@@ -36,7 +36,7 @@ extern "C" {
 typedef enum {
   KEEPKV_OK = 0,
   KEEPKV_ERR_INVALID_ARG = 1,  /* null pointer, bad shape, bad parameter            */
-  KEEPKV_ERR_UNSUPPORTED = 2,  /* head_dim / group size / budget outside the built set */
+  KEEPKV_ERR_UNSUPPORTED = 2,  /* head_dim / group size / budget / batch * heads outside the built set */
   KEEPKV_ERR_WORKSPACE = 3,    /* workspace missing or smaller than required         */
   KEEPKV_ERR_DEVICE = 4        /* HIP reported a launch error                        */
 } keepkv_status;
@@ -45,7 +45,7 @@ typedef enum { KEEPKV_F32 = 0, KEEPKV_BF16 = 1 } keepkv_dtype;
 
 /* Shape of one layer's attention; plain value struct, caller-owned (HOST memory). */
 typedef struct {
-  int32_t batch;        /* B  >= 1                                                    */
+  int32_t batch;        /* B  >= 1; B * Hkv <= 16384                                   */
   int32_t n_q_heads;    /* Hq, multiple of n_kv_heads; group G = Hq/Hkv in {1,2,4,8}    */
   int32_t n_kv_heads;   /* Hkv >= 1                                                   */
   int32_t head_dim;     /* D in {64, 128}                                             */

@@ -87,6 +87,8 @@ inline keepkv_status launch_status() {
 // all calls start behind the head.
 constexpr int kMaxUnits = 16384;                         // batch * n_kv_heads
 constexpr size_t kWorkspaceHead = kMaxUnits * sizeof(int32_t);
+// grids put (batch, kv head) on one axis and the workspace head holds one control word per pair
+inline bool units_supported(const keepkv_layout* L) { return (int64_t)L->batch * L->n_kv_heads <= kMaxUnits; }
 
 struct DecodePlan {
   int nsplit;         // workgroups per (batch, kv head)

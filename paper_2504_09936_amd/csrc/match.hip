@@ -598,6 +598,7 @@ extern "C" keepkv_status keepkv_match(const keepkv_layout* layout, const keepkv_
                                       size_t workspace_bytes, void* stream) {
   using namespace kk;
   if (!layout_ok(layout) || !cache_ok(cache) || !keep_idx || !n_evict) return KEEPKV_ERR_INVALID_ARG;
+  if (!units_supported(layout)) return KEEPKV_ERR_UNSUPPORTED;
   if (budget < 1 || budget > cache->capacity) return KEEPKV_ERR_INVALID_ARG;
   const int max_evict = cache->capacity - budget;
   if (max_evict == 0) return KEEPKV_OK;   // nothing can be evicted

@@ -354,6 +354,7 @@ extern "C" keepkv_status keepkv_merge(const keepkv_layout* layout, const keepkv_
                                       int64_t* dropped_votes, void* workspace, size_t workspace_bytes, void* stream) {
   using namespace kk;
   if (!layout_ok(layout) || !cache_ok(src) || !cache_ok(dst) || !keep_idx || !n_evict) return KEEPKV_ERR_INVALID_ARG;
+  if (!units_supported(layout)) return KEEPKV_ERR_UNSUPPORTED;
   if (budget < 1 || budget > src->capacity || dst->capacity < budget) return KEEPKV_ERR_INVALID_ARG;
   const int max_evict = src->capacity - budget;
   if (max_evict > 0 && (!evict_idx || !match)) return KEEPKV_ERR_INVALID_ARG;

@@ -55,6 +55,7 @@ extern "C" keepkv_status keepkv_score(const keepkv_layout* layout, keepkv_cache*
                                       float alpha, void* stream) {
   using namespace kk;
   if (!layout_ok(layout) || !cache_ok(cache) || !logits) return KEEPKV_ERR_INVALID_ARG;
+  if (!units_supported(layout)) return KEEPKV_ERR_UNSUPPORTED;
   if (!(alpha >= 0.f && alpha < 1.f)) return KEEPKV_ERR_INVALID_ARG;
   const int units = layout->batch * layout->n_kv_heads;
   int bx = (cache->capacity + 255) / 256;
@@ -69,6 +70,7 @@ extern "C" keepkv_status keepkv_append(const keepkv_layout* layout, keepkv_cache
                                        const void* v_t, int32_t* overflow, void* stream) {
   using namespace kk;
   if (!layout_ok(layout) || !cache_ok(cache) || !k_t || !v_t) return KEEPKV_ERR_INVALID_ARG;
+  if (!units_supported(layout)) return KEEPKV_ERR_UNSUPPORTED;
   if (layout->head_dim < 1) return KEEPKV_ERR_INVALID_ARG;
   const int units = layout->batch * layout->n_kv_heads;
   hipStream_t st = reinterpret_cast<hipStream_t>(stream);

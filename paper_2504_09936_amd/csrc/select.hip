@@ -235,6 +235,7 @@ extern "C" keepkv_status keepkv_select(const keepkv_layout* layout, const keepkv
                                        void* stream) {
   using namespace kk;
   if (!layout_ok(layout) || !cache_ok(cache) || !keep_idx || !n_evict) return KEEPKV_ERR_INVALID_ARG;
+  if (!units_supported(layout)) return KEEPKV_ERR_UNSUPPORTED;
   if (budget < 1 || budget > cache->capacity || n_sink < 0 || n_recent < 0 || n_sink + n_recent > budget)
     return KEEPKV_ERR_INVALID_ARG;
   if (budget < cache->capacity && !evict_idx) return KEEPKV_ERR_INVALID_ARG;
@@ -256,6 +257,7 @@ extern "C" keepkv_status keepkv_select_by_key(const keepkv_layout* layout, const
                                               void* workspace, size_t workspace_bytes, void* stream) {
   using namespace kk;
   if (!layout_ok(layout) || !cache || !cache->len || !rank || !keep_idx || !n_evict) return KEEPKV_ERR_INVALID_ARG;
+  if (!units_supported(layout)) return KEEPKV_ERR_UNSUPPORTED;
   if (cache->capacity < 1 || cache->capacity > (1 << 20) || !aligned16(rank)) return KEEPKV_ERR_INVALID_ARG;
   if (budget < 1 || budget > cache->capacity || n_sink < 0 || n_recent < 0 || n_sink + n_recent > budget)
     return KEEPKV_ERR_INVALID_ARG;

@@ -58,3 +58,22 @@ def test_workspace_and_argument_validation_without_device():
                                   None, 0, None) == kk.ERR_WORKSPACE
     assert lib.keepkv_select(C.byref(lay.c()), C.byref(cache), 820, 500, 500, C.c_float(0.9), C.c_void_p(16),
                              C.c_void_p(16), C.c_void_p(16), C.c_void_p(16), 1 << 30, None) == kk.ERR_INVALID_ARG
+
+
+def test_too_many_heads_is_refused_by_every_call():
+    """batch * kv heads above 16384 is outside the built range: refused on the host, nothing launched."""
+    from paper_2504_09936_amd import binding as kk
+    lib = kk._lib
+    lay = kk.Layout(4097, 16, 4, 128, kk.BF16, 0.1)       # 16388 (batch, kv head) pairs
+    cache = kk._Cache(16, 16, 16, 16, 16, 16, 884, 0)     # non-null dummies; never dereferenced on these paths
+    P = C.c_void_p(16)
+    L, K = C.byref(lay.c()), C.byref(cache)
+    assert lib.keepkv_score(L, K, P, C.c_float(0.9), None) == kk.ERR_UNSUPPORTED
+    assert lib.keepkv_append(L, K, P, P, None, None) == kk.ERR_UNSUPPORTED
+    assert lib.keepkv_decode_attn(L, K, P, P, None, None, P, 1 << 40, None) == kk.ERR_UNSUPPORTED
+    assert lib.keepkv_decode_step(L, K, P, P, P, P, None, C.c_float(0.9), None, P, 1 << 40, None) == kk.ERR_UNSUPPORTED
+    assert lib.keepkv_score_window(L, K, P, 4, C.c_float(0.9), -1, None) == kk.ERR_UNSUPPORTED
+    assert lib.keepkv_select(L, K, 820, 4, 652, C.c_float(0.9), P, P, P, P, 1 << 40, None) == kk.ERR_UNSUPPORTED
+    assert lib.keepkv_select_by_key(L, K, P, 820, 4, 652, P, P, P, P, 1 << 40, None) == kk.ERR_UNSUPPORTED
+    assert lib.keepkv_match(L, K, 820, P, P, P, C.c_float(0.8), P, None, P, 1 << 40, None) == kk.ERR_UNSUPPORTED
+    assert lib.keepkv_merge(L, K, K, 820, P, P, P, P, C.c_float(0.9), None, P, 1 << 40, None) == kk.ERR_UNSUPPORTED
