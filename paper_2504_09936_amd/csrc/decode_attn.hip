@@ -10,7 +10,10 @@
 // accumulates p * v for its 16-byte slice of V.  Lane groups and wavefronts are combined through
 // shuffles and LDS; splits are combined by the last workgroup of each head to finish (a ticket
 // counter in the workspace head), so no second kernel is launched.
+#include <math.h>
 #include <stdlib.h>
+
+#include <type_traits>
 
 #include "kk_common.hpp"
 
@@ -131,30 +134,36 @@ __device__ __forceinline__ void combine_and_finish(const DecodeParams& p, const 
     const size_t row = (size_t)unit * G + g;
     const float* src = p.partial + row * p.nsplit * (D + 2);
     float M = -INFINITY, L = 0.f, A = 0.f;
-    constexpr int CH = 8;                       // splits fetched per round trip
-    for (int s0 = 0; s0 < p.nsplit; s0 += CH) {
-      float ms[CH], ls[CH], as[CH];
+    // CH splits are fetched per round trip of device-scope loads: 8 when that covers all of them (the common
+    // case; surplus loads would only cost), 16 otherwise
+    auto fold_chunks = [&](auto ch_tag) {
+      constexpr int CH = decltype(ch_tag)::value;
+      for (int s0 = 0; s0 < p.nsplit; s0 += CH) {
+        float ms[CH], ls[CH], as[CH];
 #pragma unroll
-      for (int i = 0; i < CH; ++i) {
-        const int s = min(s0 + i, p.nsplit - 1);
-        ms[i] = ld_agent(src + s * (D + 2));
-        ls[i] = ld_agent(src + s * (D + 2) + 1);
-        as[i] = ld_agent(src + s * (D + 2) + 2 + d);
+        for (int i = 0; i < CH; ++i) {
+          const int s = min(s0 + i, p.nsplit - 1);
+          ms[i] = ld_agent(src + s * (D + 2));
+          ls[i] = ld_agent(src + s * (D + 2) + 1);
+          as[i] = ld_agent(src + s * (D + 2) + 2 + d);
+        }
+        float mc = M;
+#pragma unroll
+        for (int i = 0; i < CH; ++i) mc = fmaxf(mc, ms[i]);
+        const float c0 = (M == -INFINITY) ? 0.f : fast_exp2(M - mc);
+        L *= c0;
+        A *= c0;
+#pragma unroll
+        for (int i = 0; i < CH; ++i) {
+          const float c = (s0 + i < p.nsplit && ms[i] != -INFINITY) ? fast_exp2(ms[i] - mc) : 0.f;
+          L = fmaf(ls[i], c, L);
+          A = fmaf(as[i], c, A);
+        }
+        M = mc;
       }
-      float mc = M;
-#pragma unroll
-      for (int i = 0; i < CH; ++i) mc = fmaxf(mc, ms[i]);
-      const float c0 = (M == -INFINITY) ? 0.f : fast_exp2(M - mc);
-      L *= c0;
-      A *= c0;
-#pragma unroll
-      for (int i = 0; i < CH; ++i) {
-        const float c = (s0 + i < p.nsplit && ms[i] != -INFINITY) ? fast_exp2(ms[i] - mc) : 0.f;
-        L = fmaf(ls[i], c, L);
-        A = fmaf(as[i], c, A);
-      }
-      M = mc;
-    }
+    };
+    if (p.nsplit <= 8) fold_chunks(std::integral_constant<int, 8>{});
+    else fold_chunks(std::integral_constant<int, 16>{});
     finish(row, d, M, L, A);
   }
   KK_TS(5);
@@ -804,12 +813,13 @@ keepkv_status run_decode(const keepkv_layout* layout, const keepkv_cache* cache,
 }  // namespace
 
 DecodePlan plan_decode(const keepkv_layout* L, int capacity) {
-  // Slots per split (a multiple of 64) from a small cost model fitted to measurements on MI355X
-  // (batch 1..128, 850..32768 slots): about 512 workgroups are resident at once; a workgroup streams at
-  // no more than ~17 GB/s (its rows in flight over the memory latency) and all of them together at
-  // ~5 TB/s; every round of workgroups costs ~3 us of start-up; the last workgroup of a head combines
-  // the splits eight at a time, ~2.3 us per round trip of device-scope loads.  Few long splits starve the chip, many short
-  // ones pay for rounds and for the combine.
+  // Slots per split (a multiple of 64) from a small cost model fitted to measurements on MI355X (batch
+  // 1..128, 850..32768 slots per head).  About 512 workgroups are resident at once and every round of
+  // workgroups costs ~3 us of start-up.  A workgroup streams at no more than ~26 GB/s (its rows in flight
+  // over the memory latency); all resident workgroups together reach ~5.1 TB/s when the chip is full and
+  // ~10 % less at one workgroup per CU.  The last workgroup of a head combines the splits eight or sixteen
+  // at a time, ~2.3 / ~3.4 us per round trip of device-scope loads.  Few long splits starve the chip, many
+  // short ones pay for rounds and for the combine.
   DecodePlan pl;
   const double units = (double)L->batch * L->n_kv_heads;
   const double slot_bytes = 2.0 * L->head_dim * (L->dtype == KEEPKV_BF16 ? 2 : 4) + 24.0;
@@ -826,11 +836,14 @@ DecodePlan plan_decode(const keepkv_layout* L, int capacity) {
     const double wgs = units * n_split;
     const double resident = wgs < 512.0 ? wgs : 512.0;
     const double rounds = (double)(long)((wgs + 511.0) / 512.0);
-    double bw = 5000.0 / resident;                       // GB/s per workgroup
-    if (bw > 17.0) bw = 17.0;
-    const double streamed = (double)((cand + granule - 1) / granule * granule);          // whole iterations
-    const double t_stream = rounds * (3.0 + streamed * slot_bytes / (bw * 1e3));       // us
-    const double t_combine = n_split > 1.0 ? 1.0 + 2.3 * (double)(long)((n_split + 7.0) / 8.0) : 0.0;
+    double together = 5100.0 * pow(resident / 512.0, 0.15);                         // GB/s, all resident workgroups
+    if (together > 26.0 * resident) together = 26.0 * resident;
+    const double streamed = (double)((cand + granule - 1) / granule * granule);       // whole iterations
+    const double t_one = streamed * slot_bytes / 26.0e3;                              // us, a workgroup alone
+    const double t_all = units * capacity * slot_bytes / rounds / (together * 1e3);   // us, one round of them
+    const double t_stream = rounds * (3.0 + (t_one > t_all ? t_one : t_all));
+    const double t_trips = n_split <= 8.0 ? 2.3 : 3.4 * (double)(long)((n_split + 15.0) / 16.0);
+    const double t_combine = n_split > 1.0 ? 1.0 + t_trips + 0.02 * n_split : 0.0;
     if (t_stream + t_combine < best) {
       best = t_stream + t_combine;
       per = cand;
