@@ -488,7 +488,9 @@ __device__ __forceinline__ uint32_t pack_hi16(float lo_elem, float hi_elem) {   
   return (__builtin_bit_cast(uint32_t, lo_elem) >> 16) | (__builtin_bit_cast(uint32_t, hi_elem) & 0xFFFF0000u);
 }
 
-template <int D, int G, bool STEP>
+// ONE: a split is at most one tile per wavefront (128 slots), so there is no tile loop, no prefetch and no
+// rescaling of the accumulators (the common steady-state shape).
+template <int D, int G, bool STEP, bool ONE>
 __global__ __launch_bounds__(kWavesPerBlock* kWave, 2) void decode_mfma_kernel(DecodeParams p) {
   using T = uint16_t;
   constexpr int ROWB = D * 2, CHUNKS = ROWB / 16, KS = D / 32, NTILE = D / 16;
@@ -574,7 +576,7 @@ __global__ __launch_bounds__(kWavesPerBlock* kWave, 2) void decode_mfma_kernel(D
       s[0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a0, qb[ks], s[0], 0, 0, 0);
       s[1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a1, qb[ks], s[1], 0, 0, 0);
     }
-    if (next >= 0) issue_rows(kbytes, Kb, next);
+    if (!ONE && next >= 0) issue_rows(kbytes, Kb, next);
     // ---- logits (log2 domain, log2(votes) folded in), group-mean logit for the EMA
     float z[2][4], xm[2][4];
     float tm = -INFINITY;
@@ -602,6 +604,7 @@ __global__ __launch_bounds__(kWavesPerBlock* kWave, 2) void decode_mfma_kernel(D
     l_run = fmaf(l_run, c, ps);
     m_run = mn;
     if (!first) {                                // uniform: rescale the accumulators, row r = head r mod G
+                                                 // (with ONE only the extra tile of the appended token gets here)
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
         const float ci = __shfl(c, (lane & 48) | ((4 * q + i) % G));
@@ -662,10 +665,10 @@ __global__ __launch_bounds__(kWavesPerBlock* kWave, 2) void decode_mfma_kernel(D
       O[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a_hi, b, O[nt], 0, 0, 0);
       O[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a_lo, b, O[nt], 0, 0, 0);
     }
-    if (next >= 0) issue_rows(vbytes, Vb, next);
+    if (!ONE && next >= 0) issue_rows(vbytes, Vb, next);
   };
 
-  while (base < lim) {
+  while (base < lim) {                           // a single pass with ONE
     int pv[2][4];
 #pragma unroll
     for (int st = 0; st < 2; ++st)
@@ -680,8 +683,8 @@ __global__ __launch_bounds__(kWavesPerBlock* kWave, 2) void decode_mfma_kernel(D
     }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");       // the tile (and the scalars above) have landed
     const int next = base + kWavesPerBlock * kMTile;
-    compute(base, false, next < lim ? next : -1, pv, ls_old, no_old);
-    base = next;
+    compute(base, false, (!ONE && next < lim) ? next : -1, pv, ls_old, no_old);
+    base = ONE ? lim : next;
   }
   KK_TS(1);
   const bool grow = STEP && len_old < p.capacity;
@@ -741,13 +744,21 @@ void launch_decode(const DecodeParams& p, int units, bool step, hipStream_t st) 
     if (!valu) {
       constexpr size_t tiles = (size_t)kWavesPerBlock * 2 * kMTile * D * 2;
       // 64 KB of tile buffers at D = 128, plus the kernel's static LDS: allow it explicitly
-      static const hipError_t a1 = hipFuncSetAttribute((const void*)decode_mfma_kernel<D, G, true>,
-                                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)tiles);
-      static const hipError_t a2 = hipFuncSetAttribute((const void*)decode_mfma_kernel<D, G, false>,
-                                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)tiles);
-      (void)a1; (void)a2;                      // a refusal shows up as a launch error below
-      if (step) decode_mfma_kernel<D, G, true><<<grid, block, tiles, st>>>(p);
-      else decode_mfma_kernel<D, G, false><<<grid, block, tiles, st>>>(p);
+      static const hipError_t attr[4] = {
+          hipFuncSetAttribute((const void*)decode_mfma_kernel<D, G, true, true>,
+                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)tiles),
+          hipFuncSetAttribute((const void*)decode_mfma_kernel<D, G, true, false>,
+                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)tiles),
+          hipFuncSetAttribute((const void*)decode_mfma_kernel<D, G, false, true>,
+                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)tiles),
+          hipFuncSetAttribute((const void*)decode_mfma_kernel<D, G, false, false>,
+                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)tiles)};
+      (void)attr;                              // a refusal shows up as a launch error below
+      const bool one = p.per <= kWavesPerBlock * kMTile;
+      if (step && one) decode_mfma_kernel<D, G, true, true><<<grid, block, tiles, st>>>(p);
+      else if (step) decode_mfma_kernel<D, G, true, false><<<grid, block, tiles, st>>>(p);
+      else if (one) decode_mfma_kernel<D, G, false, true><<<grid, block, tiles, st>>>(p);
+      else decode_mfma_kernel<D, G, false, false><<<grid, block, tiles, st>>>(p);
       return;
     }
   }
