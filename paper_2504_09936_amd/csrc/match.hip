@@ -1,13 +1,12 @@
 // keepkv_match: nearest retained key by cosine similarity for every to-be-evicted key
 // (Alg. 1 lines 4-5), the one dense contraction of the method.
 //
-// bf16 caches: a workgroup of 4 wavefronts owns 256 evicted rows; each wavefront keeps its 64 rows
-// (two 32-row MFMA A operands over the whole head dimension) in registers for the entire kernel and
-// streams the retained keys through LDS in 128-column stages.  Every 32x32 f32 accumulator tile is
-// reduced on the spot: scale by 1/|k_c| of the lane's column, pack the column-block number into the
-// low mantissa bits, and fold into a per-lane running (best, second best) pair with max / med3 on
-// the integer image.  The similarity matrix is never written.  After the last stage the per-lane
-// pairs are transposed through LDS and each row is finished by one lane.
+// bf16 caches, first event (thousands of evicted rows per head): a workgroup of 4 wavefronts owns 256
+// evicted rows; each wavefront keeps its 64 rows (two 32-row MFMA operands over the whole head dimension)
+// in registers for the entire kernel and streams the retained keys through LDS in 128-column stages.
+// Every 32x32 f32 accumulator tile is reduced on the spot (scale by 1/|k_c|, running maxima); the
+// similarity matrix is never written.  Steady state (one period's worth of evicted rows): a workgroup
+// of 8 wavefronts per 64 rows, the columns split over the wavefronts.
 //
 // Exactness: the f32 result decides a row only when the best value leads the second by more than
 // the rounding envelope and is away from the threshold by as much; all other rows (a fraction of a
@@ -16,6 +15,14 @@
 #include "kk_common.hpp"
 
 namespace kk {
+// Phase timestamps for kernel tuning; compiled in only with -DKEEPKV_TRACE (never in the product build).
+#ifdef KEEPKV_TRACE
+__device__ long long kk_trace_match[8 * 2048];
+#define KX_TS(i) do { const int b_ = blockIdx.y * gridDim.x + blockIdx.x; if (threadIdx.x == 0 && b_ < 2048) { \
+  kk_trace_match[b_ * 8 + 2 * (i)] = wall_clock64(); kk_trace_match[b_ * 8 + 2 * (i) + 1] = clock64(); } } while (0)
+#else
+#define KX_TS(i) do { } while (0)
+#endif
 namespace {
 
 constexpr int kRowsPerWave = 64;
@@ -139,25 +146,49 @@ __device__ __forceinline__ void fold_tile(const f32x16_t& c0, const f32x16_t& c1
   }
 }
 
+// f32 decision of one row from its best value y1 (column c1) and an upper bound y2 of every other column's
+// value, both still lacking the factor 1/|k_e|; rows that the f32 arithmetic cannot decide are queued.
+__device__ __forceinline__ void decide_row_f32(const MatchParams& p, int unit, int j, float y1, int c1, float y2,
+                                               float ss) {
+  const float rn_e = 1.0f / sqrtf(ss);
+  const float cos1 = y1 * rn_e;
+  const bool fragile = !(y1 > 0.f) || !(ss > 0.f) || !(rn_e < INFINITY) || !((y1 - y2) * rn_e > p.delta) ||
+                       !(fabsf(cos1 - p.threshold) > p.delta) || c1 >= p.budget;
+  const size_t o = (size_t)unit * p.max_evict + j;
+  p.match[o] = (cos1 > p.threshold) ? c1 : -1;
+  if (p.sim_out != nullptr) p.sim_out[o] = cos1;
+  if (fragile) {
+    const int at = atomicAdd(p.flag_count, 1);
+    p.flag_rows[at] = (int)o;
+  }
+}
+
+// The first event's kernel.  The product is taken transposed, retained keys as the A operand and the
+// wavefront's evicted rows as B, so that lane (l32, half) holds, for ITS evicted row, the 16 retained columns
+// 8 (i / 4) + 4 half + i % 4 of each 32-column block: all values in a lane belong to one row.  Per value the
+// fold then costs a multiply by 1/|k_c| and a maximum into the running best of its column class i, plus a
+// share of a max3 tree that gives the block's best, which goes into a running (best, second best, block)
+// triple.  No column number travels with the values: at the end the winning class is the one whose running
+// best equals the overall best, and the winning block is the triple's.  Every other column's value is
+// bounded by the second best block value or by the best of the other classes, which is all that the
+// exactness test needs.
 template <int D>
-__global__ __launch_bounds__(kMWaves* kWave) void match_mfma_kernel(MatchParams p) {
+__global__ __launch_bounds__(kMWaves* kWave, 2) void match_mfma_kernel(MatchParams p) {
   constexpr int KS = D / 16;                 // MFMA k-steps over the head dimension
   constexpr int ROWB = D * 2;                // bytes per key
   constexpr int CHUNKS = ROWB / 16;          // 16-byte chunks per key
   constexpr int STAGE_BYTES = kStageCols * ROWB;
-  constexpr int EPI_BYTES = kMWaves * kRowsPerWave * 33 * 2 * 4;   // transposed (best, second) pairs
-  constexpr int REGION = 2 * STAGE_BYTES > EPI_BYTES ? 2 * STAGE_BYTES : EPI_BYTES;
   constexpr int LOADS = kStageCols * CHUNKS / (kMWaves * kWave);   // async 16-byte loads per lane per stage
 
   extern __shared__ __align__(16) unsigned char smem[];
   unsigned char* s_stage = smem;                                        // 2 stages, swizzled rows
-  float* s_rn = reinterpret_cast<float*>(smem + REGION);                // [2][kStageCols]
-  float* s_rne = s_rn + 2 * kStageCols;                                 // [kMWaves][64]
+  float* s_rn = reinterpret_cast<float*>(smem + 2 * STAGE_BYTES);       // [2][kStageCols]
 
   const int unit = blockIdx.y;
   const int n_ev = p.n_evict[unit];
   const int row_blk = blockIdx.x * kRowsPerBlock;
   if (row_blk >= n_ev) return;
+  KX_TS(0);
   const int n_keep = p.budget;               // n_evict > 0 implies the retained list is full
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -178,7 +209,8 @@ __global__ __launch_bounds__(kMWaves* kWave) void match_mfma_kernel(MatchParams 
       const int q = tid + i * (kMWaves * kWave);
       const int col_l = q / CHUNKS, phys = q % CHUNKS;
       const int slot = keep[min(s * kStageCols + col_l, n_keep - 1)];
-      const unsigned char* src = kbytes + (size_t)slot * ROWB + ((phys ^ (col_l & (CHUNKS - 1))) * 16);
+      // 32-bit offsets from the head's base (one head's keys span less than 4 GiB, checked on the host)
+      const unsigned char* src = kbytes + ((uint32_t)slot * ROWB + ((phys ^ (col_l & (CHUNKS - 1))) * 16));
       __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
                                        (__attribute__((address_space(3))) void*)(dst + (wave * 64 + i * (kMWaves * kWave)) * 16),
                                        16, 0, 0);
@@ -191,18 +223,18 @@ __global__ __launch_bounds__(kMWaves* kWave) void match_mfma_kernel(MatchParams 
   };
   issue_stage(0);
 
-  // ---- A operands: this wavefront's 64 evicted rows, resident for the whole kernel -----------------
-  bf16x8_t a[2][KS];
-  float rn_e_part[2];
+  // ---- B operands: this wavefront's 64 evicted rows, resident for the whole kernel -----------------
+  bf16x8_t e[2][KS];
+  float ss_row[2];
 #pragma unroll
   for (int t = 0; t < 2; ++t) {
     const int j = min(row_blk + wave * kRowsPerWave + t * 32 + l32, n_ev - 1);
-    const unsigned char* row = kbytes + (size_t)evict[j] * ROWB;
+    const unsigned char* row = kbytes + (uint32_t)evict[j] * (uint32_t)ROWB;
     float ss = 0.f;
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) {
       const uint4 x = *reinterpret_cast<const uint4*>(row + ks * 32 + half * 16);
-      a[t][ks] = __builtin_bit_cast(bf16x8_t, x);
+      e[t][ks] = __builtin_bit_cast(bf16x8_t, x);
       const uint32_t w[4] = {x.x, x.y, x.z, x.w};
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
@@ -211,34 +243,59 @@ __global__ __launch_bounds__(kMWaves* kWave) void match_mfma_kernel(MatchParams 
         ss = fmaf(hi, hi, ss);
       }
     }
-    rn_e_part[t] = ss + __shfl_xor(ss, 32);
+    ss_row[t] = ss + __shfl_xor(ss, 32);
   }
 
-  const int code_mask = (1 << p.code_bits) - 1;
-  // the value mask lives in a vector register so that (x & mask) | code is one v_and_or_b32 (a VOP3
-  // instruction of this target may read only one scalar register, and the code is scalar)
-  int val_mask;
-  asm volatile("v_mov_b32 %0, %1" : "=v"(val_mask) : "s"(~code_mask));
-  int b1[2][16], b2[2][16];
+  // running state per tile: best of each column class, and (best, second best, block) over block maxima.
+  // Values are compared through their integer images (for positive floats the order is the same, and a
+  // negative one loses to the initial 0): a row without a positive similarity is queued for the f64 kernel
+  // anyway, and so is one whose best image is a NaN's.
+  int cls[2][16];
+  int b1[2] = {0, 0}, b2[2] = {0, 0};
+  int g1[2] = {0, 0};
 #pragma unroll
   for (int t = 0; t < 2; ++t)
 #pragma unroll
-    for (int i = 0; i < 16; ++i) b1[t][i] = b2[t][i] = (int)0x80000000;
+    for (int i = 0; i < 16; ++i) cls[t][i] = 0;
 
   const int n_stage = (n_keep + kStageCols - 1) / kStageCols;
   // software pipeline: the MFMAs of column block cb are issued together with the fold of block
   // cb - 1.  Two accumulator sets alternate (even blocks write A and fold B, odd blocks the reverse), so
   // no accumulator is ever copied.  The first fold sees zeros and is harmless.
+  // rn[g]: 1/|k_c| of the columns of accumulator registers 4g .. 4g+3, for the block being folded; each
+  // group is replaced by the next block's as soon as its last value is folded.
   f32x16_t accA0 = {0}, accA1 = {0}, accB0 = {0}, accB1 = {0};
-  float rnA = 0.f, rnB = 0.f;
-  int codeA = 0, codeB = 0;
+  f32x4_t rn[4];
+#pragma unroll
+  for (int g = 0; g < 4; ++g) rn[g] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+  int cb_prev = 0;
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   __syncthreads();
+  KX_TS(1);
 
   constexpr int VPK = 16 / KS;               // accumulator values folded per k-step and tile
   constexpr int BPS = kStageCols / 32;       // column blocks per stage (even)
   static_assert(BPS % 2 == 0, "the accumulator sets alternate by column block");
+  static_assert(VPK == 2 || VPK == 4, "fold_vals handles two or four values per k-step");
   const int n_blk = (n_keep + 31) / 32;
+
+  // values [ks * VPK, (ks + 1) * VPK) of one finished accumulator tile: scale, class maxima, block maximum
+  auto fold_vals = [&](int ks, const f32x16_t& od, int (&c)[16], int& gm) {
+#pragma unroll
+    for (int i = ks * VPK; i < (ks + 1) * VPK; i += 2) {
+      const int k0 = __builtin_bit_cast(int, od[i] * rn[i / 4][i % 4]);
+      const int k1 = __builtin_bit_cast(int, od[i + 1] * rn[(i + 1) / 4][(i + 1) % 4]);
+      c[i] = imax(c[i], k0);
+      c[i + 1] = imax(c[i + 1], k1);
+      gm = (i == 0) ? imax(k0, k1) : imax(imax(gm, k0), k1);
+    }
+  };
+  auto fold_group = [&](int gm, int ocb, int& v1, int& v2, int& blk) {
+    blk = (gm > v1) ? ocb : blk;
+    v2 = imed3(v1, v2, gm);
+    v1 = imax(v1, gm);
+  };
+
   for (int s = 0; s < n_stage; ++s) {
     if (s + 1 < n_stage) issue_stage(s + 1);
     const unsigned char* src = s_stage + (s & 1) * STAGE_BYTES;
@@ -250,69 +307,85 @@ __global__ __launch_bounds__(kMWaves* kWave) void match_mfma_kernel(MatchParams 
     // Explicit interleave: each MFMA is followed by the fold of VPK values of the previous column
     // block, and nothing may be scheduled across the fences, so the matrix pipe and the vector ALU of
     // this wavefront run side by side.
-    auto block = [&](int cbl, f32x16_t& nw0, f32x16_t& nw1, const f32x16_t& od0, const f32x16_t& od1, float orn,
-                     int ocode) {
+    auto block = [&](int cbl, f32x16_t& nw0, f32x16_t& nw1, const f32x16_t& od0, const f32x16_t& od1) {
       const f32x16_t zero = {0};
+      // 1/|k_c| of the 16 columns that this lane's accumulator registers hold in block cbl
+      const f32x4_t* rn_src = reinterpret_cast<const f32x4_t*>(s_rn + (s & 1) * kStageCols + cbl * 32 + 4 * half);
+      int gm0 = 0, gm1 = 0;
 #pragma unroll
       for (int ks = 0; ks < KS; ++ks) {
         const bf16x8_t bnext = (ks + 1 < KS) ? frag(cbl, ks + 1) : frag((cbl + 1) % BPS, 0);
-        nw0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[0][ks], bq, ks == 0 ? zero : nw0, 0, 0, 0);
+        nw0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bq, e[0][ks], ks == 0 ? zero : nw0, 0, 0, 0);
         __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-        for (int i = ks * VPK; i < (ks + 1) * VPK; ++i) fold_one(od0[i], orn, ocode, val_mask, b1[0][i], b2[0][i]);
+        fold_vals(ks, od0, cls[0], gm0);
         __builtin_amdgcn_sched_barrier(0);
-        nw1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[1][ks], bq, ks == 0 ? zero : nw1, 0, 0, 0);
+        nw1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bq, e[1][ks], ks == 0 ? zero : nw1, 0, 0, 0);
         __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-        for (int i = ks * VPK; i < (ks + 1) * VPK; ++i) fold_one(od1[i], orn, ocode, val_mask, b1[1][i], b2[1][i]);
+        fold_vals(ks, od1, cls[1], gm1);
+        if (((ks + 1) * VPK) % 4 == 0) rn[((ks + 1) * VPK) / 4 - 1] = rn_src[2 * (((ks + 1) * VPK) / 4 - 1)];
         __builtin_amdgcn_sched_barrier(0);
         bq = bnext;
       }
+      fold_group(gm0, cb_prev, b1[0], b2[0], g1[0]);
+      fold_group(gm1, cb_prev, b1[1], b2[1], g1[1]);
     };
 #pragma unroll
     for (int cbl = 0; cbl < BPS; ++cbl) {
       const int cb = s * BPS + cbl;                           // global column block
       if (cb < n_blk) {                                       // uniform over the workgroup
-        const float rn_new = s_rn[(s & 1) * kStageCols + cbl * 32 + l32];
-        if (cbl % 2 == 0) {
-          block(cbl, accA0, accA1, accB0, accB1, rnB, codeB);
-          rnA = rn_new;
-          codeA = code_mask - cb;                             // lower column block -> larger code
-        } else {
-          block(cbl, accB0, accB1, accA0, accA1, rnA, codeA);
-          rnB = rn_new;
-          codeB = code_mask - cb;
-        }
+        if (cbl % 2 == 0) block(cbl, accA0, accA1, accB0, accB1);
+        else block(cbl, accB0, accB1, accA0, accA1);
+        cb_prev = cb;
       }
     }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
   }
-  if (n_blk & 1) fold_tile(accA0, accA1, rnA, codeA, val_mask, b1, b2);   // the last block was an even one
-  else fold_tile(accB0, accB1, rnB, codeB, val_mask, b1, b2);
-
-  // ---- transpose the per-lane pairs through LDS: [wave][row 0..63][33] x {best, second} ---------------
-  int* s_b1 = reinterpret_cast<int*>(s_stage) + wave * (kRowsPerWave * 33 * 2);
-  int* s_b2 = s_b1 + kRowsPerWave * 33;
+  KX_TS(2);
+  {                                                           // the last block is still unfolded
+    const bool even_last = (n_blk & 1) != 0;
+    int gm0 = 0, gm1 = 0;
 #pragma unroll
-  for (int t = 0; t < 2; ++t)
-#pragma unroll
-    for (int i = 0; i < 16; ++i) {
-      const int r = t * 32 + 8 * (i / 4) + 4 * half + (i % 4);   // accumulator register -> tile row
-      s_b1[r * 33 + l32] = b1[t][i];
-      s_b2[r * 33 + l32] = b2[t][i];
+    for (int ks = 0; ks < KS; ++ks) {
+      if (even_last) {
+        fold_vals(ks, accA0, cls[0], gm0);
+        fold_vals(ks, accA1, cls[1], gm1);
+      } else {
+        fold_vals(ks, accB0, cls[0], gm0);
+        fold_vals(ks, accB1, cls[1], gm1);
+      }
     }
-  if (half == 0) {
-    s_rne[wave * 64 + l32] = rn_e_part[0];
-    s_rne[wave * 64 + 32 + l32] = rn_e_part[1];
+    fold_group(gm0, cb_prev, b1[0], b2[0], g1[0]);
+    fold_group(gm1, cb_prev, b1[1], b2[1], g1[1]);
   }
-  __syncthreads();
 
-  const int j = row_blk + wave * kRowsPerWave + lane;
-  if (j >= n_ev) return;
-  int v1, c1, v2;
-  reduce_pairs(s_b1, s_b2, lane, val_mask, code_mask, v1, c1, v2);
-  decide_row(p, unit, j, v1, c1, v2, s_rne[wave * 64 + lane]);
+  // ---- finish: winning class per tile, then the two lanes of a row (the halves) meet ----------------
+  float y1[2], y2[2];
+  int c1[2];
+#pragma unroll
+  for (int t = 0; t < 2; ++t) {
+    int s1 = cls[t][0], s2 = 0, ci = 0;
+#pragma unroll
+    for (int i = 1; i < 16; ++i) {
+      const int x = cls[t][i];
+      const bool up = x > s1;
+      s2 = up ? s1 : imax(s2, x);
+      ci = up ? i : ci;
+      s1 = up ? x : s1;
+    }
+    // s1 equals b1[t]: both are the largest value of this lane's half of the row
+    const int col = 32 * g1[t] + 8 * (ci / 4) + 4 * half + (ci % 4);
+    const int rest = imax(b2[t], s2);                         // bounds every other column of this half
+    const int o1 = __shfl_xor(s1, 32), orest = __shfl_xor(rest, 32), ocol = __shfl_xor(col, 32);
+    y1[t] = __builtin_bit_cast(float, imax(s1, o1));
+    c1[t] = (s1 > o1) ? col : ((o1 > s1) ? ocol : min(col, ocol));
+    y2[t] = __builtin_bit_cast(float, imax(imax(rest, orest), imin(s1, o1)));
+  }
+  const int j = row_blk + wave * kRowsPerWave + lane;         // lane = 32 half + l32 finishes row l32 of tile `half`
+  if (j < n_ev)
+    decide_row_f32(p, unit, j, half ? y1[1] : y1[0], half ? c1[1] : c1[0], half ? y2[1] : y2[0],
+                   half ? ss_row[1] : ss_row[0]);
+  KX_TS(3);
 }
 
 // Few evicted rows per head (the steady state: one period's worth).  One workgroup of 8 wavefronts
@@ -550,8 +623,7 @@ __global__ __launch_bounds__(256) void match_exact_kernel(MatchParams p) {
 
 template <int D>
 constexpr size_t mfma_smem_bytes() {
-  constexpr size_t stage = 2 * (size_t)kStageCols * (D * 2), epi = (size_t)kMWaves * kRowsPerWave * 33 * 2 * 4;
-  return (stage > epi ? stage : epi) + 2 * kStageCols * sizeof(float) + kMWaves * 64 * sizeof(float);
+  return 2 * (size_t)kStageCols * (D * 2) + 2 * kStageCols * sizeof(float);
 }
 constexpr size_t small_smem_bytes() {
   return (size_t)kSmallWaves * 2 * 64 * 33 * 4 + (size_t)kSmallWaves * 64 * 3 * 4 + 64 * 4;
@@ -650,3 +722,9 @@ extern "C" keepkv_status keepkv_match(const keepkv_layout* layout, const keepkv_
   }
   return launch_status();
 }
+
+#ifdef KEEPKV_TRACE
+extern "C" int keepkv_trace_read_match(long long* host, int n) {
+  return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(kk::kk_trace_match), sizeof(long long) * n);
+}
+#endif
