@@ -1,9 +1,10 @@
 // keepkv_match: nearest retained key by cosine similarity for every to-be-evicted key
 // (Alg. 1 lines 4-5), the one dense contraction of the method.
 //
-// bf16 caches, first event (thousands of evicted rows per head): a workgroup of 4 wavefronts owns 256
-// evicted rows; each wavefront keeps its 64 rows (two 32-row MFMA operands over the whole head dimension)
-// in registers for the entire kernel and streams the retained keys through LDS in 128-column stages.
+// bf16 caches, first event (thousands of evicted rows per head): the retained keys of a head are first
+// gathered into a panel in list order; one workgroup of 8 wavefronts per compute unit then walks blocks of
+// 512 evicted rows in passes.  Each wavefront keeps its 64 rows (two 32-row MFMA operands over the whole
+// head dimension) in registers for a pass and the panel streams through LDS in 128-column stages.
 // Every 32x32 f32 accumulator tile is reduced on the spot (scale by 1/|k_c|, running maxima); the
 // similarity matrix is never written.  Steady state (one period's worth of evicted rows): a workgroup
 // of 8 wavefronts per 64 rows, the columns split over the wavefronts.
@@ -17,25 +18,36 @@
 namespace kk {
 // Phase timestamps for kernel tuning; compiled in only with -DKEEPKV_TRACE (never in the product build).
 #ifdef KEEPKV_TRACE
+// per workgroup: [0] start, [1] first loop start, [2] first loop end, [3] first loop's shader cycles,
+// [4..7] end of pass 0..3 (100 MHz wall clock except [3])
 __device__ long long kk_trace_match[8 * 2048];
-#define KX_TS(i) do { const int b_ = blockIdx.y * gridDim.x + blockIdx.x; if (threadIdx.x == 0 && b_ < 2048) { \
-  kk_trace_match[b_ * 8 + 2 * (i)] = wall_clock64(); kk_trace_match[b_ * 8 + 2 * (i) + 1] = clock64(); } } while (0)
+#define KX_TS(i) do { const int b_ = blockIdx.x; if (threadIdx.x == 0 && b_ < 2048) \
+  kk_trace_match[b_ * 8 + (i)] = wall_clock64(); } while (0)
+#define KX_CYC(i, v) do { const int b_ = blockIdx.x; if (threadIdx.x == 0 && b_ < 2048) \
+  kk_trace_match[b_ * 8 + (i)] = (v); } while (0)
 #else
 #define KX_TS(i) do { } while (0)
+#define KX_CYC(i, v) do { } while (0)
 #endif
 namespace {
 
 constexpr int kRowsPerWave = 64;
-constexpr int kMWaves = 4;
-constexpr int kRowsPerBlock = kRowsPerWave * kMWaves;   // 256 evicted rows per workgroup
+constexpr int kMWaves = 8;
+constexpr int kRowsPerBlock = kRowsPerWave * kMWaves;   // 512 evicted rows per workgroup and pass
 constexpr int kStageCols = 128;                         // retained keys per LDS stage
+constexpr unsigned kResidentWorkgroups = 256;           // of the first event's kernel: one on each of 256 compute units
+constexpr int kXcds = 8;                                // accelerator dies, each with its own L2
 
 // ---------------------------------------------------------------------------------------------------
-// 1/|k_c| (f32) of every retained key; 0 for padding and for zero keys.
+// 1/|k_c| (f32) of every retained key; 0 for padding and for zero keys.  With `panel`, the retained keys are
+// also copied there in list order, rn_pitch rows per head (padding rows zero), each row with its 16-byte
+// chunk c stored at position c ^ (row mod chunks): the LDS image that the first event's kernel wants, so
+// that its stage loads are straight copies that need no slot index.
 template <typename T, int D>
 __global__ __launch_bounds__(256) void rnorm_kernel(const T* __restrict__ k, const int32_t* __restrict__ keep_idx,
                                                     const int32_t* __restrict__ n_evict, float* __restrict__ rnorm,
-                                                    int capacity, int budget, int rn_pitch, int32_t* flag_count) {
+                                                    int capacity, int budget, int rn_pitch, int32_t* flag_count,
+                                                    uint4* __restrict__ panel) {
   constexpr int EPL = 16 / (int)sizeof(T), LPS = D / EPL;
   const int unit = blockIdx.y;
   if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) *flag_count = 0;   // queue of fragile rows starts empty
@@ -46,8 +58,9 @@ __global__ __launch_bounds__(256) void rnorm_kernel(const T* __restrict__ k, con
   const bool valid = r < budget;
   const int slot = valid ? keep_idx[(size_t)unit * budget + r] : 0;
   float ss = 0.f;
+  uint4 x = make_uint4(0, 0, 0, 0);
   if (valid && slot >= 0) {
-    const uint4 x = reinterpret_cast<const uint4*>(k)[((size_t)unit * capacity + slot) * LPS + sub];
+    x = reinterpret_cast<const uint4*>(k)[((size_t)unit * capacity + slot) * LPS + sub];
     if constexpr (sizeof(T) == 2) {
       const uint32_t w[4] = {x.x, x.y, x.z, x.w};
 #pragma unroll
@@ -63,6 +76,7 @@ __global__ __launch_bounds__(256) void rnorm_kernel(const T* __restrict__ k, con
       for (int i = 0; i < 4; ++i) ss = fmaf(w[i], w[i], ss);
     }
   }
+  if (panel != nullptr) panel[((size_t)unit * rn_pitch + r) * LPS + (sub ^ (r & (LPS - 1)))] = x;
   ss = group_sum<LPS>(ss);
   // positions budget .. rn_pitch - 1 are padding: zero, so padded columns score 0
   if (sub == 0) rnorm[(size_t)unit * rn_pitch + r] = (valid && ss > 0.f && slot >= 0) ? 1.0f / sqrtf(ss) : 0.f;
@@ -75,6 +89,7 @@ struct MatchParams {
   const int32_t* evict_idx;
   const int32_t* n_evict;
   const float* rnorm;
+  const unsigned char* panel;   // retained keys in list order, rows pre-swizzled (first event's kernel only)
   int32_t* match;
   float* sim_out;
   int32_t* flag_count;   // [1]
@@ -82,6 +97,7 @@ struct MatchParams {
   int capacity, budget, max_evict, rn_pitch;
   float threshold, delta;
   int code_bits;
+  int per_unit, n_units;   // first event's kernel: workgroups per head, heads
 };
 
 __device__ __forceinline__ int imax(int a, int b) { return a > b ? a : b; }
@@ -184,10 +200,22 @@ __global__ __launch_bounds__(kMWaves* kWave, 2) void match_mfma_kernel(MatchPara
   unsigned char* s_stage = smem;                                        // 2 stages, swizzled rows
   float* s_rn = reinterpret_cast<float*>(smem + 2 * STAGE_BYTES);       // [2][kStageCols]
 
-  const int unit = blockIdx.y;
+  // Workgroups are dealt to the 8 XCDs in turn, each with an L2 of its own.  All workgroups of a head are
+  // placed on one XCD (when the heads divide evenly), so that the head's retained keys, which every pass of
+  // every one of them streams again, stay in that L2.
+  int unit, first_rb;
+  if (p.n_units % kXcds == 0) {
+    const int xcd = blockIdx.x % kXcds, slot = blockIdx.x / kXcds;
+    unit = xcd * (p.n_units / kXcds) + slot / p.per_unit;
+    first_rb = slot % p.per_unit;
+  } else {
+    unit = blockIdx.x / p.per_unit;
+    first_rb = blockIdx.x % p.per_unit;
+  }
   const int n_ev = p.n_evict[unit];
-  const int row_blk = blockIdx.x * kRowsPerBlock;
-  if (row_blk >= n_ev) return;
+  const int n_rb = (n_ev + kRowsPerBlock - 1) / kRowsPerBlock;
+  int rb = first_rb;                         // this pass's block of rows; later passes: rb + per_unit, ...
+  if (rb >= n_rb) return;
   KX_TS(0);
   const int n_keep = p.budget;               // n_evict > 0 implies the retained list is full
   const int tid = threadIdx.x, lane = tid & 63;
@@ -195,46 +223,56 @@ __global__ __launch_bounds__(kMWaves* kWave, 2) void match_mfma_kernel(MatchPara
   const int l32 = lane & 31, half = lane >> 5;
 
   const unsigned char* kbytes = reinterpret_cast<const unsigned char*>(p.k) + (size_t)unit * p.capacity * ROWB;
-  const int32_t* keep = p.keep_idx + (size_t)unit * p.budget;
   const int32_t* evict = p.evict_idx + (size_t)unit * p.max_evict;
   const float* rn_c = p.rnorm + (size_t)unit * p.rn_pitch;
 
-  // ---- stage loader: global -> LDS without passing through registers.  A wavefront instruction
-  // deposits 64 consecutive 16-byte chunks; chunk c of key `col` lives at position c ^ (col mod
-  // CHUNKS) of its row, which keeps the MFMA operand reads below free of bank conflicts.
-  auto issue_stage = [&](int s) {
-    unsigned char* dst = s_stage + (s & 1) * STAGE_BYTES;
+  // ---- stage loader: global -> LDS without passing through registers.  The panel holds the head's retained
+  // keys in list order with chunk c of key `col` at position c ^ (col mod CHUNKS) of its row, which keeps the
+  // MFMA operand reads below free of bank conflicts; a stage is one contiguous piece of it, copied as is.
+  const unsigned char* panel = p.panel + (size_t)unit * p.rn_pitch * ROWB;
+  auto issue_stage = [&](int s, int buf) {
+    const unsigned char* src = panel + (size_t)s * STAGE_BYTES + tid * 16;
+    unsigned char* dst = s_stage + buf * STAGE_BYTES + wave * 64 * 16;
 #pragma unroll
-    for (int i = 0; i < LOADS; ++i) {
-      const int q = tid + i * (kMWaves * kWave);
-      const int col_l = q / CHUNKS, phys = q % CHUNKS;
-      const int slot = keep[min(s * kStageCols + col_l, n_keep - 1)];
-      // 32-bit offsets from the head's base (one head's keys span less than 4 GiB, checked on the host)
-      const unsigned char* src = kbytes + ((uint32_t)slot * ROWB + ((phys ^ (col_l & (CHUNKS - 1))) * 16));
-      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
-                                       (__attribute__((address_space(3))) void*)(dst + (wave * 64 + i * (kMWaves * kWave)) * 16),
-                                       16, 0, 0);
-    }
+    for (int i = 0; i < LOADS; ++i)
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(src + i * (kMWaves * kWave) * 16),
+                                       (__attribute__((address_space(3))) void*)(dst + i * (kMWaves * kWave) * 16), 16, 0, 0);
     if (wave < kStageCols / 64) {            // 1/|k_c| of the stage's keys (padded with zeros by rnorm_kernel)
       __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(rn_c + s * kStageCols + tid),
-                                       (__attribute__((address_space(3))) void*)(s_rn + (s & 1) * kStageCols + wave * 64),
+                                       (__attribute__((address_space(3))) void*)(s_rn + buf * kStageCols + wave * 64),
                                        4, 0, 0);
     }
   };
-  issue_stage(0);
+  int par = 0;                               // LDS buffer of the stage being consumed
+  issue_stage(0, 0);
 
-  // ---- B operands: this wavefront's 64 evicted rows, resident for the whole kernel -----------------
+  // ---- B operands: this wavefront's 64 evicted rows of the pass, resident in registers.  The byte offsets
+  // of a pass's rows are fetched one pass ahead, the rows themselves as soon as the previous pass has
+  // issued its last MFMA, so that their latency overlaps that pass's epilogue.
+  auto row_offset = [&](int rb_, int t) {
+    return (uint32_t)evict[min(rb_ * kRowsPerBlock + wave * kRowsPerWave + t * 32 + l32, n_ev - 1)] * (uint32_t)ROWB;
+  };
+  uint32_t row_off[2] = {row_offset(rb, 0), row_offset(rb, 1)};
   bf16x8_t e[2][KS];
+  auto request_rows = [&]() {
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks)
+        e[t][ks] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4*>(kbytes + row_off[t] + ks * 32 + half * 16));
+  };
+  request_rows();
+
+  const int n_stage = (n_keep + kStageCols - 1) / kStageCols;
+  const uint32_t frag0 = l32 * ROWB + (((l32 & (CHUNKS - 1)) ^ half) * 16);
+  for (;;) {                                 // one pass per iteration
   float ss_row[2];
 #pragma unroll
   for (int t = 0; t < 2; ++t) {
-    const int j = min(row_blk + wave * kRowsPerWave + t * 32 + l32, n_ev - 1);
-    const unsigned char* row = kbytes + (uint32_t)evict[j] * (uint32_t)ROWB;
     float ss = 0.f;
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) {
-      const uint4 x = *reinterpret_cast<const uint4*>(row + ks * 32 + half * 16);
-      e[t][ks] = __builtin_bit_cast(bf16x8_t, x);
+      const uint4 x = __builtin_bit_cast(uint4, e[t][ks]);
       const uint32_t w[4] = {x.x, x.y, x.z, x.w};
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
@@ -245,6 +283,8 @@ __global__ __launch_bounds__(kMWaves* kWave, 2) void match_mfma_kernel(MatchPara
     }
     ss_row[t] = ss + __shfl_xor(ss, 32);
   }
+  const int rb_next = rb + p.per_unit;
+  const bool more = rb_next < n_rb;          // uniform over the workgroup
 
   // running state per tile: best of each column class, and (best, second best, block) over block maxima.
   // Values are compared through their integer images (for positive floats the order is the same, and a
@@ -257,8 +297,6 @@ __global__ __launch_bounds__(kMWaves* kWave, 2) void match_mfma_kernel(MatchPara
   for (int t = 0; t < 2; ++t)
 #pragma unroll
     for (int i = 0; i < 16; ++i) cls[t][i] = 0;
-
-  const int n_stage = (n_keep + kStageCols - 1) / kStageCols;
   // software pipeline: the MFMAs of column block cb are issued together with the fold of block
   // cb - 1.  Two accumulator sets alternate (even blocks write A and fold B, odd blocks the reverse), so
   // no accumulator is ever copied.  The first fold sees zeros and is harmless.
@@ -271,7 +309,12 @@ __global__ __launch_bounds__(kMWaves* kWave, 2) void match_mfma_kernel(MatchPara
   int cb_prev = 0;
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   __syncthreads();
-  KX_TS(1);
+  if (rb == first_rb) KX_TS(1);
+  const long long cyc0 = clock64();
+  if (more) {                                // next pass's row offsets: in flight during this pass's first stage
+    row_off[0] = row_offset(rb_next, 0);
+    row_off[1] = row_offset(rb_next, 1);
+  }
 
   constexpr int VPK = 16 / KS;               // accumulator values folded per k-step and tile
   constexpr int BPS = kStageCols / 32;       // column blocks per stage (even)
@@ -287,7 +330,8 @@ __global__ __launch_bounds__(kMWaves* kWave, 2) void match_mfma_kernel(MatchPara
       const int k1 = __builtin_bit_cast(int, od[i + 1] * rn[(i + 1) / 4][(i + 1) % 4]);
       c[i] = imax(c[i], k0);
       c[i + 1] = imax(c[i + 1], k1);
-      gm = (i == 0) ? imax(k0, k1) : imax(imax(gm, k0), k1);
+      if (i == 0) gm = imax(k0, k1);
+      else asm("v_max3_i32 %0, %1, %2, %3" : "=v"(gm) : "v"(gm), "v"(k0), "v"(k1));   // kept in this order
     }
   };
   auto fold_group = [&](int gm, int ocb, int& v1, int& v2, int& blk) {
@@ -297,11 +341,13 @@ __global__ __launch_bounds__(kMWaves* kWave, 2) void match_mfma_kernel(MatchPara
   };
 
   for (int s = 0; s < n_stage; ++s) {
-    if (s + 1 < n_stage) issue_stage(s + 1);
-    const unsigned char* src = s_stage + (s & 1) * STAGE_BYTES;
+    if (s + 1 < n_stage) issue_stage(s + 1, par ^ 1);
+    else if (more) issue_stage(0, par ^ 1);                   // the next pass starts over at the first columns
+    // operand fragment of key 32 cbl + l32: chunk (2 ks + half) ^ (l32 mod CHUNKS) of its row, which is the
+    // lane's chunk of k-step 0 with 32 ks XORed into the byte offset
+    const uint32_t frag_cur = frag0 + par * STAGE_BYTES;
     auto frag = [&](int cbl, int ks) {
-      return *reinterpret_cast<const bf16x8_t*>(src + (cbl * 32 + l32) * ROWB +
-                                               (((ks * 2 + half) ^ (l32 & (CHUNKS - 1))) * 16));
+      return *reinterpret_cast<const bf16x8_t*>(s_stage + ((frag_cur ^ (uint32_t)(ks * 32)) + cbl * 32 * ROWB));
     };
     bf16x8_t bq = frag(0, 0);
     // Explicit interleave: each MFMA is followed by the fold of VPK values of the previous column
@@ -310,7 +356,7 @@ __global__ __launch_bounds__(kMWaves* kWave, 2) void match_mfma_kernel(MatchPara
     auto block = [&](int cbl, f32x16_t& nw0, f32x16_t& nw1, const f32x16_t& od0, const f32x16_t& od1) {
       const f32x16_t zero = {0};
       // 1/|k_c| of the 16 columns that this lane's accumulator registers hold in block cbl
-      const f32x4_t* rn_src = reinterpret_cast<const f32x4_t*>(s_rn + (s & 1) * kStageCols + cbl * 32 + 4 * half);
+      const f32x4_t* rn_src = reinterpret_cast<const f32x4_t*>(s_rn + par * kStageCols + cbl * 32 + 4 * half);
       int gm0 = 0, gm1 = 0;
 #pragma unroll
       for (int ks = 0; ks < KS; ++ks) {
@@ -340,8 +386,10 @@ __global__ __launch_bounds__(kMWaves* kWave, 2) void match_mfma_kernel(MatchPara
     }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
+    par ^= 1;
   }
-  KX_TS(2);
+  if (rb == first_rb) { KX_TS(2); KX_CYC(3, clock64() - cyc0); }
+  if (more) request_rows();                                   // the operand registers are free: next pass's rows
   {                                                           // the last block is still unfolded
     const bool even_last = (n_blk & 1) != 0;
     int gm0 = 0, gm1 = 0;
@@ -381,11 +429,14 @@ __global__ __launch_bounds__(kMWaves* kWave, 2) void match_mfma_kernel(MatchPara
     c1[t] = (s1 > o1) ? col : ((o1 > s1) ? ocol : min(col, ocol));
     y2[t] = __builtin_bit_cast(float, imax(imax(rest, orest), imin(s1, o1)));
   }
-  const int j = row_blk + wave * kRowsPerWave + lane;         // lane = 32 half + l32 finishes row l32 of tile `half`
+  const int j = rb * kRowsPerBlock + wave * kRowsPerWave + lane;   // lane = 32 half + l32 finishes row l32 of tile `half`
   if (j < n_ev)
     decide_row_f32(p, unit, j, half ? y1[1] : y1[0], half ? c1[1] : c1[0], half ? y2[1] : y2[0],
                    half ? ss_row[1] : ss_row[0]);
-  KX_TS(3);
+  { const int pass = (rb - first_rb) / p.per_unit; if (pass < 4) KX_TS(4 + pass); }
+  if (!more) break;
+  rb = rb_next;
+  }
 }
 
 // Few evicted rows per head (the steady state: one period's worth).  One workgroup of 8 wavefronts
@@ -635,19 +686,29 @@ inline int rn_pitch_of(int budget) { return (budget + kStageCols - 1) / kStageCo
 template <int D>
 keepkv_status launch_bf16(const MatchParams& p, const void* k, unsigned units, hipStream_t st) {
   constexpr int rows_per_block = 256 / (D * 2 / 16);
+  const bool small = p.max_evict <= kSmallMaxEvict;
   rnorm_kernel<uint16_t, D><<<dim3((p.rn_pitch + rows_per_block - 1) / rows_per_block, units), 256, 0, st>>>(
       (const uint16_t*)k, p.keep_idx, p.n_evict, const_cast<float*>(p.rnorm), p.capacity, p.budget, p.rn_pitch,
-      p.flag_count);
+      p.flag_count, small ? nullptr : reinterpret_cast<uint4*>(const_cast<unsigned char*>(p.panel)));
   static const hipError_t a1 = hipFuncSetAttribute((const void*)match_mfma_kernel<D>,
                                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)mfma_smem_bytes<D>());
   static const hipError_t a2 = hipFuncSetAttribute((const void*)match_small_kernel<D>,
                                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)small_smem_bytes());
   if (a1 != hipSuccess || a2 != hipSuccess) return KEEPKV_ERR_DEVICE;
-  if (p.max_evict <= kSmallMaxEvict)
+  if (small)
     match_small_kernel<D><<<dim3((p.max_evict + 63) / 64, units), kSmallWaves * kWave, small_smem_bytes(), st>>>(p);
-  else
-    match_mfma_kernel<D><<<dim3((p.max_evict + kRowsPerBlock - 1) / kRowsPerBlock, units), kMWaves * kWave,
-                           mfma_smem_bytes<D>(), st>>>(p);
+  else {
+    // One workgroup fills a compute unit (8 wavefronts of 256 registers).  With fewer heads than compute
+    // units each head gets an equal share of them, and a workgroup walks its head's row blocks in passes;
+    // with more heads than that, one workgroup per head does all passes.
+    const unsigned row_blocks = (p.max_evict + kRowsPerBlock - 1) / kRowsPerBlock;
+    unsigned per_unit = kResidentWorkgroups / units;
+    per_unit = per_unit < 1 ? 1 : (per_unit > row_blocks ? row_blocks : per_unit);
+    MatchParams q = p;
+    q.per_unit = (int)per_unit;
+    q.n_units = (int)units;
+    match_mfma_kernel<D><<<per_unit * units, kMWaves * kWave, mfma_smem_bytes<D>(), st>>>(q);
+  }
   return KEEPKV_OK;
 }
 
@@ -658,7 +719,10 @@ MatchPlan plan_match(const keepkv_layout* L, int capacity, int budget) {
   const size_t units = (size_t)L->batch * L->n_kv_heads;
   pl.rnorm_off = kWorkspaceHead;
   pl.flag_off = kWorkspaceHead + align_up(units * rn_pitch_of(budget) * sizeof(float), 256);
-  pl.bytes = pl.flag_off + align_up((1 + units * (size_t)(capacity - budget)) * sizeof(int32_t) + 256, 256);
+  pl.panel_off = pl.flag_off + align_up((1 + units * (size_t)(capacity - budget)) * sizeof(int32_t) + 256, 256);
+  // the panel is used by bf16 caches with more evictable slots than the column-split kernel takes
+  const bool panel = L->dtype == KEEPKV_BF16 && capacity - budget > kSmallMaxEvict;
+  pl.bytes = pl.panel_off + (panel ? align_up(units * rn_pitch_of(budget) * (size_t)L->head_dim * 2, 256) : 0);
   return pl;
 }
 
@@ -690,9 +754,11 @@ extern "C" keepkv_status keepkv_match(const keepkv_layout* layout, const keepkv_
   p.rnorm = reinterpret_cast<float*>(reinterpret_cast<char*>(workspace) + pl.rnorm_off);
   p.flag_count = reinterpret_cast<int32_t*>(reinterpret_cast<char*>(workspace) + pl.flag_off);
   p.flag_rows = p.flag_count + 64;
+  p.panel = reinterpret_cast<const unsigned char*>(workspace) + pl.panel_off;
   p.match = match; p.sim_out = sim_out;
   p.capacity = cache->capacity; p.budget = budget; p.max_evict = max_evict;
   p.threshold = threshold;
+  p.per_unit = 0; p.n_units = 0;   // set by the first event's launch
   int nblk = (budget + 31) / 32, bits = 1;
   while ((1 << bits) < nblk) ++bits;
   p.code_bits = bits;
