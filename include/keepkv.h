@@ -198,12 +198,14 @@ keepkv_status keepkv_merge(const keepkv_layout *layout, const keepkv_cache *src,
  * published peaks.  keepkv_probe_read: `n_workgroups` workgroups stream `bytes` (a multiple of
  * 16) of DEVICE memory at `src` once with coalesced 16-byte loads; nothing is written except
  * possibly the DEVICE float `sink`.  keepkv_probe_mfma: every wavefront of `n_workgroups`
- * workgroups (4 wavefronts each) issues 4 * iters independent 32x32x16 bf16 MFMAs; *flops (HOST,
- * may be NULL) receives the floating-point operations of the launch.  Time them with events. */
+ * workgroups (4 wavefronts each) issues 4 * iters independent 32x32x16 bf16 MFMAs, on operands
+ * that are all (nearly) one, or, with random_operands != 0, pseudo-random bf16 values (the
+ * sustained clock and so the rate depend on the data); *flops (HOST, may be NULL) receives the
+ * floating-point operations of the launch.  Time them with events. */
 keepkv_status keepkv_probe_read(const void *src, size_t bytes, int32_t n_workgroups, float *sink,
                                 void *stream);
-keepkv_status keepkv_probe_mfma(int32_t n_workgroups, int32_t iters, float *sink, double *flops,
-                                void *stream);
+keepkv_status keepkv_probe_mfma(int32_t n_workgroups, int32_t iters, int32_t random_operands,
+                                float *sink, double *flops, void *stream);
 
 #ifdef __cplusplus
 }

@@ -58,7 +58,7 @@ _lib.keepkv_match.argtypes = [C.POINTER(_Layout), C.POINTER(_Cache), C.c_int32, 
 _lib.keepkv_merge.argtypes = [C.POINTER(_Layout), C.POINTER(_Cache), C.POINTER(_Cache), C.c_int32, _P, _P, _P,
                               _P, C.c_float, _P, _P, C.c_size_t, _P]
 _lib.keepkv_probe_read.argtypes = [_P, C.c_size_t, C.c_int32, _P, _P]
-_lib.keepkv_probe_mfma.argtypes = [C.c_int32, C.c_int32, _P, C.POINTER(C.c_double), _P]
+_lib.keepkv_probe_mfma.argtypes = [C.c_int32, C.c_int32, C.c_int32, _P, C.POINTER(C.c_double), _P]
 for _f in ("probe_read", "probe_mfma", "append", "decode_attn", "decode_step", "workspace_init", "score", "score_window", "select",
            "select_by_key", "match",
            "merge"):
@@ -194,9 +194,10 @@ def probe_read(src, n_workgroups: int, sink) -> None:
     _check(_lib.keepkv_probe_read(_ptr(src), _nbytes(src), n_workgroups, _ptr(sink), _stream()), "keepkv_probe_read")
 
 
-def probe_mfma(n_workgroups: int, iters: int, sink) -> float:
+def probe_mfma(n_workgroups: int, iters: int, sink, random_operands: bool = False) -> float:
     flops = C.c_double(0.0)
-    _check(_lib.keepkv_probe_mfma(n_workgroups, iters, _ptr(sink), C.byref(flops), _stream()), "keepkv_probe_mfma")
+    _check(_lib.keepkv_probe_mfma(n_workgroups, iters, 1 if random_operands else 0, _ptr(sink), C.byref(flops), _stream()),
+           "keepkv_probe_mfma")
     return flops.value
 
 

@@ -154,6 +154,7 @@ def test_measurement_probes_run_and_validate_arguments():
     kk.probe_read(buf, 64, sink)
     kk.probe_read(buf[: 16 * 1000 + 16], 7, sink)            # ragged share per workgroup
     flops = kk.probe_mfma(8, 10, sink)
+    assert kk.probe_mfma(8, 10, sink, True) == flops         # random operands: the same instruction count
     torch.cuda.synchronize()
     assert flops == 8 * 4 * 10 * 4 * 2 * 32 * 32 * 16
     assert sink.sum().item() == 0.0                          # the sinks are never written in practice
