@@ -136,6 +136,13 @@ def test_stress_shape_reduced_batch():
     _run(w, 0, n_window=2, n_steps=w.period, threshold=-2.0, sample=[(0, 2), (1, 7)])
 
 
+def test_odd_head_count_with_uneven_passes():
+    """9 heads (not a multiple of the 8 XCDs) with 31 blocks of evicted rows each: the first event's match
+    workgroups take one or two passes, the last one ragged; the sampled heads sit at both ends."""
+    w = W.CONFIGS["stress"].scaled(batch=3, n_q_heads=6, n_kv_heads=3)
+    _run(w, 2, n_window=2, n_steps=4, threshold=0.5, sample=[(0, 0), (2, 2)])
+
+
 @pytest.mark.parametrize("cfg,kw,window,causal", [
     ("llama3_8b", {}, 32, False),
     ("llama3_8b", {}, 32, True),
