@@ -129,43 +129,60 @@ __device__ __forceinline__ void combine_and_finish(const DecodeParams& p, const 
   __syncthreads();
   KK_TS(4);
   if (!s_last) return;
-  for (int idx = threadIdx.x; idx < G * D; idx += kWavesPerBlock * kWave) {
-    const int g = idx / D, d = idx % D;
-    const size_t row = (size_t)unit * G + g;
-    const float* src = p.partial + row * p.nsplit * (D + 2);
-    float M = -INFINITY, L = 0.f, A = 0.f;
-    // CH splits are fetched per round trip of device-scope loads: 8 when that covers all of them (the common
-    // case; surplus loads would only cost), 16 otherwise
-    auto fold_chunks = [&](auto ch_tag) {
-      constexpr int CH = decltype(ch_tag)::value;
-      for (int s0 = 0; s0 < p.nsplit; s0 += CH) {
-        float ms[CH], ls[CH], as[CH];
+  // CH splits of EB output elements are fetched per round trip of device-scope loads: 8 splits of two
+  // elements when that covers all splits (the common case; surplus loads would only cost), else 16 of one
+  constexpr int kThreads = kWavesPerBlock * kWave;
+  constexpr int kPerThread = (G * D + kThreads - 1) / kThreads;   // output elements per thread
+  auto combine = [&](auto ch_tag, auto eb_tag) {
+    constexpr int CH = decltype(ch_tag)::value, EB = decltype(eb_tag)::value;
+    for (int e0 = 0; e0 < kPerThread; e0 += EB) {
+      int idx[EB];
+      const float* src[EB];
+      float M[EB], L[EB], A[EB];
 #pragma unroll
-        for (int i = 0; i < CH; ++i) {
-          const int s = min(s0 + i, p.nsplit - 1);
-          ms[i] = ld_agent(src + s * (D + 2));
-          ls[i] = ld_agent(src + s * (D + 2) + 1);
-          as[i] = ld_agent(src + s * (D + 2) + 2 + d);
-        }
-        float mc = M;
-#pragma unroll
-        for (int i = 0; i < CH; ++i) mc = fmaxf(mc, ms[i]);
-        const float c0 = (M == -INFINITY) ? 0.f : fast_exp2(M - mc);
-        L *= c0;
-        A *= c0;
-#pragma unroll
-        for (int i = 0; i < CH; ++i) {
-          const float c = (s0 + i < p.nsplit && ms[i] != -INFINITY) ? fast_exp2(ms[i] - mc) : 0.f;
-          L = fmaf(ls[i], c, L);
-          A = fmaf(as[i], c, A);
-        }
-        M = mc;
+      for (int j = 0; j < EB; ++j) {
+        idx[j] = min((int)threadIdx.x + (e0 + j) * kThreads, G * D - 1);   // surplus threads repeat the last element
+        src[j] = p.partial + ((size_t)unit * G + idx[j] / D) * p.nsplit * (D + 2);
+        M[j] = -INFINITY;
+        L[j] = 0.f;
+        A[j] = 0.f;
       }
-    };
-    if (p.nsplit <= 8) fold_chunks(std::integral_constant<int, 8>{});
-    else fold_chunks(std::integral_constant<int, 16>{});
-    finish(row, d, M, L, A);
-  }
+      for (int s0 = 0; s0 < p.nsplit; s0 += CH) {
+        float ms[EB][CH], ls[EB][CH], as[EB][CH];
+#pragma unroll
+        for (int j = 0; j < EB; ++j)
+#pragma unroll
+          for (int i = 0; i < CH; ++i) {
+            const int s = min(s0 + i, p.nsplit - 1);
+            ms[j][i] = ld_agent(src[j] + s * (D + 2));
+            ls[j][i] = ld_agent(src[j] + s * (D + 2) + 1);
+            as[j][i] = ld_agent(src[j] + s * (D + 2) + 2 + idx[j] % D);
+          }
+#pragma unroll
+        for (int j = 0; j < EB; ++j) {
+          float mc = M[j];
+#pragma unroll
+          for (int i = 0; i < CH; ++i) mc = fmaxf(mc, ms[j][i]);
+          const float c0 = (M[j] == -INFINITY) ? 0.f : fast_exp2(M[j] - mc);
+          L[j] *= c0;
+          A[j] *= c0;
+#pragma unroll
+          for (int i = 0; i < CH; ++i) {
+            const float c = (s0 + i < p.nsplit && ms[j][i] != -INFINITY) ? fast_exp2(ms[j][i] - mc) : 0.f;
+            L[j] = fmaf(ls[j][i], c, L[j]);
+            A[j] = fmaf(as[j][i], c, A[j]);
+          }
+          M[j] = mc;
+        }
+      }
+#pragma unroll
+      for (int j = 0; j < EB; ++j)
+        if ((int)threadIdx.x + (e0 + j) * kThreads < G * D)
+          finish((size_t)unit * G + idx[j] / D, idx[j] % D, M[j], L[j], A[j]);
+    }
+  };
+  if (p.nsplit <= 8) combine(std::integral_constant<int, 8>{}, std::integral_constant<int, (kPerThread >= 2 ? 2 : 1)>{});
+  else combine(std::integral_constant<int, 16>{}, std::integral_constant<int, 1>{});
   KK_TS(5);
   if (threadIdx.x == 0) {
     __hip_atomic_store(&p.ticket[unit], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // ready for the next launch
