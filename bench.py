@@ -208,16 +208,34 @@ def main():
         kk.match(lay, c, Bud, keep, evict_s, n_ev, T, match_s, None, wsp)
         kk.merge(lay, c, d, Bud, keep, evict_s, n_ev, match_s, alpha, dropped[layer], wsp)
 
+    deferred = []                                # events whose side-stream work is still to be enqueued
+
+    def launch_deferred():
+        # The side-stream work of an event is enqueued one step late: it depends on the event recorded right
+        # after its layer's decode step all the same, but the main stream's next step is then already in the
+        # queue (or graph) when the branch is created, and it is the branch, not the chain of decode steps,
+        # that moves to another hardware queue.
+        while deferred:
+            c, d, layer, fork = deferred.pop(0)
+            side.wait_event(fork)
+            with torch.cuda.stream(side):
+                compress(c, d, layer, ws_side)
+                pending[layer] = torch.cuda.Event()
+                pending[layer].record()
+
     def one_step(i):
         nonlocal n_events
         layer = i % R
         t = step_no[layer]
         c = caches[layer][cur[layer]]
         main = torch.cuda.current_stream()
+        if any(x[2] == layer for x in deferred):  # (a single layer in rotation: its event cannot wait a step)
+            launch_deferred()
         if pending[layer] is not None:           # the layer's last compression event ran on the side stream
             main.wait_event(pending[layer])
             pending[layer] = None
         decode(c, layer, t % per_layer, since[layer])
+        launch_deferred()
         step_no[layer] = t + 1
         since[layer] += 1
         if since[layer] == P:
@@ -225,17 +243,16 @@ def main():
             if args.no_overlap:
                 compress(c, d, layer, ws)
             else:
-                side.wait_stream(main)
-                with torch.cuda.stream(side):
-                    compress(c, d, layer, ws_side)
-                    pending[layer] = torch.cuda.Event()
-                    pending[layer].record()
+                fork = torch.cuda.Event()
+                fork.record()                    # on the main stream, right after this layer's step
+                deferred.append((c, d, layer, fork))
             cur[layer] = 1 - cur[layer]
             since[layer] = 0
             n_events += 1
 
     def join_side():
         if not args.no_overlap:
+            launch_deferred()
             torch.cuda.current_stream().wait_stream(side)
             for layer in range(R):
                 pending[layer] = None
