@@ -146,6 +146,19 @@ def test_ragged_heads_and_under_budget():
     _run_compress_stagewise(w, lay, c, ws, alpha, U.f32(-2.0))
 
 
+def test_ragged_heads_with_several_match_passes():
+    """40 heads (5 per XCD) whose evicted rows range from none to 8 blocks of 512: the first event's match
+    workgroups (6 per head) take two passes on the full heads and none or a ragged one on the short ones."""
+    w = W.CONFIGS["llama3_8b"].scaled(batch=5, context=4000)
+    alpha = U.f32(0.9)
+    lay, c, ws = _observed_cache(w, 5, 2, alpha)
+    g = np.random.default_rng(5)
+    lens = g.choice([4000, 3999, 2100, 913, 401, 400, 37], size=(5, 8)).astype(np.int32)
+    lens[0, 0], lens[4, 7] = 4000, 4000
+    c.len[:] = torch.from_numpy(lens).cuda()
+    _run_compress_stagewise(w, lay, c, ws, alpha, U.f32(0.6))
+
+
 def test_select_exact_ties_keep_lowest_index():
     kk = U.kk()
     w = W.CONFIGS["llama3_8b"].scaled(batch=1, context=900)
