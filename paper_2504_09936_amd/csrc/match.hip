@@ -83,6 +83,7 @@ __global__ __launch_bounds__(256) void rnorm_kernel(const T* __restrict__ k, con
 }
 
 // ---------------------------------------------------------------------------------------------------
+struct ExactPartial;
 struct MatchParams {
   const void* k;
   const int32_t* keep_idx;
@@ -92,6 +93,8 @@ struct MatchParams {
   const unsigned char* panel;   // retained keys in list order, rows pre-swizzled (first event's kernel only)
   int32_t* match;
   float* sim_out;
+  struct ExactPartial* exact_partial;   // [kExactResident] per-share results of the f64 kernel
+  int32_t* exact_ticket;                // control words at the head of the workspace
   int32_t* flag_count;   // [1]
   int32_t* flag_rows;    // [units * max_evict]: unit * max_evict + j
   int capacity, budget, max_evict, rn_pitch;
@@ -578,8 +581,19 @@ __global__ void flag_all_kernel(const int32_t* __restrict__ n_evict, int32_t* fl
 __global__ void zero_counter_kernel(int32_t* c) { *c = 0; }
 
 // ---------------------------------------------------------------------------------------------------
-// f64 evaluation of queued rows: one workgroup per row, threads stride over the retained keys (each
-// thread evaluates whole keys, channels in index order, so the sums match an index-order f64 sum).
+// f64 evaluation of queued rows: threads stride over the retained keys (each thread evaluates whole keys,
+// channels in index order, so the sums match an index-order f64 sum).  One workgroup per row; when the
+// queue is so short that the compute units would mostly idle (the steady state: a handful of rows), up to
+// kExactMaxParts workgroups per row, each over a contiguous share of the retained list.  Their results
+// meet the way the decode splits do: device-scope stores, a ticket, the last one to arrive combines and
+// clears the ticket (the tickets are control words at the head of the workspace, zero between calls).
+constexpr int kExactMaxParts = 8;
+constexpr int kExactResident = 256;     // workgroups of this kernel that run at once (its registers allow one per compute unit)
+struct ExactPartial {
+  unsigned long long best_bits;
+  int best_c, pad;
+};
+
 template <typename T, int D>
 __global__ __launch_bounds__(256) void match_exact_kernel(MatchParams p) {
   __shared__ double s_e[D];
@@ -589,7 +603,15 @@ __global__ __launch_bounds__(256) void match_exact_kernel(MatchParams p) {
   const int n_flag = *p.flag_count;
   const T* kall = reinterpret_cast<const T*>(p.k);
   constexpr int EPV = 16 / (int)sizeof(T), NV = D / EPV;
-  for (int f = blockIdx.x; f < n_flag; f += gridDim.x) {
+  int parts = 1;
+  {
+    const int room = imin((int)gridDim.x, kExactResident);
+    while (parts < kExactMaxParts && (long)n_flag * (parts * 2) <= (long)room) parts *= 2;
+  }
+  const int share = (p.budget + parts - 1) / parts;
+  for (int w = blockIdx.x; w < n_flag * parts; w += gridDim.x) {
+    const int f = w / parts, part = w % parts;
+    const int c_lo = part * share, c_hi = imin(p.budget, c_lo + share);
     const int o = p.flag_rows[f];
     const int unit = o / p.max_evict, j = o % p.max_evict;
     const T* kunit = kall + (size_t)unit * p.capacity * D;
@@ -606,7 +628,7 @@ __global__ __launch_bounds__(256) void match_exact_kernel(MatchParams p) {
     const double rn_e = 1.0 / sqrt(ss_e);
     double best = -INFINITY;
     int best_c = 0x7FFFFFFF;
-    for (int c = tid; c < p.budget; c += 256) {
+    for (int c = c_lo + tid; c < c_hi; c += 256) {
       const int slot = keep[c];
       if (slot < 0) continue;
       const T* kc = kunit + (size_t)slot * D;
@@ -666,8 +688,35 @@ __global__ __launch_bounds__(256) void match_exact_kernel(MatchParams p) {
           best = s_best[w];
           best_c = s_bestc[w];
         }
-      p.match[o] = (best > (double)p.threshold) ? best_c : -1;
-      if (p.sim_out != nullptr) p.sim_out[o] = (float)best;
+      bool finish = parts == 1;
+      if (!finish) {
+        // with parts > 1 every workgroup has at most one work item, w < gridDim.x
+        ExactPartial* mine = p.exact_partial + w;
+        __hip_atomic_store(&mine->best_bits, __builtin_bit_cast(unsigned long long, best), __ATOMIC_RELAXED,
+                           __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_store(&mine->best_c, best_c, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");          // the two stores have completed
+        finish = __hip_atomic_fetch_add(&p.exact_ticket[f], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == parts - 1;
+        if (finish) {                     // the last share of this row: join them, in list order
+          best = -INFINITY;
+          best_c = 0x7FFFFFFF;
+          for (int q = 0; q < parts; ++q) {
+            const ExactPartial* r = p.exact_partial + f * parts + q;
+            const double rb = __builtin_bit_cast(double, __hip_atomic_load(&r->best_bits, __ATOMIC_RELAXED,
+                                                                           __HIP_MEMORY_SCOPE_AGENT));
+            const int rc = __hip_atomic_load(&r->best_c, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (rb > best) {
+              best = rb;
+              best_c = rc;
+            }
+          }
+          __hip_atomic_store(&p.exact_ticket[f], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // ready for the next call
+        }
+      }
+      if (finish) {
+        p.match[o] = (best > (double)p.threshold) ? best_c : -1;
+        if (p.sim_out != nullptr) p.sim_out[o] = (float)best;
+      }
     }
   }
 }
@@ -722,7 +771,8 @@ MatchPlan plan_match(const keepkv_layout* L, int capacity, int budget) {
   pl.panel_off = pl.flag_off + align_up((1 + units * (size_t)(capacity - budget)) * sizeof(int32_t) + 256, 256);
   // the panel is used by bf16 caches with more evictable slots than the column-split kernel takes
   const bool panel = L->dtype == KEEPKV_BF16 && capacity - budget > kSmallMaxEvict;
-  pl.bytes = pl.panel_off + (panel ? align_up(units * rn_pitch_of(budget) * (size_t)L->head_dim * 2, 256) : 0);
+  pl.partial_off = pl.panel_off + (panel ? align_up(units * rn_pitch_of(budget) * (size_t)L->head_dim * 2, 256) : 0);
+  pl.bytes = pl.partial_off + (size_t)kExactResident * 16;
   return pl;
 }
 
@@ -755,6 +805,8 @@ extern "C" keepkv_status keepkv_match(const keepkv_layout* layout, const keepkv_
   p.flag_count = reinterpret_cast<int32_t*>(reinterpret_cast<char*>(workspace) + pl.flag_off);
   p.flag_rows = p.flag_count + 64;
   p.panel = reinterpret_cast<const unsigned char*>(workspace) + pl.panel_off;
+  p.exact_partial = reinterpret_cast<ExactPartial*>(reinterpret_cast<char*>(workspace) + pl.partial_off);
+  p.exact_ticket = reinterpret_cast<int32_t*>(workspace);
   p.match = match; p.sim_out = sim_out;
   p.capacity = cache->capacity; p.budget = budget; p.max_evict = max_evict;
   p.threshold = threshold;
