@@ -25,9 +25,12 @@ __device__ long long kk_trace_match[8 * 2048];
   kk_trace_match[b_ * 8 + (i)] = wall_clock64(); } while (0)
 #define KX_CYC(i, v) do { const int b_ = blockIdx.x; if (threadIdx.x == 0 && b_ < 2048) \
   kk_trace_match[b_ * 8 + (i)] = (v); } while (0)
+// the steady-state kernel: indexed by head
+#define KS_TS(i) do { if (threadIdx.x == 0 && blockIdx.y < 256) kk_trace_match[blockIdx.y * 8 + (i)] = wall_clock64(); } while (0)
 #else
 #define KX_TS(i) do { } while (0)
 #define KX_CYC(i, v) do { } while (0)
+#define KS_TS(i) do { } while (0)
 #endif
 namespace {
 
@@ -442,129 +445,193 @@ __global__ __launch_bounds__(kMWaves* kWave, 2) void match_mfma_kernel(MatchPara
   }
 }
 
-// Few evicted rows per head (the steady state: one period's worth).  One workgroup of 8 wavefronts
-// per 64-row block; every wavefront holds the same 64 rows and takes every 8th column block, reading
-// the retained keys straight from global memory, so the work of one head spreads over a whole
-// compute unit instead of a single wavefront.
+// Few evicted rows per head (the steady state: one period's worth).  One workgroup of 8 wavefronts per
+// 64-row block, so the work of one head spreads over a whole compute unit instead of a single
+// wavefront.  The 64 evicted rows are copied once into LDS (swizzled like the stages above) and serve as
+// the B operand of every wavefront; a wavefront takes every 8th block of 32 retained columns and requests
+// the keys of four of its blocks at once, straight into registers as A operands, because the kernel is
+// all memory latency: nothing is reused and little is computed.  The fold is the transposed one of the
+// first event's kernel (a lane holds one evicted row; class maxima and a (best, second, block) triple).
 constexpr int kSmallWaves = 8;
+constexpr int kSmallBatch = 4;        // column blocks in flight per wavefront
 template <int D>
-__global__ __launch_bounds__(kSmallWaves* kWave) void match_small_kernel(MatchParams p) {
-  constexpr int KS = D / 16, ROWB = D * 2;
+__global__ __launch_bounds__(kSmallWaves* kWave, 2) void match_small_kernel(MatchParams p) {
+  constexpr int KS = D / 16, ROWB = D * 2, CHUNKS = ROWB / 16;
+  constexpr int ROW_LOADS = 64 * CHUNKS / (kSmallWaves * kWave);       // 16-byte copies per thread for the 64 rows
   extern __shared__ __align__(16) unsigned char smem[];
-  int* s_pairs = reinterpret_cast<int*>(smem);                          // [kSmallWaves][2][64 * 33]
-  int* s_top = s_pairs + kSmallWaves * 2 * 64 * 33;                     // [kSmallWaves][64][3]
-  float* s_rne = reinterpret_cast<float*>(s_top + kSmallWaves * 64 * 3);  // [64]
+  unsigned char* s_rows = smem;                                         // [64][ROWB], chunk c at c ^ (row mod CHUNKS)
+  int* s_top = reinterpret_cast<int*>(smem + 64 * ROWB);                // [kSmallWaves][64][3]
+  float* s_rn = reinterpret_cast<float*>(s_top + kSmallWaves * 64 * 3); // [rn_pitch]
 
   const int unit = blockIdx.y;
+  KS_TS(0);
   const int n_ev = p.n_evict[unit];
   const int row_blk = blockIdx.x * 64;
   if (row_blk >= n_ev) return;
+  KS_TS(1);
   const int n_keep = p.budget;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int l32 = lane & 31, half = lane >> 5;
   const unsigned char* kbytes = reinterpret_cast<const unsigned char*>(p.k) + (size_t)unit * p.capacity * ROWB;
   const int32_t* keep = p.keep_idx + (size_t)unit * p.budget;
   const int32_t* evict = p.evict_idx + (size_t)unit * p.max_evict;
   const float* rn_c = p.rnorm + (size_t)unit * p.rn_pitch;
+  const int ncb = (n_keep + 31) / 32;
 
-  bf16x8_t a[2][KS];
-  float rn_e_part[2];
+  // ---- requests, all issued before the first wait ---------------------------------------------------
+  // (1) slot numbers of the evicted rows this thread copies, and of the first batch's retained keys
+  int ev_slot[ROW_LOADS];
 #pragma unroll
-  for (int t = 0; t < 2; ++t) {
-    const int j = min(row_blk + t * 32 + l32, n_ev - 1);
-    const unsigned char* row = kbytes + (size_t)evict[j] * ROWB;
-    float ss = 0.f;
+  for (int i = 0; i < ROW_LOADS; ++i) {
+    const int q = tid + i * (kSmallWaves * kWave);
+    ev_slot[i] = evict[min(row_blk + q / CHUNKS, n_ev - 1)];
+  }
+  auto col_slot = [&](int cb) { return keep[min(cb * 32 + l32, n_keep - 1)]; };
+  int slot[kSmallBatch];
 #pragma unroll
-    for (int ks = 0; ks < KS; ++ks) {
-      const uint4 x = *reinterpret_cast<const uint4*>(row + ks * 32 + half * 16);
-      a[t][ks] = __builtin_bit_cast(bf16x8_t, x);
-      const uint32_t w[4] = {x.x, x.y, x.z, x.w};
+  for (int i = 0; i < kSmallBatch; ++i) slot[i] = col_slot(min(wave + i * kSmallWaves, ncb - 1));
+  // (2) 1/|k_c| of the whole retained list -> LDS (zero beyond the list: rnorm_kernel pads it)
+  for (int c = tid; c < p.rn_pitch; c += kSmallWaves * kWave)
+    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(rn_c + c),
+                                     (__attribute__((address_space(3))) void*)(s_rn + (c - lane)), 4, 0, 0);
+  // (3) the evicted rows -> LDS; a wavefront instruction deposits 64 consecutive 16-byte chunks
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const float lo = bf16_lo(w[i]), hi = bf16_hi(w[i]);
-        ss = fmaf(lo, lo, ss);
-        ss = fmaf(hi, hi, ss);
+  for (int i = 0; i < ROW_LOADS; ++i) {
+    const int q = tid + i * (kSmallWaves * kWave);
+    const int r = q / CHUNKS, phys = q % CHUNKS;
+    const unsigned char* src = kbytes + ((uint32_t)ev_slot[i] * ROWB + ((phys ^ (r & (CHUNKS - 1))) * 16));
+    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
+                                     (__attribute__((address_space(3))) void*)(s_rows + (q - lane) * 16), 16, 0, 0);
+  }
+  // (4) the first batch of retained keys, as A operands: lane (l32, half) holds chunks 2 ks + half of column l32
+  uint4 akey[kSmallBatch][KS];
+  auto request_keys = [&]() {
+#pragma unroll
+    for (int i = 0; i < kSmallBatch; ++i) {
+      const unsigned char* row = kbytes + ((uint32_t)slot[i] * ROWB + half * 16);
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) akey[i][ks] = *reinterpret_cast<const uint4*>(row + ks * 32);
+    }
+  };
+  request_keys();
+
+  int cls[2][16];
+  int b1[2] = {0, 0}, b2[2] = {0, 0}, g1[2] = {0, 0};
+#pragma unroll
+  for (int t = 0; t < 2; ++t)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) cls[t][i] = 0;
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  __syncthreads();                           // rows and 1/|k_c| are in LDS
+  KS_TS(2);
+
+  const uint32_t frag0 = l32 * ROWB + (((l32 & (CHUNKS - 1)) ^ half) * 16);
+  auto efrag = [&](int t, int ks) {          // B operand: evicted row 32 t + l32, chunk (2 ks + half) ^ (row mod CHUNKS)
+    return *reinterpret_cast<const bf16x8_t*>(s_rows + ((frag0 ^ (uint32_t)(ks * 32)) + t * 32 * ROWB));
+  };
+  for (int cb0 = wave; cb0 < ncb; cb0 += kSmallBatch * kSmallWaves) {
+#pragma unroll
+    for (int i = 0; i < kSmallBatch; ++i) {
+      const int cb = cb0 + i * kSmallWaves;
+      if (cb < ncb) {                        // uniform over the wavefront
+        asm volatile("" ::: "memory");       // the evicted rows are read from LDS again for every block: kept
+                                             // in registers beside four blocks of keys they would spill
+        // 1/|k_c| of the 16 columns that this lane's accumulator registers hold in this block
+        const f32x4_t* rn_src = reinterpret_cast<const f32x4_t*>(s_rn + cb * 32 + 4 * half);
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {        // one 32-row tile after the other: 16 accumulator registers
+          f32x16_t acc = {0};
+#pragma unroll
+          for (int ks = 0; ks < KS; ++ks)
+            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, akey[i][ks]), efrag(t, ks), acc, 0, 0, 0);
+          int gm = 0;
+#pragma unroll
+          for (int g = 0; g < 4; ++g) {
+            const f32x4_t rn = rn_src[2 * g];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+              const int k = __builtin_bit_cast(int, acc[4 * g + e] * rn[e]);
+              cls[t][4 * g + e] = imax(cls[t][4 * g + e], k);
+              gm = imax(gm, k);
+            }
+          }
+          g1[t] = (gm > b1[t]) ? cb : g1[t];
+          b2[t] = imed3(b1[t], b2[t], gm);
+          b1[t] = imax(b1[t], gm);
+        }
       }
     }
-    rn_e_part[t] = ss + __shfl_xor(ss, 32);
-  }
-  const int code_mask = (1 << p.code_bits) - 1;
-  // the value mask lives in a vector register so that (x & mask) | code is one v_and_or_b32 (a VOP3
-  // instruction of this target may read only one scalar register, and the code is scalar)
-  int val_mask;
-  asm volatile("v_mov_b32 %0, %1" : "=v"(val_mask) : "s"(~code_mask));
-  int b1[2][16], b2[2][16];
+    if (cb0 + kSmallBatch * kSmallWaves < ncb) {   // a long retained list: the next batch (its latency is exposed)
 #pragma unroll
-  for (int t = 0; t < 2; ++t)
-#pragma unroll
-    for (int i = 0; i < 16; ++i) b1[t][i] = b2[t][i] = (int)0x80000000;
-
-  const int ncb = (n_keep + 31) / 32;
-  auto load_b = [&](int cb, uint4 (&bf)[KS], float& rn) {
-    const int col = cb * 32 + l32;
-    const int slot = keep[min(col, n_keep - 1)];
-    const unsigned char* row = kbytes + (size_t)slot * ROWB + half * 16;
-#pragma unroll
-    for (int ks = 0; ks < KS; ++ks) bf[ks] = *reinterpret_cast<const uint4*>(row + ks * 32);
-    rn = rn_c[col];                          // zero beyond the retained keys
-  };
-  uint4 bcur[KS], bnext[KS];
-  float rcur = 0.f, rnext = 0.f;
-  if (wave < ncb) load_b(wave, bcur, rcur);
-  for (int cb = wave; cb < ncb; cb += kSmallWaves) {
-    if (cb + kSmallWaves < ncb) load_b(cb + kSmallWaves, bnext, rnext);
-    f32x16_t c0 = {0}, c1 = {0};
-#pragma unroll
-    for (int ks = 0; ks < KS; ++ks) {
-      const bf16x8_t bfrag = __builtin_bit_cast(bf16x8_t, bcur[ks]);
-      c0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[0][ks], bfrag, c0, 0, 0, 0);
-      c1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[1][ks], bfrag, c1, 0, 0, 0);
+      for (int i = 0; i < kSmallBatch; ++i)
+        slot[i] = col_slot(min(cb0 + (kSmallBatch + i) * kSmallWaves, ncb - 1));
+      request_keys();
     }
-    fold_tile(c0, c1, rcur, code_mask - cb, val_mask, b1, b2);
-#pragma unroll
-    for (int ks = 0; ks < KS; ++ks) bcur[ks] = bnext[ks];
-    rcur = rnext;
   }
 
-  int* s_b1 = s_pairs + wave * (2 * 64 * 33);
-  int* s_b2 = s_b1 + 64 * 33;
+  KS_TS(3);
+  // ---- this wavefront's result per row: winning class per tile, then the two halves of a row meet ----
+  int y1[2], y2[2], c1[2];
 #pragma unroll
-  for (int t = 0; t < 2; ++t)
+  for (int t = 0; t < 2; ++t) {
+    int s1 = cls[t][0], s2 = 0, ci = 0;
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
-      const int r = t * 32 + 8 * (i / 4) + 4 * half + (i % 4);
-      s_b1[r * 33 + l32] = b1[t][i];
-      s_b2[r * 33 + l32] = b2[t][i];
+    for (int i = 1; i < 16; ++i) {
+      const int x = cls[t][i];
+      const bool up = x > s1;
+      s2 = up ? s1 : imax(s2, x);
+      ci = up ? i : ci;
+      s1 = up ? x : s1;
     }
-  if (wave == 0 && half == 0) {
-    s_rne[l32] = rn_e_part[0];
-    s_rne[32 + l32] = rn_e_part[1];
+    const int col = 32 * g1[t] + 8 * (ci / 4) + 4 * half + (ci % 4);
+    const int rest = imax(b2[t], s2);                         // bounds every other column of this half
+    const int o1 = __shfl_xor(s1, 32), orest = __shfl_xor(rest, 32), ocol = __shfl_xor(col, 32);
+    y1[t] = imax(s1, o1);
+    c1[t] = (s1 > o1) ? col : ((o1 > s1) ? ocol : min(col, ocol));
+    y2[t] = imax(imax(rest, orest), imin(s1, o1));
   }
-  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
-  __builtin_amdgcn_wave_barrier();
-  {
-    int v1, c1, v2;
-    reduce_pairs(s_b1, s_b2, lane, val_mask, code_mask, v1, c1, v2);   // this wavefront's column blocks
+  {                                                           // lane = 32 half + l32 speaks for row l32 of tile `half`
     int* t3 = s_top + (wave * 64 + lane) * 3;
-    t3[0] = v1; t3[1] = c1; t3[2] = v2;
+    t3[0] = half ? y1[1] : y1[0];
+    t3[1] = half ? c1[1] : c1[0];
+    t3[2] = half ? y2[1] : y2[0];
   }
   __syncthreads();
+  KS_TS(4);
   if (wave != 0) return;
   const int j = row_blk + lane;
   if (j >= n_ev) return;
-  int v1 = (int)0x80000000, v2 = (int)0x80000000, c1 = 0;
+  int v1 = (int)0x80000000, v2 = (int)0x80000000, cc = 0;
   for (int w = 0; w < kSmallWaves; ++w) {
     const int* t3 = s_top + (w * 64 + lane) * 3;
     const int val = t3[0], col = t3[1], val2 = t3[2];
-    if (val > v1 || (val == v1 && col < c1)) {
+    if (val > v1 || (val == v1 && col < cc)) {
       v2 = imax(v1, val2);
       v1 = val;
-      c1 = col;
+      cc = col;
     } else {
       v2 = imax(v2, val);
     }
   }
-  decide_row(p, unit, j, v1, c1, v2, s_rne[lane]);
+  // |k_e|^2 of this lane's row, from the LDS copy
+  float ss = 0.f;
+  {
+    const unsigned char* row = s_rows + lane * ROWB;
+#pragma unroll
+    for (int c = 0; c < CHUNKS; ++c) {
+      const uint4 x = *reinterpret_cast<const uint4*>(row + c * 16);   // the order of the chunks does not matter here
+      const uint32_t w4[4] = {x.x, x.y, x.z, x.w};
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const float lo = bf16_lo(w4[i]), hi = bf16_hi(w4[i]);
+        ss = fmaf(lo, lo, ss);
+        ss = fmaf(hi, hi, ss);
+      }
+    }
+  }
+  decide_row(p, unit, j, v1, cc, v2, ss);
+  KS_TS(5);
 }
 
 // queue every live evicted row (f32 caches)
@@ -725,8 +792,8 @@ template <int D>
 constexpr size_t mfma_smem_bytes() {
   return 2 * (size_t)kStageCols * (D * 2) + 2 * kStageCols * sizeof(float);
 }
-constexpr size_t small_smem_bytes() {
-  return (size_t)kSmallWaves * 2 * 64 * 33 * 4 + (size_t)kSmallWaves * 64 * 3 * 4 + 64 * 4;
+inline size_t small_smem_bytes(int head_dim, int rn_pitch) {   // evicted rows, per-wavefront results, 1/|k_c|
+  return (size_t)64 * head_dim * 2 + (size_t)kSmallWaves * 64 * 3 * 4 + (size_t)rn_pitch * 4;
 }
 constexpr int kSmallMaxEvict = 256;   // up to this many evictable slots per head the column-split kernel is used
 
@@ -742,10 +809,12 @@ keepkv_status launch_bf16(const MatchParams& p, const void* k, unsigned units, h
   static const hipError_t a1 = hipFuncSetAttribute((const void*)match_mfma_kernel<D>,
                                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)mfma_smem_bytes<D>());
   static const hipError_t a2 = hipFuncSetAttribute((const void*)match_small_kernel<D>,
-                                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)small_smem_bytes());
+                                                   hipFuncAttributeMaxDynamicSharedMemorySize,
+                                                   (int)small_smem_bytes(D, rn_pitch_of(4096)));
   if (a1 != hipSuccess || a2 != hipSuccess) return KEEPKV_ERR_DEVICE;
   if (small)
-    match_small_kernel<D><<<dim3((p.max_evict + 63) / 64, units), kSmallWaves * kWave, small_smem_bytes(), st>>>(p);
+    match_small_kernel<D><<<dim3((p.max_evict + 63) / 64, units), kSmallWaves * kWave,
+                            small_smem_bytes(D, p.rn_pitch), st>>>(p);
   else {
     // One workgroup fills a compute unit (8 wavefronts of 256 registers).  With fewer heads than compute
     // units each head gets an equal share of them, and a workgroup walks its head's row blocks in passes;
