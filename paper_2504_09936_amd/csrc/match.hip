@@ -102,7 +102,6 @@ struct MatchParams {
   int32_t* flag_rows;    // [units * max_evict]: unit * max_evict + j
   int capacity, budget, max_evict, rn_pitch;
   float threshold, delta;
-  int code_bits;
   int per_unit, n_units;   // first event's kernel: workgroups per head, heads
 };
 
@@ -111,27 +110,9 @@ __device__ __forceinline__ int imin(int a, int b) { return a < b ? a : b; }
 // median of three; the backend folds this into v_med3_i32
 __device__ __forceinline__ int imed3(int a, int b, int c) { return imax(imin(a, b), imin(imax(a, b), c)); }
 
-// Row r of a wavefront's 64 rows is finished by lane r: reduce the 32 per-column-class pairs, then
-// decide from the f32 value or queue the row for the f64 kernel.
-__device__ __forceinline__ void reduce_pairs(const int* s_b1, const int* s_b2, int row, int val_mask, int code_mask,
-                                             int& v1, int& c1, int& v2) {
-  v1 = (int)0x80000000; v2 = (int)0x80000000; c1 = 0;
-#pragma unroll 8
-  for (int q = 0; q < 32; ++q) {
-    const int k1 = s_b1[row * 33 + q], k2 = s_b2[row * 33 + q];
-    const int val = k1 & val_mask;
-    const int col = (code_mask - (k1 & code_mask)) * 32 + q;
-    const int val2 = k2 & val_mask;
-    if (val > v1 || (val == v1 && col < c1)) {
-      v2 = imax(v1, val2);
-      v1 = val;
-      c1 = col;
-    } else {
-      v2 = imax(v2, val);
-    }
-  }
-}
-
+// Decision of one row from the integer images of its best value v1 (column c1) and of an upper bound v2 of
+// every other column's value, both still lacking the factor 1/|k_e| (ss = |k_e|^2); a row that the f32
+// arithmetic cannot decide is queued for the f64 kernel.
 __device__ __forceinline__ void decide_row(const MatchParams& p, int unit, int j, int v1, int c1, int v2, float ss) {
   const float rn_e = 1.0f / sqrtf(ss);
   const float y1 = __builtin_bit_cast(float, v1), y2 = (v2 > 0) ? __builtin_bit_cast(float, v2) : 0.f;
@@ -144,27 +125,6 @@ __device__ __forceinline__ void decide_row(const MatchParams& p, int unit, int j
   if (fragile) {
     const int at = atomicAdd(p.flag_count, 1);
     p.flag_rows[at] = (int)o;
-  }
-}
-
-// fold one scaled similarity into a running (best, second best) pair: 4 vector instructions
-__device__ __forceinline__ void fold_one(float c, float rn, int code, int val_mask, int& b1, int& b2) {
-  const int k = (__builtin_bit_cast(int, c * rn) & val_mask) | code;
-  b2 = imed3(b1, b2, k);
-  b1 = imax(b1, k);
-}
-
-// fold one pair of 32x32 accumulator tiles (rows of A tile 0 / 1, one column block) into the running pairs
-__device__ __forceinline__ void fold_tile(const f32x16_t& c0, const f32x16_t& c1, float rn, int code, int val_mask,
-                                          int (&b1)[2][16], int (&b2)[2][16]) {
-#pragma unroll
-  for (int i = 0; i < 16; ++i) {
-    const int k0 = (__builtin_bit_cast(int, c0[i] * rn) & val_mask) | code;
-    b2[0][i] = imed3(b1[0][i], b2[0][i], k0);
-    b1[0][i] = imax(b1[0][i], k0);
-    const int k1 = (__builtin_bit_cast(int, c1[i] * rn) & val_mask) | code;
-    b2[1][i] = imed3(b1[1][i], b2[1][i], k1);
-    b1[1][i] = imax(b1[1][i], k1);
   }
 }
 
@@ -316,7 +276,9 @@ __global__ __launch_bounds__(kMWaves* kWave, 2) void match_mfma_kernel(MatchPara
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   __syncthreads();
   if (rb == first_rb) KX_TS(1);
+#ifdef KEEPKV_TRACE
   const long long cyc0 = clock64();
+#endif
   if (more) {                                // next pass's row offsets: in flight during this pass's first stage
     row_off[0] = row_offset(rb_next, 0);
     row_off[1] = row_offset(rb_next, 1);
@@ -880,10 +842,10 @@ extern "C" keepkv_status keepkv_match(const keepkv_layout* layout, const keepkv_
   p.capacity = cache->capacity; p.budget = budget; p.max_evict = max_evict;
   p.threshold = threshold;
   p.per_unit = 0; p.n_units = 0;   // set by the first event's launch
-  int nblk = (budget + 31) / 32, bits = 1;
-  while ((1 << bits) < nblk) ++bits;
-  p.code_bits = bits;
-  p.delta = 1.0e-5f + 1.5f * ldexpf(1.0f, bits - 23);
+  // Margin below which the f32 result does not decide a row.  An f32 similarity carries the accumulation of
+  // D exact products (at most D * 2^-24 relative to |k_e||k_c|, far less in practice) and the roundings of
+  // the two norms; what is compared are two such values, or one and the threshold.
+  p.delta = 1.6e-5f;
 
   p.rn_pitch = rn_pitch_of(budget);
   if (layout->dtype != KEEPKV_BF16) zero_counter_kernel<<<1, 1, 0, st>>>(p.flag_count);   // bf16: done by rnorm_kernel
