@@ -77,8 +77,8 @@ int32_t keepkv_version(void);
 /* Bytes of DEVICE workspace sufficient for any call below on a cache of `capacity` slots
  * compressed to `budget` slots (pure host function; 0 on invalid arguments).  The
  * workspace is scratch and must not be shared by calls that may run concurrently.  Its
- * first 64 KiB hold control words that must be zero when a call starts: clear them once
- * with keepkv_workspace_init after allocating; every call leaves them zero again. */
+ * head (64 KiB + 256 bytes) holds control words that must be zero when a call starts: clear
+ * them once with keepkv_workspace_init after allocating; every call leaves them zero again. */
 size_t keepkv_workspace_bytes(const keepkv_layout *layout, int32_t capacity, int32_t budget);
 
 /* Clear the control words at the head of a freshly allocated DEVICE workspace (one small

@@ -86,7 +86,8 @@ inline keepkv_status launch_status() {
 // calls; keepkv_workspace_init clears them and every kernel leaves them cleared.  Scratch areas of
 // all calls start behind the head.
 constexpr int kMaxUnits = 16384;                         // batch * n_kv_heads
-constexpr size_t kWorkspaceHead = kMaxUnits * sizeof(int32_t);
+constexpr size_t kMatchCountersOff = kMaxUnits * sizeof(int32_t);   // match: [0] queued rows, [1] finished workgroups
+constexpr size_t kWorkspaceHead = kMatchCountersOff + 256;
 // grids put (batch, kv head) on one axis and the workspace head holds one control word per pair
 inline bool units_supported(const keepkv_layout* L) { return (int64_t)L->batch * L->n_kv_heads <= kMaxUnits; }
 

@@ -49,11 +49,9 @@ constexpr int kXcds = 8;                                // accelerator dies, eac
 template <typename T, int D>
 __global__ __launch_bounds__(256) void rnorm_kernel(const T* __restrict__ k, const int32_t* __restrict__ keep_idx,
                                                     const int32_t* __restrict__ n_evict, float* __restrict__ rnorm,
-                                                    int capacity, int budget, int rn_pitch, int32_t* flag_count,
-                                                    uint4* __restrict__ panel) {
+                                                    int capacity, int budget, int rn_pitch, uint4* __restrict__ panel) {
   constexpr int EPL = 16 / (int)sizeof(T), LPS = D / EPL;
   const int unit = blockIdx.y;
-  if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) *flag_count = 0;   // queue of fragile rows starts empty
   if (n_evict[unit] <= 0) return;
   const int r = blockIdx.x * (256 / LPS) + threadIdx.x / LPS;
   const int sub = threadIdx.x % LPS;
@@ -98,7 +96,8 @@ struct MatchParams {
   float* sim_out;
   struct ExactPartial* exact_partial;   // [kExactResident] per-share results of the f64 kernel
   int32_t* exact_ticket;                // control words at the head of the workspace
-  int32_t* flag_count;   // [1]
+  int32_t* flag_count;   // [1] rows queued for the f64 kernel; zero between calls (the f64 kernel clears it)
+  int32_t* exact_done;   // [1] workgroups of the f64 kernel that have finished; zero between calls
   int32_t* flag_rows;    // [units * max_evict]: unit * max_evict + j
   int capacity, budget, max_evict, rn_pitch;
   float threshold, delta;
@@ -412,8 +411,9 @@ __global__ __launch_bounds__(kMWaves* kWave, 2) void match_mfma_kernel(MatchPara
 // wavefront.  The 64 evicted rows are copied once into LDS (swizzled like the stages above) and serve as
 // the B operand of every wavefront; a wavefront takes every 8th block of 32 retained columns and requests
 // the keys of four of its blocks at once, straight into registers as A operands, because the kernel is
-// all memory latency: nothing is reused and little is computed.  The fold is the transposed one of the
-// first event's kernel (a lane holds one evicted row; class maxima and a (best, second, block) triple).
+// all memory latency: nothing is reused and little is computed.  1/|k_c| is formed here from the operand
+// registers (the two lanes of a column hold one half of its channels each).  The fold is the transposed one
+// of the first event's kernel (a lane holds one evicted row; class maxima and a (best, second, block) triple).
 constexpr int kSmallWaves = 8;
 constexpr int kSmallBatch = 4;        // column blocks in flight per wavefront
 template <int D>
@@ -423,7 +423,7 @@ __global__ __launch_bounds__(kSmallWaves* kWave, 2) void match_small_kernel(Matc
   extern __shared__ __align__(16) unsigned char smem[];
   unsigned char* s_rows = smem;                                         // [64][ROWB], chunk c at c ^ (row mod CHUNKS)
   int* s_top = reinterpret_cast<int*>(smem + 64 * ROWB);                // [kSmallWaves][64][3]
-  float* s_rn = reinterpret_cast<float*>(s_top + kSmallWaves * 64 * 3); // [rn_pitch]
+  float* s_rn = reinterpret_cast<float*>(s_top + kSmallWaves * 64 * 3); // [kSmallWaves][32]: a wavefront's current block
 
   const int unit = blockIdx.y;
   KS_TS(0);
@@ -438,7 +438,6 @@ __global__ __launch_bounds__(kSmallWaves* kWave, 2) void match_small_kernel(Matc
   const unsigned char* kbytes = reinterpret_cast<const unsigned char*>(p.k) + (size_t)unit * p.capacity * ROWB;
   const int32_t* keep = p.keep_idx + (size_t)unit * p.budget;
   const int32_t* evict = p.evict_idx + (size_t)unit * p.max_evict;
-  const float* rn_c = p.rnorm + (size_t)unit * p.rn_pitch;
   const int ncb = (n_keep + 31) / 32;
 
   // ---- requests, all issued before the first wait ---------------------------------------------------
@@ -451,13 +450,10 @@ __global__ __launch_bounds__(kSmallWaves* kWave, 2) void match_small_kernel(Matc
   }
   auto col_slot = [&](int cb) { return keep[min(cb * 32 + l32, n_keep - 1)]; };
   int slot[kSmallBatch];
+  bool slot_ok[kSmallBatch];
 #pragma unroll
   for (int i = 0; i < kSmallBatch; ++i) slot[i] = col_slot(min(wave + i * kSmallWaves, ncb - 1));
-  // (2) 1/|k_c| of the whole retained list -> LDS (zero beyond the list: rnorm_kernel pads it)
-  for (int c = tid; c < p.rn_pitch; c += kSmallWaves * kWave)
-    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(rn_c + c),
-                                     (__attribute__((address_space(3))) void*)(s_rn + (c - lane)), 4, 0, 0);
-  // (3) the evicted rows -> LDS; a wavefront instruction deposits 64 consecutive 16-byte chunks
+  // (2) the evicted rows -> LDS; a wavefront instruction deposits 64 consecutive 16-byte chunks
 #pragma unroll
   for (int i = 0; i < ROW_LOADS; ++i) {
     const int q = tid + i * (kSmallWaves * kWave);
@@ -466,12 +462,13 @@ __global__ __launch_bounds__(kSmallWaves* kWave, 2) void match_small_kernel(Matc
     __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
                                      (__attribute__((address_space(3))) void*)(s_rows + (q - lane) * 16), 16, 0, 0);
   }
-  // (4) the first batch of retained keys, as A operands: lane (l32, half) holds chunks 2 ks + half of column l32
+  // (3) the first batch of retained keys, as A operands: lane (l32, half) holds chunks 2 ks + half of column l32
   uint4 akey[kSmallBatch][KS];
   auto request_keys = [&]() {
 #pragma unroll
     for (int i = 0; i < kSmallBatch; ++i) {
-      const unsigned char* row = kbytes + ((uint32_t)slot[i] * ROWB + half * 16);
+      slot_ok[i] = slot[i] >= 0;             // (a negative slot number: slot 0 stands in, its column scores 0)
+      const unsigned char* row = kbytes + ((uint32_t)max(slot[i], 0) * ROWB + half * 16);
 #pragma unroll
       for (int ks = 0; ks < KS; ++ks) akey[i][ks] = *reinterpret_cast<const uint4*>(row + ks * 32);
     }
@@ -485,7 +482,7 @@ __global__ __launch_bounds__(kSmallWaves* kWave, 2) void match_small_kernel(Matc
 #pragma unroll
     for (int i = 0; i < 16; ++i) cls[t][i] = 0;
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-  __syncthreads();                           // rows and 1/|k_c| are in LDS
+  __syncthreads();                           // the rows are in LDS
   KS_TS(2);
 
   const uint32_t frag0 = l32 * ROWB + (((l32 & (CHUNKS - 1)) ^ half) * 16);
@@ -499,8 +496,30 @@ __global__ __launch_bounds__(kSmallWaves* kWave, 2) void match_small_kernel(Matc
       if (cb < ncb) {                        // uniform over the wavefront
         asm volatile("" ::: "memory");       // the evicted rows are read from LDS again for every block: kept
                                              // in registers beside four blocks of keys they would spill
-        // 1/|k_c| of the 16 columns that this lane's accumulator registers hold in this block
-        const f32x4_t* rn_src = reinterpret_cast<const f32x4_t*>(s_rn + cb * 32 + 4 * half);
+        // 1/|k_c| of this block's columns: each lane squares its half of column l32's channels, the halves
+        // meet, and the 32 values pass through this wavefront's corner of LDS to reach the lanes that hold
+        // the columns' products (registers 4 g + e of a lane: columns 8 g + 4 half + e).  Zero for a column
+        // beyond the list, a negative slot number or a zero key: such a column scores 0.
+        {
+          float ssq = 0.f;
+#pragma unroll
+          for (int ks = 0; ks < KS; ++ks) {
+            const uint32_t w4[4] = {akey[i][ks].x, akey[i][ks].y, akey[i][ks].z, akey[i][ks].w};
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+              const float lo = bf16_lo(w4[e]), hi = bf16_hi(w4[e]);
+              ssq = fmaf(lo, lo, ssq);
+              ssq = fmaf(hi, hi, ssq);
+            }
+          }
+          ssq += __shfl_xor(ssq, 32);
+          const bool real = cb * 32 + l32 < n_keep && slot_ok[i] && ssq > 0.f;
+          if (half == 0) s_rn[wave * 32 + l32] = real ? 1.0f / sqrtf(ssq) : 0.f;
+          __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+          __builtin_amdgcn_wave_barrier();
+          __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        }
+        const f32x4_t* rn_src = reinterpret_cast<const f32x4_t*>(s_rn + wave * 32 + 4 * half);
 #pragma unroll
         for (int t = 0; t < 2; ++t) {        // one 32-row tile after the other: 16 accumulator registers
           f32x16_t acc = {0};
@@ -607,7 +626,6 @@ __global__ void flag_all_kernel(const int32_t* __restrict__ n_evict, int32_t* fl
   }
 }
 
-__global__ void zero_counter_kernel(int32_t* c) { *c = 0; }
 
 // ---------------------------------------------------------------------------------------------------
 // f64 evaluation of queued rows: threads stride over the retained keys (each thread evaluates whole keys,
@@ -748,14 +766,23 @@ __global__ __launch_bounds__(256) void match_exact_kernel(MatchParams p) {
       }
     }
   }
+  // The queue counter is a control word that must be zero when the next call starts.  Every workgroup has
+  // read it by now (the barrier: also the threads that had no work); the last workgroup to get here clears
+  // it, and the exit counter with it.
+  __syncthreads();
+  if (tid == 0 &&
+      __hip_atomic_fetch_add(p.exact_done, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == (int)gridDim.x - 1) {
+    __hip_atomic_store(p.flag_count, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __hip_atomic_store(p.exact_done, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  }
 }
 
 template <int D>
 constexpr size_t mfma_smem_bytes() {
   return 2 * (size_t)kStageCols * (D * 2) + 2 * kStageCols * sizeof(float);
 }
-inline size_t small_smem_bytes(int head_dim, int rn_pitch) {   // evicted rows, per-wavefront results, 1/|k_c|
-  return (size_t)64 * head_dim * 2 + (size_t)kSmallWaves * 64 * 3 * 4 + (size_t)rn_pitch * 4;
+inline size_t small_smem_bytes(int head_dim) {   // evicted rows, per-wavefront results, 1/|k_c| of a block per wavefront
+  return (size_t)64 * head_dim * 2 + (size_t)kSmallWaves * 64 * 3 * 4 + (size_t)kSmallWaves * 32 * 4;
 }
 constexpr int kSmallMaxEvict = 256;   // up to this many evictable slots per head the column-split kernel is used
 
@@ -765,18 +792,19 @@ template <int D>
 keepkv_status launch_bf16(const MatchParams& p, const void* k, unsigned units, hipStream_t st) {
   constexpr int rows_per_block = 256 / (D * 2 / 16);
   const bool small = p.max_evict <= kSmallMaxEvict;
-  rnorm_kernel<uint16_t, D><<<dim3((p.rn_pitch + rows_per_block - 1) / rows_per_block, units), 256, 0, st>>>(
-      (const uint16_t*)k, p.keep_idx, p.n_evict, const_cast<float*>(p.rnorm), p.capacity, p.budget, p.rn_pitch,
-      p.flag_count, small ? nullptr : reinterpret_cast<uint4*>(const_cast<unsigned char*>(p.panel)));
+  if (!small)   // the steady-state kernel forms its own norms
+    rnorm_kernel<uint16_t, D><<<dim3((p.rn_pitch + rows_per_block - 1) / rows_per_block, units), 256, 0, st>>>(
+        (const uint16_t*)k, p.keep_idx, p.n_evict, const_cast<float*>(p.rnorm), p.capacity, p.budget, p.rn_pitch,
+        reinterpret_cast<uint4*>(const_cast<unsigned char*>(p.panel)));
   static const hipError_t a1 = hipFuncSetAttribute((const void*)match_mfma_kernel<D>,
                                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)mfma_smem_bytes<D>());
   static const hipError_t a2 = hipFuncSetAttribute((const void*)match_small_kernel<D>,
                                                    hipFuncAttributeMaxDynamicSharedMemorySize,
-                                                   (int)small_smem_bytes(D, rn_pitch_of(4096)));
+                                                   (int)small_smem_bytes(D));
   if (a1 != hipSuccess || a2 != hipSuccess) return KEEPKV_ERR_DEVICE;
   if (small)
     match_small_kernel<D><<<dim3((p.max_evict + 63) / 64, units), kSmallWaves * kWave,
-                            small_smem_bytes(D, p.rn_pitch), st>>>(p);
+                            small_smem_bytes(D), st>>>(p);
   else {
     // One workgroup fills a compute unit (8 wavefronts of 256 registers).  With fewer heads than compute
     // units each head gets an equal share of them, and a workgroup walks its head's row blocks in passes;
@@ -833,8 +861,10 @@ extern "C" keepkv_status keepkv_match(const keepkv_layout* layout, const keepkv_
   MatchParams p;
   p.k = cache->k; p.keep_idx = keep_idx; p.evict_idx = evict_idx; p.n_evict = n_evict;
   p.rnorm = reinterpret_cast<float*>(reinterpret_cast<char*>(workspace) + pl.rnorm_off);
-  p.flag_count = reinterpret_cast<int32_t*>(reinterpret_cast<char*>(workspace) + pl.flag_off);
-  p.flag_rows = p.flag_count + 64;
+  // queue counter and the f64 kernel's exit counter: control words, zero between calls
+  p.flag_count = reinterpret_cast<int32_t*>(reinterpret_cast<char*>(workspace) + kMatchCountersOff);
+  p.exact_done = p.flag_count + 1;
+  p.flag_rows = reinterpret_cast<int32_t*>(reinterpret_cast<char*>(workspace) + pl.flag_off);
   p.panel = reinterpret_cast<const unsigned char*>(workspace) + pl.panel_off;
   p.exact_partial = reinterpret_cast<ExactPartial*>(reinterpret_cast<char*>(workspace) + pl.partial_off);
   p.exact_ticket = reinterpret_cast<int32_t*>(workspace);
@@ -848,7 +878,6 @@ extern "C" keepkv_status keepkv_match(const keepkv_layout* layout, const keepkv_
   p.delta = 1.6e-5f;
 
   p.rn_pitch = rn_pitch_of(budget);
-  if (layout->dtype != KEEPKV_BF16) zero_counter_kernel<<<1, 1, 0, st>>>(p.flag_count);   // bf16: done by rnorm_kernel
   long eb = (long)units * max_evict / 16;      // queued rows are a small fraction of all rows
   const int exact_blocks = (int)(eb < 64 ? 64 : (eb > 2048 ? 2048 : eb));
   if (layout->dtype == KEEPKV_BF16) {
