@@ -171,9 +171,14 @@ struct MergeParams {
   const int32_t* n_evict;
   const int32_t* start;
   const int32_t* members;
-  int scap, dcap, budget;
+  const int32_t* match;        // the direct variant reads the match and evict lists itself
+  const int32_t* evict_idx;
+  int64_t* dropped_votes;
+  int scap, dcap, budget, max_evict;
   double ln_alpha;
 };
+
+constexpr int kDirectMaxEvict = 256;   // up to this many evictable slots per head no CSR list is built
 
 // ln s_hat_i = ln S_i - ln(1 - alpha^n_i); -inf when never observed
 __device__ __forceinline__ double log_s_hat(float log_s, int n, double ln_alpha) {
@@ -196,9 +201,16 @@ __device__ __forceinline__ double group_sum_f64(double x) {
   return x;
 }
 
-template <typename T, int D>
+// DIRECT (few evictable slots per head, the steady state): no CSR list has been built; the workgroup reads
+// the head's match and evict lists into LDS and every lane group picks its own members out of them, in list
+// (= ascending slot) order, so the summation order is the CSR variant's.  The first workgroup of a head
+// also adds the votes of the unmatched evicted slots to the head's dropped count.
+template <typename T, int D, bool DIRECT>
 __global__ __launch_bounds__(256) void merge_apply_kernel(MergeParams p) {
   constexpr int EPL = 16 / (int)sizeof(T), LPS = D / EPL, GPB = 256 / LPS;
+  __shared__ int s_match[DIRECT ? kDirectMaxEvict : 1], s_evict[DIRECT ? kDirectMaxEvict : 1];
+  __shared__ int s_mem[DIRECT ? GPB : 1][DIRECT ? kDirectMaxEvict : 1];
+  __shared__ long long s_drop;
   const int unit = blockIdx.y;
   const int r = blockIdx.x * GPB + threadIdx.x / LPS;
   const int sub = threadIdx.x % LPS;
@@ -208,12 +220,47 @@ __global__ __launch_bounds__(256) void merge_apply_kernel(MergeParams p) {
     const int n = p.slen[unit];
     p.dlen[unit] = n < p.budget ? n : p.budget;
   }
+  const size_t sbase = (size_t)unit * p.scap, dbase = (size_t)unit * p.dcap;
+  int n_ev = 0;
+  if constexpr (DIRECT) {
+    n_ev = min(p.n_evict[unit], kDirectMaxEvict);
+    if (threadIdx.x == 0) s_drop = 0;
+    for (int i = threadIdx.x; i < n_ev; i += 256) {
+      s_match[i] = p.match[(size_t)unit * p.max_evict + i];
+      s_evict[i] = p.evict_idx[(size_t)unit * p.max_evict + i];
+    }
+    __syncthreads();
+    if (blockIdx.x == 0 && p.dropped_votes != nullptr) {       // uniform over the workgroup
+      long long drop = 0;
+      for (int i = threadIdx.x; i < n_ev; i += 256)
+        if (s_match[i] < 0) drop += p.svotes[sbase + s_evict[i]];
+      if (drop != 0) atomicAdd((unsigned long long*)&s_drop, (unsigned long long)drop);
+      __syncthreads();
+      if (threadIdx.x == 0 && s_drop != 0) p.dropped_votes[unit] += s_drop;   // no other workgroup touches it
+    }
+  }
   if (r >= p.budget) return;
   // two dependent round trips per row: (slot number, member range), then (rows, scalars)
   const int c = p.keep_idx[(size_t)unit * p.budget + r];
-  const int m0 = p.start[(size_t)unit * (p.budget + 1) + r], m1 = p.start[(size_t)unit * (p.budget + 1) + r + 1];
+  int m0 = 0, m1 = 0;
+  if constexpr (!DIRECT) {
+    m0 = p.start[(size_t)unit * (p.budget + 1) + r];
+    m1 = p.start[(size_t)unit * (p.budget + 1) + r + 1];
+  } else {
+    // this group's members: positions of the evict list whose target is r, LPS candidates at a time
+    int* mine = s_mem[threadIdx.x / LPS];
+    for (int i0 = 0; i0 < n_ev; i0 += LPS) {
+      const bool hit = i0 + sub < n_ev && s_match[i0 + sub] == r;
+      const unsigned long long wave_hits = __ballot(hit);
+      const unsigned int hits = (unsigned int)(wave_hits >> gbase) & (unsigned int)((1ull << LPS) - 1ull);   // LPS <= 32
+      if (hit) mine[m1 + __popc(hits & ((1u << sub) - 1u))] = s_evict[i0 + sub];
+      m1 += __popc(hits);
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");   // the list is read back by this group's own lanes
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+  }
   if (c < 0) return;
-  const size_t sbase = (size_t)unit * p.scap, dbase = (size_t)unit * p.dcap;
   const uint4* sk = reinterpret_cast<const uint4*>(p.sk);
   const uint4* sv = reinterpret_cast<const uint4*>(p.sv);
   uint4* dk = reinterpret_cast<uint4*>(p.dk);
@@ -235,7 +282,7 @@ __global__ __launch_bounds__(256) void merge_apply_kernel(MergeParams p) {
     return;
   }
 
-  const int32_t* mem = p.members + sbase + m0;
+  const int32_t* mem = DIRECT ? s_mem[threadIdx.x / LPS] : p.members + sbase + m0;
   const double E_c = log_s_hat(ls_c, n_c, p.ln_alpha);
 
   // pass 1 over the scalars: largest ln s_hat and total votes of the group
@@ -379,23 +426,36 @@ extern "C" keepkv_status keepkv_merge(const keepkv_layout* layout, const keepkv_
                                                        hipFuncAttributeMaxDynamicSharedMemorySize, kMaxEvict * 4);
     if (attr != hipSuccess) return KEEPKV_ERR_DEVICE;
   }
-  merge_group_kernel<<<units, kGroupThreads, key_bytes, st>>>(match, evict_idx, n_evict, src->votes, start, members,
-                                                              dropped_votes, src->capacity, budget, max_evict);
+  const bool direct = max_evict <= kDirectMaxEvict;   // the steady state: the apply kernel finds its members itself
+  if (!direct)
+    merge_group_kernel<<<units, kGroupThreads, key_bytes, st>>>(match, evict_idx, n_evict, src->votes, start, members,
+                                                                dropped_votes, src->capacity, budget, max_evict);
   MergeParams p;
   p.sk = src->k; p.sv = src->v; p.svotes = src->votes; p.slog_s = src->log_s; p.sn_obs = src->n_obs; p.slen = src->len;
   p.dk = dst->k; p.dv = dst->v; p.dvotes = dst->votes; p.dlog_s = dst->log_s; p.dn_obs = dst->n_obs; p.dlen = dst->len;
   p.keep_idx = keep_idx; p.n_evict = n_evict; p.start = start; p.members = members;
-  p.scap = src->capacity; p.dcap = dst->capacity; p.budget = budget;
+  p.match = match; p.evict_idx = evict_idx; p.dropped_votes = dropped_votes;
+  p.scap = src->capacity; p.dcap = dst->capacity; p.budget = budget; p.max_evict = max_evict;
   p.ln_alpha = alpha > 0.f ? log((double)alpha) : -INFINITY;
   const int esz = layout->dtype == KEEPKV_BF16 ? 2 : 4;
   const int lps = layout->head_dim * esz / 16, gpb = 256 / lps;
   const dim3 grid((budget + gpb - 1) / gpb, units);
   if (layout->dtype == KEEPKV_BF16) {
-    if (layout->head_dim == 128) merge_apply_kernel<uint16_t, 128><<<grid, 256, 0, st>>>(p);
-    else merge_apply_kernel<uint16_t, 64><<<grid, 256, 0, st>>>(p);
+    if (layout->head_dim == 128) {
+      if (direct) merge_apply_kernel<uint16_t, 128, true><<<grid, 256, 0, st>>>(p);
+      else merge_apply_kernel<uint16_t, 128, false><<<grid, 256, 0, st>>>(p);
+    } else {
+      if (direct) merge_apply_kernel<uint16_t, 64, true><<<grid, 256, 0, st>>>(p);
+      else merge_apply_kernel<uint16_t, 64, false><<<grid, 256, 0, st>>>(p);
+    }
   } else {
-    if (layout->head_dim == 128) merge_apply_kernel<float, 128><<<grid, 256, 0, st>>>(p);
-    else merge_apply_kernel<float, 64><<<grid, 256, 0, st>>>(p);
+    if (layout->head_dim == 128) {
+      if (direct) merge_apply_kernel<float, 128, true><<<grid, 256, 0, st>>>(p);
+      else merge_apply_kernel<float, 128, false><<<grid, 256, 0, st>>>(p);
+    } else {
+      if (direct) merge_apply_kernel<float, 64, true><<<grid, 256, 0, st>>>(p);
+      else merge_apply_kernel<float, 64, false><<<grid, 256, 0, st>>>(p);
+    }
   }
   return launch_status();
 }
