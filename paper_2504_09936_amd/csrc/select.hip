@@ -8,6 +8,12 @@
 #include "kk_common.hpp"
 
 namespace kk {
+#ifdef KEEPKV_TRACE
+__device__ long long kk_trace_select[16 * 1024];
+#define KS_TS(i) do { if (threadIdx.x == 0 && blockIdx.x < 1024) kk_trace_select[blockIdx.x * 16 + (i)] = wall_clock64(); } while (0)
+#else
+#define KS_TS(i) do { } while (0)
+#endif
 namespace {
 
 constexpr int kSelThreads = 1024;
@@ -18,28 +24,40 @@ __device__ __forceinline__ uint64_t sortable_u64(double x) {
   return (b >> 63) ? ~b : (b | 0x8000000000000000ull);
 }
 
-// exclusive prefix sum over the block (thread order); returns the block total through `total`
-__device__ __forceinline__ int block_excl_scan(int v, int* s_wave, int& total) {
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  int incl = v;
-#pragma unroll
-  for (int off = 1; off < 64; off <<= 1) {
-    const int t = __shfl_up(incl, off);
-    if (lane >= off) incl += t;
-  }
-  __syncthreads();  // s_wave may still be read from a previous call
-  if (lane == 63) s_wave[wave] = incl;
-  __syncthreads();
-  int before = 0, tot = 0;
-  constexpr int nw = kSelThreads / 64;
-#pragma unroll
-  for (int w = 0; w < nw; ++w) {
-    const int t = s_wave[w];
-    before += (w < wave) ? t : 0;
-    tot += t;
-  }
-  total = tot;
-  return before + incl - v;
+template <int CTRL>
+__device__ __forceinline__ uint32_t dpp_u32(uint32_t x) {
+  return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, CTRL, 0xF, 0xF, true);
+}
+// OR over the wavefront, delivered to every lane (quad swaps, mirrors within 8 and 16 lanes, then two exchanges)
+__device__ __forceinline__ uint32_t wave_or(uint32_t x) {
+  x |= dpp_u32<0xB1>(x);
+  x |= dpp_u32<0x4E>(x);
+  x |= dpp_u32<0x141>(x);
+  x |= dpp_u32<0x140>(x);
+  x |= (uint32_t)__shfl_xor((int)x, 16);
+  x |= (uint32_t)__shfl_xor((int)x, 32);
+  return x;
+}
+
+// inclusive prefix sum over the wavefront in lane order: shifts within each row of 16 lanes (lanes without a
+// source add zero), then lane 15 of rows 0 and 2 is added to rows 1 and 3, then lane 31 to rows 2 and 3
+template <int CTRL, int ROWS>
+__device__ __forceinline__ int dpp_add(int x) {
+  return x + __builtin_amdgcn_update_dpp(0, x, CTRL, ROWS, 0xF, true);
+}
+__device__ __forceinline__ int wave_incl_scan(int x) {
+  x = dpp_add<0x111, 0xF>(x);   // row_shr:1
+  x = dpp_add<0x112, 0xF>(x);   // row_shr:2
+  x = dpp_add<0x114, 0xF>(x);   // row_shr:4
+  x = dpp_add<0x118, 0xF>(x);   // row_shr:8
+  x = dpp_add<0x142, 0xA>(x);   // row_bcast:15 into rows 1 and 3
+  x = dpp_add<0x143, 0xC>(x);   // row_bcast:31 into rows 2 and 3
+  return x;
+}
+
+// number of set bits of `mask` below the calling lane
+__device__ __forceinline__ int rank_in_wave(uint64_t mask) {
+  return (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
 }
 
 // EXT: the ranking value is read from a caller-supplied array (passed as log_s; n_obs and votes
@@ -52,13 +70,32 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(
     const int32_t* __restrict__ len, uint64_t* __restrict__ keys, int32_t* __restrict__ keep_idx,
     int32_t* __restrict__ evict_idx, int32_t* __restrict__ n_evict, int capacity, int budget, int n_sink,
     int n_recent, double ln_alpha) {
+  constexpr int kWaves = kSelThreads / 64;
   __shared__ int s_hist[256];
-  __shared__ int s_wave[kSelThreads / 64];
+  __shared__ int s_eq[kWaves], s_kept[kWaves];
+  __shared__ uint64_t s_or[kWaves], s_nand[kWaves];
   __shared__ int s_digit, s_need, s_bucket;
   extern __shared__ __align__(16) uint64_t s_keys[];
 
   const int unit = blockIdx.x;
-  const int tid = threadIdx.x;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  KS_TS(0);
+  const size_t base = (size_t)unit * capacity;
+  const int lo = n_sink;
+  // the first four candidate slots of every thread are requested together with the head's length
+  int nn[4], pv[4];
+  float ls[4];
+  uint64_t k_or = 0, k_nand = 0;              // OR of this thread's keys and of their complements
+  auto request = [&](int i0) {
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int i = min(i0 + u * kSelThreads, capacity - 1);
+      nn[u] = EXT ? 1 : n_obs[base + i];
+      pv[u] = EXT ? 1 : votes[base + i];
+      ls[u] = log_s[base + i];
+    }
+  };
+  request(lo + tid);
   const int n = len[unit];
   int32_t* keep_out = keep_idx + (size_t)unit * budget;
   int32_t* evict_out = evict_idx + (size_t)unit * (capacity - budget);
@@ -69,135 +106,206 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(
     return;
   }
 
-  const size_t base = (size_t)unit * capacity;
+  KS_TS(13);
   uint64_t* key_g = keys + base;
   auto key = [&](int i) -> uint64_t& {
     if constexpr (LDSKEYS) return s_keys[i];
     else return key_g[i];
   };
-  const int lo = n_sink, hi = n - n_recent;   // candidates are [lo, hi)
+  const int hi = n - n_recent;   // candidates are [lo, hi)
   const int n_heavy = budget - n_sink - n_recent;
 
   for (int i0 = lo + tid; i0 < hi; i0 += 4 * kSelThreads) {     // four slots per round trip
-    int nn[4], pv[4];
-    float ls[4];
+    double x[4];
+    if (EXT) {
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
-      const int i = min(i0 + u * kSelThreads, hi - 1);
-      nn[u] = EXT ? 1 : n_obs[base + i];
-      pv[u] = EXT ? 1 : votes[base + i];
-      ls[u] = log_s[base + i];
+      for (int u = 0; u < 4; ++u) x[u] = (ls[u] == ls[u]) ? (double)ls[u] : -INFINITY;     // NaN ranks lowest
+    } else {
+      // ln p + ln S - ln(1 - alpha^n).  ln p is exactly zero for p = 1, and the last term once alpha^n is
+      // below half an ulp of 1: most slots need neither, and the f64 library routines are some hundreds of
+      // instructions each, so a wavefront evaluates them only for the slots where one of its lanes needs it.
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const bool valid = i0 + u * kSelThreads < hi;
+        const double t = (double)nn[u] * ln_alpha;
+        x[u] = (double)ls[u];
+        if (__any(valid && pv[u] != 1)) x[u] = log((double)pv[u]) + x[u];
+        if (__any(valid && t > -40.0)) x[u] -= (t > -40.0) ? log(-expm1(t)) : 0.0;
+      }
+#pragma unroll
+      for (int u = 0; u < 4; ++u)
+        if (nn[u] <= 0) x[u] = -INFINITY;
     }
+    if (i0 + 4 * kSelThreads < hi) request(i0 + 4 * kSelThreads);
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
       const int i = i0 + u * kSelThreads;
       if (i < hi) {
-        double x;
-        if (EXT) {
-          x = (ls[u] == ls[u]) ? (double)ls[u] : -INFINITY;     // NaN ranks lowest
-        } else if (nn[u] <= 0) {
-          x = -INFINITY;
-        } else {
-          x = log((double)pv[u]) + (double)ls[u];
-          if (ln_alpha > -INFINITY) x -= log(-expm1((double)nn[u] * ln_alpha));
-        }
-        key(i) = sortable_u64(x);
+        const uint64_t k = sortable_u64(x[u]);
+        key(i) = k;
+        k_or |= k;
+        k_nand |= ~k;
       }
     }
   }
+  // which bits differ between any two candidate keys of the head
+  {
+    const uint32_t o_lo = wave_or((uint32_t)k_or), o_hi = wave_or((uint32_t)(k_or >> 32));
+    const uint32_t a_lo = wave_or((uint32_t)k_nand), a_hi = wave_or((uint32_t)(k_nand >> 32));
+    if (lane == 0) {
+      s_or[wave] = ((uint64_t)o_hi << 32) | o_lo;
+      s_nand[wave] = ((uint64_t)a_hi << 32) | a_lo;
+    }
+  }
+  if (tid < 256) s_hist[tid] = 0;
   __syncthreads();
+  KS_TS(1);
+  uint64_t all_or = 0, all_nand = 0;
+#pragma unroll
+  for (int w = 0; w < kWaves; ++w) {
+    all_or |= s_or[w];
+    all_nand |= s_nand[w];
+  }
+  const uint64_t varying = all_or & all_nand;      // a bit that is 1 in some key and 0 in another
 
-  // ---- radix select: tau = n_heavy-th largest key, need = how many keys equal to tau are kept
+  // ---- radix select: tau = n_heavy-th largest key, need = how many keys equal to tau are kept.
+  // A digit in which no two keys differ (the sign and exponent bits, as a rule) needs no histogram: it would
+  // put every candidate into one bin, and same-address LDS atomics are served one lane at a time.
   uint64_t prefix = 0;
   int need = n_heavy;
   if (n_heavy > 0) {
+    int n_cand = hi - lo;                             // keys that agree with the prefix so far
+    bool first_hist = true;
     for (int pass = 7; pass >= 0; --pass) {
-      if (tid < 256) s_hist[tid] = 0;
-      __syncthreads();
       const int shift = 8 * pass;
-      for (int i0 = lo + tid; i0 < hi; i0 += 4 * kSelThreads) {   // four keys per round trip
-        uint64_t k4[4];
+      int digit, bucket;
+      if (((varying >> shift) & 255u) == 0) {
+        digit = (int)((all_or >> shift) & 255u);
+        bucket = n_cand;
+      } else {
+        // s_hist is zero here: cleared before the keys' barrier, and by the scan below after each use
+        for (int i0 = lo + tid; i0 < hi; i0 += 4 * kSelThreads) {   // four keys per round trip
+          uint64_t k4[4];
 #pragma unroll
-        for (int u = 0; u < 4; ++u) k4[u] = key(min(i0 + u * kSelThreads, hi - 1));
+          for (int u = 0; u < 4; ++u) k4[u] = key(min(i0 + u * kSelThreads, hi - 1));
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
-          const uint64_t k = k4[u];
-          const bool in = (i0 + u * kSelThreads < hi) && ((pass == 7) || ((k >> (shift + 8)) == prefix));
-          if (in) atomicAdd(&s_hist[(int)((k >> shift) & 255u)], 1);
-        }
-      }
-      __syncthreads();
-      if (tid < 64) {
-        // lane covers digits 255-4*lane .. 252-4*lane, i.e. descending order over lanes
-        int c[4], t = 0;
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-          c[j] = s_hist[255 - 4 * tid - j];
-          t += c[j];
-        }
-        int incl = t;
-#pragma unroll
-        for (int off = 1; off < 64; off <<= 1) {
-          const int u = __shfl_up(incl, off);
-          if (tid >= off) incl += u;
-        }
-        const uint64_t mask = __ballot(incl >= need);
-        const int first = __ffsll((long long)mask) - 1;   // mask != 0: the candidates outnumber `need`
-        if (tid == first) {
-          int run = incl - t;
-#pragma unroll
-          for (int j = 0; j < 4; ++j) {
-            if (run + c[j] >= need) {
-              s_digit = 255 - 4 * tid - j;
-              s_need = need - run;
-              s_bucket = c[j];
-              break;
+          for (int u = 0; u < 4; ++u) {
+            const uint64_t k = k4[u];
+            const bool in = (i0 + u * kSelThreads < hi) && (first_hist || ((k >> (shift + 8)) == prefix));
+            const int d = (int)((k >> shift) & 255u);
+            // leading digits are shared by most keys: the lanes that agree with the first lane's digit add
+            // their count once instead of queueing on one LDS word
+            const uint64_t act = __ballot(in);
+            if (act != 0) {
+              const int first = __ffsll((long long)act) - 1;
+              const int d0 = __builtin_amdgcn_readlane(d, first);
+              const uint64_t same = __ballot(in && d == d0);
+              if (in && d != d0) atomicAdd(&s_hist[d], 1);
+              if (lane == first) atomicAdd(&s_hist[d0], __popcll(same));
             }
-            run += c[j];
           }
         }
+        first_hist = false;
+        __syncthreads();
+        if (tid < 64) {
+          // lane covers digits 255-4*lane .. 252-4*lane, i.e. descending order over lanes
+          int c[4], t = 0;
+#pragma unroll
+          for (int j = 0; j < 4; ++j) {
+            c[j] = s_hist[255 - 4 * tid - j];
+            s_hist[255 - 4 * tid - j] = 0;
+            t += c[j];
+          }
+          const int incl = wave_incl_scan(t);
+          const uint64_t mask = __ballot(incl >= need);
+          const int first = __ffsll((long long)mask) - 1;   // mask != 0: the candidates outnumber `need`
+          if (tid == first) {
+            int run = incl - t;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+              if (run + c[j] >= need) {
+                s_digit = 255 - 4 * tid - j;
+                s_need = need - run;
+                s_bucket = c[j];
+                break;
+              }
+              run += c[j];
+            }
+          }
+        }
+        __syncthreads();          // s_digit is next written behind the next histogram's barrier
+        digit = s_digit;
+        need = s_need;
+        bucket = s_bucket;
       }
-      __syncthreads();
-      prefix = (prefix << 8) | (uint64_t)s_digit;
-      need = s_need;
-      const bool whole_bucket = (s_bucket == need);   // every key with this prefix is kept: stop refining
-      __syncthreads();
-      if (whole_bucket && pass > 0 && prefix != 0) {
-        // keep exactly the keys >= prefix << shift, i.e. key > tau with no equal keys to count
-        prefix = (prefix << shift) - 1;                // prefix != 0 here: the candidates outnumber `need`
+      KS_TS(2 + (7 - pass));
+      prefix = (prefix << 8) | (uint64_t)digit;
+      n_cand = bucket;
+      if (bucket == need && pass > 0 && prefix != 0) {
+        // every key with this prefix is kept: stop refining and keep exactly the keys >= prefix << shift,
+        // i.e. key > tau with no equal keys to count (prefix != 0: the candidates outnumber `need`)
+        prefix = (prefix << shift) - 1;
         need = 0;
         break;
       }
     }
   }
+  KS_TS(10);
   const uint64_t tau = prefix;
   const int need_eq = need;
 
   // ---- ordered compaction ------------------------------------------------------------------------
-  const int ipt = (n + kSelThreads - 1) / kSelThreads;
-  const int i0 = min(n, tid * ipt), i1 = min(n, i0 + ipt);
-  int eq = 0;
-  if (n_heavy > 0)
-    for (int i = max(i0, lo); i < min(i1, hi); ++i) eq += (key(i) == tau);
-  int total;
-  const int eq_start = block_excl_scan(eq, s_wave, total);   // equal keys at lower indices
-  auto kept = [&](int i, int& er) -> bool {
-    if (i < lo || i >= hi) return true;
-    if (n_heavy <= 0) return false;
-    const uint64_t k = key(i);
-    if (k > tau) return true;
-    if (k == tau) return er++ < need_eq;
-    return false;
+  // A wavefront owns a run of 64-slot chunks, lane = slot within the chunk; positions inside a chunk come
+  // from a ballot, the wavefronts exchange their totals through LDS.  Equal keys are kept lowest index first.
+  const int n_chunks = (n + 63) >> 6;
+  const int cpw = (n_chunks + kWaves - 1) / kWaves;
+  const int c0 = min(n_chunks, wave * cpw), c1 = min(n_chunks, c0 + cpw);
+  const bool count_equal = n_heavy > 0 && need_eq > 0;          // uniform over the workgroup
+  int eq_run = 0;
+  if (count_equal) {
+    int cnt = 0;
+    for (int c = c0; c < c1; ++c) {
+      const int i = c * 64 + lane;
+      cnt += __popcll(__ballot(i >= lo && i < hi && key(i) == tau));
+    }
+    if (lane == 0) s_eq[wave] = cnt;
+    __syncthreads();
+    for (int w = 0; w < wave; ++w) eq_run += s_eq[w];          // equal keys at lower indices
+  }
+  // which slots of chunk c are kept; eq advances over the chunk's equal keys
+  auto kept_mask = [&](int c, int& eq) -> uint64_t {
+    const int i = c * 64 + lane;
+    const bool cand = i >= lo && i < hi;
+    const uint64_t k = (cand && n_heavy > 0) ? key(i) : 0;
+    bool kept = i < n && (!cand || (n_heavy > 0 && k > tau));
+    if (count_equal) {                                          // every lane takes part in the ballot
+      const bool is_eq = cand && k == tau;
+      const uint64_t m_eq = __ballot(is_eq);
+      if (is_eq) kept = eq + rank_in_wave(m_eq) < need_eq;
+      eq += __popcll(m_eq);
+    }
+    return __ballot(kept);
   };
-  int nk = 0, er = eq_start;
-  for (int i = i0; i < i1; ++i) nk += kept(i, er);
-  int kpos = block_excl_scan(nk, s_wave, total);             // kept slots at lower indices
-  er = eq_start;
-  for (int i = i0; i < i1; ++i) {
-    if (kept(i, er)) keep_out[kpos++] = i;
-    else evict_out[i - kpos] = i;
+  int nk = 0, eq = eq_run;
+  for (int c = c0; c < c1; ++c) nk += __popcll(kept_mask(c, eq));
+  if (lane == 0) s_kept[wave] = nk;
+  __syncthreads();
+  KS_TS(11);
+  int kpos = 0;
+  for (int w = 0; w < wave; ++w) kpos += s_kept[w];            // kept slots at lower indices
+  eq = eq_run;
+  for (int c = c0; c < c1; ++c) {
+    const int i = c * 64 + lane;
+    const uint64_t m = kept_mask(c, eq);
+    const int at = kpos + rank_in_wave(m);
+    if (i < n) {
+      if ((m >> lane) & 1) keep_out[at] = i;
+      else evict_out[i - at] = i;
+    }
+    kpos += __popcll(m);
   }
   if (tid == 0) n_evict[unit] = n - budget;
+  KS_TS(12);
 }
 
 }  // namespace
@@ -271,3 +379,9 @@ extern "C" keepkv_status keepkv_select_by_key(const keepkv_layout* layout, const
       cache->capacity, budget, n_sink, n_recent, 0.0);
   return launch_status();
 }
+
+#ifdef KEEPKV_TRACE
+extern "C" int keepkv_trace_read_select(long long* host, int n) {
+  return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(kk::kk_trace_select), sizeof(long long) * n);
+}
+#endif
