@@ -275,3 +275,90 @@ def test_degenerate_inputs(alpha):
     c.votes[0, 3] = torch.from_numpy(g.integers(1, 1000, N).astype(np.int32)).cuda()
     _run_compress_stagewise(w, lay, c, ws, alpha, U.f32(-2.0))
     _run_compress_stagewise(w, lay, c, ws, alpha, U.f32(0.8))
+
+
+def _digit_pattern_ranks(cap, seed):
+    """Sixteen ranking arrays, each aimed at one branch of the radix select: digits in which no two keys
+    differ, two heavily repeated values, mixed signs, zeros of both signs and denormals, values that differ
+    only in their last mantissa bits, long tie runs across the selection boundary, infinities and NaN."""
+    g = np.random.default_rng(seed)
+    r = np.zeros((16, cap), dtype=np.float32)
+    r[0] = 1.5
+    r[1] = np.where(np.arange(cap) % 2 == 0, -2.0, 3.0)
+    r[2] = g.standard_normal(cap) * 4
+    r[3] = g.choice(np.array([0.0, -0.0, 1e-45, -1e-45, 3e-39, -3e-39, 1e-38], dtype=np.float32), cap)
+    r[4] = (np.float32(1.0).view(np.uint32) + g.integers(0, 64, cap).astype(np.uint32)).view(np.float32)
+    r[5] = g.integers(0, 16, cap)
+    r[6] = -np.inf
+    r[6, g.integers(0, cap, 30)] = g.standard_normal(30)
+    r[7] = np.nan
+    r[7, g.integers(0, cap, cap // 20)] = g.standard_normal(cap // 20)
+    r[8] = g.standard_normal(cap)
+    r[8, g.integers(0, cap, cap // 2)] = np.inf
+    r[9] = np.arange(cap) * 0.25 - 100
+    r[10] = -np.arange(cap) * 0.25 + 100
+    r[11] = g.standard_normal(cap)
+    r[11, cap // 4: cap // 4 + cap // 3] = 0.125                       # one long run of equal values
+    r[12] = g.standard_normal(cap) * np.where(g.integers(0, 2, cap) == 0, 1e30, 1e-30)
+    r[13] = -7.0
+    r[13, cap // 2] = -6.5
+    r[14] = np.where(g.integers(0, 2, cap) == 0, np.float32(1.0), np.nextafter(np.float32(1.0), np.float32(2.0)))
+    r[15] = g.standard_normal(cap) - 9.0
+    return r
+
+
+@pytest.mark.parametrize("cap,budget,n_sink,n_recent", [
+    (900, 90, 4, 16), (900, 20, 4, 16), (8192 + 37, 820, 4, 64), (8192 + 37, 4096, 0, 0), (20000, 700, 4, 64)])
+def test_select_by_key_digit_patterns(cap, budget, n_sink, n_recent):
+    """Index lists bit for bit those of the oracle for ranking values built to reach every branch of the
+    radix select, at capacities with the keys in LDS and in the workspace, full and ragged lengths,
+    and with no heavy-hitter positions at all (budget = sinks + recent)."""
+    kk = U.kk()
+    B, H = 2, 8
+    lay = kk.Layout(B, 4 * H, H, 128, kk.BF16, 128 ** -0.5)
+    c = kk.Cache(lay, cap)
+    ws = kk.new_workspace(lay, cap, budget)
+    rank = _digit_pattern_ranks(cap, cap + budget).reshape(B, H, cap)
+    g = np.random.default_rng(budget)
+    keep = torch.full((B, H, budget), -7, dtype=torch.int32, device="cuda")
+    evict = torch.full((B, H, cap - budget), -7, dtype=torch.int32, device="cuda")
+    n_ev = torch.full((B, H), -7, dtype=torch.int32, device="cuda")
+    for lens in (np.full((B, H), cap, dtype=np.int32),
+                 g.integers(budget + 1, cap + 1, size=(B, H)).astype(np.int32)):
+        c.len[:] = torch.from_numpy(lens).cuda()
+        kk.select_by_key(lay, c, torch.from_numpy(rank).cuda(), budget, n_sink, n_recent, keep, evict, n_ev, ws)
+        torch.cuda.synchronize()
+        keep_h, evict_h, n_ev_h = keep.cpu().numpy(), evict.cpu().numpy(), n_ev.cpu().numpy()
+        for b in range(B):
+            for h in range(H):
+                n = int(lens[b, h])
+                rk, re = O.select_by_key(rank[b, h], n, budget, n_sink, n_recent)
+                assert n_ev_h[b, h] == len(re), (b, h)
+                assert np.array_equal(keep_h[b, h, :len(rk)], rk), (b, h, n)
+                assert np.array_equal(evict_h[b, h, :len(re)], re), (b, h, n)
+
+
+@pytest.mark.parametrize("alpha", [0.9, 0.999, 0.5])
+def test_select_skips_only_logarithms_that_are_zero(alpha):
+    """The kernel evaluates ln p and ln(1 - alpha^n) only where they are not exactly zero.  Observation counts
+    on both sides of the point where alpha^n drops below half an ulp of 1, slots never observed, and votes
+    of one and of more than one, mixed within and across wavefronts: index lists equal the oracle's."""
+    kk = U.kk()
+    w = W.CONFIGS["llama3_8b"].scaled(batch=2, context=3000)
+    alpha = U.f32(alpha)
+    lay, c = U.new_cache(w, capacity=3000)
+    ws = U.workspace(lay, c.capacity, w.budget)
+    B, H, n = w.batch, w.n_kv_heads, 3000
+    g = np.random.default_rng(11)
+    edge = int(40.0 / -np.log(alpha))
+    n_obs = g.integers(max(1, edge - 40), edge + 40, size=(B, H, n)).astype(np.int32)
+    n_obs[:, :, :1000] = (n - np.arange(1000)).astype(np.int32)        # old slots: the term vanishes (alpha 0.9, 0.5)
+    n_obs[0, :, 1500:1600] = 0                                         # never observed
+    votes = np.ones((B, H, n), dtype=np.int32)
+    votes[:, :, 64:128] = g.integers(1, 9, size=(B, H, 64))            # one wavefront's worth with votes
+    votes[1, :, ::5] = g.integers(2, 50, size=(H, 600))
+    c.n_obs[:] = torch.from_numpy(n_obs).cuda()
+    c.votes[:] = torch.from_numpy(votes).cuda()
+    c.log_s[:] = torch.from_numpy((g.standard_normal((B, H, n)) * 3 - 8).astype(np.float32)).cuda()
+    c.len[:] = n
+    _run_compress_stagewise(w, lay, c, ws, alpha, U.f32(0.8), check_merge=False)
