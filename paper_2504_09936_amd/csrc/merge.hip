@@ -22,6 +22,7 @@ namespace {
 
 constexpr int kGroupThreads = 1024;
 constexpr int kMaxBudget = 4096;
+constexpr int kRankSortMax = 256;      // longest group that is ordered by counting instead of the sorting network
 constexpr int kMaxEvict = 32768;          // sort keys are (target << 15) | position
 constexpr double kEllGuard = 1.0e-3;
 
@@ -31,12 +32,12 @@ constexpr double kEllGuard = 1.0e-3;
 __global__ __launch_bounds__(kGroupThreads) void merge_group_kernel(
     const int32_t* __restrict__ match, const int32_t* __restrict__ evict_idx, const int32_t* __restrict__ n_evict,
     const int32_t* __restrict__ votes, int32_t* __restrict__ start, int32_t* __restrict__ members,
-    int64_t* __restrict__ dropped_votes, int capacity, int budget, int max_evict) {
-  extern __shared__ unsigned int s_key[];          // pow2ceil(max_evict) sort keys
+    int64_t* __restrict__ dropped_votes, int capacity, int budget, int max_evict, int key_words) {
+  extern __shared__ unsigned int s_key[];          // key_words words: pow2ceil(max_evict) sort keys, twice if that fits
   __shared__ int s_cnt[kMaxBudget + 1];
   __shared__ int s_wave[kGroupThreads / 64];
   __shared__ long long s_drop;
-  __shared__ int s_nm;
+  __shared__ int s_nm, s_longest;
   const int unit = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int n_ev = n_evict[unit];
   const int32_t* mt = match + (size_t)unit * max_evict;
@@ -49,24 +50,26 @@ __global__ __launch_bounds__(kGroupThreads) void merge_group_kernel(
   if (tid == 0) {
     s_drop = 0;
     s_nm = 0;
+    s_longest = 0;
   }
   __syncthreads();
   // histogram of targets; matched slots append their key to the (unordered) sort buffer, unmatched
-  // slots give up their votes.  Loads of four slots are issued together.
+  // slots give up their votes.  Loads of eight slots are issued together (two dependent round trips per batch).
   long long drop = 0;
-  for (int j0 = tid; j0 < n_ev; j0 += 4 * kGroupThreads) {
-    int t[4], e[4];
+  constexpr int kBatch = 8;
+  for (int j0 = tid; j0 < n_ev; j0 += kBatch * kGroupThreads) {
+    int t[kBatch], e[kBatch];
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
+    for (int u = 0; u < kBatch; ++u) {
       const int j = min(j0 + u * kGroupThreads, n_ev - 1);
       t[u] = mt[j];
       e[u] = ev[j];
     }
-    int pv[4];
+    int pv[kBatch];
 #pragma unroll
-    for (int u = 0; u < 4; ++u) pv[u] = votes[(size_t)unit * capacity + e[u]];
+    for (int u = 0; u < kBatch; ++u) pv[u] = votes[(size_t)unit * capacity + e[u]];
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
+    for (int u = 0; u < kBatch; ++u) {
       const int j = j0 + u * kGroupThreads;
       if (j < n_ev) {
         if (t[u] >= 0) {
@@ -78,7 +81,10 @@ __global__ __launch_bounds__(kGroupThreads) void merge_group_kernel(
       }
     }
   }
-  if (drop != 0) atomicAdd((unsigned long long*)&s_drop, (unsigned long long)drop);
+  // one LDS add per wavefront: adds to one word are served a lane at a time
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) drop += __shfl_xor(drop, off);
+  if (lane == 0 && drop != 0) atomicAdd((unsigned long long*)&s_drop, (unsigned long long)drop);
   __syncthreads();
   KM_TS(1);
   const int n_matched = s_nm;
@@ -89,8 +95,14 @@ __global__ __launch_bounds__(kGroupThreads) void merge_group_kernel(
   // exclusive scan of s_cnt[0..budget): thread t owns a contiguous run of positions
   const int per = (budget + kGroupThreads - 1) / kGroupThreads;
   const int r0 = min(budget, tid * per), r1 = min(budget, r0 + per);
-  int mine = 0;
-  for (int r = r0; r < r1; ++r) mine += s_cnt[r];
+  int mine = 0, longest = 0;
+  for (int r = r0; r < r1; ++r) {
+    mine += s_cnt[r];
+    longest = max(longest, s_cnt[r]);
+  }
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) longest = max(longest, __shfl_xor(longest, off));
+  if (lane == 0 && longest > 0) atomicMax(&s_longest, longest);
   int incl = mine;
 #pragma unroll
   for (int off = 1; off < 64; off <<= 1) {
@@ -103,13 +115,63 @@ __global__ __launch_bounds__(kGroupThreads) void merge_group_kernel(
   for (int w = 0; w < wave; ++w) before += s_wave[w];
   int run = before + incl - mine;
   for (int r = r0; r < r1; ++r) {
+    const int cnt = s_cnt[r];
     st[r] = run;
-    run += s_cnt[r];
+    s_cnt[r] = run;                                  // from here on: where the group's next member goes
+    run += cnt;
   }
   if (tid == kGroupThreads - 1) st[budget] = run;
   if (tid == 0 && dropped_votes != nullptr && s_drop != 0) dropped_votes[unit] += s_drop;
   KM_TS(2);
   if (n_matched == 0) return;                       // uniform over the block
+
+  if (s_longest <= kRankSortMax && 2 * n2 <= key_words) {   // uniform over the block
+    // Short groups (the rule): every key is dropped into its group's range in arrival order, then takes the
+    // place given by the number of smaller keys in its group.  Three barriers; the sorting network below needs
+    // 91 stages for 8192 keys and takes five times as long.
+    __syncthreads();                                // cursors complete
+    unsigned int* s_place = s_key + n2;             // the keys again, grouped; the launch reserves both halves
+    for (int u0 = 0; u0 * kGroupThreads < n_matched; u0 += 8) {   // eight keys per thread at a time
+      unsigned int mykey[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        const int i = tid + (u0 + u) * kGroupThreads;
+        mykey[u] = i < n_matched ? s_key[i] : 0u;
+      }
+#pragma unroll
+      for (int u = 0; u < 8; ++u)
+        if (tid + (u0 + u) * kGroupThreads < n_matched) s_place[atomicAdd(&s_cnt[mykey[u] >> 15], 1)] = mykey[u];
+    }
+    __syncthreads();                                // s_cnt[r] is now the end of group r
+    for (int u0 = 0; u0 * kGroupThreads < n_matched; u0 += 8) {
+      unsigned int key[8];
+      int slot[8], g0[8], g1[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        const int i = min(tid + (u0 + u) * kGroupThreads, n_matched - 1);
+        key[u] = s_key[i];
+        slot[u] = ev[key[u] & 0x7FFFu];
+        const int r = (int)(key[u] >> 15);
+        g0[u] = r > 0 ? s_cnt[r - 1] : 0;
+        g1[u] = s_cnt[r];
+      }
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        int rank = 0;
+        for (int m = g0[u]; m < g1[u]; m += 4) {    // four members per round trip
+          unsigned int o[4];
+#pragma unroll
+          for (int q = 0; q < 4; ++q) o[q] = s_place[min(m + q, g1[u] - 1)];
+#pragma unroll
+          for (int q = 0; q < 4; ++q) rank += (m + q < g1[u]) && o[q] < key[u];
+        }
+        if (tid + (u0 + u) * kGroupThreads < n_matched) mem[g0[u] + rank] = slot[u];
+      }
+    }
+    KM_TS(3);
+    KM_TS(4);
+    return;
+  }
 
   // bitonic sort, ascending.  Thread i + 1024 m handles pair i of every stage; for strides j <= 64 both
   // elements of all pairs of a wavefront lie in that wavefront's own 128-element blocks, so those stages
@@ -421,7 +483,8 @@ extern "C" keepkv_status keepkv_merge(const keepkv_layout* layout, const keepkv_
 
   size_t key_bytes = 4;
   while (key_bytes < (size_t)max_evict * 4) key_bytes <<= 1;
-  if (key_bytes > 64 * 1024) {
+  if (key_bytes <= kMaxEvict * 4 / 2) key_bytes *= 2;   // room for the grouped copy of the keys (counting path)
+  if (key_bytes > 32 * 1024) {
     static const hipError_t attr = hipFuncSetAttribute((const void*)merge_group_kernel,
                                                        hipFuncAttributeMaxDynamicSharedMemorySize, kMaxEvict * 4);
     if (attr != hipSuccess) return KEEPKV_ERR_DEVICE;
@@ -429,7 +492,8 @@ extern "C" keepkv_status keepkv_merge(const keepkv_layout* layout, const keepkv_
   const bool direct = max_evict <= kDirectMaxEvict;   // the steady state: the apply kernel finds its members itself
   if (!direct)
     merge_group_kernel<<<units, kGroupThreads, key_bytes, st>>>(match, evict_idx, n_evict, src->votes, start, members,
-                                                                dropped_votes, src->capacity, budget, max_evict);
+                                                                dropped_votes, src->capacity, budget, max_evict,
+                                                                (int)(key_bytes / 4));
   MergeParams p;
   p.sk = src->k; p.sv = src->v; p.svotes = src->votes; p.slog_s = src->log_s; p.sn_obs = src->n_obs; p.slen = src->len;
   p.dk = dst->k; p.dv = dst->v; p.dvotes = dst->votes; p.dlog_s = dst->log_s; p.dn_obs = dst->n_obs; p.dlen = dst->len;

@@ -362,3 +362,28 @@ def test_select_skips_only_logarithms_that_are_zero(alpha):
     c.log_s[:] = torch.from_numpy((g.standard_normal((B, H, n)) * 3 - 8).astype(np.float32)).cuda()
     c.len[:] = n
     _run_compress_stagewise(w, lay, c, ws, alpha, U.f32(0.8), check_merge=False)
+
+
+def test_merge_groups_short_long_and_mixed():
+    """keepkv_merge orders each target's members by counting when every group is short and with a sorting
+    network when one is long.  Heads with exact copies of a retained key among the evicted keys (groups of
+    one hundred, of a few hundred and of thousands of members) beside heads with ordinary short groups:
+    every stage equals the oracle, so both orderings give the same ascending member lists."""
+    w = W.CONFIGS["llama3_8b"].scaled(batch=2, context=6000, ratio=0.1)
+    alpha = U.f32(0.9)
+    K, V = W.make_cache(w, 21)
+    g = np.random.default_rng(21)
+    B, H, n = w.batch, w.n_kv_heads, w.context
+    log_s = (g.standard_normal((B, H, n)) * 0.5 - 6).astype(np.float32)
+    log_s[:, :, 100] = 0.0                                  # slot 100 is retained everywhere
+    copies = {(0, 1): 100, (0, 2): 256, (0, 3): 257, (0, 5): 400, (1, 0): 3000, (1, 4): 5200}
+    for (b, h), m in copies.items():
+        K[b, h, 200:200 + m] = K[b, h, 100] * np.where(g.integers(0, 2, m) == 0, 1.0, 2.0)[:, None]
+        log_s[b, h, 200:200 + m] = -30.0                    # all of them evicted
+    lay, c = U.new_cache(w, capacity=n, K=K, V=V)
+    ws = U.workspace(lay, c.capacity, w.budget)
+    c.log_s[:] = torch.from_numpy(log_s).cuda()
+    c.n_obs[:] = 7
+    c.votes[:] = torch.from_numpy(g.integers(1, 4, size=(B, H, n)).astype(np.int32)).cuda()
+    n_matched = _run_compress_stagewise(w, lay, c, ws, alpha, U.f32(0.8))
+    assert n_matched >= sum(copies.values())
