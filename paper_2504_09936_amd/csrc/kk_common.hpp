@@ -110,6 +110,7 @@ struct MatchPlan {
   size_t flag_off;    // int32 [1 + B*Hkv*(capacity-budget)]  counter + flagged row list
   size_t panel_off;   // bf16 [B*Hkv, padded budget, D]  retained keys gathered for the first event's kernel
   size_t partial_off; // per-share results of the f64 kernel when it splits queued rows
+  size_t small_partial_off; // per-share results of the steady-state kernel when workgroups share a row block
   size_t bytes;
 };
 MatchPlan plan_match(const keepkv_layout* L, int capacity, int budget);

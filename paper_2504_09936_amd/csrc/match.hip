@@ -102,6 +102,8 @@ struct MatchParams {
   int capacity, budget, max_evict, rn_pitch;
   float threshold, delta;
   int per_unit, n_units;   // first event's kernel: workgroups per head, heads
+  int small_parts;         // steady-state kernel: workgroups that share the retained list of one 64-row block
+  int32_t* small_partial;  // [row blocks * small_parts][64][3] their per-row results
 };
 
 __device__ __forceinline__ int imax(int a, int b) { return a > b ? a : b; }
@@ -416,6 +418,7 @@ __global__ __launch_bounds__(kMWaves* kWave, 2) void match_mfma_kernel(MatchPara
 // of the first event's kernel (a lane holds one evicted row; class maxima and a (best, second, block) triple).
 constexpr int kSmallWaves = 8;
 constexpr int kSmallBatch = 4;        // column blocks in flight per wavefront
+constexpr int kSmallMaxParts = 4;     // workgroups that may share one 64-row block
 template <int D>
 __global__ __launch_bounds__(kSmallWaves* kWave, 2) void match_small_kernel(MatchParams p) {
   constexpr int KS = D / 16, ROWB = D * 2, CHUNKS = ROWB / 16;
@@ -426,10 +429,11 @@ __global__ __launch_bounds__(kSmallWaves* kWave, 2) void match_small_kernel(Matc
   float* s_rn = reinterpret_cast<float*>(s_top + kSmallWaves * 64 * 3); // [kSmallWaves][32]: a wavefront's current block
 
   const int unit = blockIdx.y;
+  const int part = blockIdx.z, parts = p.small_parts;
   KS_TS(0);
   const int n_ev = p.n_evict[unit];
   const int row_blk = blockIdx.x * 64;
-  if (row_blk >= n_ev) return;
+  if (row_blk >= n_ev) return;                 // all parts of the block alike
   KS_TS(1);
   const int n_keep = p.budget;
   const int tid = threadIdx.x, lane = tid & 63;
@@ -449,10 +453,12 @@ __global__ __launch_bounds__(kSmallWaves* kWave, 2) void match_small_kernel(Matc
     ev_slot[i] = evict[min(row_blk + q / CHUNKS, n_ev - 1)];
   }
   auto col_slot = [&](int cb) { return keep[min(cb * 32 + l32, n_keep - 1)]; };
+  // column blocks of this wavefront: first_cb, first_cb + stride, ...; kSmallBatch of them in flight
+  const int first_cb = part * kSmallWaves + wave, stride = parts * kSmallWaves;
   int slot[kSmallBatch];
   bool slot_ok[kSmallBatch];
 #pragma unroll
-  for (int i = 0; i < kSmallBatch; ++i) slot[i] = col_slot(min(wave + i * kSmallWaves, ncb - 1));
+  for (int i = 0; i < kSmallBatch; ++i) slot[i] = col_slot(min(first_cb + i * stride, ncb - 1));
   // (2) the evicted rows -> LDS; a wavefront instruction deposits 64 consecutive 16-byte chunks
 #pragma unroll
   for (int i = 0; i < ROW_LOADS; ++i) {
@@ -464,16 +470,18 @@ __global__ __launch_bounds__(kSmallWaves* kWave, 2) void match_small_kernel(Matc
   }
   // (3) the first batch of retained keys, as A operands: lane (l32, half) holds chunks 2 ks + half of column l32
   uint4 akey[kSmallBatch][KS];
-  auto request_keys = [&]() {
+  auto request_keys = [&](int cb_first) {
 #pragma unroll
     for (int i = 0; i < kSmallBatch; ++i) {
       slot_ok[i] = slot[i] >= 0;             // (a negative slot number: slot 0 stands in, its column scores 0)
-      const unsigned char* row = kbytes + ((uint32_t)max(slot[i], 0) * ROWB + half * 16);
+      if (cb_first + i * stride < ncb) {     // uniform over the wavefront; blocks beyond the list are not fetched
+        const unsigned char* row = kbytes + ((uint32_t)max(slot[i], 0) * ROWB + half * 16);
 #pragma unroll
-      for (int ks = 0; ks < KS; ++ks) akey[i][ks] = *reinterpret_cast<const uint4*>(row + ks * 32);
+        for (int ks = 0; ks < KS; ++ks) akey[i][ks] = *reinterpret_cast<const uint4*>(row + ks * 32);
+      }
     }
   };
-  request_keys();
+  request_keys(first_cb);
 
   int cls[2][16];
   int b1[2] = {0, 0}, b2[2] = {0, 0}, g1[2] = {0, 0};
@@ -489,10 +497,10 @@ __global__ __launch_bounds__(kSmallWaves* kWave, 2) void match_small_kernel(Matc
   auto efrag = [&](int t, int ks) {          // B operand: evicted row 32 t + l32, chunk (2 ks + half) ^ (row mod CHUNKS)
     return *reinterpret_cast<const bf16x8_t*>(s_rows + ((frag0 ^ (uint32_t)(ks * 32)) + t * 32 * ROWB));
   };
-  for (int cb0 = wave; cb0 < ncb; cb0 += kSmallBatch * kSmallWaves) {
+  for (int cb0 = first_cb; cb0 < ncb; cb0 += kSmallBatch * stride) {
 #pragma unroll
     for (int i = 0; i < kSmallBatch; ++i) {
-      const int cb = cb0 + i * kSmallWaves;
+      const int cb = cb0 + i * stride;
       if (cb < ncb) {                        // uniform over the wavefront
         asm volatile("" ::: "memory");       // the evicted rows are read from LDS again for every block: kept
                                              // in registers beside four blocks of keys they would spill
@@ -543,11 +551,11 @@ __global__ __launch_bounds__(kSmallWaves* kWave, 2) void match_small_kernel(Matc
         }
       }
     }
-    if (cb0 + kSmallBatch * kSmallWaves < ncb) {   // a long retained list: the next batch (its latency is exposed)
+    if (cb0 + kSmallBatch * stride < ncb) {   // a long retained list: the next batch (its latency is exposed)
 #pragma unroll
       for (int i = 0; i < kSmallBatch; ++i)
-        slot[i] = col_slot(min(cb0 + (kSmallBatch + i) * kSmallWaves, ncb - 1));
-      request_keys();
+        slot[i] = col_slot(min(cb0 + (kSmallBatch + i) * stride, ncb - 1));
+      request_keys(cb0 + kSmallBatch * stride);
     }
   }
 
@@ -582,11 +590,8 @@ __global__ __launch_bounds__(kSmallWaves* kWave, 2) void match_small_kernel(Matc
   KS_TS(4);
   if (wave != 0) return;
   const int j = row_blk + lane;
-  if (j >= n_ev) return;
   int v1 = (int)0x80000000, v2 = (int)0x80000000, cc = 0;
-  for (int w = 0; w < kSmallWaves; ++w) {
-    const int* t3 = s_top + (w * 64 + lane) * 3;
-    const int val = t3[0], col = t3[1], val2 = t3[2];
+  auto join = [&](int val, int col, int val2) {      // another share's (best, column, runner-up) for this row
     if (val > v1 || (val == v1 && col < cc)) {
       v2 = imax(v1, val2);
       v1 = val;
@@ -594,7 +599,40 @@ __global__ __launch_bounds__(kSmallWaves* kWave, 2) void match_small_kernel(Matc
     } else {
       v2 = imax(v2, val);
     }
+  };
+  for (int w = 0; w < kSmallWaves; ++w) {
+    const int* t3 = s_top + (w * 64 + lane) * 3;
+    join(t3[0], t3[1], t3[2]);
   }
+  if (parts > 1) {
+    // The workgroups that share this row block meet the way the decode splits do: device-scope stores of the
+    // per-row results, a ticket (a control word at the head of the workspace, zero between calls), and the
+    // last one to arrive joins all shares, in list order, and clears the ticket.
+    const int blk = unit * (int)gridDim.x + (int)blockIdx.x;
+    int32_t* mine = p.small_partial + ((size_t)(blk * parts + part) * 64 + lane) * 3;
+    __hip_atomic_store(mine + 0, v1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __hip_atomic_store(mine + 1, cc, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __hip_atomic_store(mine + 2, v2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");          // the wavefront's stores have completed
+    int ticket = 0;
+    if (lane == 0) ticket = __hip_atomic_fetch_add(&p.exact_ticket[blk], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    ticket = __builtin_amdgcn_readfirstlane(ticket);
+    if (ticket != parts - 1) return;
+    v1 = (int)0x80000000; v2 = (int)0x80000000; cc = 0;
+    int val[kSmallMaxParts], col[kSmallMaxParts], val2[kSmallMaxParts];
+#pragma unroll
+    for (int q = 0; q < kSmallMaxParts; ++q) {       // one round trip for all shares
+      const int32_t* r = p.small_partial + ((size_t)(blk * parts + min(q, parts - 1)) * 64 + lane) * 3;
+      val[q] = __hip_atomic_load(r + 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      col[q] = __hip_atomic_load(r + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      val2[q] = __hip_atomic_load(r + 2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+#pragma unroll
+    for (int q = 0; q < kSmallMaxParts; ++q)
+      if (q < parts) join(val[q], col[q], val2[q]);
+    if (lane == 0) __hip_atomic_store(&p.exact_ticket[blk], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  }
+  if (j >= n_ev) return;
   // |k_e|^2 of this lane's row, from the LDS copy
   float ss = 0.f;
   {
@@ -785,6 +823,7 @@ inline size_t small_smem_bytes(int head_dim) {   // evicted rows, per-wavefront 
   return (size_t)64 * head_dim * 2 + (size_t)kSmallWaves * 64 * 3 * 4 + (size_t)kSmallWaves * 32 * 4;
 }
 constexpr int kSmallMaxEvict = 256;   // up to this many evictable slots per head the column-split kernel is used
+constexpr int kSmallMaxShares = 256;  // workgroups of that kernel when row blocks are shared (one per compute unit)
 
 inline int rn_pitch_of(int budget) { return (budget + kStageCols - 1) / kStageCols * kStageCols; }
 
@@ -802,10 +841,18 @@ keepkv_status launch_bf16(const MatchParams& p, const void* k, unsigned units, h
                                                    hipFuncAttributeMaxDynamicSharedMemorySize,
                                                    (int)small_smem_bytes(D));
   if (a1 != hipSuccess || a2 != hipSuccess) return KEEPKV_ERR_DEVICE;
-  if (small)
-    match_small_kernel<D><<<dim3((p.max_evict + 63) / 64, units), kSmallWaves * kWave,
-                            small_smem_bytes(D), st>>>(p);
-  else {
+  if (small) {
+    // With few heads the row blocks alone leave most compute units idle, and one compute unit takes long to
+    // pull a head's whole retained list: up to four workgroups share a row block, each over every fourth
+    // batch of column blocks, as long as all of them are resident at once.
+    const int row_blocks = (p.max_evict + 63) / 64, ncb = (p.budget + 31) / 32;
+    int parts = 1;
+    while (parts < kSmallMaxParts && (long)units * row_blocks * (parts * 2) <= kSmallMaxShares && parts * 2 * kSmallWaves < ncb + kSmallWaves)
+      parts *= 2;
+    MatchParams q = p;
+    q.small_parts = parts;
+    match_small_kernel<D><<<dim3(row_blocks, units, parts), kSmallWaves * kWave, small_smem_bytes(D), st>>>(q);
+  } else {
     // One workgroup fills a compute unit (8 wavefronts of 256 registers).  With fewer heads than compute
     // units each head gets an equal share of them, and a workgroup walks its head's row blocks in passes;
     // with more heads than that, one workgroup per head does all passes.
@@ -831,7 +878,8 @@ MatchPlan plan_match(const keepkv_layout* L, int capacity, int budget) {
   // the panel is used by bf16 caches with more evictable slots than the column-split kernel takes
   const bool panel = L->dtype == KEEPKV_BF16 && capacity - budget > kSmallMaxEvict;
   pl.partial_off = pl.panel_off + (panel ? align_up(units * rn_pitch_of(budget) * (size_t)L->head_dim * 2, 256) : 0);
-  pl.bytes = pl.partial_off + (size_t)kExactResident * 16;
+  pl.small_partial_off = pl.partial_off + (size_t)kExactResident * 16;
+  pl.bytes = pl.small_partial_off + (size_t)kSmallMaxShares * 64 * 3 * sizeof(int32_t);
   return pl;
 }
 
@@ -868,6 +916,8 @@ extern "C" keepkv_status keepkv_match(const keepkv_layout* layout, const keepkv_
   p.panel = reinterpret_cast<const unsigned char*>(workspace) + pl.panel_off;
   p.exact_partial = reinterpret_cast<ExactPartial*>(reinterpret_cast<char*>(workspace) + pl.partial_off);
   p.exact_ticket = reinterpret_cast<int32_t*>(workspace);
+  p.small_parts = 1;
+  p.small_partial = reinterpret_cast<int32_t*>(reinterpret_cast<char*>(workspace) + pl.small_partial_off);
   p.match = match; p.sim_out = sim_out;
   p.capacity = cache->capacity; p.budget = budget; p.max_evict = max_evict;
   p.threshold = threshold;

@@ -387,3 +387,19 @@ def test_merge_groups_short_long_and_mixed():
     c.votes[:] = torch.from_numpy(g.integers(1, 4, size=(B, H, n)).astype(np.int32)).cuda()
     n_matched = _run_compress_stagewise(w, lay, c, ws, alpha, U.f32(0.8))
     assert n_matched >= sum(copies.values())
+
+
+@pytest.mark.parametrize("batch,period,budget_slots", [(1, 64, 820), (16, 64, 820), (17, 64, 820), (2, 200, 300), (4, 64, 40)])
+def test_steady_state_match_shared_row_blocks(batch, period, budget_slots):
+    """A period's worth of evictable slots per head.  With few heads up to four workgroups share the retained
+    list of a 64-row block and join their per-row results through a ticket; with many heads a block has one
+    workgroup.  8, 128 and 136 heads, several row blocks, a retained list shorter than the shares' column
+    batches: every stage equals the oracle, twice in a row on the same workspace (the tickets return to zero)."""
+    n = budget_slots + period
+    w = W.CONFIGS["llama3_8b"].scaled(batch=batch, context=n, ratio=(budget_slots - 0.5) / n, period=period)
+    assert w.budget == budget_slots
+    alpha = U.f32(0.9)
+    lay, c, ws = _observed_cache(w, 31 + batch, 2, alpha, dup=True)
+    for rep in range(2):
+        n_matched = _run_compress_stagewise(w, lay, c, ws, alpha, U.f32(0.5), check_merge=(rep == 0 and batch <= 4))
+    assert n_matched > 0
