@@ -46,41 +46,53 @@ constexpr int kXcds = 8;                                // accelerator dies, eac
 // also copied there in list order, rn_pitch rows per head (padding rows zero), each row with its 16-byte
 // chunk c stored at position c ^ (row mod chunks): the LDS image that the first event's kernel wants, so
 // that its stage loads are straight copies that need no slot index.
+constexpr int kRnormRows = 4;
 template <typename T, int D>
 __global__ __launch_bounds__(256) void rnorm_kernel(const T* __restrict__ k, const int32_t* __restrict__ keep_idx,
                                                     const int32_t* __restrict__ n_evict, float* __restrict__ rnorm,
                                                     int capacity, int budget, int rn_pitch, uint4* __restrict__ panel) {
-  constexpr int EPL = 16 / (int)sizeof(T), LPS = D / EPL;
+  constexpr int EPL = 16 / (int)sizeof(T), LPS = D / EPL, RPB = 256 / LPS;
   const int unit = blockIdx.y;
-  if (n_evict[unit] <= 0) return;
-  const int r = blockIdx.x * (256 / LPS) + threadIdx.x / LPS;
   const int sub = threadIdx.x % LPS;
-  if (r >= rn_pitch) return;
-  const bool valid = r < budget;
-  const int slot = valid ? keep_idx[(size_t)unit * budget + r] : 0;
-  float ss = 0.f;
-  uint4 x = make_uint4(0, 0, 0, 0);
-  if (valid && slot >= 0) {
-    x = reinterpret_cast<const uint4*>(k)[((size_t)unit * capacity + slot) * LPS + sub];
-    if constexpr (sizeof(T) == 2) {
-      const uint32_t w[4] = {x.x, x.y, x.z, x.w};
+  // kRnormRows rows per lane group, all requested before the first wait (slot numbers beside the head's
+  // eviction count, then the rows)
+  int r[kRnormRows], slot[kRnormRows];
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const float a = bf16_lo(w[i]), b = bf16_hi(w[i]);
+  for (int i = 0; i < kRnormRows; ++i) {
+    r[i] = (blockIdx.x * kRnormRows + i) * RPB + threadIdx.x / LPS;
+    slot[i] = r[i] < budget ? keep_idx[(size_t)unit * budget + r[i]] : -1;
+  }
+  if (n_evict[unit] <= 0) return;
+  uint4 x[kRnormRows];
+#pragma unroll
+  for (int i = 0; i < kRnormRows; ++i) {
+    x[i] = make_uint4(0, 0, 0, 0);
+    if (slot[i] >= 0) x[i] = reinterpret_cast<const uint4*>(k)[((size_t)unit * capacity + slot[i]) * LPS + sub];
+  }
+#pragma unroll
+  for (int i = 0; i < kRnormRows; ++i) {
+    if (r[i] >= rn_pitch) continue;              // whole lane groups
+    float ss = 0.f;
+    if constexpr (sizeof(T) == 2) {
+      const uint32_t w[4] = {x[i].x, x[i].y, x[i].z, x[i].w};
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const float a = bf16_lo(w[e]), b = bf16_hi(w[e]);
         ss = fmaf(a, a, ss);
         ss = fmaf(b, b, ss);
       }
     } else {
-      const float w[4] = {__builtin_bit_cast(float, x.x), __builtin_bit_cast(float, x.y),
-                          __builtin_bit_cast(float, x.z), __builtin_bit_cast(float, x.w)};
+      const float w[4] = {__builtin_bit_cast(float, x[i].x), __builtin_bit_cast(float, x[i].y),
+                          __builtin_bit_cast(float, x[i].z), __builtin_bit_cast(float, x[i].w)};
 #pragma unroll
-      for (int i = 0; i < 4; ++i) ss = fmaf(w[i], w[i], ss);
+      for (int e = 0; e < 4; ++e) ss = fmaf(w[e], w[e], ss);
     }
+    if (panel != nullptr) panel[((size_t)unit * rn_pitch + r[i]) * LPS + (sub ^ (r[i] & (LPS - 1)))] = x[i];
+    ss = group_sum<LPS>(ss);
+    // positions budget .. rn_pitch - 1 are padding: zero, so padded columns score 0; so do zero keys and
+    // negative slot numbers
+    if (sub == 0) rnorm[(size_t)unit * rn_pitch + r[i]] = ss > 0.f ? 1.0f / sqrtf(ss) : 0.f;
   }
-  if (panel != nullptr) panel[((size_t)unit * rn_pitch + r) * LPS + (sub ^ (r & (LPS - 1)))] = x;
-  ss = group_sum<LPS>(ss);
-  // positions budget .. rn_pitch - 1 are padding: zero, so padded columns score 0
-  if (sub == 0) rnorm[(size_t)unit * rn_pitch + r] = (valid && ss > 0.f && slot >= 0) ? 1.0f / sqrtf(ss) : 0.f;
 }
 
 // ---------------------------------------------------------------------------------------------------
@@ -832,7 +844,7 @@ keepkv_status launch_bf16(const MatchParams& p, const void* k, unsigned units, h
   constexpr int rows_per_block = 256 / (D * 2 / 16);
   const bool small = p.max_evict <= kSmallMaxEvict;
   if (!small)   // the steady-state kernel forms its own norms
-    rnorm_kernel<uint16_t, D><<<dim3((p.rn_pitch + rows_per_block - 1) / rows_per_block, units), 256, 0, st>>>(
+    rnorm_kernel<uint16_t, D><<<dim3((p.rn_pitch + rows_per_block * kRnormRows - 1) / (rows_per_block * kRnormRows), units), 256, 0, st>>>(
         (const uint16_t*)k, p.keep_idx, p.n_evict, const_cast<float*>(p.rnorm), p.capacity, p.budget, p.rn_pitch,
         reinterpret_cast<uint4*>(const_cast<unsigned char*>(p.panel)));
   static const hipError_t a1 = hipFuncSetAttribute((const void*)match_mfma_kernel<D>,
@@ -929,7 +941,7 @@ extern "C" keepkv_status keepkv_match(const keepkv_layout* layout, const keepkv_
 
   p.rn_pitch = rn_pitch_of(budget);
   long eb = (long)units * max_evict / 16;      // queued rows are a small fraction of all rows
-  const int exact_blocks = (int)(eb < 64 ? 64 : (eb > 2048 ? 2048 : eb));
+  const int exact_blocks = (int)(eb < 64 ? 64 : (eb > 512 ? 512 : eb));   // every workgroup ends with one add to a shared counter
   if (layout->dtype == KEEPKV_BF16) {
     keepkv_status rc;
     if (layout->head_dim == 128) {
