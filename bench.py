@@ -45,8 +45,11 @@ def parse():
     ap.add_argument("--threshold", type=float, default=None, help="merging threshold T (default: workload's, 0.8)")
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying a HIP graph")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--no-overlap", action="store_true",
-                    help="compress on the decode stream, all layers in the same round (no staggering, no second stream)")
+    ap.add_argument("--overlap", choices=("auto", "on", "off"), default="auto",
+                    help="run each compression event on a second stream beside the other layers' decode steps.  "
+                         "A branch to a second queue costs the decode stream 20-35 us per event whatever its length, "
+                         "an event on the decode stream its own 50-60 us: auto overlaps when events are frequent "
+                         "(period <= 32), where the side stream also has to hide several events at once")
     ap.add_argument("--unfused", action="store_true",
                     help="use keepkv_append + keepkv_decode_attn + keepkv_score instead of keepkv_decode_step")
     ap.add_argument("--window", type=int, default=None, help="observation passes before the first event")
@@ -84,6 +87,7 @@ def main():
         w = w.scaled(window=args.window)
     R, K, Wm = args.layers, args.steps, args.warmup
     B, Hq, H, D, P, Bud, N = w.batch, w.n_q_heads, w.n_kv_heads, w.head_dim, w.period, w.budget, w.context
+    args.overlap = args.overlap == "on" or (args.overlap == "auto" and P <= 32)
     alpha = float(np.float32(w.alpha))
     T = float(np.float32(w.threshold if args.threshold is None else args.threshold))
     bf16 = w.dtype == "bf16"
@@ -185,10 +189,10 @@ def main():
     step_no = [0] * R          # decode steps done per layer
     n_events = 0
     # Compression phases are staggered over the layers (layer L's first period is shorter by L*P/R steps), so
-    # that the events are spread evenly over the steps instead of all layers compressing in the same round;
-    # each event then runs on a second stream next to the decode steps of the other layers.  A layer's next
-    # decode step waits for its own event only.
-    since = [0 if args.no_overlap else (layer * P) // R for layer in range(R)]   # steps since the layer's last event
+    # that the events are spread evenly over the steps instead of all layers compressing in the same round.
+    # With --overlap each event runs on a second stream next to the decode steps of the other layers, and a
+    # layer's next decode step waits for its own event only.
+    since = [(layer * P) // R for layer in range(R)]   # steps since the layer's last event
     side = torch.cuda.Stream()
     ws_side = kk.new_workspace(lay, N, Bud)
     pending = [None] * R
@@ -240,7 +244,7 @@ def main():
         since[layer] += 1
         if since[layer] == P:
             d = caches[layer][1 - cur[layer]]
-            if args.no_overlap:
+            if not args.overlap:
                 compress(c, d, layer, ws)
             else:
                 fork = torch.cuda.Event()
@@ -251,7 +255,7 @@ def main():
             n_events += 1
 
     def join_side():
-        if not args.no_overlap:
+        if args.overlap:
             launch_deferred()
             torch.cuda.current_stream().wait_stream(side)
             for layer in range(R):
@@ -458,7 +462,7 @@ def main():
         "config": {"workload": f"{w.name}: B={B} Hq={Hq} Hkv={H} D={D} {w.dtype}, context {N} -> budget {Bud} "
                                f"({w.ratio:.0%}), period {P}, T={T:g}, alpha={alpha:g}",
                    "layers_rotated": R, "graph": not args.no_graph, "fused_step": not args.unfused, "compress_events_timed": timed_events,
-                   "compress_overlapped": not args.no_overlap},
+                   "compress_overlapped": args.overlap},
         "roofline": roofline,
         "cpu_baseline": cpu,
         "kernels_us": {

@@ -1,6 +1,7 @@
-"""GPU check of the launch configuration that bench.py times: decode steps of several layers in rotation inside one
-HIP graph, each layer's compression event on a second stream beside the other layers' steps (enqueued one
-step late, joined before the layer's next step), index lists and the side workspace shared by all events.
+"""GPU check of the launch configurations that bench.py times: decode steps of several layers in rotation inside one
+HIP graph, each layer's compression event either on the same stream or on a second stream beside the other
+layers' steps (enqueued one step late, joined before the layer's next step), index lists and the side
+workspace shared by all events.
 The same sequence launched eagerly on a single stream must leave every cache in the same state bit for bit
 (all kernels are deterministic), whatever the streams overlap; the eager sequence itself is what the other
 GPU tests compare with the oracle.  The graph is replayed from identical starting states several times, with
@@ -26,8 +27,8 @@ def _state(caches, cur, dropped):
     return out
 
 
-@pytest.mark.parametrize("period,layers", [(8, 4), (5, 3)])
-def test_graph_with_side_stream_equals_eager_single_stream(period, layers):
+@pytest.mark.parametrize("period,layers,overlap", [(8, 4, True), (5, 3, True), (8, 4, False)])
+def test_graph_equals_eager_single_stream(period, layers, overlap):
     kk = U.kk()
     w = W.CONFIGS["llama3_8b"].scaled(batch=2, context=400, ratio=0.25, period=period)
     B, H, Hq, D, Bud, P, R = w.batch, w.n_kv_heads, w.n_q_heads, w.head_dim, w.budget, period, layers
@@ -120,14 +121,14 @@ def test_graph_with_side_stream_equals_eager_single_stream(period, layers):
     ref = _state(caches_a, cur_a, dropped_a)
     assert int(dropped_a.sum().item()) >= 0 and all(int(c[cu].len.max().item()) <= cap for c, cu in zip(caches_a, cur_a))
 
-    # one graph, events on a side stream; replayed three times from the same starting state
+    # one graph, events on a side stream or in line; replayed three times from the same starting state
     caches_b, dropped_b = fresh(), torch.zeros(R, B, H, dtype=torch.int64, device="cuda")
     start = [[[t.clone() for t in (c.k, c.v, c.votes, c.log_s, c.n_obs, c.len)] for c in pair] for pair in caches_b]
     stream, side = torch.cuda.Stream(), torch.cuda.Stream()
     graph = torch.cuda.CUDAGraph()
     torch.cuda.synchronize()
     with torch.cuda.graph(graph, stream=stream):
-        cur_b = run(caches_b, dropped_b, True, side)
+        cur_b = run(caches_b, dropped_b, overlap, side)
     assert cur_b == cur_a
     for replay in range(3):
         for pair, saved in zip(caches_b, start):          # eager work between the replays: restore the state
