@@ -17,6 +17,7 @@ __device__ long long kk_trace_select[16 * 1024];
 namespace {
 
 constexpr int kSelThreads = 1024;
+constexpr int kTermTable = 2048;       // ln(1 - alpha^n) is tabulated for n below this (alpha up to 0.98 in full)
 
 __device__ __forceinline__ uint64_t sortable_u64(double x) {
   x = x + 0.0;  // -0.0 -> +0.0
@@ -69,8 +70,9 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(
     const float* __restrict__ log_s, const int32_t* __restrict__ n_obs, const int32_t* __restrict__ votes,
     const int32_t* __restrict__ len, uint64_t* __restrict__ keys, int32_t* __restrict__ keep_idx,
     int32_t* __restrict__ evict_idx, int32_t* __restrict__ n_evict, int capacity, int budget, int n_sink,
-    int n_recent, double ln_alpha) {
+    int n_recent, double ln_alpha, int n_table) {
   constexpr int kWaves = kSelThreads / 64;
+  __shared__ double s_lnterm[EXT ? 1 : kTermTable];
   __shared__ int s_hist[256];
   __shared__ int s_eq[kWaves], s_kept[kWaves];
   __shared__ uint64_t s_or[kWaves], s_nand[kWaves];
@@ -107,6 +109,13 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(
   }
 
   KS_TS(13);
+  // ln(1 - alpha^n) depends on the observation count alone, and the f64 library routines behind it are some
+  // hundreds of instructions: one evaluation per count (n_table of them: beyond, the term rounds to zero)
+  // instead of one per slot
+  if constexpr (!EXT) {
+    for (int m = tid; m < n_table; m += kSelThreads) s_lnterm[m] = m > 0 ? log(-expm1((double)m * ln_alpha)) : 0.0;
+    __syncthreads();
+  }
   uint64_t* key_g = keys + base;
   auto key = [&](int i) -> uint64_t& {
     if constexpr (LDSKEYS) return s_keys[i];
@@ -122,15 +131,18 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(
       for (int u = 0; u < 4; ++u) x[u] = (ls[u] == ls[u]) ? (double)ls[u] : -INFINITY;     // NaN ranks lowest
     } else {
       // ln p + ln S - ln(1 - alpha^n).  ln p is exactly zero for p = 1, and the last term once alpha^n is
-      // below half an ulp of 1: most slots need neither, and the f64 library routines are some hundreds of
-      // instructions each, so a wavefront evaluates them only for the slots where one of its lanes needs it.
+      // below half an ulp of 1; a wavefront evaluates ln p only for the slots where one of its lanes needs it
+      // and takes the last term from the table.
 #pragma unroll
       for (int u = 0; u < 4; ++u) {
         const bool valid = i0 + u * kSelThreads < hi;
         const double t = (double)nn[u] * ln_alpha;
         x[u] = (double)ls[u];
         if (__any(valid && pv[u] != 1)) x[u] = log((double)pv[u]) + x[u];
-        if (__any(valid && t > -40.0)) x[u] -= (t > -40.0) ? log(-expm1(t)) : 0.0;
+        const bool need = t > -40.0, listed = nn[u] > 0 && nn[u] < n_table;
+        double term = (need && listed) ? s_lnterm[nn[u]] : 0.0;
+        if (__any(valid && need && !listed)) term = (need && !listed) ? log(-expm1(t)) : term;   // alpha close to 1
+        x[u] -= term;
       }
 #pragma unroll
       for (int u = 0; u < 4; ++u)
@@ -316,15 +328,23 @@ template <bool EXT>
 void launch_select(int units, hipStream_t st, const float* log_s, const int32_t* n_obs, const int32_t* votes,
                    const int32_t* len, uint64_t* keys, int32_t* keep_idx, int32_t* evict_idx, int32_t* n_evict,
                    int capacity, int budget, int n_sink, int n_recent, double ln_alpha) {
+  // counts from which alpha^n is below half an ulp of 1 (n ln alpha <= -40) need no table entry
+  int n_table = 0;
+  if (!EXT && ln_alpha > -INFINITY && ln_alpha < 0.0) {
+    const double n_zero = ceil(40.0 / -ln_alpha) + 1.0;
+    n_table = n_zero < (double)kTermTable ? (int)n_zero : kTermTable;
+  }
   if (capacity <= kSelLdsKeys) {
     static const hipError_t attr = hipFuncSetAttribute((const void*)select_kernel<EXT, true>,
                                                        hipFuncAttributeMaxDynamicSharedMemorySize, kSelLdsKeys * 8);
     (void)attr;                              // a refusal shows up as a launch error
     select_kernel<EXT, true><<<units, kSelThreads, (size_t)capacity * 8, st>>>(
-        log_s, n_obs, votes, len, keys, keep_idx, evict_idx, n_evict, capacity, budget, n_sink, n_recent, ln_alpha);
+        log_s, n_obs, votes, len, keys, keep_idx, evict_idx, n_evict, capacity, budget, n_sink, n_recent, ln_alpha,
+        n_table);
   } else {
     select_kernel<EXT, false><<<units, kSelThreads, 0, st>>>(
-        log_s, n_obs, votes, len, keys, keep_idx, evict_idx, n_evict, capacity, budget, n_sink, n_recent, ln_alpha);
+        log_s, n_obs, votes, len, keys, keep_idx, evict_idx, n_evict, capacity, budget, n_sink, n_recent, ln_alpha,
+        n_table);
   }
 }
 
