@@ -17,6 +17,7 @@ __device__ long long kk_trace_select[16 * 1024];
 namespace {
 
 constexpr int kSelThreads = 1024;
+constexpr int kVotesTable = 256;       // ln p is tabulated for vote counts below this
 constexpr int kTermTable = 2048;       // ln(1 - alpha^n) is tabulated for n below this (alpha up to 0.98 in full)
 
 __device__ __forceinline__ uint64_t sortable_u64(double x) {
@@ -73,6 +74,7 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(
     int n_recent, double ln_alpha, int n_table) {
   constexpr int kWaves = kSelThreads / 64;
   __shared__ double s_lnterm[EXT ? 1 : kTermTable];
+  __shared__ double s_lnvotes[EXT ? 1 : kVotesTable];
   __shared__ int s_hist[256];
   __shared__ int s_eq[kWaves], s_kept[kWaves];
   __shared__ uint64_t s_or[kWaves], s_nand[kWaves];
@@ -114,6 +116,8 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(
   // instead of one per slot
   if constexpr (!EXT) {
     for (int m = tid; m < n_table; m += kSelThreads) s_lnterm[m] = m > 0 ? log(-expm1((double)m * ln_alpha)) : 0.0;
+    // (the last wavefronts take the votes table: the first ones have the other one's entries)
+    if (tid >= kSelThreads - kVotesTable) s_lnvotes[kSelThreads - 1 - tid] = log((double)(kSelThreads - 1 - tid));
     __syncthreads();
   }
   uint64_t* key_g = keys + base;
@@ -130,15 +134,16 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(
 #pragma unroll
       for (int u = 0; u < 4; ++u) x[u] = (ls[u] == ls[u]) ? (double)ls[u] : -INFINITY;     // NaN ranks lowest
     } else {
-      // ln p + ln S - ln(1 - alpha^n).  ln p is exactly zero for p = 1, and the last term once alpha^n is
-      // below half an ulp of 1; a wavefront evaluates ln p only for the slots where one of its lanes needs it
-      // and takes the last term from the table.
+      // ln p + ln S - ln(1 - alpha^n), the two logarithms from the tables; a wavefront evaluates them itself
+      // only where one of its lanes has a count beyond a table.
 #pragma unroll
       for (int u = 0; u < 4; ++u) {
         const bool valid = i0 + u * kSelThreads < hi;
         const double t = (double)nn[u] * ln_alpha;
         x[u] = (double)ls[u];
-        if (__any(valid && pv[u] != 1)) x[u] = log((double)pv[u]) + x[u];
+        const bool small_p = pv[u] >= 1 && pv[u] < kVotesTable;
+        if (__any(valid && !small_p)) x[u] = (small_p ? s_lnvotes[pv[u]] : log((double)pv[u])) + x[u];
+        else x[u] = s_lnvotes[small_p ? pv[u] : 1] + x[u];
         const bool need = t > -40.0, listed = nn[u] > 0 && nn[u] < n_table;
         double term = (need && listed) ? s_lnterm[nn[u]] : 0.0;
         if (__any(valid && need && !listed)) term = (need && !listed) ? log(-expm1(t)) : term;   // alpha close to 1
