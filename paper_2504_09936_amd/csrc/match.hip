@@ -7,7 +7,8 @@
 // head dimension) in registers for a pass and the panel streams through LDS in 128-column stages.
 // Every 32x32 f32 accumulator tile is reduced on the spot (scale by 1/|k_c|, running maxima); the
 // similarity matrix is never written.  Steady state (one period's worth of evicted rows): a workgroup
-// of 8 wavefronts per 64 rows, the columns split over the wavefronts.
+// of 8 wavefronts per 64 rows, the columns split over the wavefronts (and, with few heads, over up to
+// four such workgroups that join their results through a ticket).
 //
 // Exactness: the f32 result decides a row only when the best value leads the second by more than
 // the rounding envelope and is away from the threshold by as much; all other rows (a fraction of a

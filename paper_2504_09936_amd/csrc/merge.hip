@@ -3,9 +3,11 @@
 // destination cache.
 //
 // Two kernels.  (1) Per head, the evicted slots are grouped by merge target into a CSR list: an LDS
-// histogram of match[], a block scan for the row starts, and a bitonic sort of (target, position)
-// keys in LDS, so every group lists its members in ascending slot order (deterministic summation
-// order, no float atomics).  (2) One lane group (LPS lanes, 16 bytes of a row each) per retained
+// histogram of match[], a block scan for the row starts, and the (target, position) keys put in
+// order in LDS (by counting inside each group when all groups are short, else by a bitonic network),
+// so every group lists its members in ascending slot order (deterministic summation order, no float
+// atomics).  With few evictable slots per head this kernel is not launched: the second one finds each
+// group's members in the match list itself.  (2) One lane group (LPS lanes, 16 bytes of a row each) per retained
 // position gathers its group: the merge weights w_i = p_i s_hat_i are formed in f64 relative to
 // the group's largest ln s_hat, one member per lane, and broadcast; K and V rows are accumulated in
 // f32 and scaled once at the end.  Positions without members are copied bit for bit.
@@ -27,8 +29,8 @@ constexpr int kMaxEvict = 32768;          // sort keys are (target << 15) | posi
 constexpr double kEllGuard = 1.0e-3;
 
 // Groups the evicted slots of one head by merge target.  Keys (target << 15 | position in the evict
-// list) are sorted with a bitonic network in LDS, so each group's members come out in ascending slot
-// order; CSR starts come from a histogram and a block scan.
+// list) are put in ascending order in LDS, so each group's members come out in ascending slot order;
+// CSR starts come from a histogram and a block scan.
 __global__ __launch_bounds__(kGroupThreads) void merge_group_kernel(
     const int32_t* __restrict__ match, const int32_t* __restrict__ evict_idx, const int32_t* __restrict__ n_evict,
     const int32_t* __restrict__ votes, int32_t* __restrict__ start, int32_t* __restrict__ members,

@@ -3,11 +3,13 @@
 //
 // One 1024-thread workgroup per head.  The ranking value ln p + ln s_hat is formed in f64 and
 // mapped to an order-preserving u64, the (budget - n_sink - n_recent)-th largest is found by an
-// 8-bit most-significant-digit radix select (LDS histograms, wavefront scan), and the slots are
-// then compacted in index order so that equal values keep the lower index first.
+// 8-bit most-significant-digit radix select (LDS histograms, wavefront scan; digits in which no two
+// keys differ are skipped), and the slots are then compacted in index order so that equal values
+// keep the lower index first.
 #include "kk_common.hpp"
 
 namespace kk {
+// Phase timestamps for kernel tuning; compiled in only with -DKEEPKV_TRACE (never in the product build).
 #ifdef KEEPKV_TRACE
 __device__ long long kk_trace_select[16 * 1024];
 #define KS_TS(i) do { if (threadIdx.x == 0 && blockIdx.x < 1024) kk_trace_select[blockIdx.x * 16 + (i)] = wall_clock64(); } while (0)
