@@ -165,7 +165,7 @@ def test_decode_step_equals_append_attend_score(name, w, hint):
         o_ref, _, lg_ref = O.attend(oc, q.astype(np.float64), w.scale)
         O.observe(oc, lg_ref, alpha)
         np.testing.assert_array_equal(c.len.cpu().numpy(), oc.len)
-        err = U.rel_err_rows(U.to_host(out), W.round_storage(o_ref, w.dtype))
+        err = U.storage_err_rows(U.to_host(out), o_ref, w.dtype)
         assert err.max() <= TOL, (name, t, err.max())
         for b in range(B):
             for h in range(H):
@@ -207,7 +207,7 @@ def test_decode_extreme_values(name, w):
     assert np.abs(lg_ref).max() > 100.0
     got = U.to_host(out)
     assert np.isfinite(got).all()
-    err = U.rel_err_rows(got, W.round_storage(o_ref, w.dtype))
+    err = U.storage_err_rows(got, o_ref, w.dtype)
     assert err.max() <= TOL, (name, err.max())
     np.testing.assert_allclose(logits.cpu().numpy(), lg_ref, rtol=2e-3, atol=2e-3)
     np.testing.assert_allclose(lse.cpu().numpy(), lse_ref, rtol=1e-4, atol=2e-3)

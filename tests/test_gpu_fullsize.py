@@ -47,7 +47,7 @@ def _run(w, seed, n_window, n_steps, threshold, sample):
     got = U.to_host(out)
     for (b, h), oc in pre.items():
         o_ref, _, lg = O.attend(oc, q[b:b + 1, h * G:(h + 1) * G].astype(np.float64), w.scale)
-        err = U.rel_err_rows(got[b, h * G:(h + 1) * G], W.round_storage(o_ref[0], w.dtype))
+        err = U.storage_err_rows(got[b, h * G:(h + 1) * G], o_ref[0], w.dtype)
         assert err.max() <= TOL, ("window attention", b, h, err.max())
         np.testing.assert_allclose(logits[b, h].cpu().numpy(), lg[0, 0], rtol=2e-3, atol=2e-3)
 
@@ -82,8 +82,8 @@ def _run(w, seed, n_window, n_steps, threshold, sample):
         res = O.merge(oc.k[0, 0], oc.v[0, 0], oc.votes[0, 0], oc.log_S[0, 0], oc.n_obs[0, 0], rk, re, tgt, alpha)
         np.testing.assert_array_equal(small.votes[b, h, :Bud].cpu().numpy(), res.votes)
         assert dropped[b, h].item() == res.dropped
-        ev_ = U.rel_err_rows(U.to_host(small.v[b, h, :Bud]), W.round_storage(res.v, w.dtype))
-        ek = U.rel_err_rows(U.to_host(small.k[b, h, :Bud]), W.round_storage(res.k, w.dtype))
+        ev_ = U.storage_err_rows(U.to_host(small.v[b, h, :Bud]), res.v, w.dtype)
+        ek = U.storage_err_rows(U.to_host(small.k[b, h, :Bud]), res.k, w.dtype)
         well = ~(np.abs(res.ell_bar) < 4 * O.ELL_GUARD)
         assert ev_.max() <= TOL and ek[well].max(initial=0) <= TOL, (b, h, ev_.max(), ek[well].max(initial=0))
 
@@ -104,7 +104,7 @@ def _run(w, seed, n_window, n_steps, threshold, sample):
         oc.append(k_t[b:b + 1, h:h + 1], v_t[b:b + 1, h:h + 1])
         o_ref, _, lg = O.attend(oc, q[b:b + 1, h * G:(h + 1) * G].astype(np.float64), w.scale)
         O.observe(oc, lg, alpha)
-        err = U.rel_err_rows(got[b, h * G:(h + 1) * G], W.round_storage(o_ref[0], w.dtype))
+        err = U.storage_err_rows(got[b, h * G:(h + 1) * G], o_ref[0], w.dtype)
         assert err.max() <= TOL, ("decode step", b, h, err.max())
         n = Bud + n_steps
         np.testing.assert_allclose(small.log_s[b, h, :n].cpu().numpy(), oc.log_S[0, 0, :n], rtol=2e-3, atol=2e-3)

@@ -75,7 +75,7 @@ def test_random_shape(seed):
     oc.append(k_t.astype(np.float64), v_t.astype(np.float64))
     o_ref, _, lg = O.attend(oc, q.astype(np.float64), w.scale)
     O.observe(oc, lg, alpha)
-    err = U.rel_err_rows(U.to_host(out), W.round_storage(o_ref, w.dtype))
+    err = U.storage_err_rows(U.to_host(out), o_ref, w.dtype)
     assert err.max() <= TOL, (seed, float(err.max()))
     assert np.array_equal(c.len.cpu().numpy(), oc.len)
     for b in range(B):
