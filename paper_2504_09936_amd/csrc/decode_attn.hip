@@ -50,11 +50,14 @@ struct DecodeParams {
   int nsplit;
   int per;          // slots per split
   int len_hint;     // caller's upper bound on len (0: none)
+  int waves;        // wavefronts per workgroup of the matrix-core kernel (4 or 8)
   float scale;
   float ln_alpha, ln_1m_alpha;
 };
 
-constexpr int kWavesPerBlock = 4;
+constexpr int kWavesPerBlock = 4;   // the vector-ALU kernel
+// The matrix-core kernel comes with 4 and with 8 wavefronts per workgroup (64 / 128 KB of tile buffers at
+// D = 128: two workgroups or one per compute unit); plan_decode picks.
 
 
 __device__ __forceinline__ void st_agent(float* p, float v) {
@@ -68,7 +71,7 @@ __device__ __forceinline__ float ld_agent(const float* p) {
 // deposited in LDS and a barrier has passed: reduce them; a single split finishes the head, otherwise the
 // partial result goes to the workspace and the last workgroup of the head to arrive combines the splits,
 // resets the ticket and (step mode) publishes the new len.
-template <typename T, int D, int G, int kParts, bool STEP>
+template <typename T, int D, int G, int kParts, bool STEP, int WAVES>
 __device__ __forceinline__ void combine_and_finish(const DecodeParams& p, const float* s_m, const float* s_l,
                                                    const float* s_acc, int* s_last_p, int unit, int split, bool grow,
                                                    int len) {
@@ -83,7 +86,7 @@ __device__ __forceinline__ void combine_and_finish(const DecodeParams& p, const 
     if (d == 0 && p.lse_out != nullptr) p.lse_out[row] = (L > 0.f) ? (M + fast_log2(L)) * kLn2 : -INFINITY;
   };
 
-  for (int idx = threadIdx.x; idx < G * D; idx += kWavesPerBlock * kWave) {
+  for (int idx = threadIdx.x; idx < G * D; idx += WAVES * kWave) {
     const int g = idx / D, d = idx % D;
     float M = s_m[g];
 #pragma unroll
@@ -131,7 +134,7 @@ __device__ __forceinline__ void combine_and_finish(const DecodeParams& p, const 
   if (!s_last) return;
   // CH splits of EB output elements are fetched per round trip of device-scope loads: 8 splits of two
   // elements when that covers all splits (the common case; surplus loads would only cost), else 16 of one
-  constexpr int kThreads = kWavesPerBlock * kWave;
+  constexpr int kThreads = WAVES * kWave;
   constexpr int kPerThread = (G * D + kThreads - 1) / kThreads;   // output elements per thread
   auto combine = [&](auto ch_tag, auto eb_tag) {
     constexpr int CH = decltype(ch_tag)::value, EB = decltype(eb_tag)::value;
@@ -473,7 +476,7 @@ __global__ __launch_bounds__(kWavesPerBlock* kWave) void decode_attn_kernel(Deco
   __syncthreads();
   KK_TS(2);
 
-  combine_and_finish<T, D, G, kParts, STEP>(p, s_m, s_l, s_acc, &s_last, unit, split, grow, len);
+  combine_and_finish<T, D, G, kParts, STEP, kWavesPerBlock>(p, s_m, s_l, s_acc, &s_last, unit, split, grow, len);
 }
 
 // ---------------------------------------------------------------------------------------------------
@@ -507,13 +510,13 @@ __device__ __forceinline__ uint32_t pack_hi16(float lo_elem, float hi_elem) {   
 
 // ONE: a split is at most one tile per wavefront (128 slots), so there is no tile loop, no prefetch and no
 // rescaling of the accumulators (the common steady-state shape).
-template <int D, int G, bool STEP, bool ONE>
-__global__ __launch_bounds__(kWavesPerBlock* kWave, 2) void decode_mfma_kernel(DecodeParams p) {
+template <int D, int G, bool STEP, bool ONE, int kMfmaWaves>
+__global__ __launch_bounds__(kMfmaWaves* kWave, 2) void decode_mfma_kernel(DecodeParams p) {
   using T = uint16_t;
   constexpr int ROWB = D * 2, CHUNKS = ROWB / 16, KS = D / 32, NTILE = D / 16;
   constexpr int TILE_BYTES = kMTile * ROWB;
   constexpr int LOADS = TILE_BYTES / (kWave * 16);
-  constexpr int kParts = kWavesPerBlock;
+  constexpr int kParts = kMfmaWaves;
   extern __shared__ __align__(16) unsigned char smem_raw[];     // [wave][K tile | V tile]; later the deposit
   __shared__ int s_last;
   __shared__ __align__(16) unsigned char s_new[2 * ROWB];       // step mode: the appended token's K row, V row
@@ -524,7 +527,7 @@ __global__ __launch_bounds__(kWavesPerBlock* kWave, 2) void decode_mfma_kernel(D
   KK_TS(0);
   const int len_old = p.len[unit];
   const int start = split * p.per;
-  const bool takes_new = STEP && split == p.nsplit - 1 && wave == kWavesPerBlock - 1;
+  const bool takes_new = STEP && split == p.nsplit - 1 && wave == kMfmaWaves - 1;
   if (takes_new && lane < 2 * CHUNKS) {        // asynchronous copy of (k_t, v_t) into LDS, awaited after the loop
     const unsigned char* src = reinterpret_cast<const unsigned char*>(lane < CHUNKS ? p.k_t : p.v_t) +
                                (size_t)unit * ROWB + (lane % CHUNKS) * 16;
@@ -699,7 +702,7 @@ __global__ __launch_bounds__(kWavesPerBlock* kWave, 2) void decode_mfma_kernel(D
       no_old = p.n_obs[at];
     }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");       // the tile (and the scalars above) have landed
-    const int next = base + kWavesPerBlock * kMTile;
+    const int next = base + kMfmaWaves * kMTile;
     compute(base, false, (!ONE && next < lim) ? next : -1, pv, ls_old, no_old);
     base = ONE ? lim : next;
   }
@@ -745,7 +748,7 @@ __global__ __launch_bounds__(kWavesPerBlock* kWave, 2) void decode_mfma_kernel(D
   }
   __syncthreads();
   KK_TS(2);
-  combine_and_finish<T, D, G, kParts, STEP>(p, s_m, s_l, s_acc, &s_last, unit, split, grow, len);
+  combine_and_finish<T, D, G, kParts, STEP, kMfmaWaves>(p, s_m, s_l, s_acc, &s_last, unit, split, grow, len);
 }
 
 template <typename T, int D, int G>
@@ -759,23 +762,29 @@ void launch_decode(const DecodeParams& p, int units, bool step, hipStream_t st) 
   if constexpr (sizeof(T) == 2) {
     static const bool valu = getenv("KEEPKV_DECODE_VALU") != nullptr;     // tuning aid: the vector-ALU kernel
     if (!valu) {
-      constexpr size_t tiles = (size_t)kWavesPerBlock * 2 * kMTile * D * 2;
-      // 64 KB of tile buffers at D = 128, plus the kernel's static LDS: allow it explicitly
-      static const hipError_t attr[4] = {
-          hipFuncSetAttribute((const void*)decode_mfma_kernel<D, G, true, true>,
-                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)tiles),
-          hipFuncSetAttribute((const void*)decode_mfma_kernel<D, G, true, false>,
-                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)tiles),
-          hipFuncSetAttribute((const void*)decode_mfma_kernel<D, G, false, true>,
-                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)tiles),
-          hipFuncSetAttribute((const void*)decode_mfma_kernel<D, G, false, false>,
-                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)tiles)};
-      (void)attr;                              // a refusal shows up as a launch error below
-      const bool one = p.per <= kWavesPerBlock * kMTile;
-      if (step && one) decode_mfma_kernel<D, G, true, true><<<grid, block, tiles, st>>>(p);
-      else if (step) decode_mfma_kernel<D, G, true, false><<<grid, block, tiles, st>>>(p);
-      else if (one) decode_mfma_kernel<D, G, false, true><<<grid, block, tiles, st>>>(p);
-      else decode_mfma_kernel<D, G, false, false><<<grid, block, tiles, st>>>(p);
+      auto go = [&](auto waves_tag) {
+        constexpr int WV = decltype(waves_tag)::value;
+        constexpr size_t tiles = (size_t)WV * 2 * kMTile * D * 2;
+        // 64 or 128 KB of tile buffers at D = 128, plus the kernel's static LDS: allow it explicitly
+        static const hipError_t attr[4] = {
+            hipFuncSetAttribute((const void*)decode_mfma_kernel<D, G, true, true, WV>,
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)tiles),
+            hipFuncSetAttribute((const void*)decode_mfma_kernel<D, G, true, false, WV>,
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)tiles),
+            hipFuncSetAttribute((const void*)decode_mfma_kernel<D, G, false, true, WV>,
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)tiles),
+            hipFuncSetAttribute((const void*)decode_mfma_kernel<D, G, false, false, WV>,
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)tiles)};
+        (void)attr;                              // a refusal shows up as a launch error below
+        const dim3 mblock(WV * kWave);
+        const bool one = p.per <= WV * kMTile;
+        if (step && one) decode_mfma_kernel<D, G, true, true, WV><<<grid, mblock, tiles, st>>>(p);
+        else if (step) decode_mfma_kernel<D, G, true, false, WV><<<grid, mblock, tiles, st>>>(p);
+        else if (one) decode_mfma_kernel<D, G, false, true, WV><<<grid, mblock, tiles, st>>>(p);
+        else decode_mfma_kernel<D, G, false, false, WV><<<grid, mblock, tiles, st>>>(p);
+      };
+      if (p.waves == 8) go(std::integral_constant<int, 8>{});
+      else go(std::integral_constant<int, 4>{});
       return;
     }
   }
@@ -821,7 +830,7 @@ keepkv_status run_decode(const keepkv_layout* layout, const keepkv_cache* cache,
   p.out = out; p.logits_out = logits_out; p.lse_out = lse_out;
   p.partial = reinterpret_cast<float*>(reinterpret_cast<char*>(workspace) + pl.partial_off);
   p.ticket = reinterpret_cast<int32_t*>(workspace);
-  p.n_kv_heads = layout->n_kv_heads; p.capacity = cache->capacity; p.nsplit = pl.nsplit; p.per = pl.per; p.scale = layout->scale;
+  p.n_kv_heads = layout->n_kv_heads; p.capacity = cache->capacity; p.nsplit = pl.nsplit; p.per = pl.per; p.waves = pl.waves; p.scale = layout->scale;
   p.len_hint = cache->len_hint > 0 ? cache->len_hint : 0;
   p.ln_alpha = (step && alpha > 0.f) ? logf(alpha) : -INFINITY;
   p.ln_1m_alpha = step ? log1pf(-alpha) : 0.f;
@@ -841,46 +850,63 @@ keepkv_status run_decode(const keepkv_layout* layout, const keepkv_cache* cache,
 }  // namespace
 
 DecodePlan plan_decode(const keepkv_layout* L, int capacity) {
-  // Slots per split (a multiple of 64) from a small cost model fitted to measurements on MI355X (batch
-  // 1..128, 850..32768 slots per head).  About 512 workgroups are resident at once and every round of
-  // workgroups costs ~3 us of start-up.  A workgroup streams at no more than ~26 GB/s (its rows in flight
-  // over the memory latency); all resident workgroups together reach ~5.1 TB/s when the chip is full and
-  // ~10 % less at one workgroup per CU.  The last workgroup of a head combines the splits eight or sixteen
-  // at a time, ~2.3 / ~3.4 us per round trip of device-scope loads.  Few long splits starve the chip, many
-  // short ones pay for rounds and for the combine.
+  // Slots per split, and for the matrix-core kernel its workgroup size, from a small cost model fitted to
+  // measurements on MI355X (batch 1..128, 850..32768 slots per head).  Workgroups of 4 wavefronts fit two to
+  // a compute unit (512 resident), those of 8 wavefronts one (128 KB of tile buffers at D = 128: 256
+  // resident; 512 at D = 64).  Every round of workgroups costs ~3 us of start-up.  A wavefront streams at no
+  // more than ~6.5 GB/s when all its tiles are requested at once and ~4.4 GB/s when it loops (its rows in
+  // flight over the memory latency); all resident workgroups together reach ~5.1 TB/s when the chip is
+  // full, and a compute unit with two workgroups beside one with a single one sets the pace.  The last
+  // workgroup of a head combines the splits eight or sixteen at a time, ~2.3 / ~3.4 us per round trip of
+  // device-scope loads.  Few long splits starve the chip, many short ones pay for rounds and for the
+  // combine.  On the Llama-3-8B shape (64 heads, ~850 slots) 4 splits of 8 wavefronts are exactly one
+  // workgroup per compute unit: 11.2 us against 11.9 us for 7 splits of 4 wavefronts (448 workgroups on 256
+  // compute units); at 128 heads and more the smaller workgroups win (two rounds instead of four at batch 128).
   DecodePlan pl;
   const double units = (double)L->batch * L->n_kv_heads;
   const double slot_bytes = 2.0 * L->head_dim * (L->dtype == KEEPKV_BF16 ? 2 : 4) + 24.0;
-  // slots a workgroup consumes per loop iteration: 4 wavefronts x 32-slot tiles (bf16, matrix-core kernel);
-  // the f32 kernel's lane groups cover 64 or 128 (see launch_decode)
+  static const bool valu = getenv("KEEPKV_DECODE_VALU") != nullptr;
+  const bool mfma = L->dtype == KEEPKV_BF16 && !valu;
   const int rv = L->head_dim * (L->dtype == KEEPKV_BF16 ? 2 : 4) / 16;
-  const long granule = L->dtype == KEEPKV_BF16 ? 128 : (rv >= 32 ? 64 : 128);
   long per = 128;
+  int waves = kWavesPerBlock;
   double best = 1e300;
-  const long max_ns = (capacity + 63) / 64 < 1024 ? (capacity + 63) / 64 : 1024;
-  for (long ns = 1; ns <= max_ns; ++ns) {
-    const long cand = ((capacity + ns - 1) / ns + 63) / 64 * 64;
-    const double n_split = (double)((capacity + cand - 1) / cand);
-    const double wgs = units * n_split;
-    const double resident = wgs < 512.0 ? wgs : 512.0;
-    const double rounds = (double)(long)((wgs + 511.0) / 512.0);
-    double together = 5100.0 * pow(resident / 512.0, 0.15);                         // GB/s, all resident workgroups
-    if (together > 26.0 * resident) together = 26.0 * resident;
-    const double streamed = (double)((cand + granule - 1) / granule * granule);       // whole iterations
-    const double t_one = streamed * slot_bytes / 26.0e3;                              // us, a workgroup alone
-    const double t_all = units * capacity * slot_bytes / rounds / (together * 1e3);   // us, one round of them
-    const double t_stream = rounds * (3.0 + (t_one > t_all ? t_one : t_all));
-    const double t_trips = n_split <= 8.0 ? 2.3 : 3.4 * (double)(long)((n_split + 15.0) / 16.0);
-    const double t_combine = n_split > 1.0 ? 1.0 + t_trips + 0.02 * n_split : 0.0;
-    if (t_stream + t_combine < best) {
-      best = t_stream + t_combine;
-      per = cand;
+  for (int wv = 4; wv <= (mfma ? 8 : 4); wv += 4) {
+    // a split is a whole number of `unit_slots`; a workgroup consumes `granule` slots per loop iteration
+    const long unit_slots = mfma ? kMTile : 64;
+    const long granule = mfma ? (long)wv * kMTile : (L->dtype == KEEPKV_BF16 ? 128 : (rv >= 32 ? 64 : 128));
+    const double res_max = (mfma && (size_t)wv * 2 * kMTile * L->head_dim * 2 > 72 * 1024) ? 256.0 : 512.0;
+    const long max_ns = (capacity + unit_slots - 1) / unit_slots < 1024 ? (capacity + unit_slots - 1) / unit_slots : 1024;
+    for (long ns = 1; ns <= max_ns; ++ns) {
+      const long cand = ((capacity + ns - 1) / ns + unit_slots - 1) / unit_slots * unit_slots;
+      const double n_split = (double)((capacity + cand - 1) / cand);
+      const double wgs = units * n_split;
+      const double resident = wgs < res_max ? wgs : res_max;
+      const double rounds = (double)(long)((wgs + res_max - 1.0) / res_max);
+      const double wg_rate = (cand <= granule ? 6.5 : 4.4) * wv;                        // GB/s
+      double together = 5100.0 * pow(resident / res_max, 0.15);                         // GB/s, all resident workgroups
+      if (resident > 256.0) together *= (resident / 256.0) / (double)(long)((resident + 255.0) / 256.0);
+      if (together > wg_rate * resident) together = wg_rate * resident;
+      const double streamed = (double)((cand + granule - 1) / granule * granule);       // whole iterations
+      const double t_one = streamed * slot_bytes / (wg_rate * 1e3);                     // us, a workgroup alone
+      const double t_all = units * capacity * slot_bytes / rounds / (together * 1e3);   // us, one round of them
+      const double t_stream = rounds * (3.0 + (t_one > t_all ? t_one : t_all));
+      const double t_trips = n_split <= 8.0 ? 2.3 : 3.4 * (double)(long)((n_split + 15.0) / 16.0);
+      const double t_combine = n_split > 1.0 ? 1.0 + t_trips + 0.02 * n_split : 0.0;
+      if (t_stream + t_combine < best) {
+        best = t_stream + t_combine;
+        per = cand;
+        waves = wv;
+      }
     }
   }
+  static const long forced_waves = [] { const char* e = getenv("KEEPKV_DECODE_WAVES"); return e ? atol(e) : 0L; }();
+  if (mfma && (forced_waves == 4 || forced_waves == 8)) waves = (int)forced_waves;
+  pl.waves = waves;
   static const long forced = [] { const char* e = getenv("KEEPKV_DECODE_CHUNK"); return e ? atol(e) : 0L; }();
-  if (forced >= 64) per = forced / 64 * 64;
+  if (forced >= 64) per = mfma ? forced / 32 * 32 : forced / 64 * 64;
   long ns = (capacity + per - 1) / per;
-  if (ns > 1024) { ns = 1024; per = ((capacity + ns - 1) / ns + 63) / 64 * 64; ns = (capacity + per - 1) / per; }
+  if (ns > 1024) { ns = 1024; per = ((capacity + ns - 1) / ns + 63) / 64 * 64; ns = (capacity + per - 1) / per; }   // (max_ns caps it already)
   pl.nsplit = (int)ns;
   pl.per = (int)per;
   pl.partial_off = kWorkspaceHead;

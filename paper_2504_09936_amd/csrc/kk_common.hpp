@@ -93,7 +93,8 @@ inline bool units_supported(const keepkv_layout* L) { return (int64_t)L->batch *
 
 struct DecodePlan {
   int nsplit;         // workgroups per (batch, kv head)
-  int per;            // slots per split (multiple of 64)
+  int per;            // slots per split (a multiple of 32; of 64 for the vector-ALU kernel)
+  int waves;          // wavefronts per workgroup of the matrix-core kernel (4 or 8)
   size_t partial_off; // float [B*Hq, nsplit, D + 2]
   size_t bytes;
 };
