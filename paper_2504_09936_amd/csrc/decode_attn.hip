@@ -2,8 +2,9 @@
 // split-K over slots, optionally fused with the cache append (Sec. 3.1) and the EMA score update
 // (Eq. 8) so that one decode step of one layer is a single kernel.
 //
-// One workgroup (4 wavefronts) handles one (batch, kv head, split).  A slot's row (D elements)
-// is spread over LPS consecutive lanes, 16 bytes per lane, so one wavefront load instruction
+// One workgroup handles one (batch, kv head, split).  bf16 caches run both contractions on the matrix
+// cores (decode_mfma_kernel below, 4 or 8 wavefronts per workgroup).  In the vector-ALU kernel (f32
+// caches, 4 wavefronts) a slot's row (D elements) is spread over LPS consecutive lanes, 16 bytes per lane, so one wavefront load instruction
 // streams 64/LPS whole rows, fully coalesced.  Each lane group computes the G logits of its
 // slot with bf16 dot2 (or f32 fma) plus a DPP all-reduce inside the group, keeps its own
 // online-softmax state in the log2 domain with log2(votes) folded into the logit, and
@@ -508,7 +509,7 @@ __device__ __forceinline__ uint32_t pack_hi16(float lo_elem, float hi_elem) {   
   return (__builtin_bit_cast(uint32_t, lo_elem) >> 16) | (__builtin_bit_cast(uint32_t, hi_elem) & 0xFFFF0000u);
 }
 
-// ONE: a split is at most one tile per wavefront (128 slots), so there is no tile loop, no prefetch and no
+// ONE: a split is at most one tile per wavefront (128 or 256 slots), so there is no tile loop, no prefetch and no
 // rescaling of the accumulators (the common steady-state shape).
 template <int D, int G, bool STEP, bool ONE, int kMfmaWaves>
 __global__ __launch_bounds__(kMfmaWaves* kWave, 2) void decode_mfma_kernel(DecodeParams p) {
