@@ -81,6 +81,14 @@ int32_t keepkv_version(void);
  * them once with keepkv_workspace_init after allocating; every call leaves them zero again. */
 size_t keepkv_workspace_bytes(const keepkv_layout *layout, int32_t capacity, int32_t budget);
 
+/* How keepkv_decode_attn / keepkv_decode_step will be launched for this layout and capacity (host-side
+ * arithmetic, no device call): one workgroup of `wavefronts` wavefronts per (b, h, split), n_split splits of
+ * slots_per_split slots per head.  The outputs are HOST pointers and may be NULL.  The plan comes from a cost
+ * model of the split-K decode (Eq. 6 evaluated per split and combined); it does not change results beyond
+ * the summation order of the splits. */
+keepkv_status keepkv_decode_plan(const keepkv_layout *layout, int32_t capacity, int32_t *n_split,
+                                 int32_t *slots_per_split, int32_t *wavefronts);
+
 /* Clear the control words at the head of a freshly allocated DEVICE workspace (one small
  * kernel on `stream`; no memset, so it may be captured in a HIP graph). */
 keepkv_status keepkv_workspace_init(void *workspace, size_t workspace_bytes, void *stream);

@@ -59,12 +59,14 @@ _lib.keepkv_merge.argtypes = [C.POINTER(_Layout), C.POINTER(_Cache), C.POINTER(_
                               _P, C.c_float, _P, _P, C.c_size_t, _P]
 _lib.keepkv_probe_read.argtypes = [_P, C.c_size_t, C.c_int32, _P, _P]
 _lib.keepkv_probe_mfma.argtypes = [C.c_int32, C.c_int32, C.c_int32, _P, C.POINTER(C.c_double), _P]
-for _f in ("probe_read", "probe_mfma", "append", "decode_attn", "decode_step", "workspace_init", "score", "score_window", "select",
+_lib.keepkv_decode_plan.argtypes = [C.POINTER(_Layout), C.c_int32, C.POINTER(C.c_int32), C.POINTER(C.c_int32),
+                                    C.POINTER(C.c_int32)]
+for _f in ("decode_plan", "probe_read", "probe_mfma", "append", "decode_attn", "decode_step", "workspace_init", "score", "score_window", "select",
            "select_by_key", "match",
            "merge"):
     getattr(_lib, "keepkv_" + _f).restype = C.c_int
 
-EXPORTS = ["keepkv_strerror", "keepkv_version", "keepkv_workspace_bytes", "keepkv_workspace_init",
+EXPORTS = ["keepkv_strerror", "keepkv_version", "keepkv_workspace_bytes", "keepkv_workspace_init", "keepkv_decode_plan",
            "keepkv_append", "keepkv_decode_attn", "keepkv_decode_step", "keepkv_score", "keepkv_score_window", "keepkv_select",
            "keepkv_select_by_key", "keepkv_match", "keepkv_merge", "keepkv_probe_read", "keepkv_probe_mfma"]
 
@@ -181,6 +183,14 @@ def select(layout: Layout, cache: Cache, budget: int, n_sink: int, n_recent: int
                               _ptr(keep_idx), _ptr(evict_idx), _ptr(n_evict), _ptr(workspace),
                               0 if workspace is None else workspace.numel() * workspace.element_size(),
                               _stream()), "keepkv_select")
+
+
+def decode_plan(layout: Layout, capacity: int):
+    """(n_split, slots_per_split, wavefronts) of a decode call on this layout and capacity."""
+    ns, per, wv = C.c_int32(0), C.c_int32(0), C.c_int32(0)
+    _check(_lib.keepkv_decode_plan(C.byref(layout.c()), capacity, C.byref(ns), C.byref(per), C.byref(wv)),
+           "keepkv_decode_plan")
+    return ns.value, per.value, wv.value
 
 
 def select_by_key(layout: Layout, cache: Cache, rank, budget: int, n_sink: int, n_recent: int,

@@ -30,6 +30,18 @@ extern "C" keepkv_status keepkv_workspace_init(void* workspace, size_t workspace
   return launch_status();
 }
 
+extern "C" keepkv_status keepkv_decode_plan(const keepkv_layout* layout, int32_t capacity, int32_t* n_split,
+                                            int32_t* slots_per_split, int32_t* wavefronts) {
+  using namespace kk;
+  if (!layout_ok(layout) || capacity < 1 || capacity > (1 << 20)) return KEEPKV_ERR_INVALID_ARG;
+  if (!layout_supported(layout) || !units_supported(layout)) return KEEPKV_ERR_UNSUPPORTED;
+  const DecodePlan pl = plan_decode(layout, capacity);
+  if (n_split) *n_split = pl.nsplit;
+  if (slots_per_split) *slots_per_split = pl.per;
+  if (wavefronts) *wavefronts = layout->dtype == KEEPKV_BF16 ? pl.waves : 4;
+  return KEEPKV_OK;
+}
+
 extern "C" size_t keepkv_workspace_bytes(const keepkv_layout* layout, int32_t capacity, int32_t budget) {
   using namespace kk;
   if (!layout_ok(layout) || capacity < 1 || capacity > (1 << 20) || budget < 1 || budget > capacity) return 0;

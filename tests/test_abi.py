@@ -77,3 +77,23 @@ def test_too_many_heads_is_refused_by_every_call():
     assert lib.keepkv_select_by_key(L, K, P, 820, 4, 652, P, P, P, P, 1 << 40, None) == kk.ERR_UNSUPPORTED
     assert lib.keepkv_match(L, K, 820, P, P, P, C.c_float(0.8), P, None, P, 1 << 40, None) == kk.ERR_UNSUPPORTED
     assert lib.keepkv_merge(L, K, K, 820, P, P, P, P, C.c_float(0.9), None, P, 1 << 40, None) == kk.ERR_UNSUPPORTED
+
+
+def test_decode_plan_is_host_arithmetic():
+    """keepkv_decode_plan needs no device: the benchmark shape gets 4 splits of 224 slots on 8-wavefront workgroups
+    (256 workgroups, one per compute unit), a batch of 128 one split per head on 4-wavefront workgroups, an f32
+    cache the vector-ALU kernel's 4 wavefronts; bad arguments are refused."""
+    from paper_2504_09936_amd import binding as kk
+    bench = kk.Layout(8, 32, 8, 128, kk.BF16, 128 ** -0.5)
+    assert kk.decode_plan(bench, 884) == (4, 224, 8)
+    n_split, per, waves = kk.decode_plan(kk.Layout(128, 64, 8, 128, kk.BF16, 128 ** -0.5), 884)
+    assert (n_split, waves) == (1, 4) and per >= 884
+    for lay, cap in ((bench, 1), (bench, 5000), (kk.Layout(1, 8, 8, 64, kk.BF16, 0.125), 333), (kk.Layout(3, 6, 3, 128, kk.F32, 0.1), 700)):
+        n_split, per, waves = kk.decode_plan(lay, cap)
+        assert n_split >= 1 and n_split * per >= cap and (n_split - 1) * per < cap and waves in (4, 8)
+        assert per % 32 == 0
+    assert kk.decode_plan(kk.Layout(3, 6, 3, 128, kk.F32, 0.1), 700)[2] == 4
+    with pytest.raises(kk.KeepKVError):
+        kk.decode_plan(bench, 0)
+    with pytest.raises(kk.KeepKVError):
+        kk.decode_plan(kk.Layout(8, 32, 8, 96, kk.BF16, 0.1), 884)        # unsupported head dimension

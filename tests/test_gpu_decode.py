@@ -27,7 +27,18 @@ CASES = [
     ("bf16_mixture", _case("long_32k", batch=1, context=4100)),
     ("bf16_g1", _case("llama3_8b", batch=1, n_q_heads=8, n_kv_heads=8, context=555)),
     ("bf16_d64_g8", _case("llama3_8b", batch=2, n_q_heads=32, n_kv_heads=4, head_dim=64, context=300)),
+    ("bf16_many_heads", _case("llama3_8b", batch=40, context=300)),     # 320 heads: the 4-wavefront workgroups
 ]
+
+
+def test_cases_cover_both_workgroup_sizes_of_the_matrix_core_kernel():
+    """The decode plan picks 8 wavefronts per workgroup for few heads and 4 for many; the parity cases above
+    run under both (and under one and several splits)."""
+    kk = U.kk()
+    plans = {name: kk.decode_plan(U.layout_of(w), w.context) for name, w in CASES if w.dtype == "bf16"}
+    assert plans["bf16_g4"][2] == 8 and plans["bf16_many_heads"][2] == 4, plans
+    assert {p[2] for p in plans.values()} == {4, 8}
+    assert any(p[0] == 1 for p in plans.values()) and any(p[0] > 1 for p in plans.values()), plans
 
 
 @pytest.mark.parametrize("hint", [False, True], ids=["wait_for_len", "len_hint"])
@@ -118,8 +129,8 @@ def test_score_and_append_match_oracle(alpha):
 
 
 @pytest.mark.parametrize("hint", [False, True], ids=["wait_for_len", "len_hint"])
-@pytest.mark.parametrize("name,w", [CASES[0], CASES[1], CASES[2], CASES[3], CASES[6], CASES[7]],
-                         ids=[CASES[i][0] for i in (0, 1, 2, 3, 6, 7)])
+@pytest.mark.parametrize("name,w", [CASES[0], CASES[1], CASES[2], CASES[3], CASES[6], CASES[7], CASES[8]],
+                         ids=[CASES[i][0] for i in (0, 1, 2, 3, 6, 7, 8)])
 def test_decode_step_equals_append_attend_score(name, w, hint):
     """The fused single-kernel step against the oracle's append -> attention -> EMA update."""
     kk = U.kk()
