@@ -494,6 +494,27 @@ __global__ __launch_bounds__(kWavesPerBlock* kWave) void decode_attn_kernel(Deco
 // P is split into two bf16 terms (hi + lo, 16 significant bits), V is bf16 already, accumulation f32.
 // Output rows are heads again (row r = head r mod G), 16 channels per MFMA.
 constexpr int kMTile = 32;
+// Per wavefront, behind the tile buffers: the head group's query rows (whole 1 KB pieces, one asynchronous
+// 16-byte copy per lane each) and the tile's votes, ln S and observation counts (4 bytes per lane each).
+constexpr int mfma_stage_bytes(int D, int G) { return (G * D * 2 + 1023) / 1024 * 1024 + 3 * 256; }
+
+// LDS reads that the compiler does not see as such.  It orders an LDS read that it cannot tell apart from an
+// outstanding global -> LDS copy behind ALL outstanding copies; these are for data whose copy the caller has
+// already awaited, while later copies (to other addresses) are still under way.  The wait for the read itself
+// is part of the statement.
+typedef __attribute__((ext_vector_type(4))) int i32x4_t;
+__device__ __forceinline__ i32x4_t lds_read_b128_awaited(const void* lds_ptr) {
+  i32x4_t r;
+  const uint32_t a = (uint32_t)(uintptr_t)(const __attribute__((address_space(3))) void*)lds_ptr;
+  asm volatile("ds_read_b128 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=v"(r) : "v"(a) : "memory");
+  return r;
+}
+__device__ __forceinline__ int lds_read_b32_awaited(const void* lds_ptr) {
+  int r;
+  const uint32_t a = (uint32_t)(uintptr_t)(const __attribute__((address_space(3))) void*)lds_ptr;
+  asm volatile("ds_read_b32 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=v"(r) : "v"(a) : "memory");
+  return r;
+}
 
 typedef __attribute__((ext_vector_type(4))) short v4i16_t;
 
@@ -542,6 +563,23 @@ __global__ __launch_bounds__(kMfmaWaves* kWave, 2) void decode_mfma_kernel(Decod
   const unsigned char* vbytes = reinterpret_cast<const unsigned char*>(p.v) + ubase * ROWB;
   unsigned char* Kb = smem_raw + wave * (2 * TILE_BYTES);
   unsigned char* Vb = Kb + TILE_BYTES;
+  // ONE: everything this wavefront waits for travels as asynchronous global -> LDS copies, requested in the
+  // order query rows, K rows, votes and EMA state, V rows.  Such copies complete in the order of issue, so a
+  // wait that leaves the V rows' LOADS copies outstanding guarantees all the others: the score product and
+  // the softmax run while the V rows still travel.  (Loads into registers in the same queue would make the
+  // compiler wait for everything at their first use.)
+  constexpr int Q_PIECES = (G * ROWB + 1023) / 1024;
+  unsigned char* s_q = smem_raw + kMfmaWaves * 2 * TILE_BYTES + wave * mfma_stage_bytes(D, G);
+  unsigned char* s_sc = s_q + Q_PIECES * 1024;                  // [votes | ln S | n_obs][64] 4-byte words
+  if constexpr (ONE) {
+    const unsigned char* qbase = reinterpret_cast<const unsigned char*>(p.q) + (size_t)unit * G * ROWB;
+#pragma unroll
+    for (int j = 0; j < Q_PIECES; ++j) {
+      const int c = min(j * kWave + lane, G * CHUNKS - 1);       // surplus lanes repeat the last chunk
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(qbase + c * 16),
+                                       (__attribute__((address_space(3))) void*)(s_q + j * 1024), 16, 0, 0);
+    }
+  }
 
   // chunk c of row r of a tile sits at position c ^ (r mod CHUNKS); rows at or beyond `bound` are never read
   auto issue_rows = [&](const unsigned char* rows, unsigned char* buf, int tbase) {
@@ -557,12 +595,28 @@ __global__ __launch_bounds__(kMfmaWaves* kWave, 2) void decode_mfma_kernel(Decod
   int base = start + wave * kMTile;
   if (base < lim) {
     issue_rows(kbytes, Kb, base);
+    if constexpr (ONE) {                         // slot base + lane of the tile (lanes beyond the tile repeat a slot)
+      const size_t at = ubase + min(base + lane, bound - 1);
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(p.votes + at),
+                                       (__attribute__((address_space(3))) void*)s_sc, 4, 0, 0);
+      if constexpr (STEP) {
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(p.log_s + at),
+                                         (__attribute__((address_space(3))) void*)(s_sc + 256), 4, 0, 0);
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(p.n_obs + at),
+                                         (__attribute__((address_space(3))) void*)(s_sc + 512), 4, 0, 0);
+      }
+    }
     issue_rows(vbytes, Vb, base);
   }
 
   // B operand of the score product: column l16 is head l16 mod G, this lane's 8 channels of every k-step
   bf16x8_t qb[KS];
-  {
+  auto read_q = [&]() {                          // ONE: from this wavefront's LDS copy, once it has landed
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks)
+      qb[ks] = *reinterpret_cast<const bf16x8_t*>(s_q + (l16 % G) * ROWB + ks * 64 + q * 16);
+  };
+  if constexpr (!ONE) {
     const unsigned char* qrow = reinterpret_cast<const unsigned char*>(p.q) + ((size_t)unit * G + (l16 % G)) * ROWB;
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) qb[ks] = *reinterpret_cast<const bf16x8_t*>(qrow + ks * 64 + q * 16);
@@ -579,23 +633,64 @@ __global__ __launch_bounds__(kMfmaWaves* kWave, 2) void decode_mfma_kernel(Decod
   // One tile.  `extra`: the appended token alone (row 0 of the tile, copied from s_new).
   // `next`: the wavefront's next tile (or -1); its K rows are requested as soon as the score product has
   // consumed the K buffer, its V rows after the second product, so both travel during the arithmetic.
-  auto compute = [&](int tbase, bool extra, int next, const int (&pv)[2][4], float ls_old, int no_old) {
+  // `v_in_flight`: the V rows are still outstanding when the call starts (ONE, the wavefront's own tile).
+  auto compute = [&](int tbase, bool extra, int next, const int (&pv)[2][4], float ls_old, int no_old,
+                     bool v_in_flight) {
     const int n_live = extra ? 1 : max(0, min(kMTile, live_end - tbase));
-    if (n_live < kMTile) {                       // uniform: clear the V rows of masked slots (0 * garbage could be NaN)
-      for (int c = n_live * CHUNKS + lane; c < kMTile * CHUNKS; c += kWave)
-        *reinterpret_cast<uint4*>(Vb + c * 16) = make_uint4(0, 0, 0, 0);
-      __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
-      __builtin_amdgcn_wave_barrier();
-    }
+    auto clear_masked_v = [&]() {
+      if (n_live < kMTile) {                     // uniform: clear the V rows of masked slots (0 * garbage could be NaN)
+        for (int c = n_live * CHUNKS + lane; c < kMTile * CHUNKS; c += kWave)
+          *reinterpret_cast<uint4*>(Vb + c * 16) = make_uint4(0, 0, 0, 0);
+        __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+      }
+    };
+    if (!v_in_flight) clear_masked_v();
     // ---- S^T = K Q^T
     f32x4_t s[2] = {f32x4_t{0.f, 0.f, 0.f, 0.f}, f32x4_t{0.f, 0.f, 0.f, 0.f}};
+    if (v_in_flight) {
+      // the K tile through reads that the compiler does not order behind the V rows' copies (see above)
+      i32x4_t a0[KS], a1[KS];
+      uint32_t ad[KS];
 #pragma unroll
-    for (int ks = 0; ks < KS; ++ks) {
-      const int off = l16 * ROWB + (((4 * ks + q) ^ (l16 & (CHUNKS - 1))) * 16);
-      const bf16x8_t a0 = *reinterpret_cast<const bf16x8_t*>(Kb + off);
-      const bf16x8_t a1 = *reinterpret_cast<const bf16x8_t*>(Kb + off + 16 * ROWB);
-      s[0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a0, qb[ks], s[0], 0, 0, 0);
-      s[1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a1, qb[ks], s[1], 0, 0, 0);
+      for (int ks = 0; ks < KS; ++ks)
+        ad[ks] = (uint32_t)(uintptr_t)(const __attribute__((address_space(3))) void*)(
+            Kb + l16 * ROWB + (((4 * ks + q) ^ (l16 & (CHUNKS - 1))) * 16));
+      if constexpr (KS == 4) {                   // D = 128: rows 16 .. 31 of the tile are 4096 bytes further
+        static_assert(KS != 4 || 16 * ROWB == 4096, "offset in the statement below");
+        asm volatile(
+            "ds_read_b128 %0, %8\n\tds_read_b128 %1, %8 offset:4096\n\t"
+            "ds_read_b128 %2, %9\n\tds_read_b128 %3, %9 offset:4096\n\t"
+            "ds_read_b128 %4, %10\n\tds_read_b128 %5, %10 offset:4096\n\t"
+            "ds_read_b128 %6, %11\n\tds_read_b128 %7, %11 offset:4096\n\t"
+            "s_waitcnt lgkmcnt(0)"
+            : "=&v"(a0[0]), "=&v"(a1[0]), "=&v"(a0[1]), "=&v"(a1[1]), "=&v"(a0[2]), "=&v"(a1[2]), "=&v"(a0[3]), "=&v"(a1[3])
+            : "v"(ad[0]), "v"(ad[1]), "v"(ad[2]), "v"(ad[3])
+            : "memory");
+      } else {                                   // D = 64: 2048 bytes further
+        static_assert(KS == 4 || (KS == 2 && 16 * ROWB == 2048), "offset in the statement below");
+        asm volatile(
+            "ds_read_b128 %0, %4\n\tds_read_b128 %1, %4 offset:2048\n\t"
+            "ds_read_b128 %2, %5\n\tds_read_b128 %3, %5 offset:2048\n\t"
+            "s_waitcnt lgkmcnt(0)"
+            : "=&v"(a0[0]), "=&v"(a1[0]), "=&v"(a0[1]), "=&v"(a1[1])
+            : "v"(ad[0]), "v"(ad[1])
+            : "memory");
+      }
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) {
+        s[0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a0[ks]), qb[ks], s[0], 0, 0, 0);
+        s[1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a1[ks]), qb[ks], s[1], 0, 0, 0);
+      }
+    } else {
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) {
+        const int off = l16 * ROWB + (((4 * ks + q) ^ (l16 & (CHUNKS - 1))) * 16);
+        const bf16x8_t a0 = *reinterpret_cast<const bf16x8_t*>(Kb + off);
+        const bf16x8_t a1 = *reinterpret_cast<const bf16x8_t*>(Kb + off + 16 * ROWB);
+        s[0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a0, qb[ks], s[0], 0, 0, 0);
+        s[1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a1, qb[ks], s[1], 0, 0, 0);
+      }
     }
     if (!ONE && next >= 0) issue_rows(kbytes, Kb, next);
     // ---- logits (log2 domain, log2(votes) folded in), group-mean logit for the EMA
@@ -634,27 +729,10 @@ __global__ __launch_bounds__(kMfmaWaves* kWave, 2) void decode_mfma_kernel(Decod
       }
     }
     first = false;
-    // ---- EMA update (Eq. 8) and optional logit output: lane (l16 < 8, q) owns slot 16 (l16 / 4) + 4 q + l16 % 4
-    {
-      float x = xm[0][0];
-#pragma unroll
-      for (int st = 0; st < 2; ++st)
-#pragma unroll
-        for (int i = 0; i < 4; ++i) x = (l16 == 4 * st + i) ? xm[st][i] : x;
-      const int row_mine = 16 * (l16 >> 2) + 4 * q + (l16 & 3);
-      const bool mine = l16 < 8 && row_mine < n_live;
-      const size_t at = ubase + (extra ? len_old : tbase + row_mine);
-      if (p.logits_out != nullptr && mine) p.logits_out[at] = x;
-      if constexpr (STEP) {
-        const float a = p.ln_alpha + ls_old, b = p.ln_1m_alpha + x;
-        const float hi = fmaxf(a, b), lo = fminf(a, b);
-        // ln(e^hi + e^lo) = hi + ln(1 + e^(lo - hi)) with the hardware exp2 / log2 (absolute error ~1e-7)
-        const float r = (lo == -INFINITY) ? hi : hi + kLn2 * fast_log2(1.f + fast_exp2((lo - hi) * kLog2e));
-        if (mine) {
-          p.log_s[at] = r;
-          p.n_obs[at] = no_old + 1;
-        }
-      }
+    if (v_in_flight) {                           // before any store is issued: only the V rows are outstanding
+      // (tied to the softmax sum, so that the wait is not scheduled ahead of the arithmetic it is meant to hide)
+      asm volatile("s_waitcnt vmcnt(0)" : "+v"(l_run) : : "memory");
+      clear_masked_v();
     }
     // ---- O += P V with P = hi + lo in bf16
     uint4 ah, al;
@@ -687,31 +765,74 @@ __global__ __launch_bounds__(kMfmaWaves* kWave, 2) void decode_mfma_kernel(Decod
       O[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a_lo, b, O[nt], 0, 0, 0);
     }
     if (!ONE && next >= 0) issue_rows(vbytes, Vb, next);
+    // ---- EMA update (Eq. 8) and optional logit output: lane (l16 < 8, q) owns slot 16 (l16 / 4) + 4 q + l16 % 4.
+    // After the second product: the compiler orders the V reads behind every outstanding memory operation,
+    // and stores issued before them would be waited for.
+    {
+      float x = xm[0][0];
+#pragma unroll
+      for (int st = 0; st < 2; ++st)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) x = (l16 == 4 * st + i) ? xm[st][i] : x;
+      const int row_mine = 16 * (l16 >> 2) + 4 * q + (l16 & 3);
+      const bool mine = l16 < 8 && row_mine < n_live;
+      const size_t at = ubase + (extra ? len_old : tbase + row_mine);
+      if (p.logits_out != nullptr && mine) p.logits_out[at] = x;
+      if constexpr (STEP) {
+        const float a = p.ln_alpha + ls_old, b = p.ln_1m_alpha + x;
+        const float hi = fmaxf(a, b), lo = fminf(a, b);
+        // ln(e^hi + e^lo) = hi + ln(1 + e^(lo - hi)) with the hardware exp2 / log2 (absolute error ~1e-7)
+        const float r = (lo == -INFINITY) ? hi : hi + kLn2 * fast_log2(1.f + fast_exp2((lo - hi) * kLog2e));
+        if (mine) {
+          p.log_s[at] = r;
+          p.n_obs[at] = no_old + 1;
+        }
+      }
+    }
   };
 
   while (base < lim) {                           // a single pass with ONE
     int pv[2][4];
-#pragma unroll
-    for (int st = 0; st < 2; ++st)
-#pragma unroll
-      for (int i = 0; i < 4; ++i) pv[st][i] = p.votes[ubase + min(base + 16 * st + 4 * q + i, bound - 1)];
     float ls_old = -INFINITY;
     int no_old = 0;
-    if constexpr (STEP) {
-      const size_t at = ubase + min(base + 16 * (l16 >> 2) + 4 * q + (l16 & 3), bound - 1);
-      ls_old = p.log_s[at];
-      no_old = p.n_obs[at];
+    if constexpr (ONE) {
+      // all copies but the youngest LOADS (the V rows) have landed: query rows, K rows, votes and EMA state
+      asm volatile("s_waitcnt vmcnt(%0)" ::"n"(LOADS) : "memory");
+      read_q();
+#pragma unroll
+      for (int st = 0; st < 2; ++st) {
+        const i32x4_t x = lds_read_b128_awaited(s_sc + (16 * st + 4 * q) * 4);
+        pv[st][0] = x[0], pv[st][1] = x[1], pv[st][2] = x[2], pv[st][3] = x[3];
+      }
+      if constexpr (STEP) {
+        const int mine = 16 * (l16 >> 2) + 4 * q + (l16 & 3);
+        ls_old = __builtin_bit_cast(float, lds_read_b32_awaited(s_sc + 256 + mine * 4));
+        no_old = lds_read_b32_awaited(s_sc + 512 + mine * 4);
+      }
+      compute(base, false, -1, pv, ls_old, no_old, true);
+      base = lim;
+    } else {
+#pragma unroll
+      for (int st = 0; st < 2; ++st)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) pv[st][i] = p.votes[ubase + min(base + 16 * st + 4 * q + i, bound - 1)];
+      if constexpr (STEP) {
+        const size_t at = ubase + min(base + 16 * (l16 >> 2) + 4 * q + (l16 & 3), bound - 1);
+        ls_old = p.log_s[at];
+        no_old = p.n_obs[at];
+      }
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");     // the tile (and the scalars above) have landed
+      const int next = base + kMfmaWaves * kMTile;
+      compute(base, false, next < lim ? next : -1, pv, ls_old, no_old, false);
+      base = next;
     }
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");       // the tile (and the scalars above) have landed
-    const int next = base + kMfmaWaves * kMTile;
-    compute(base, false, (!ONE && next < lim) ? next : -1, pv, ls_old, no_old);
-    base = ONE ? lim : next;
   }
   KK_TS(1);
   const bool grow = STEP && len_old < p.capacity;
   const int len = grow ? len_old + 1 : len_old;
   if (takes_new) {
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");       // the copy of the new token has landed
+    if constexpr (ONE) read_q();                 // (a wavefront without a tile of its own has not read them yet)
     if (grow) {
       if (lane < 2 * CHUNKS) {
         const uint4 x = *reinterpret_cast<const uint4*>(s_new + lane * 16);
@@ -724,7 +845,7 @@ __global__ __launch_bounds__(kMfmaWaves* kWave, 2) void decode_mfma_kernel(Decod
       __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
       __builtin_amdgcn_wave_barrier();
       const int one[2][4] = {{1, 1, 1, 1}, {1, 1, 1, 1}};
-      compute(0, true, -1, one, -INFINITY, 0);
+      compute(0, true, -1, one, -INFINITY, 0, false);
     }
   }
 
@@ -765,8 +886,9 @@ void launch_decode(const DecodeParams& p, int units, bool step, hipStream_t st) 
     if (!valu) {
       auto go = [&](auto waves_tag) {
         constexpr int WV = decltype(waves_tag)::value;
-        constexpr size_t tiles = (size_t)WV * 2 * kMTile * D * 2;
-        // 64 or 128 KB of tile buffers at D = 128, plus the kernel's static LDS: allow it explicitly
+        constexpr size_t tiles = (size_t)WV * 2 * kMTile * D * 2 + (size_t)WV * mfma_stage_bytes(D, G);
+        // 64 or 128 KB of tile buffers at D = 128, the per-wavefront staging of queries and scalars, plus the
+        // kernel's static LDS: allow it explicitly
         static const hipError_t attr[4] = {
             hipFuncSetAttribute((const void*)decode_mfma_kernel<D, G, true, true, WV>,
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)tiles),
