@@ -32,7 +32,7 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0
 # HBM bytes per launch of the fused decode kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled
 # by the copy-probe calibration (profiles/decode_hbm_traffic_llama3_8b.md).  Counters cannot be
 # read from inside this process, so the figure is the recorded one for the default workload.
-PMC_TRAFFIC_BYTES = {"llama3_8b": int((14461.4 * 2.00 + 1162.7 * 1.00) * 1024)}
+PMC_TRAFFIC_BYTES = {"llama3_8b": int((14470.7 * 2.00 + 1162.6 * 1.00) * 1024)}
 
 
 def parse():
