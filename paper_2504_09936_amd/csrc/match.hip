@@ -229,17 +229,20 @@ __global__ __launch_bounds__(kMWaves* kWave, 2) void match_mfma_kernel(MatchPara
   // ---- B operands: this wavefront's 64 evicted rows of the pass, resident in registers.  The byte offsets
   // of a pass's rows are fetched one pass ahead, the rows themselves as soon as the previous pass has
   // issued its last MFMA, so that their latency overlaps that pass's epilogue.
+  // (the slot numbers as loaded: any arithmetic on them would be a first use, and the compiler waits for a
+  // load at its first use -- here that is request_rows(), a whole pass later)
   auto row_offset = [&](int rb_, int t) {
-    return (uint32_t)evict[min(rb_ * kRowsPerBlock + wave * kRowsPerWave + t * 32 + l32, n_ev - 1)] * (uint32_t)ROWB;
+    return evict[min(rb_ * kRowsPerBlock + wave * kRowsPerWave + t * 32 + l32, n_ev - 1)];
   };
-  uint32_t row_off[2] = {row_offset(rb, 0), row_offset(rb, 1)};
+  int row_off[2] = {row_offset(rb, 0), row_offset(rb, 1)};
   bf16x8_t e[2][KS];
   auto request_rows = [&]() {
 #pragma unroll
     for (int t = 0; t < 2; ++t)
 #pragma unroll
       for (int ks = 0; ks < KS; ++ks)
-        e[t][ks] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4*>(kbytes + row_off[t] + ks * 32 + half * 16));
+        e[t][ks] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4*>(
+            kbytes + (uint32_t)row_off[t] * (uint32_t)ROWB + ks * 32 + half * 16));
   };
   request_rows();
 
@@ -472,18 +475,16 @@ __global__ __launch_bounds__(kSmallWaves* kWave, 2) void match_small_kernel(Matc
   bool slot_ok[kSmallBatch];
 #pragma unroll
   for (int i = 0; i < kSmallBatch; ++i) slot[i] = col_slot(min(first_cb + i * stride, ncb - 1));
-  // (2) the evicted rows -> LDS; a wavefront instruction deposits 64 consecutive 16-byte chunks
-#pragma unroll
-  for (int i = 0; i < ROW_LOADS; ++i) {
-    const int q = tid + i * (kSmallWaves * kWave);
-    const int r = q / CHUNKS, phys = q % CHUNKS;
-    const unsigned char* src = kbytes + ((uint32_t)ev_slot[i] * ROWB + ((phys ^ (r & (CHUNKS - 1))) * 16));
-    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
-                                     (__attribute__((address_space(3))) void*)(s_rows + (q - lane) * 16), 16, 0, 0);
-  }
-  // (3) the first batch of retained keys, as A operands: lane (l32, half) holds chunks 2 ks + half of column l32
+  // (2) the first batch of retained keys, as A operands: lane (l32, half) holds chunks 2 ks + half of column l32.
+  // They are requested BEFORE the evicted rows' asynchronous copies: the compiler waits for a load into
+  // registers (here the slot numbers) behind every outstanding asynchronous copy, so the other order put the
+  // rows' whole round trip in front of these requests, and each block's requests behind the previous block's.
   uint4 akey[kSmallBatch][KS];
   auto request_keys = [&](int cb_first) {
+    // one wait for all slot numbers, then all requests: a wait placed behind a conditional batch of requests
+    // would cover that batch as well
+    static_assert(kSmallBatch == 4, "the statement below names four slot numbers");
+    asm volatile("" : "+v"(slot[0]), "+v"(slot[1]), "+v"(slot[2]), "+v"(slot[3]));   // first use of all four: here
 #pragma unroll
     for (int i = 0; i < kSmallBatch; ++i) {
       slot_ok[i] = slot[i] >= 0;             // (a negative slot number: slot 0 stands in, its column scores 0)
@@ -494,7 +495,20 @@ __global__ __launch_bounds__(kSmallWaves* kWave, 2) void match_small_kernel(Matc
       }
     }
   };
+  // (the evicted rows' slot numbers too have their first use here, ahead of the key requests: their wait
+  // would otherwise come behind those requests and cover them)
+#pragma unroll
+  for (int i = 0; i < ROW_LOADS; ++i) asm volatile("" : "+v"(ev_slot[i]));
   request_keys(first_cb);
+  // (3) the evicted rows -> LDS; a wavefront instruction deposits 64 consecutive 16-byte chunks
+#pragma unroll
+  for (int i = 0; i < ROW_LOADS; ++i) {
+    const int q = tid + i * (kSmallWaves * kWave);
+    const int r = q / CHUNKS, phys = q % CHUNKS;
+    const unsigned char* src = kbytes + ((uint32_t)ev_slot[i] * ROWB + ((phys ^ (r & (CHUNKS - 1))) * 16));
+    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
+                                     (__attribute__((address_space(3))) void*)(s_rows + (q - lane) * 16), 16, 0, 0);
+  }
 
   int cls[2][16];
   int b1[2] = {0, 0}, b2[2] = {0, 0}, g1[2] = {0, 0};
