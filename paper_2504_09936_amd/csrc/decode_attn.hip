@@ -608,6 +608,25 @@ __global__ __launch_bounds__(kMfmaWaves* kWave, 2) void decode_mfma_kernel(Decod
     }
     issue_rows(vbytes, Vb, base);
   }
+  // !ONE: the votes and EMA state of a tile are requested one tile ahead, like its rows (into registers: they
+  // are first used behind the loop's full wait)
+  int pv_next[2][4];
+  float ls_next = -INFINITY;
+  int no_next = 0;
+  auto request_scalars = [&](int tbase) {
+#pragma unroll
+    for (int st = 0; st < 2; ++st)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) pv_next[st][i] = p.votes[ubase + min(tbase + 16 * st + 4 * q + i, bound - 1)];
+    if constexpr (STEP) {
+      const size_t at = ubase + min(tbase + 16 * (l16 >> 2) + 4 * q + (l16 & 3), bound - 1);
+      ls_next = p.log_s[at];
+      no_next = p.n_obs[at];
+    }
+  };
+  if constexpr (!ONE) {
+    if (base < lim) request_scalars(base);
+  }
 
   // B operand of the score product: column l16 is head l16 mod G, this lane's 8 channels of every k-step
   bf16x8_t qb[KS];
@@ -692,7 +711,10 @@ __global__ __launch_bounds__(kMfmaWaves* kWave, 2) void decode_mfma_kernel(Decod
         s[1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a1, qb[ks], s[1], 0, 0, 0);
       }
     }
-    if (!ONE && next >= 0) issue_rows(kbytes, Kb, next);
+    if (!ONE && next >= 0) {
+      issue_rows(kbytes, Kb, next);
+      request_scalars(next);
+    }
     // ---- logits (log2 domain, log2(votes) folded in), group-mean logit for the EMA
     float z[2][4], xm[2][4];
     float tm = -INFINITY;
@@ -812,16 +834,13 @@ __global__ __launch_bounds__(kMfmaWaves* kWave, 2) void decode_mfma_kernel(Decod
       compute(base, false, -1, pv, ls_old, no_old, true);
       base = lim;
     } else {
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");     // the tile and its scalars have landed
 #pragma unroll
       for (int st = 0; st < 2; ++st)
 #pragma unroll
-        for (int i = 0; i < 4; ++i) pv[st][i] = p.votes[ubase + min(base + 16 * st + 4 * q + i, bound - 1)];
-      if constexpr (STEP) {
-        const size_t at = ubase + min(base + 16 * (l16 >> 2) + 4 * q + (l16 & 3), bound - 1);
-        ls_old = p.log_s[at];
-        no_old = p.n_obs[at];
-      }
-      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");     // the tile (and the scalars above) have landed
+        for (int i = 0; i < 4; ++i) pv[st][i] = pv_next[st][i];
+      ls_old = ls_next;
+      no_old = no_next;
       const int next = base + kMfmaWaves * kMTile;
       compute(base, false, next < lim ? next : -1, pv, ls_old, no_old, false);
       base = next;
