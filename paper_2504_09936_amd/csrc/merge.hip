@@ -285,13 +285,39 @@ __global__ __launch_bounds__(256) void merge_apply_kernel(MergeParams p) {
     p.dlen[unit] = n < p.budget ? n : p.budget;
   }
   const size_t sbase = (size_t)unit * p.scap, dbase = (size_t)unit * p.dcap;
+  const uint4* sk = reinterpret_cast<const uint4*>(p.sk);
+  const uint4* sv = reinterpret_cast<const uint4*>(p.sv);
+  // The slot number of this position is requested first, and with DIRECT the retained row and its scalars are
+  // requested before the head's lists are waited for: requests complete in the order of issue, so the
+  // lists' round trip and the row's overlap instead of following each other.
+  const int c = r < p.budget ? p.keep_idx[(size_t)unit * p.budget + r] : -1;
   int n_ev = 0;
+  uint4 kc = make_uint4(0, 0, 0, 0), vc = make_uint4(0, 0, 0, 0);
+  int p_c = 0, n_c = 0;
+  float ls_c = 0.f;
+  auto request_row = [&]() {
+    const size_t at = sbase + max(c, 0);           // (a negative slot number: slot 0 stands in, unused)
+    kc = sk[at * LPS + sub];
+    vc = sv[at * LPS + sub];
+    p_c = p.svotes[at];
+    ls_c = p.slog_s[at];
+    n_c = p.sn_obs[at];
+  };
   if constexpr (DIRECT) {
     n_ev = min(p.n_evict[unit], kDirectMaxEvict);
     if (threadIdx.x == 0) s_drop = 0;
-    for (int i = threadIdx.x; i < n_ev; i += 256) {
-      s_match[i] = p.match[(size_t)unit * p.max_evict + i];
-      s_evict[i] = p.evict_idx[(size_t)unit * p.max_evict + i];
+    int mt[kDirectMaxEvict / 256], ev[kDirectMaxEvict / 256];
+    static_assert(kDirectMaxEvict == 256, "one list entry per thread");
+    mt[0] = ev[0] = 0;
+    if (n_ev > 0) {                                // uniform over the workgroup (the lists may be absent otherwise)
+      const int li = min((int)threadIdx.x, n_ev - 1);
+      mt[0] = p.match[(size_t)unit * p.max_evict + li];
+      ev[0] = p.evict_idx[(size_t)unit * p.max_evict + li];
+    }
+    request_row();
+    if ((int)threadIdx.x < n_ev) {
+      s_match[threadIdx.x] = mt[0];
+      s_evict[threadIdx.x] = ev[0];
     }
     __syncthreads();
     if (blockIdx.x == 0 && p.dropped_votes != nullptr) {       // uniform over the workgroup
@@ -304,8 +330,7 @@ __global__ __launch_bounds__(256) void merge_apply_kernel(MergeParams p) {
     }
   }
   if (r >= p.budget) return;
-  // two dependent round trips per row: (slot number, member range), then (rows, scalars)
-  const int c = p.keep_idx[(size_t)unit * p.budget + r];
+  // (without DIRECT: two dependent round trips per row, (slot number, member range), then (rows, scalars))
   int m0 = 0, m1 = 0;
   if constexpr (!DIRECT) {
     m0 = p.start[(size_t)unit * (p.budget + 1) + r];
@@ -325,15 +350,10 @@ __global__ __launch_bounds__(256) void merge_apply_kernel(MergeParams p) {
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
   }
   if (c < 0) return;
-  const uint4* sk = reinterpret_cast<const uint4*>(p.sk);
-  const uint4* sv = reinterpret_cast<const uint4*>(p.sv);
   uint4* dk = reinterpret_cast<uint4*>(p.dk);
   uint4* dv = reinterpret_cast<uint4*>(p.dv);
   const int nm = m1 - m0;                        // evicted members of this group
-  const uint4 kc = sk[(sbase + c) * LPS + sub], vc = sv[(sbase + c) * LPS + sub];
-  const int p_c = p.svotes[sbase + c];
-  const float ls_c = p.slog_s[sbase + c];
-  const int n_c = p.sn_obs[sbase + c];
+  if constexpr (!DIRECT) request_row();
 
   if (nm == 0) {                                  // nothing merged here: copy
     dk[(dbase + r) * LPS + sub] = kc;
