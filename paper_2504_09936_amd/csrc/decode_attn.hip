@@ -773,15 +773,49 @@ __global__ __launch_bounds__(kMfmaWaves* kWave, 2) void decode_mfma_kernel(Decod
     const bf16x8_t a_hi = __builtin_bit_cast(bf16x8_t, ah), a_lo = __builtin_bit_cast(bf16x8_t, al);
     // transpose read: lane s of a 16-lane block supplies the address of row s / 4, columns 4 (s mod 4) .. + 3, and
     // receives column s of the block's four rows
+    // The V tile has landed (awaited above or at the top of the loop) while the next tile's K rows may be on
+    // their way: the reads go through a statement the compiler does not order behind those copies.
     const int vrow = 4 * q + (l16 >> 2);
+    typedef __attribute__((ext_vector_type(2))) uint32_t u32x2_t;
+    u32x2_t b0[NTILE], b1[NTILE];
+    uint32_t va[NTILE];
 #pragma unroll
     for (int nt = 0; nt < NTILE; ++nt) {
       const int chunk = 2 * nt + ((l16 & 3) >> 1);
-      const unsigned char* va = Vb + vrow * ROWB + ((chunk ^ (vrow & (CHUNKS - 1))) * 16) + (l16 & 1) * 8;
-      const v4i16_t b0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) v4i16_t*)va);
-      const v4i16_t b1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) v4i16_t*)(va + 16 * ROWB));
-      const uint4 bw = make_uint4(__builtin_bit_cast(uint2, b0).x, __builtin_bit_cast(uint2, b0).y,
-                                  __builtin_bit_cast(uint2, b1).x, __builtin_bit_cast(uint2, b1).y);
+      va[nt] = (uint32_t)(uintptr_t)(const __attribute__((address_space(3))) void*)(
+          Vb + vrow * ROWB + ((chunk ^ (vrow & (CHUNKS - 1))) * 16) + (l16 & 1) * 8);
+    }
+    if constexpr (NTILE == 8) {                  // D = 128: rows 16 .. 31 of the tile are 4096 bytes further
+      static_assert(NTILE != 8 || 16 * ROWB == 4096, "offset in the statement below");
+      asm volatile(
+          "ds_read_b64_tr_b16 %0, %16\n\tds_read_b64_tr_b16 %1, %16 offset:4096\n\t"
+          "ds_read_b64_tr_b16 %2, %17\n\tds_read_b64_tr_b16 %3, %17 offset:4096\n\t"
+          "ds_read_b64_tr_b16 %4, %18\n\tds_read_b64_tr_b16 %5, %18 offset:4096\n\t"
+          "ds_read_b64_tr_b16 %6, %19\n\tds_read_b64_tr_b16 %7, %19 offset:4096\n\t"
+          "ds_read_b64_tr_b16 %8, %20\n\tds_read_b64_tr_b16 %9, %20 offset:4096\n\t"
+          "ds_read_b64_tr_b16 %10, %21\n\tds_read_b64_tr_b16 %11, %21 offset:4096\n\t"
+          "ds_read_b64_tr_b16 %12, %22\n\tds_read_b64_tr_b16 %13, %22 offset:4096\n\t"
+          "ds_read_b64_tr_b16 %14, %23\n\tds_read_b64_tr_b16 %15, %23 offset:4096\n\t"
+          "s_waitcnt lgkmcnt(0)"
+          : "=&v"(b0[0]), "=&v"(b1[0]), "=&v"(b0[1]), "=&v"(b1[1]), "=&v"(b0[2]), "=&v"(b1[2]), "=&v"(b0[3]), "=&v"(b1[3]),
+            "=&v"(b0[4]), "=&v"(b1[4]), "=&v"(b0[5]), "=&v"(b1[5]), "=&v"(b0[6]), "=&v"(b1[6]), "=&v"(b0[7]), "=&v"(b1[7])
+          : "v"(va[0]), "v"(va[1]), "v"(va[2]), "v"(va[3]), "v"(va[4]), "v"(va[5]), "v"(va[6]), "v"(va[7])
+          : "memory");
+    } else {                                     // D = 64: 2048 bytes further
+      static_assert(NTILE == 8 || (NTILE == 4 && 16 * ROWB == 2048), "offset in the statement below");
+      asm volatile(
+          "ds_read_b64_tr_b16 %0, %8\n\tds_read_b64_tr_b16 %1, %8 offset:2048\n\t"
+          "ds_read_b64_tr_b16 %2, %9\n\tds_read_b64_tr_b16 %3, %9 offset:2048\n\t"
+          "ds_read_b64_tr_b16 %4, %10\n\tds_read_b64_tr_b16 %5, %10 offset:2048\n\t"
+          "ds_read_b64_tr_b16 %6, %11\n\tds_read_b64_tr_b16 %7, %11 offset:2048\n\t"
+          "s_waitcnt lgkmcnt(0)"
+          : "=&v"(b0[0]), "=&v"(b1[0]), "=&v"(b0[1]), "=&v"(b1[1]), "=&v"(b0[2]), "=&v"(b1[2]), "=&v"(b0[3]), "=&v"(b1[3])
+          : "v"(va[0]), "v"(va[1]), "v"(va[2]), "v"(va[3])
+          : "memory");
+    }
+#pragma unroll
+    for (int nt = 0; nt < NTILE; ++nt) {
+      const uint4 bw = make_uint4(b0[nt][0], b0[nt][1], b1[nt][0], b1[nt][1]);
       const bf16x8_t b = __builtin_bit_cast(bf16x8_t, bw);
       O[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a_hi, b, O[nt], 0, 0, 0);
       O[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a_lo, b, O[nt], 0, 0, 0);
