@@ -16,7 +16,8 @@
  *    and return without waiting.  Calls on one stream execute in order.
  *  - Arguments are validated on the host before anything is enqueued; on a non-OK status
  *    nothing was launched and no output was touched.  KEEPKV_ERR_DEVICE reports a failed
- *    launch (hipGetLastError).  No exception crosses this boundary; there is no global state.
+ *    launch (hipGetLastError).  No exception crosses this boundary; there is no global state
+ *    and no environment variable is read.
  *  - Storage dtype of Q, K, V, O is f32 or bf16; all accumulation is f32 (f64 where an
  *    integer decision or a merge weight depends on it).
  *  - Scores are natural logarithms: log_s holds ln S_i of Eq. 8 (uncorrected EMA of the
@@ -66,6 +67,15 @@ typedef struct {
                         /* rows without waiting for len; slots in [len, len_hint) may    */
                         /* then be read but never influence a result.  A hint below some */
                         /* len gives undefined (memory-safe) results.                    */
+  int32_t  plan_slots_per_split; /* optional launch override for the decode calls (0 = the cost   */
+                        /* model of keepkv_decode_plan decides): slots per split, rounded down to */
+                        /* a multiple of 32 (bf16 matrix-core kernel) or 64, at least 64.         */
+  int32_t  plan_wavefronts;      /* optional (0 = automatic): 4 or 8 wavefronts per workgroup of   */
+                        /* the bf16 matrix-core kernel; -1 runs a bf16 cache on the vector-ALU    */
+                        /* kernel of the f32 path.  Overrides change the launch shape only (the   */
+                        /* summation order of Eq. 6 across splits), never the meaning; with one   */
+                        /* the workspace must hold 64 KiB + 256 + B*Hq*n_split*(D+2)*4 bytes,     */
+                        /* n_split = ceil(capacity / slots per split) <= 1024.                    */
 } keepkv_cache;
 
 /* Human-readable name of a status (static string). */

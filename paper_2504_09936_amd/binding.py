@@ -33,7 +33,8 @@ class _Layout(C.Structure):
 
 class _Cache(C.Structure):
     _fields_ = [("k", C.c_void_p), ("v", C.c_void_p), ("votes", C.c_void_p), ("log_s", C.c_void_p),
-                ("n_obs", C.c_void_p), ("len", C.c_void_p), ("capacity", C.c_int32), ("len_hint", C.c_int32)]
+                ("n_obs", C.c_void_p), ("len", C.c_void_p), ("capacity", C.c_int32), ("len_hint", C.c_int32),
+                ("plan_slots_per_split", C.c_int32), ("plan_wavefronts", C.c_int32)]
 
 
 _P = C.c_void_p
@@ -114,6 +115,8 @@ class Cache:
         B, H, D = layout.batch, layout.n_kv_heads, layout.head_dim
         self.layout, self.capacity = layout, capacity
         self.len_hint = 0     # host-side upper bound on len (0 = unknown); see keepkv_cache.len_hint
+        self.plan_slots_per_split = 0   # decode launch overrides (0 = automatic); see keepkv_cache
+        self.plan_wavefronts = 0
         self.k = torch.zeros(B, H, capacity, D, dtype=layout.torch_dtype, device=device)
         self.v = torch.zeros(B, H, capacity, D, dtype=layout.torch_dtype, device=device)
         self.votes = torch.zeros(B, H, capacity, dtype=torch.int32, device=device)
@@ -123,7 +126,8 @@ class Cache:
 
     def c(self) -> _Cache:
         return _Cache(self.k.data_ptr(), self.v.data_ptr(), self.votes.data_ptr(), self.log_s.data_ptr(),
-                      self.n_obs.data_ptr(), self.len.data_ptr(), self.capacity, int(self.len_hint))
+                      self.n_obs.data_ptr(), self.len.data_ptr(), self.capacity, int(self.len_hint),
+                      int(self.plan_slots_per_split), int(self.plan_wavefronts))
 
 
 def version() -> int:

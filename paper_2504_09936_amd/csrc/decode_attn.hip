@@ -12,7 +12,6 @@
 // shuffles and LDS; splits are combined by the last workgroup of each head to finish (a ticket
 // counter in the workspace head), so no second kernel is launched.
 #include <math.h>
-#include <stdlib.h>
 
 #include <type_traits>
 
@@ -123,10 +122,12 @@ __device__ __forceinline__ void combine_and_finish(const DecodeParams& p, const 
   KK_TS(3);
   // ---- the last workgroup of this head to arrive combines the splits ------------------------------
   // The partial results were stored write-through at device scope, so it is enough that every
-  // wavefront's stores have completed (workgroup-scope release = wait on the store counter) before
-  // the ticket is taken; a device-scope release fence here would write back the whole L2 per
-  // workgroup.  The combining workgroup reads the partials with device-scope loads.
-  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+  // wavefront's stores have completed before the ticket is taken: each wavefront waits on its own
+  // memory counter (stores count there on this part), then the barrier orders all of them before
+  // thread 0's ticket.  A workgroup-scope release fence emits no such wait here (the workgroup shares
+  // one L2, so the compiler needs none for that scope), and a device-scope release fence would write
+  // back the whole L2 per workgroup.  The combining workgroup reads the partials with device-scope loads.
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   __syncthreads();
   if (threadIdx.x == 0)
     s_last = (__hip_atomic_fetch_add(&p.ticket[unit], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == p.nsplit - 1);
@@ -927,7 +928,7 @@ __global__ __launch_bounds__(kMfmaWaves* kWave, 2) void decode_mfma_kernel(Decod
 }
 
 template <typename T, int D, int G>
-void launch_decode(const DecodeParams& p, int units, bool step, hipStream_t st) {
+keepkv_status launch_decode(const DecodeParams& p, int units, bool step, bool valu, hipStream_t st) {
   // 8 lanes per slot (16 channels each at D = 128 bf16) halves the cross-lane reduction work; the
   // widest group keeps 16 lanes per slot so that its accumulators still fit two waves per SIMD.
   constexpr int RV = D * (int)sizeof(T) / 16;                       // 16-byte vectors per row
@@ -935,55 +936,56 @@ void launch_decode(const DecodeParams& p, int units, bool step, hipStream_t st) 
   constexpr int U = 4;
   const dim3 grid(units * p.nsplit), block(kWavesPerBlock * kWave);
   if constexpr (sizeof(T) == 2) {
-    static const bool valu = getenv("KEEPKV_DECODE_VALU") != nullptr;     // tuning aid: the vector-ALU kernel
     if (!valu) {
-      auto go = [&](auto waves_tag) {
+      auto go = [&](auto waves_tag) -> keepkv_status {
         constexpr int WV = decltype(waves_tag)::value;
         constexpr size_t tiles = (size_t)WV * 2 * kMTile * D * 2 + (size_t)WV * mfma_stage_bytes(D, G);
         // 64 or 128 KB of tile buffers at D = 128, the per-wavefront staging of queries and scalars, plus the
-        // kernel's static LDS: allow it explicitly
-        static const hipError_t attr[4] = {
+        // kernel's static LDS: allow it explicitly (once per process and instance)
+        static const bool allowed =
             hipFuncSetAttribute((const void*)decode_mfma_kernel<D, G, true, true, WV>,
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)tiles),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)tiles) == hipSuccess &&
             hipFuncSetAttribute((const void*)decode_mfma_kernel<D, G, true, false, WV>,
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)tiles),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)tiles) == hipSuccess &&
             hipFuncSetAttribute((const void*)decode_mfma_kernel<D, G, false, true, WV>,
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)tiles),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)tiles) == hipSuccess &&
             hipFuncSetAttribute((const void*)decode_mfma_kernel<D, G, false, false, WV>,
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)tiles)};
-        (void)attr;                              // a refusal shows up as a launch error below
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)tiles) == hipSuccess;
+        if (!allowed) return KEEPKV_ERR_DEVICE;
         const dim3 mblock(WV * kWave);
         const bool one = p.per <= WV * kMTile;
         if (step && one) decode_mfma_kernel<D, G, true, true, WV><<<grid, mblock, tiles, st>>>(p);
         else if (step) decode_mfma_kernel<D, G, true, false, WV><<<grid, mblock, tiles, st>>>(p);
         else if (one) decode_mfma_kernel<D, G, false, true, WV><<<grid, mblock, tiles, st>>>(p);
         else decode_mfma_kernel<D, G, false, false, WV><<<grid, mblock, tiles, st>>>(p);
+        return KEEPKV_OK;
       };
-      if (p.waves == 8) go(std::integral_constant<int, 8>{});
-      else go(std::integral_constant<int, 4>{});
-      return;
+      if (p.waves == 8) return go(std::integral_constant<int, 8>{});
+      return go(std::integral_constant<int, 4>{});
     }
   }
   constexpr int parts = kWavesPerBlock * (kWave / (LPS < 16 ? 16 : LPS));
   constexpr size_t smem = (size_t)parts * G * (D + 2) * sizeof(float);
   if constexpr (smem > 64 * 1024) {
-    static const hipError_t a1 = hipFuncSetAttribute((const void*)decode_attn_kernel<T, D, G, LPS, U, true>,
-                                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-    static const hipError_t a2 = hipFuncSetAttribute((const void*)decode_attn_kernel<T, D, G, LPS, U, false>,
-                                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-    (void)a1; (void)a2;
+    static const bool allowed =
+        hipFuncSetAttribute((const void*)decode_attn_kernel<T, D, G, LPS, U, true>,
+                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem) == hipSuccess &&
+        hipFuncSetAttribute((const void*)decode_attn_kernel<T, D, G, LPS, U, false>,
+                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem) == hipSuccess;
+    if (!allowed) return KEEPKV_ERR_DEVICE;
   }
   if (step) decode_attn_kernel<T, D, G, LPS, U, true><<<grid, block, smem, st>>>(p);
   else decode_attn_kernel<T, D, G, LPS, U, false><<<grid, block, smem, st>>>(p);
+  return KEEPKV_OK;
 }
 
 template <typename T, int D>
-void dispatch_g(const DecodeParams& p, int units, int G, bool step, hipStream_t st) {
+keepkv_status dispatch_g(const DecodeParams& p, int units, int G, bool step, bool valu, hipStream_t st) {
   switch (G) {
-    case 1: launch_decode<T, D, 1>(p, units, step, st); break;
-    case 2: launch_decode<T, D, 2>(p, units, step, st); break;
-    case 4: launch_decode<T, D, 4>(p, units, step, st); break;
-    default: launch_decode<T, D, 8>(p, units, step, st); break;
+    case 1: return launch_decode<T, D, 1>(p, units, step, valu, st);
+    case 2: return launch_decode<T, D, 2>(p, units, step, valu, st);
+    case 4: return launch_decode<T, D, 4>(p, units, step, valu, st);
+    default: return launch_decode<T, D, 8>(p, units, step, valu, st);
   }
 }
 
@@ -997,7 +999,9 @@ keepkv_status run_decode(const keepkv_layout* layout, const keepkv_cache* cache,
   if (!layout_supported(layout)) return KEEPKV_ERR_UNSUPPORTED;
   const int units = layout->batch * layout->n_kv_heads;
   if (units > kMaxUnits) return KEEPKV_ERR_UNSUPPORTED;
-  const DecodePlan pl = plan_decode(layout, cache->capacity);
+  const int fw = cache->plan_wavefronts, fp = cache->plan_slots_per_split;
+  if (!(fw == 0 || fw == 4 || fw == 8 || fw == -1) || fp < 0 || (fp > 0 && fp < 64)) return KEEPKV_ERR_INVALID_ARG;
+  const DecodePlan pl = plan_decode(layout, cache->capacity, fp, fw);
   if (pl.nsplit > 1 && (!workspace || workspace_bytes < pl.bytes || !aligned16(workspace))) return KEEPKV_ERR_WORKSPACE;
 
   DecodeParams p;
@@ -1013,19 +1017,21 @@ keepkv_status run_decode(const keepkv_layout* layout, const keepkv_cache* cache,
 
   const int G = layout->n_q_heads / layout->n_kv_heads;
   hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+  keepkv_status rc;
   if (layout->dtype == KEEPKV_BF16) {
-    if (layout->head_dim == 128) dispatch_g<uint16_t, 128>(p, units, G, step, st);
-    else dispatch_g<uint16_t, 64>(p, units, G, step, st);
+    if (layout->head_dim == 128) rc = dispatch_g<uint16_t, 128>(p, units, G, step, pl.valu, st);
+    else rc = dispatch_g<uint16_t, 64>(p, units, G, step, pl.valu, st);
   } else {
-    if (layout->head_dim == 128) dispatch_g<float, 128>(p, units, G, step, st);
-    else dispatch_g<float, 64>(p, units, G, step, st);
+    if (layout->head_dim == 128) rc = dispatch_g<float, 128>(p, units, G, step, false, st);
+    else rc = dispatch_g<float, 64>(p, units, G, step, false, st);
   }
+  if (rc != KEEPKV_OK) return rc;
   return launch_status();
 }
 
 }  // namespace
 
-DecodePlan plan_decode(const keepkv_layout* L, int capacity) {
+DecodePlan plan_decode(const keepkv_layout* L, int capacity, int force_per, int force_waves) {
   // Slots per split, and for the matrix-core kernel its workgroup size, from a small cost model fitted to
   // measurements on MI355X (batch 1..128, 850..32768 slots per head).  Workgroups of 4 wavefronts fit two to
   // a compute unit (512 resident), those of 8 wavefronts one (128 KB of tile buffers at D = 128: 256
@@ -1041,7 +1047,7 @@ DecodePlan plan_decode(const keepkv_layout* L, int capacity) {
   DecodePlan pl;
   const double units = (double)L->batch * L->n_kv_heads;
   const double slot_bytes = 2.0 * L->head_dim * (L->dtype == KEEPKV_BF16 ? 2 : 4) + 24.0;
-  static const bool valu = getenv("KEEPKV_DECODE_VALU") != nullptr;
+  const bool valu = L->dtype == KEEPKV_BF16 && force_waves == -1;
   const bool mfma = L->dtype == KEEPKV_BF16 && !valu;
   const int rv = L->head_dim * (L->dtype == KEEPKV_BF16 ? 2 : 4) / 16;
   long per = 128;
@@ -1076,11 +1082,10 @@ DecodePlan plan_decode(const keepkv_layout* L, int capacity) {
       }
     }
   }
-  static const long forced_waves = [] { const char* e = getenv("KEEPKV_DECODE_WAVES"); return e ? atol(e) : 0L; }();
-  if (mfma && (forced_waves == 4 || forced_waves == 8)) waves = (int)forced_waves;
+  if (mfma && (force_waves == 4 || force_waves == 8)) waves = force_waves;
   pl.waves = waves;
-  static const long forced = [] { const char* e = getenv("KEEPKV_DECODE_CHUNK"); return e ? atol(e) : 0L; }();
-  if (forced >= 64) per = mfma ? forced / 32 * 32 : forced / 64 * 64;
+  pl.valu = valu;
+  if (force_per >= 64) per = mfma ? force_per / 32 * 32 : force_per / 64 * 64;
   long ns = (capacity + per - 1) / per;
   if (ns > 1024) { ns = 1024; per = ((capacity + ns - 1) / ns + 63) / 64 * 64; ns = (capacity + per - 1) / per; }   // (max_ns caps it already)
   pl.nsplit = (int)ns;

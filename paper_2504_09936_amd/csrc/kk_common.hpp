@@ -95,10 +95,12 @@ struct DecodePlan {
   int nsplit;         // workgroups per (batch, kv head)
   int per;            // slots per split (a multiple of 32; of 64 for the vector-ALU kernel)
   int waves;          // wavefronts per workgroup of the matrix-core kernel (4 or 8)
+  bool valu;          // a bf16 cache on the vector-ALU kernel (only by the caller's override)
   size_t partial_off; // float [B*Hq, nsplit, D + 2]
   size_t bytes;
 };
-DecodePlan plan_decode(const keepkv_layout* L, int capacity);
+// force_per / force_waves: the caller's overrides (keepkv_cache.plan_slots_per_split / plan_wavefronts), 0 = none
+DecodePlan plan_decode(const keepkv_layout* L, int capacity, int force_per = 0, int force_waves = 0);
 
 struct SelectPlan {
   size_t keys_off;    // uint64 [B*Hkv, capacity]

@@ -640,7 +640,7 @@ __global__ __launch_bounds__(kSmallWaves* kWave, 2) void match_small_kernel(Matc
     __hip_atomic_store(mine + 0, v1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     __hip_atomic_store(mine + 1, cc, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     __hip_atomic_store(mine + 2, v2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");          // the wavefront's stores have completed
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");                // the wavefront's write-through stores have completed
     int ticket = 0;
     if (lane == 0) ticket = __hip_atomic_fetch_add(&p.exact_ticket[blk], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     ticket = __builtin_amdgcn_readfirstlane(ticket);
@@ -807,7 +807,7 @@ __global__ __launch_bounds__(256) void match_exact_kernel(MatchParams p) {
         __hip_atomic_store(&mine->best_bits, __builtin_bit_cast(unsigned long long, best), __ATOMIC_RELAXED,
                            __HIP_MEMORY_SCOPE_AGENT);
         __hip_atomic_store(&mine->best_c, best_c, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");          // the two stores have completed
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");                // the two write-through stores have completed
         finish = __hip_atomic_fetch_add(&p.exact_ticket[f], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == parts - 1;
         if (finish) {                     // the last share of this row: join them, in list order
           best = -INFINITY;

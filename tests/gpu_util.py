@@ -60,21 +60,26 @@ def workspace(lay, capacity, budget):
     return kk().new_workspace(lay, capacity, budget)
 
 
-def storage_err_rows(got, ref, dtype, slack=5e-5):
+def storage_err_rows(got, ref, dtype, slack=5e-6, return_forgiven=False):
     """Per-vector relative error of a result stored in `dtype` against the fp64 reference `ref` rounded to
     that storage.  Two correct evaluations round an element to neighbouring bf16 values when the exact
     value lies within the arithmetic's own error of the midpoint between them (one bf16 ulp is up to
     2^-7 of the element, so a single such element can exceed the vector tolerance by itself): an element
     that is adjacent to the rounded reference while the reference is within `slack` of the vector's norm
-    of their midpoint counts as equal."""
+    of their midpoint counts as equal.  `slack` is the f32 accumulation error of the kernels relative to the
+    vector (a few 1e-7 observed; 5e-6 allowed).  With `return_forgiven` the number of elements the rule
+    applied to is returned as well, so that a test can bound it."""
     got, ref = np.asarray(got, np.float64), np.asarray(ref, np.float64)
     r = np.asarray(W.round_storage(ref, dtype), np.float64)
+    forgiven = 0
     if dtype == "bf16":
         norm = np.linalg.norm(ref, axis=-1, keepdims=True)
         adjacent = (got != r) & (np.abs(got - r) <= 2.0 ** -7 * np.abs(r) * 1.001)
         at_midpoint = np.abs(ref - 0.5 * (got + r)) <= slack * norm
+        forgiven = int((adjacent & at_midpoint).sum())
         got = np.where(adjacent & at_midpoint, r, got)
-    return rel_err_rows(got, r)
+    err = rel_err_rows(got, r)
+    return (err, forgiven) if return_forgiven else err
 
 
 def rel_err_rows(got, ref):

@@ -28,6 +28,15 @@ def test_storage_err_rows_forgives_only_midpoint_neighbours():
     got2 = _bf16(ref2)
     got2[0, 3] = lo
     assert U.storage_err_rows(got2, ref2, "bf16")[0] > 1e-3
+    # ... and so is an exact value 2e-4 from the midpoint (1e-5 of this vector's norm: beyond the arithmetic's error)
+    ref4 = ref.copy()
+    ref4[0, 3] = 0.5 * (lo + hi) + 2e-4
+    assert 2e-4 > 5e-6 * np.linalg.norm(ref4[0])
+    got4 = _bf16(ref4)
+    got4[0, 3] = lo
+    err4, n4 = U.storage_err_rows(got4, ref4, "bf16", return_forgiven=True)
+    assert err4[0] > 1e-3 and n4 == 0
+    assert U.storage_err_rows(got, ref, "bf16", return_forgiven=True)[1] == 1
     # two ulps away is never forgiven, midpoint or not
     got3 = _bf16(ref)
     got3[0, 3] = lo - (hi - lo)
