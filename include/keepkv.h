@@ -134,6 +134,22 @@ keepkv_status keepkv_decode_step(const keepkv_layout *layout, keepkv_cache *cach
                                  float alpha, int32_t *overflow, void *workspace,
                                  size_t workspace_bytes, void *stream);
 
+/* keepkv_decode_step for callers that cannot allocate device memory and hold no workspace: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, meaning and
+ * results as keepkv_decode_step, without the workspace: the split partial results and tickets live in a
+ * static device array inside the library (64 KiB + 256 bytes of control words + 4 MiB; every GPU the
+ * library runs on holds its own copy until the process ends).  Nothing is allocated or freed, by this
+ * call or by anything it calls.  A shape whose partial results exceed the array
+ * (B * Hq * n_split * (D + 2) * 4 bytes > 4 MiB with n_split > 1, see keepkv_decode_plan) is refused with
+ * KEEPKV_ERR_UNSUPPORTED before anything is launched.  All calls on one GPU share that GPU's array: calls
+ * that may overlap there (different streams, no dependency) race and must use keepkv_decode_step with
+ * workspaces of their own.  The first call on a device looks up the array's address and enqueues one
+ * small kernel on `stream` that clears the control words; every call leaves them zero. */
+keepkv_status keepkv_decode_step_static(const keepkv_layout *layout, keepkv_cache *cache,
+                                        const void *q, const void *k_t, const void *v_t, void *out,
+                                        float *logits_out, float alpha, int32_t *overflow,
+                                        void *stream);
+
 /* EMA score update (Eq. 8, t > L branch; Alg. 1 line 6) on the live slots:
  *     S_i <- alpha S_i + (1 - alpha) exp(logits[i]),  n_obs_i += 1
  * held as log_s_i = ln S_i.  logits: DEVICE f32 [B, Hkv, capacity] as written by

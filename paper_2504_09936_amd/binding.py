@@ -48,6 +48,7 @@ _lib.keepkv_decode_attn.argtypes = [C.POINTER(_Layout), C.POINTER(_Cache), _P, _
 _lib.keepkv_workspace_init.argtypes = [_P, C.c_size_t, _P]
 _lib.keepkv_decode_step.argtypes = [C.POINTER(_Layout), C.POINTER(_Cache), _P, _P, _P, _P, _P, C.c_float, _P, _P,
                                     C.c_size_t, _P]
+_lib.keepkv_decode_step_static.argtypes = [C.POINTER(_Layout), C.POINTER(_Cache), _P, _P, _P, _P, _P, C.c_float, _P, _P]
 _lib.keepkv_score.argtypes = [C.POINTER(_Layout), C.POINTER(_Cache), _P, C.c_float, _P]
 _lib.keepkv_score_window.argtypes = [C.POINTER(_Layout), C.POINTER(_Cache), _P, C.c_int32, C.c_float, C.c_int32, _P]
 _lib.keepkv_select.argtypes = [C.POINTER(_Layout), C.POINTER(_Cache), C.c_int32, C.c_int32, C.c_int32,
@@ -62,13 +63,13 @@ _lib.keepkv_probe_read.argtypes = [_P, C.c_size_t, C.c_int32, _P, _P]
 _lib.keepkv_probe_mfma.argtypes = [C.c_int32, C.c_int32, C.c_int32, _P, C.POINTER(C.c_double), _P]
 _lib.keepkv_decode_plan.argtypes = [C.POINTER(_Layout), C.c_int32, C.POINTER(C.c_int32), C.POINTER(C.c_int32),
                                     C.POINTER(C.c_int32)]
-for _f in ("decode_plan", "probe_read", "probe_mfma", "append", "decode_attn", "decode_step", "workspace_init", "score", "score_window", "select",
+for _f in ("decode_step_static", "decode_plan", "probe_read", "probe_mfma", "append", "decode_attn", "decode_step", "workspace_init", "score", "score_window", "select",
            "select_by_key", "match",
            "merge"):
     getattr(_lib, "keepkv_" + _f).restype = C.c_int
 
 EXPORTS = ["keepkv_strerror", "keepkv_version", "keepkv_workspace_bytes", "keepkv_workspace_init", "keepkv_decode_plan",
-           "keepkv_append", "keepkv_decode_attn", "keepkv_decode_step", "keepkv_score", "keepkv_score_window", "keepkv_select",
+           "keepkv_append", "keepkv_decode_attn", "keepkv_decode_step", "keepkv_decode_step_static", "keepkv_score", "keepkv_score_window", "keepkv_select",
            "keepkv_select_by_key", "keepkv_match", "keepkv_merge", "keepkv_probe_read", "keepkv_probe_mfma"]
 
 
@@ -157,6 +158,12 @@ def decode_step(layout: Layout, cache: Cache, q, k_t, v_t, out, logits_out, alph
     _check(_lib.keepkv_decode_step(C.byref(layout.c()), C.byref(cache.c()), _ptr(q), _ptr(k_t), _ptr(v_t), _ptr(out),
                                    _ptr(logits_out), alpha, _ptr(overflow), _ptr(workspace), _nbytes(workspace),
                                    _stream()), "keepkv_decode_step")
+
+
+def decode_step_static(layout: Layout, cache: Cache, q, k_t, v_t, out, logits_out, alpha: float, overflow) -> None:
+    _check(_lib.keepkv_decode_step_static(C.byref(layout.c()), C.byref(cache.c()), _ptr(q), _ptr(k_t), _ptr(v_t),
+                                          _ptr(out), _ptr(logits_out), alpha, _ptr(overflow), _stream()),
+           "keepkv_decode_step_static")
 
 
 def append(layout: Layout, cache: Cache, k_t, v_t, overflow=None) -> None:

@@ -13,6 +13,8 @@
 // counter in the workspace head), so no second kernel is launched.
 #include <math.h>
 
+#include <mutex>
+
 #include <type_traits>
 
 #include "kk_common.hpp"
@@ -1029,6 +1031,41 @@ keepkv_status run_decode(const keepkv_layout* layout, const keepkv_cache* cache,
   return launch_status();
 }
 
+// ---- scratch for the entry point that takes no workspace --------------------------------------------------
+// One array per GPU, held by the code object until the process ends.  In host code `scratch` is only a handle:
+// the device address comes from hipGetSymbolAddress, once per device with that device current, and that address
+// is what kernels receive.
+constexpr size_t kStaticPartialBytes = (size_t)4 << 20;
+constexpr size_t kStaticScratchBytes = kWorkspaceHead + kStaticPartialBytes;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+constexpr int kMaxDevices = 64;
+void* g_scratch_ptr[kMaxDevices];     // per device, filled on the first call there
+std::mutex g_scratch_mutex;
+
+__global__ void clear_words_kernel(int32_t* w, int n) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) w[i] = 0;
+}
+
+keepkv_status static_scratch(void** out, hipStream_t st) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return KEEPKV_ERR_DEVICE;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (g_scratch_ptr[dev] == nullptr) {
+    void* ptr = nullptr;
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || ptr == nullptr) return KEEPKV_ERR_DEVICE;
+    // The control words (split tickets) must be zero when a call starts.  Every launch leaves them zero, so
+    // they are cleared once, ahead of the first launch on this device (a kernel: it may be captured).
+    const int n = (int)(kWorkspaceHead / sizeof(int32_t));
+    clear_words_kernel<<<(n + 255) / 256, 256, 0, st>>>(reinterpret_cast<int32_t*>(ptr), n);
+    if (hipGetLastError() != hipSuccess) return KEEPKV_ERR_DEVICE;
+    g_scratch_ptr[dev] = ptr;
+  }
+  *out = g_scratch_ptr[dev];
+  return KEEPKV_OK;
+}
+
 }  // namespace
 
 DecodePlan plan_decode(const keepkv_layout* L, int capacity, int force_per, int force_waves) {
@@ -1110,6 +1147,27 @@ extern "C" keepkv_status keepkv_decode_step(const keepkv_layout* layout, keepkv_
                                             void* stream) {
   return kk::run_decode(layout, cache, q, k_t, v_t, out, logits_out, nullptr, alpha, overflow, true, workspace,
                         workspace_bytes, stream);
+}
+
+extern "C" keepkv_status keepkv_decode_step_static(const keepkv_layout* layout, keepkv_cache* cache, const void* q,
+                                                   const void* k_t, const void* v_t, void* out, float* logits_out,
+                                                   float alpha, int32_t* overflow, void* stream) {
+  using namespace kk;
+  // validate first (nothing is launched, not even the one-time clear, on bad arguments), then size
+  if (!layout_ok(layout) || !cache_ok(cache) || !q || !out || !k_t || !v_t) return KEEPKV_ERR_INVALID_ARG;
+  if (!aligned16(q) || !aligned16(out) || !aligned16(cache->k) || !aligned16(cache->v) || !aligned16(k_t) ||
+      !aligned16(v_t) || !(alpha >= 0.f && alpha < 1.f))
+    return KEEPKV_ERR_INVALID_ARG;
+  if (!layout_supported(layout) || !units_supported(layout)) return KEEPKV_ERR_UNSUPPORTED;
+  const int fw = cache->plan_wavefronts, fp = cache->plan_slots_per_split;
+  if (!(fw == 0 || fw == 4 || fw == 8 || fw == -1) || fp < 0 || (fp > 0 && fp < 64)) return KEEPKV_ERR_INVALID_ARG;
+  const DecodePlan pl = plan_decode(layout, cache->capacity, fp, fw);
+  if (pl.nsplit > 1 && pl.bytes > kStaticScratchBytes) return KEEPKV_ERR_UNSUPPORTED;   // partials beyond the static array
+  void* ptr = nullptr;
+  const keepkv_status rc = static_scratch(&ptr, reinterpret_cast<hipStream_t>(stream));
+  if (rc != KEEPKV_OK) return rc;
+  return run_decode(layout, cache, q, k_t, v_t, out, logits_out, nullptr, alpha, overflow, true, ptr,
+                    kStaticScratchBytes, stream);
 }
 
 #ifdef KEEPKV_TRACE

@@ -1,0 +1,105 @@
+"""keepkv_decode_step_static (the entry point for callers that cannot allocate: no workspace argument, split
+partials and tickets in a static device array of the library) against keepkv_decode_step on identical cache
+copies: two calls in a row, the second on a smaller input, results bit for bit those of the workspace call
+(same kernels, same plan), which the other tests hold to the oracle's bar.  Also the size limit and that the
+call performs no device allocation as seen by torch's allocator statistics."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2504_09936_amd import workloads as W
+from tests import gpu_util as U
+
+pytestmark = pytest.mark.gpu
+
+
+def _state(w, cap, seed):
+    g = np.random.default_rng(seed)
+    B, H = w.batch, w.n_kv_heads
+    K, V = W.make_cache(w.scaled(context=cap), seed)
+    lens = g.integers(max(1, cap - 100), cap, size=(B, H)).astype(np.int32)
+    lens.flat[0] = cap                         # a head at capacity (overflow path)
+    if lens.size > 1:
+        lens.flat[1] = 0                       # an empty head
+    votes = g.integers(1, 6, size=(B, H, cap)).astype(np.int32)
+    log_s = g.standard_normal((B, H, cap)).astype(np.float32)
+    n_obs = g.integers(1, 40, size=(B, H, cap)).astype(np.int32)
+
+    def make():
+        lay, c = U.new_cache(w, capacity=cap, K=K, V=V, votes=votes, lens=lens)
+        c.log_s[:] = torch.from_numpy(log_s).cuda()
+        c.n_obs[:] = torch.from_numpy(n_obs).cuda()
+        return lay, c
+    return make
+
+
+def _same(a, b):
+    for name in ("k", "v", "votes", "log_s", "n_obs", "len"):
+        x, y = getattr(a, name), getattr(b, name)
+        if x.dtype == torch.bfloat16:
+            x, y = x.view(torch.int16), y.view(torch.int16)
+        if x.dtype == torch.float32:
+            x, y = x.view(torch.int32), y.view(torch.int32)
+        assert torch.equal(x, y), name
+
+
+def _run_pair(w, cap, seed, steps):
+    kk = U.kk()
+    make = _state(w, cap, seed)
+    lay, ca = make()
+    _, cb = make()
+    ws = U.workspace(lay, cap, max(1, cap // 2))
+    nsplit = kk.decode_plan(lay, cap)[0]
+    alpha = U.f32(0.9)
+    B, D = w.batch, w.head_dim
+    out_a = torch.zeros(B, w.n_q_heads, D, dtype=lay.torch_dtype, device="cuda")
+    out_b = torch.full_like(out_a, 3.0)
+    lg_a = torch.zeros(B, w.n_kv_heads, cap, dtype=torch.float32, device="cuda")
+    lg_b = torch.ones_like(lg_a)
+    ov_a = torch.zeros(1, dtype=torch.int32, device="cuda")
+    ov_b = torch.zeros(1, dtype=torch.int32, device="cuda")
+    for t in range(steps):
+        q = U.to_device(W.make_query(w, seed, t), w.dtype)
+        k_t, v_t = W.make_token(w, seed, t)
+        k_t, v_t = U.to_device(k_t, w.dtype), U.to_device(v_t, w.dtype)
+        kk.decode_step(lay, ca, q, k_t, v_t, out_a, lg_a, alpha, ov_a, ws)
+        torch.cuda.synchronize()
+        before = torch.cuda.memory_stats()["allocation.all.allocated"]
+        kk.decode_step_static(lay, cb, q, k_t, v_t, out_b, lg_b, alpha, ov_b)
+        torch.cuda.synchronize()
+        assert torch.cuda.memory_stats()["allocation.all.allocated"] == before
+        assert torch.equal(out_a.view(torch.int16 if out_a.dtype == torch.bfloat16 else torch.int32),
+                           out_b.view(torch.int16 if out_b.dtype == torch.bfloat16 else torch.int32)), (w.name, t)
+        lens = ca.len.cpu().numpy()
+        for b in range(B):
+            for h in range(w.n_kv_heads):
+                n = lens[b, h]
+                assert torch.equal(lg_a[b, h, :n].view(torch.int32), lg_b[b, h, :n].view(torch.int32))
+        _same(ca, cb)
+        assert ov_a.item() == ov_b.item() == 1
+    return nsplit
+
+
+def test_static_scratch_entry_point_equals_workspace_call_twice_second_smaller():
+    big = W.CONFIGS["llama3_8b"].scaled(batch=4, context=884)          # several splits per head
+    small = W.CONFIGS["llama3_8b"].scaled(batch=1, n_q_heads=8, n_kv_heads=2, context=300)
+    ns_big = _run_pair(big, 884, 21, 2)
+    ns_small = _run_pair(small, 300, 22, 2)
+    assert ns_big > 1 and ns_small >= 1
+    ns_g8 = _run_pair(W.CONFIGS["llama3_70b"].scaled(batch=2, context=500), 500, 23, 1)   # G = 8 after the small one
+    assert ns_g8 >= 1
+
+
+def test_static_scratch_entry_point_refuses_what_does_not_fit():
+    kk = U.kk()
+    w = W.CONFIGS["llama3_8b"].scaled(batch=4, context=16384)
+    lay = U.layout_of(w)
+    c = kk.Cache(lay, 64)            # storage far smaller than the claimed capacity: the call must not launch
+    c.capacity = 16384
+    c.plan_slots_per_split = 64      # 256 splits per head: 4 * 32 * 256 * 130 * 4 bytes of partials = 17 MB > 4 MiB
+    z = torch.zeros(w.batch, w.n_q_heads, w.head_dim, dtype=torch.bfloat16, device="cuda")
+    kv = torch.zeros(w.batch, w.n_kv_heads, w.head_dim, dtype=torch.bfloat16, device="cuda")
+    with pytest.raises(kk.KeepKVError) as e:
+        kk.decode_step_static(lay, c, z, kv, kv, z, None, 0.9, None)
+    assert e.value.status == kk.ERR_UNSUPPORTED
+    torch.cuda.synchronize()
