@@ -286,8 +286,8 @@ __global__ __launch_bounds__(kWavesPerBlock* kWave) void decode_attn_kernel(Deco
         pv[j] = p.votes[ubase + s];              // unconditional and in bounds: a branch behind a
 #pragma unroll                                   // load would serialise the row loads
         for (int v = 0; v < VPL; ++v) {
-          kk_[j][v] = ka[v * LPS];
-          vv_[j][v] = va[v * LPS];
+          kk_[j][v] = load_once(ka + v * LPS);
+          vv_[j][v] = load_once(va + v * LPS);
         }
       }
     }
@@ -497,6 +497,11 @@ __global__ __launch_bounds__(kWavesPerBlock* kWave) void decode_attn_kernel(Deco
 // P is split into two bf16 terms (hi + lo, 16 significant bits), V is bf16 already, accumulation f32.
 // Output rows are heads again (row r = head r mod G), 16 channels per MFMA.
 constexpr int kMTile = 32;
+// Cache policy of the K / V row loads: every row is read once per launch, so the loads carry the non-temporal
+// hint (the `nt` bit) and do not displace what the caches hold for reuse (a plain stream of 453 MB read this way
+// measured 6.9 TB/s against 6.0 TB/s without the hint, and the small read-modify-write traffic of the EMA state
+// beside it cost 1 us instead of 12).
+constexpr int kStreamOnce = 2;
 // Per wavefront, behind the tile buffers: the head group's query rows (whole 1 KB pieces, one asynchronous
 // 16-byte copy per lane each) and the tile's votes, ln S and observation counts (4 bytes per lane each).
 constexpr int mfma_stage_bytes(int D, int G) { return (G * D * 2 + 1023) / 1024 * 1024 + 3 * 256; }
@@ -564,8 +569,11 @@ __global__ __launch_bounds__(kMfmaWaves* kWave, 2) void decode_mfma_kernel(Decod
   const size_t ubase = (size_t)unit * p.capacity;
   const unsigned char* kbytes = reinterpret_cast<const unsigned char*>(p.k) + ubase * ROWB;
   const unsigned char* vbytes = reinterpret_cast<const unsigned char*>(p.v) + ubase * ROWB;
-  unsigned char* Kb = smem_raw + wave * (2 * TILE_BYTES);
-  unsigned char* Vb = Kb + TILE_BYTES;
+  // ONE: [K tile | V tile] of the wavefront's single tile.  Otherwise the K rows travel straight into registers
+  // (below) and the two buffers hold the V rows of the current and of the next tile.
+  unsigned char* const Tb = smem_raw + wave * (2 * TILE_BYTES);
+  unsigned char* const Kb = Tb;
+  unsigned char* Vb = ONE ? Tb + TILE_BYTES : Tb;
   // ONE: everything this wavefront waits for travels as asynchronous global -> LDS copies, requested in the
   // order query rows, K rows, votes and EMA state, V rows.  Such copies complete in the order of issue, so a
   // wait that leaves the V rows' LOADS copies outstanding guarantees all the others: the score product and
@@ -592,12 +600,26 @@ __global__ __launch_bounds__(kMfmaWaves* kWave, 2) void decode_mfma_kernel(Decod
       const int row = c / CHUNKS, phys = c % CHUNKS;
       const size_t off = (size_t)min(tbase + row, bound - 1) * ROWB + ((phys ^ (row & (CHUNKS - 1))) * 16);
       __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(rows + off),
-                                       (__attribute__((address_space(3))) void*)(buf + i * (kWave * 16)), 16, 0, 0);
+                                       (__attribute__((address_space(3))) void*)(buf + i * (kWave * 16)), 16, 0, kStreamOnce);
+    }
+  };
+  // !ONE: the K rows of a tile are loaded in the layout of the score product's A operand (lane (l16, q): rows
+  // l16 and 16 + l16 of the tile, chunk 4 ks + q of the row for k-step ks), one tile ahead, so a tile's K rows
+  // pass through no LDS at all and a wavefront has a whole tile (K in registers, V on its way to the other LDS
+  // buffer) in flight during all of the arithmetic on the current one.
+  bf16x8_t kn[2][KS], kreg[2][KS];
+  auto issue_k = [&](int tbase) {
+#pragma unroll
+    for (int st = 0; st < 2; ++st) {
+      const unsigned char* row = kbytes + (size_t)min(tbase + 16 * st + l16, bound - 1) * ROWB + q * 16;
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) kn[st][ks] = __builtin_nontemporal_load(reinterpret_cast<const bf16x8_t*>(row + ks * 64));
     }
   };
   int base = start + wave * kMTile;
   if (base < lim) {
-    issue_rows(kbytes, Kb, base);
+    if constexpr (ONE) issue_rows(kbytes, Kb, base);
+    else issue_k(base);
     if constexpr (ONE) {                         // slot base + lane of the tile (lanes beyond the tile repeat a slot)
       const size_t at = ubase + min(base + lane, bound - 1);
       __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(p.votes + at),
@@ -644,6 +666,12 @@ __global__ __launch_bounds__(kMfmaWaves* kWave, 2) void decode_mfma_kernel(Decod
     for (int ks = 0; ks < KS; ++ks) qb[ks] = *reinterpret_cast<const bf16x8_t*>(qrow + ks * 64 + q * 16);
   }
 
+  // Tile loop, step mode: the updated EMA state (ln S, n) of a split is collected in LDS (the staging area the
+  // single-tile variant uses for queries and scalars) and written out by the whole workgroup once all tiles
+  // are done, when it fits: many small stores spread over the streaming phase slow the row stream down more
+  // than their bytes account for, one burst per workgroup less so.
+  unsigned char* const s_stage = smem_raw + kMfmaWaves * 2 * TILE_BYTES;
+  const bool staged = !ONE && STEP && (size_t)p.per * 8 <= (size_t)kMfmaWaves * mfma_stage_bytes(D, G);
   const float sl2 = p.scale * kLog2e;
   float m_run = -INFINITY, l_run = 0.f;
   f32x4_t O[NTILE];
@@ -668,9 +696,22 @@ __global__ __launch_bounds__(kMfmaWaves* kWave, 2) void decode_mfma_kernel(Decod
       }
     };
     if (!v_in_flight) clear_masked_v();
+    if (!ONE && next >= 0) {
+      // the next tile: K rows and scalars into registers, V rows into the other buffer (after the clearing
+      // stores above: the compiler orders LDS stores behind outstanding copies into LDS)
+      issue_k(next);
+      request_scalars(next);
+      issue_rows(vbytes, Tb + (Vb == Tb ? TILE_BYTES : 0), next);
+    }
     // ---- S^T = K Q^T
     f32x4_t s[2] = {f32x4_t{0.f, 0.f, 0.f, 0.f}, f32x4_t{0.f, 0.f, 0.f, 0.f}};
-    if (v_in_flight) {
+    if constexpr (!ONE) {
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) {
+        s[0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kreg[0][ks], qb[ks], s[0], 0, 0, 0);
+        s[1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kreg[1][ks], qb[ks], s[1], 0, 0, 0);
+      }
+    } else if (v_in_flight) {
       // the K tile through reads that the compiler does not order behind the V rows' copies (see above)
       i32x4_t a0[KS], a1[KS];
       uint32_t ad[KS];
@@ -713,10 +754,6 @@ __global__ __launch_bounds__(kMfmaWaves* kWave, 2) void decode_mfma_kernel(Decod
         s[0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a0, qb[ks], s[0], 0, 0, 0);
         s[1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a1, qb[ks], s[1], 0, 0, 0);
       }
-    }
-    if (!ONE && next >= 0) {
-      issue_rows(kbytes, Kb, next);
-      request_scalars(next);
     }
     // ---- logits (log2 domain, log2(votes) folded in), group-mean logit for the EMA
     float z[2][4], xm[2][4];
@@ -823,7 +860,6 @@ __global__ __launch_bounds__(kMfmaWaves* kWave, 2) void decode_mfma_kernel(Decod
       O[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a_hi, b, O[nt], 0, 0, 0);
       O[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a_lo, b, O[nt], 0, 0, 0);
     }
-    if (!ONE && next >= 0) issue_rows(vbytes, Vb, next);
     // ---- EMA update (Eq. 8) and optional logit output: lane (l16 < 8, q) owns slot 16 (l16 / 4) + 4 q + l16 % 4.
     // After the second product: the compiler orders the V reads behind every outstanding memory operation,
     // and stores issued before them would be waited for.
@@ -843,8 +879,17 @@ __global__ __launch_bounds__(kMfmaWaves* kWave, 2) void decode_mfma_kernel(Decod
         // ln(e^hi + e^lo) = hi + ln(1 + e^(lo - hi)) with the hardware exp2 / log2 (absolute error ~1e-7)
         const float r = (lo == -INFINITY) ? hi : hi + kLn2 * fast_log2(1.f + fast_exp2((lo - hi) * kLog2e));
         if (mine) {
-          p.log_s[at] = r;
-          p.n_obs[at] = no_old + 1;
+          if (staged && !extra) {
+            // (a statement the compiler does not see as an LDS store: it would order one behind the next
+            // tile's outstanding copies into LDS)
+            const uint32_t sa = (uint32_t)(uintptr_t)(const __attribute__((address_space(3))) void*)(
+                s_stage + (size_t)(tbase - start + row_mine) * 8);
+            const float2 rn = make_float2(r, __builtin_bit_cast(float, no_old + 1));
+            asm volatile("ds_write_b64 %0, %1" : : "v"(sa), "v"(rn) : "memory");
+          } else {
+            p.log_s[at] = r;
+            p.n_obs[at] = no_old + 1;
+          }
         }
       }
     }
@@ -871,15 +916,28 @@ __global__ __launch_bounds__(kMfmaWaves* kWave, 2) void decode_mfma_kernel(Decod
       compute(base, false, -1, pv, ls_old, no_old, true);
       base = lim;
     } else {
-      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");     // the tile and its scalars have landed
+      // the tile's K rows (registers), V rows (LDS) and scalars have landed; the K registers pass through the
+      // statement so that no use of them is scheduled ahead of the wait
+      if constexpr (KS == 4)
+        asm volatile("s_waitcnt vmcnt(0)"
+                     : "+v"(kn[0][0]), "+v"(kn[0][1]), "+v"(kn[0][2]), "+v"(kn[0][3]), "+v"(kn[1][0]), "+v"(kn[1][1]),
+                       "+v"(kn[1][2]), "+v"(kn[1][3])
+                     :
+                     : "memory");
+      else
+        asm volatile("s_waitcnt vmcnt(0)" : "+v"(kn[0][0]), "+v"(kn[0][1]), "+v"(kn[1][0]), "+v"(kn[1][1]) : : "memory");
 #pragma unroll
-      for (int st = 0; st < 2; ++st)
+      for (int st = 0; st < 2; ++st) {
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) kreg[st][ks] = kn[st][ks];
 #pragma unroll
         for (int i = 0; i < 4; ++i) pv[st][i] = pv_next[st][i];
+      }
       ls_old = ls_next;
       no_old = no_next;
       const int next = base + kMfmaWaves * kMTile;
       compute(base, false, next < lim ? next : -1, pv, ls_old, no_old, false);
+      Vb = Tb + (Vb == Tb ? TILE_BYTES : 0);
       base = next;
     }
   }
@@ -890,10 +948,20 @@ __global__ __launch_bounds__(kMfmaWaves* kWave, 2) void decode_mfma_kernel(Decod
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");       // the copy of the new token has landed
     if constexpr (ONE) read_q();                 // (a wavefront without a tile of its own has not read them yet)
     if (grow) {
+      if constexpr (!ONE) {                      // the K operand of a tile whose row 0 is the new key, zero elsewhere
+        Vb = Tb;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+          const uint4 x = *reinterpret_cast<const uint4*>(s_new + (4 * ks + q) * 16);
+          const uint4 z4 = make_uint4(0, 0, 0, 0);
+          kreg[0][ks] = __builtin_bit_cast(bf16x8_t, l16 == 0 ? x : z4);
+          kreg[1][ks] = __builtin_bit_cast(bf16x8_t, z4);
+        }
+      }
       if (lane < 2 * CHUNKS) {
         const uint4 x = *reinterpret_cast<const uint4*>(s_new + lane * 16);
         // row 0 of the tile (its swizzle is the identity) and the cache row of the new slot
-        *reinterpret_cast<uint4*>((lane < CHUNKS ? Kb : Vb) + (lane % CHUNKS) * 16) = x;
+        if (ONE || lane >= CHUNKS) *reinterpret_cast<uint4*>((lane < CHUNKS ? Kb : Vb) + (lane % CHUNKS) * 16) = x;
         unsigned char* dst = reinterpret_cast<unsigned char*>(lane < CHUNKS ? p.k : p.v) + (ubase + len_old) * ROWB;
         *reinterpret_cast<uint4*>(dst + (lane % CHUNKS) * 16) = x;
       }
@@ -908,7 +976,17 @@ __global__ __launch_bounds__(kMfmaWaves* kWave, 2) void decode_mfma_kernel(Decod
   // ---- deposit this wavefront's state; the workgroup reduces kParts of them -------------------------
   float l_tot = l_run + __shfl_xor(l_run, 16);
   l_tot += __shfl_xor(l_tot, 32);
+  if constexpr (!ONE && STEP) asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // the staged EMA state is in LDS
   __syncthreads();                               // every wavefront is done with its tile buffers
+  if constexpr (!ONE && STEP) {
+    if (staged) {                                // the split's updated EMA state, slot by slot
+      for (int j = threadIdx.x; j < live_end - start; j += kMfmaWaves * kWave) {
+        const float2 rn = *reinterpret_cast<const float2*>(s_stage + (size_t)j * 8);
+        p.log_s[ubase + start + j] = rn.x;
+        p.n_obs[ubase + start + j] = __builtin_bit_cast(int, rn.y);
+      }
+    }
+  }
   float* s_m = reinterpret_cast<float*>(smem_raw);     // [kParts][G]
   float* s_l = s_m + kParts * G;                       // [kParts][G]
   float* s_acc = s_l + kParts * G;                     // [kParts][G][D]

@@ -49,6 +49,13 @@ __device__ __forceinline__ float group_sum(float x) {
   return x;
 }
 
+// ---- loads of data that is read once per launch (non-temporal hint: do not keep it in the caches) ----------
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4_t;
+__device__ __forceinline__ uint4 load_once(const uint4* p) {
+  const u32x4_t r = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(p));
+  return make_uint4(r[0], r[1], r[2], r[3]);
+}
+
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 __device__ __forceinline__ float fast_log2(float x) { return __builtin_amdgcn_logf(x); }
 
