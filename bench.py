@@ -10,7 +10,9 @@ synthetic (paper_2504_09936_amd.workloads) and resident in HBM before the timed 
 The timed region is one HIP graph of exactly K steps.
 
 Prints ONE JSON line; `value` is decode tokens/s per layer for the whole hot path
-(batch x steps / time), with a `roofline` object for the decode-attention kernel and a
+(batch x steps / median time of five replays of the K-step graph; how many compression events fell into the K
+steps is `config.compress_events_timed`, and `decode_tokens_per_s`, `compress_us_per_layer` and
+`tokens_per_s_with_events_amortised` give the metric's two halves whatever K is), with a `roofline` object for the decode-attention kernel and a
 `cpu_baseline` object (the numpy oracle on the host cores, bounded sample).
 """
 from __future__ import annotations
@@ -28,11 +30,110 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0      # MI355X HBM3E
+N_REPLAY = 5               # timed replays of the K-step graph; the median is reported
 MFMA_BF16_PEAK_TFLOPS = 2500.0
-# HBM bytes per launch of the fused decode kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled
-# by the copy-probe calibration (profiles/decode_hbm_traffic_llama3_8b.md).  Counters cannot be
-# read from inside this process, so the figure is the recorded one for the default workload.
-PMC_TRAFFIC_BYTES = {"llama3_8b": int((14470.7 * 2.00 + 1162.6 * 1.00) * 1024)}
+
+
+def traffic_from_profile(workload: str, kernel: str):
+    """HBM bytes per launch of the decode kernel as recorded in profiles/decode_hbm_traffic_<workload>.md
+    (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE in KiB per dispatch, each scaled by what the same counter reads
+    for a plain copy of known size).  Counters cannot be read from inside this process; the recorded figure
+    is used only if the summary is for exactly the kernel instance this run launches, else None."""
+    import re
+    path = os.path.join(ROOT, "profiles", f"decode_hbm_traffic_{workload}.md")
+    try:
+        text = open(path).read()
+    except OSError:
+        return None
+    m = re.search(r"<!--\s*bench:\s*kernel=(\S+)\s+fetch_kib=([0-9.]+)\s+write_kib=([0-9.]+)\s+fetch_factor=([0-9.]+)\s+"
+                  r"write_factor=([0-9.]+)\s*-->", text)
+    if not m or m.group(1) != kernel:
+        return None
+    fetch, write, ff, wf = (float(m.group(i)) for i in range(2, 6))
+    return int((fetch * ff + write * wf) * 1024)
+
+
+def _limit_blas_threads():
+    try:
+        from threadpoolctl import threadpool_limits
+        threadpool_limits(1)
+    except Exception:
+        pass
+
+
+def oracle_units_worker(job):
+    """cpu_baseline leg (runs in a process of its own that imports numpy, the oracle and the input generators
+    only): decode steps of one layer on a subset of its (batch, kv head) units, starting from a cache of
+    `budget` tokens of the workload's recipe; returns its wall time."""
+    import time as _t
+
+    import numpy as _np
+
+    from oracle import keepkv_oracle as O
+    from paper_2504_09936_amd import workloads as W
+    w = W.CONFIGS[job["workload"]]
+    units, n_steps, alpha, T = job["units"], job["n_steps"], job["alpha"], job["T"]
+    bf16 = w.dtype == "bf16"
+    G, Bud, cap = w.group, w.budget, w.budget + w.period
+    K0, V0 = W.make_cache(w.scaled(context=Bud), 0)
+    caches = []
+    for b, h in units:
+        oc = O.Cache(1, 1, cap, w.head_dim)
+        oc.k[0, 0, :Bud], oc.v[0, 0, :Bud] = K0[b, h], V0[b, h]
+        oc.votes[0, 0, :Bud] = 1
+        oc.len[0, 0] = Bud
+        caches.append(oc)
+    del K0, V0
+    t0 = _t.perf_counter()
+    for t in range(n_steps):
+        k_t, v_t = W.make_token(w, 0, t)
+        q = W.make_query(w, 0, t).astype(_np.float64)
+        for (b, h), oc in zip(units, caches):
+            if int(oc.len[0, 0]) == cap:
+                O.compress(oc, Bud, w.n_sink, w.n_recent, alpha, T, exact_any_order=bf16,
+                           storage_round=(W.round_bf16 if bf16 else None))
+            oc.append(k_t[b:b + 1, h:h + 1], v_t[b:b + 1, h:h + 1])
+            _, _, lg = O.attend(oc, q[b:b + 1, h * G:(h + 1) * G], w.scale)
+            O.observe(oc, lg, alpha)
+    return _t.perf_counter() - t0
+
+
+def run_cpu_baseline(w, alpha, T):
+    """The oracle as it stands (numpy float64, a Python loop over (batch, kv head) units) on one layer of the
+    workload: (i) one process with the BLAS pool held to one thread, (ii) one process per host core available
+    to this process (affinity mask), the layer's units dealt over them.  Both run the same decode steps
+    (append, attention, score; a compression event every period).  Runs before this process touches the GPU:
+    the worker processes are started from a process that holds no GPU state."""
+    import multiprocessing as mp
+    B, H, P = w.batch, w.n_kv_heads, w.period
+    n_aff = len(os.sched_getaffinity(0))
+    all_units = [(b, h) for b in range(B) for h in range(H)]
+    ctx = mp.get_context("spawn")
+
+    def run_pool(n_proc, n_steps, units):
+        shares = [units[i::n_proc] for i in range(n_proc)]
+        shares = [u for u in shares if u]
+        jobs = [{"workload": w.name, "units": u, "n_steps": n_steps, "alpha": alpha, "T": T} for u in shares]
+        with ctx.Pool(len(shares), initializer=_limit_blas_threads) as pool:
+            times = pool.map(oracle_units_worker, jobs)
+        return max(times), len(shares)            # the slowest worker's loop: the job's time without process start-up
+
+    # calibrate on a few units, then size both legs to about ten seconds each
+    cal_units = all_units[:: max(1, len(all_units) // 4)][:4]
+    t_cal, _ = run_pool(1, 8, cal_units)
+    per_unit_step = max(t_cal, 1e-4) / (8 * len(cal_units))
+    n1 = int(max(8, min(8 * P, 10.0 / (per_unit_step * len(all_units)))))
+    t1, _ = run_pool(1, n1, all_units)
+    n_proc = min(n_aff, len(all_units))
+    nN = int(max(8, min(32 * P, 10.0 * n_proc / (per_unit_step * len(all_units)))))
+    tN, used = run_pool(n_proc, nN, all_units)
+    return {"value": round(B * nN / tN, 1), "unit": "tokens/s", "cores": int(used), "kind": "oracle",
+            "sample": f"one layer of the same workload (a cache of {w.budget} tokens of its recipe), {nN} decode steps "
+                      f"(append, attention, score; a compression event every {P} steps), numpy float64, the layer's "
+                      f"{len(all_units)} (batch, kv head) units dealt over {used} processes of one thread each "
+                      f"(affinity mask: {n_aff} cores)",
+            "single_thread": {"value": round(B * n1 / t1, 1), "unit": "tokens/s", "cores": 1,
+                              "sample": f"{n1} decode steps, one process, BLAS pool held to one thread"}}
 
 
 def parse():
@@ -65,10 +166,16 @@ def main():
               "kv heads or batch would shard across GPUs with no exchange). Run with --gpus 1.", file=sys.stderr)
         sys.exit(2)
 
+    from paper_2504_09936_amd import workloads as W
+    cpu = None
+    if not args.no_cpu_baseline and not args.copy_probe:
+        w_ = W.CONFIGS[args.workload]
+        cpu = run_cpu_baseline(w_, float(np.float32(w_.alpha)),
+                               float(np.float32(w_.threshold if args.threshold is None else args.threshold)))
+
     import torch
 
     from paper_2504_09936_amd import binding as kk
-    from paper_2504_09936_amd import workloads as W
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
@@ -279,18 +386,42 @@ def main():
             stop.record()
         torch.cuda.synchronize()
     else:
+        # Every replay must run the K steps (and events) that were captured, on the state they were captured
+        # for: appending the same tokens to a cache that already holds them would feed the events exact
+        # duplicates.  The caches of all layers are put back before each replay (outside the timed region).
+        fields = ("k", "v", "votes", "log_s", "n_obs", "len")
+        state_at_capture = [[{f_: getattr(c, f_).clone() for f_ in fields} for c in pair] for pair in caches]
+        dropped_at_capture = dropped.clone()
         graph = torch.cuda.CUDAGraph()
         with torch.cuda.graph(graph, stream=stream):
             for i in range(Wm, Wm + K):
                 one_step(i)
             join_side()
         torch.cuda.synchronize()
-        with torch.cuda.stream(stream):
-            start.record()
-            graph.replay()
-            stop.record()
-        torch.cuda.synchronize()
-    elapsed_ms = start.elapsed_time(stop)
+
+        def restore_state():
+            for pair, saved in zip(caches, state_at_capture):
+                for c, st in zip(pair, saved):
+                    for f_ in fields:
+                        getattr(c, f_).copy_(st[f_])
+            dropped.copy_(dropped_at_capture)
+
+        replay_ms = []
+        for rep in range(1 + N_REPLAY):           # one untimed replay first
+            restore_state()
+            torch.cuda.synchronize()
+            with torch.cuda.stream(stream):
+                start.record()
+                graph.replay()
+                stop.record()
+            torch.cuda.synchronize()
+            if rep > 0:
+                replay_ms.append(start.elapsed_time(stop))
+    if args.no_graph:
+        replay_ms = [start.elapsed_time(stop)]
+    elapsed_ms = float(np.median(replay_ms))
+    if not args.no_graph:
+        del state_at_capture
     timed_events = n_events
     overflow_check = max(int(c[cu].len.max().item()) for c, cu in zip(caches, cur))
     assert overflow_check <= cap
@@ -315,14 +446,17 @@ def main():
         for layer in range(R):
             compress(caches[layer][cur[layer]], caches[layer][1 - cur[layer]], layer, ws)
     torch.cuda.synchronize()
-    g0, g1 = ev(), ev()
-    with torch.cuda.stream(stream):
-        egraph.replay()
-        g0.record()
-        egraph.replay()
-        g1.record()
-    torch.cuda.synchronize()
-    event_graph_us = g0.elapsed_time(g1) * 1e3 / R
+    eg_runs = []
+    for rep in range(1 + N_REPLAY):
+        g0, g1 = ev(), ev()
+        with torch.cuda.stream(stream):
+            g0.record()
+            egraph.replay()
+            g1.record()
+        torch.cuda.synchronize()
+        if rep > 0:
+            eg_runs.append(g0.elapsed_time(g1) * 1e3 / R)
+    event_graph_us = float(np.median(eg_runs))
     dropped.copy_(dropped_saved)
     for layer in range(R):
         c = caches[layer][cur[layer]]
@@ -351,13 +485,21 @@ def main():
             layer = i % R
             decode(caches[layer][cur[layer]], layer, (base_step[layer] + i // R) % per_layer, i // R)
     torch.cuda.synchronize()
-    d0, d1 = ev(), ev()
-    with torch.cuda.stream(stream):
-        d0.record()
-        dgraph.replay()
-        d1.record()
-    torch.cuda.synchronize()
-    dec_us = d0.elapsed_time(d1) * 1e3 / n_dec
+    lens_dec = [c[cu].len.clone() for c, cu in zip(caches, cur)]
+    dec_runs = []
+    for rep in range(1 + N_REPLAY):
+        for c, cu, l in zip(caches, cur, lens_dec):
+            c[cu].len.copy_(l)
+        torch.cuda.synchronize()
+        d0, d1 = ev(), ev()
+        with torch.cuda.stream(stream):
+            d0.record()
+            dgraph.replay()
+            d1.record()
+        torch.cuda.synchronize()
+        if rep > 0:
+            dec_runs.append(d0.elapsed_time(d1) * 1e3 / n_dec)
+    dec_us = float(np.median(dec_runs))
     live_mean = Bud + (P // 2 + 1) / 2.0          # slots per head attended, averaged over the replay
     slots = B * H * live_mean
 
@@ -404,9 +546,16 @@ def main():
                 "read_1GiB_GBps": round((1 << 30) / big_us / 1e3, 1),
                 "mfma_bf16_TFLOPs": round(flops_box[-1] / mfma_us / 1e6, 1),
                 "mfma_bf16_random_operands_TFLOPs": round(flops_box[-1] / mfma_rand_us / 1e6, 1)}
-    roofline = {"bound": "hbm", "kernel": "decode_mfma_kernel" if bf16 else "decode_attn_kernel", "achieved": round(achieved, 1),
+    ns_, per_, wv_ = kk.decode_plan(lay, cap)
+    if bf16:
+        kernel_instance = (f"decode_mfma_kernel<{D},{Hq // H},{'false' if args.unfused else 'true'},"
+                           f"{'true' if per_ <= wv_ * 32 else 'false'},{wv_}>")
+    else:
+        kernel_instance = "decode_attn_kernel"
+    traffic = traffic_from_profile(w.name, kernel_instance)
+    roofline = {"bound": "hbm", "kernel": kernel_instance, "achieved": round(achieved, 1),
                 "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
-                "traffic": (PMC_TRAFFIC_BYTES.get(w.name) if not args.unfused else None), "bytes_per_launch": int(dec_bytes),
+                "traffic": traffic, "bytes_per_launch": int(dec_bytes),
                 "avg_launch_us": round(dec_us, 2),
                 "frac_of_measured_read": round(achieved / measured["read_decode_working_set_GBps"], 4)}
 
@@ -418,42 +567,11 @@ def main():
     match_first_tflops = 2.0 * M1 * Bud * D * B * H / (match_first_us * 1e-6) / 1e12
 
     # ------------------------------------------------------------------ CPU baseline: the oracle on one layer
-    cpu = None
-    if not args.no_cpu_baseline:
-        from oracle import keepkv_oracle as O
-        try:
-            from threadpoolctl import threadpool_info
-            cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
-        except Exception:
-            cores = 1
-        src = caches[0][cur[0]]
-        oc = O.Cache(B, H, cap, D)
-        f = (lambda t_: W.from_bf16_bits(t_.view(torch.int16).cpu().numpy().view(np.uint16))) if bf16 else (lambda t_: t_.cpu().numpy())
-        oc.k[:], oc.v[:] = f(src.k), f(src.v)
-        oc.votes[:], oc.n_obs[:], oc.len[:] = src.votes.cpu().numpy(), src.n_obs.cpu().numpy(), src.len.cpu().numpy()
-        oc.log_S[:] = src.log_s.cpu().numpy().astype(np.float64)
-        room = cap - int(oc.len.max())
-        n_cpu = 2 * P
-        tc = time.perf_counter()
-        done = 0
-        for t in range(n_cpu):
-            if int(oc.len.max()) == cap:
-                O.compress(oc, Bud, w.n_sink, w.n_recent, alpha, T, exact_any_order=bf16,
-                           storage_round=(W.round_bf16 if bf16 else None))
-            k_t, v_t = W.make_token(w, 0, t)
-            oc.append(k_t, v_t)
-            q = W.make_query(w, 0, t).astype(np.float64)
-            _, _, lg = O.attend(oc, q, w.scale)
-            O.observe(oc, lg, alpha)
-            done += 1
-            if time.perf_counter() - tc > 30.0:
-                break
-        dt = time.perf_counter() - tc
-        cpu = {"value": round(B * done / dt, 1), "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
-               "sample": f"one layer, {done} decode steps of the same workload (append, attention, score; "
-                         f"a compression event every {P} steps), numpy float64"}
-
     tokens_per_s = B * K / (elapsed_ms * 1e-3)
+    first_event_us = sum(float(np.median(first[k_])) for k_ in ("select", "match", "merge"))
+    # the metric's two halves, independent of how many events fell into the K timed steps: the decode step
+    # alone, and a step with one steady-state event per `period` steps of a layer amortised in
+    amortised_us = dec_us + event_graph_us / P
     res = {
         "metric": "decode attn tokens/s + compress us/layer at 10% budget; % HBM/MFMA roofline",
         "value": round(tokens_per_s, 1), "unit": "tokens/s", "n_gpus": 1, "steps": K, "warmup": Wm,
@@ -465,6 +583,11 @@ def main():
                    "compress_overlapped": args.overlap},
         "roofline": roofline,
         "cpu_baseline": cpu,
+        "decode_tokens_per_s": round(B / (dec_us * 1e-6), 1),
+        "compress_us_per_layer": {"steady_event": round(event_graph_us, 1), "first_event": round(first_event_us, 1),
+                                  "period": P},
+        "tokens_per_s_with_events_amortised": round(B / (amortised_us * 1e-6), 1),
+        "timed_replays_ms": [round(x, 4) for x in replay_ms],
         "kernels_us": {
             "decode_step": round(dec_us, 2),
             "compress_steady": {k_: (round(float(np.median(v_)), 1) if v_ else None) for k_, v_ in comp.items()},

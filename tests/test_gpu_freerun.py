@@ -25,6 +25,10 @@ TOL_MERGE_ALL = 5e-2
 # any original key; the slot's logit then amplifies the last-bit differences of the two sides' states, and the
 # outputs of that kv head are no longer comparable (they are still required to be finite).
 ILL_SCALE = 8.0
+# Units (batch, kv head) left out of the output comparison for that reason, per case: the number seen when the
+# case was set up; more than that fails, so a change that makes many keys ill-conditioned cannot hide here.
+MAX_ILL = {("tiny", 0.8): 1, ("tiny", -2.0): 2, ("llama3_8b", 0.8): 0, ("llama3_8b", -2.0): 7,
+           ("long_32k", 0.8): 4, ("stress", 0.8): 0}
 
 
 def _oracle_event(oc, w, alpha, T, rnd, ill):
@@ -147,13 +151,14 @@ def _free_run(w, seed, threshold):
                                atol=TOL_MERGE_ALL if threshold < -1 else 5e-3)
     print(f"free run {w.name} T={threshold}: worst output error {worst:.2e}, "
           f"{len(ill)} of {B * H} units with an ill-conditioned merged key")
-    return worst
+    return worst, len(ill)
 
 
 @pytest.mark.parametrize("threshold", [0.8, -2.0])
 def test_tiny_f32_whole_run_is_index_identical(threshold):
     """512 tokens -> 52 slots, 32 window queries, 64 decode steps, an event every 32 steps."""
-    _free_run(W.CONFIGS["tiny"], 0, threshold)
+    _, n_ill = _free_run(W.CONFIGS["tiny"], 0, threshold)
+    assert n_ill <= MAX_ILL[("tiny", threshold)]
 
 
 @pytest.mark.parametrize("cfg,kw,threshold", [
@@ -163,4 +168,5 @@ def test_tiny_f32_whole_run_is_index_identical(threshold):
     ("stress", {"batch": 1, "context": 1280, "steps": 64, "period": 16}, 0.8),
 ])
 def test_bf16_whole_run(cfg, kw, threshold):
-    _free_run(W.CONFIGS[cfg].scaled(**kw), 1, threshold)
+    _, n_ill = _free_run(W.CONFIGS[cfg].scaled(**kw), 1, threshold)
+    assert n_ill <= MAX_ILL[(cfg, threshold)], "more units than seen before were left out of the output comparison"

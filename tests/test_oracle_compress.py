@@ -326,3 +326,33 @@ def test_guard_and_unobserved_members():
     r = O.merge(k, v, one, np.array([0.5, -np.inf, 0.0]), np.array([2, 0, 2]), [0, 2], [1], [0], 0.9)
     np.testing.assert_allclose(r.v[0], v[0]); assert r.votes[0] == 2
     np.testing.assert_allclose(r.k[0], k[0] * math.log(math.exp(0.5 - math.log(1 - 0.81)) / 2) / (0.5 - math.log(1 - 0.81)), rtol=1e-13)
+
+
+def test_unobserved_retained_slot_takes_its_observed_members_score():
+    """Reading R12 for a retained slot that was never observed (n = 0, weight 0) absorbing an observed member:
+    the merged slot is all the member's key direction and value, carries both votes, and its score obeys the
+    mass identity p_r s_hat_r = sum p s_hat (App. A.4) with the observation count raised to 1."""
+    alpha = 0.9
+    k = np.array([[1.0, 2.0], [3.0, -1.0], [0.5, 0.5]]); v = np.array([[1.0, 0.0], [0.0, 4.0], [2.0, 2.0]])
+    votes = np.array([2, 3, 1])
+    n_obs = np.array([0, 5, 4])                                   # slot 0 (retained) unobserved, slot 1 (member) observed
+    E1 = 0.7                                                      # ln s_hat of the member
+    log_S = np.array([-np.inf, E1 + math.log(1 - alpha ** 5), 0.1])
+    r = O.merge(k, v, votes, log_S, n_obs, [0, 2], [1], [0], alpha)
+    assert r.votes[0] == 5 and r.n_obs[0] == 1 and not r.guarded[0]
+    np.testing.assert_allclose(r.v[0], v[1], rtol=1e-14)          # the only member with weight
+    L = math.log(3 * math.exp(E1) / 5)                            # ln(sum p s_hat / sum p)
+    np.testing.assert_allclose(r.k[0], k[1] * (L / E1), rtol=1e-13)
+    np.testing.assert_allclose(r.log_S[0], L + math.log(1 - alpha ** 1), rtol=1e-13)
+    np.testing.assert_allclose(5 * math.exp(r.log_S[0] - math.log(1 - alpha)), 3 * math.exp(E1), rtol=1e-13)
+    # the untouched retained slot is a copy
+    assert r.votes[1] == 1 and r.n_obs[1] == 4 and r.log_S[1] == 0.1
+
+
+def test_perturbation_bound_values():
+    """Theorem 3's right-hand side 2 eps (1 + eps) gamma / (1 - eps)^2 at values worked by hand."""
+    assert O.perturbation_bound(0.5, 1.0) == pytest.approx(6.0, rel=1e-15)          # 2 * .5 * 1.5 / .25
+    assert O.perturbation_bound(0.0, 3.0) == 0.0
+    assert O.perturbation_bound(0.1, 2.0) == pytest.approx(2 * 0.1 * 1.1 * 2.0 / 0.81, rel=1e-15)
+    assert O.perturbation_bound(0.2, 1.0) == pytest.approx(0.75, rel=1e-15)         # .4 * 1.2 / .64
+    assert O.perturbation_bound(0.5, 2.0) == 2 * O.perturbation_bound(0.5, 1.0)      # linear in gamma

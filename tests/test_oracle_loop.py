@@ -129,3 +129,69 @@ def test_theorem3_across_events_on_a_small_stress_instance():
             shat_post = [O.log_s_hat(c.log_S[0, h], c.n_obs[0, h], alpha) for h in range(2)]
             shadow = (pre, trace, {"pre": shat_pre, "post": shat_post})
     assert checked >= 16
+
+
+def test_theorem3_on_a_stress_recipe_instance_reports_the_vacuous_fraction(capsys):
+    """The stress configuration's own recipe at reduced batch and context: Mistral-7B-like head layout
+    (grouped-query attention 4 : 1, head dim 128), AR(1) keys and values (rho = 0.98) continued by the decode
+    tokens, the workload's peaked queries, an event every 16 steps, merge-all (T = -2).  For every event and
+    every later step until the next event, per query head: theta = |o_unmerged - o_merged| against Thm 3's bound
+    with eps taken over all merged members and merged slots (s_hat frozen at merge time, from the group-mean
+    query; s from the head's own query) and gamma over the value distances to members.  The bound is checked
+    whenever eps < 1; the fraction of (event, step, head) triples with eps >= 1, where it says nothing, is
+    reported (with grouped queries the EMA of the group-mean query predicts a single head's score poorly)."""
+    w = W.CONFIGS["stress"].scaled(batch=1, n_q_heads=8, n_kv_heads=2, context=640, ratio=0.1, steps=48, window=8)
+    assert w.head_dim == 128 and w.group == 4 and w.period == 16 and w.key_model == "ar1"
+    alpha, seed, T = 0.9, 5, -2.0
+    H, G = w.n_kv_heads, w.group
+    K, V = W.make_cache(w, seed)
+    c = O.Cache(1, H, w.capacity + w.steps, w.head_dim)
+    c.k[:, :, : w.context], c.v[:, :, : w.context], c.votes[:, :, : w.context], c.len[:] = K, V, 1, w.context
+    for t in range(w.window):
+        O.observe(c, O.attend(c, W.make_query(w, seed, -w.window + t).astype(np.float64), w.scale)[2], alpha)
+    shadow, prev = None, (K[:, :, -1], V[:, :, -1])
+    checked = vacuous = 0
+    worst = 0.0
+    for t in range(-1, w.steps):
+        if t >= 0:
+            prev = W.make_token(w, seed, t, prev=prev)
+            c.append(*prev)
+            q = W.make_query(w, seed, t).astype(np.float64)
+            o_m, _, logits = O.attend(c, q, w.scale)
+            if shadow is not None:
+                pre, trace, shat = shadow
+                pre.append(*prev)
+                o_f, _, _ = O.attend(pre, q, w.scale)
+                for h in range(H):
+                    keep, evict, tgt = trace[h]
+                    targets = np.unique(tgt[tgt >= 0])
+                    mem = np.concatenate([evict[tgt >= 0], keep[targets]])
+                    n_pre, n_post = int(pre.len[0, h]), int(c.len[0, h])
+                    vv = pre.v[0, h, :n_pre]
+                    gamma = max(np.linalg.norm(vv - vv[j], axis=1).max() for j in mem)
+                    for g_ in range(G):
+                        qh = q[0, h * G + g_]
+                        s_pre = w.scale * pre.k[0, h, :n_pre] @ qh           # ln s of the head's own query
+                        s_post = w.scale * c.k[0, h, :n_post] @ qh
+                        dev = np.concatenate([shat["pre"][h][mem] - s_pre[mem], shat["post"][h][targets] - s_post[targets]])
+                        eps = float(np.abs(1.0 - np.exp(dev)).max())
+                        theta = float(np.linalg.norm(o_f[0, h * G + g_] - o_m[0, h * G + g_]))
+                        if eps < 1.0:
+                            bound = O.perturbation_bound(eps, gamma)
+                            assert theta < bound, (t, h, g_, theta, bound, eps)
+                            worst = max(worst, theta / bound)
+                            checked += 1
+                        else:
+                            vacuous += 1
+            O.observe(c, logits, alpha)
+        if t == -1 or (c.len == w.budget + w.period).all():
+            pre = copy.deepcopy(c)
+            shat_pre = [O.log_s_hat(c.log_S[0, h], c.n_obs[0, h], alpha) for h in range(H)]
+            trace = O.compress(c, w.budget, w.n_sink, w.n_recent, alpha, T)
+            shat_post = [O.log_s_hat(c.log_S[0, h], c.n_obs[0, h], alpha) for h in range(H)]
+            shadow = (pre, trace, {"pre": shat_pre, "post": shat_post})
+    total = checked + vacuous
+    assert total == w.steps * H * G
+    with capsys.disabled():
+        print(f"\n[Thm 3, stress recipe] {total} (event, step, head) triples: bound vacuous (eps >= 1) in "
+              f"{vacuous} ({vacuous / total:.1%}); checked {checked}, largest theta / bound {worst:.3g}")
