@@ -21,13 +21,18 @@ Readings taken where the paper is silent (each is restated at the function it af
   * an evicted slot with no retained key above the threshold is dropped (plain
     eviction, Eq. 4) and its votes are added to a per-head `dropped` counter;
   * the merged key's scale ln(W/P) / (sum w ln s / W) is replaced by 1 when the
-    denominator's magnitude is below `ELL_GUARD` (the formula is singular there).
+    denominator's magnitude is below `ELL_GUARD` (the formula is singular there);
+  * merge-first prefill (App. B.4 gives the order, no algorithm): every slot links to its most
+    similar earlier key if above the threshold; a linked slot is absorbed by its target unless
+    the target is itself absorbed; each receiving slot and the slots it absorbs are merged in one
+    multi-way ZIP merge; the eviction strategy then runs on the shorter cache.
 
 Parity pins (tests/test_oracle_*.py): textbook softmax attention and vote duplication
 (decode_attn); closed-form EMA sums (score_update); brute-force sort / cosine matrix
 (select, match); Theorem 2, Lemma 4, the pairwise Eq. 7 and vote / mass conservation
-(merge); Theorem 3 (perturbation_bound).  The guard branch of `merge` has no pin in the
-paper: parity unpinned for guarded slots.
+(merge); Theorem 3 (perturbation_bound); brute force, Theorem 2, vote conservation and the
+duplicate-key case of Lemma 4 (merge-first prefill).  The guard branch of `merge` has no pin in
+the paper: parity unpinned for guarded slots.
 """
 from __future__ import annotations
 
@@ -309,6 +314,80 @@ def merge(k, v, votes, log_S, n_obs, keep_idx, evict_idx, target, alpha):
         else:
             out.log_S[r] = L + math.log(-math.expm1(n_r * math.log(alpha)))
     return out
+
+
+# --------------------------------------------------------------------------- merge-first prefill (Sec. 3.3.2, App. B.4)
+def prefill_nearest_earlier(k, length, threshold, exact_any_order=False):
+    """For every live slot i its most similar EARLIER key (App. B.4: during prefill, merge by key similarity
+    before the eviction strategy is applied).
+
+    U[i, j] = cos(k_i, k_j) for j < i, evaluated as in `match`; near[i] = the first maximiser j of U[i, :i] if
+    U[i, near] > threshold (strict), else -1; slot 0 has no earlier key.  Returns (near [length] int64,
+    sim [length] float64 = max_j U[i, j], -inf for slot 0).
+    """
+    k = np.asarray(k, dtype=np.float64)[:length]
+    near = np.full(length, -1, dtype=np.int64)
+    sim = np.full(length, -np.inf)
+    if length < 2:
+        return near, sim
+    with np.errstate(divide="ignore", invalid="ignore"):
+        rn = 1.0 / np.sqrt(_dots_self(k))
+        U = (_dots(k, k, exact_any_order) * rn[:, None]) * rn[None, :]
+    U = np.where(np.isfinite(U), U, -np.inf)
+    for i in range(1, length):
+        row = U[i, :i]
+        j = int(row.argmax())                              # first maximiser
+        sim[i] = row[j]
+        if row[j] > threshold:
+            near[i] = j
+    return near, sim
+
+
+def prefill_groups(near):
+    """Merge groups of the merge-first prefill pass from the nearest-earlier-key links.
+
+    The links near[i] -> j < i form a forest.  A slot is absorbed by the slot it links to unless that slot is
+    itself absorbed (a slot that has been merged away cannot receive): walking down from a tree's first slot,
+    slots at odd depth are absorbed by their parent, slots at even depth stay and receive their children.
+    Every group is therefore one receiving slot plus slots whose own best earlier key it is, each with
+    similarity above the threshold to it; chains of similar neighbours are not collapsed transitively.
+    Returns (root_idx ascending, absorbed_idx ascending, target = position in root_idx of each absorbed slot).
+    """
+    near = np.asarray(near, dtype=np.int64)
+    n = near.shape[0]
+    absorbed = np.zeros(n, dtype=bool)
+    for i in range(n):                                     # links point to lower indices: one ascending pass
+        j = int(near[i])
+        absorbed[i] = j >= 0 and not absorbed[j]
+    root_idx = np.flatnonzero(~absorbed).astype(np.int64)
+    absorbed_idx = np.flatnonzero(absorbed).astype(np.int64)
+    pos = np.full(n, -1, dtype=np.int64)
+    pos[root_idx] = np.arange(root_idx.shape[0])
+    return root_idx, absorbed_idx, pos[near[absorbed_idx]]
+
+
+def prefill_merge_first(cache, alpha, threshold, exact_any_order=False, storage_round=None):
+    """The merging half of the merge-first prefill policy on every (batch, kv head), in place: nearest earlier
+    key per slot, groups as in `prefill_groups`, one multi-way ZIP merge per group (`merge`), the surviving
+    slots compacted in their original order.  Nothing is dropped; votes are conserved.  The eviction strategy
+    (`compress`) is then applied to the shorter cache by the caller.  Returns per-head (near, root_idx)."""
+    trace = []
+    for b in range(cache.B):
+        for h in range(cache.H):
+            n = int(cache.len[b, h])
+            near, _ = prefill_nearest_earlier(cache.k[b, h], n, threshold, exact_any_order)
+            roots, absorbed, tgt = prefill_groups(near)
+            res = merge(cache.k[b, h], cache.v[b, h], cache.votes[b, h], cache.log_S[b, h], cache.n_obs[b, h],
+                        roots, absorbed, tgt, alpha)
+            nk = roots.shape[0]
+            kk, vv = res.k, res.v
+            if storage_round is not None:
+                kk, vv = storage_round(kk), storage_round(vv)
+            cache.k[b, h, :nk], cache.v[b, h, :nk] = kk, vv
+            cache.votes[b, h, :nk], cache.log_S[b, h, :nk], cache.n_obs[b, h, :nk] = res.votes, res.log_S, res.n_obs
+            cache.len[b, h] = nk
+            trace.append((near, roots))
+    return trace
 
 
 # --------------------------------------------------------------------------- Theorem 3

@@ -10,6 +10,7 @@ import pytest
 from tests import test_oracle_attn as TA
 from tests import test_oracle_compress as TC
 from tests import test_oracle_loop as TL
+from tests import test_oracle_prefill as TP
 
 _SRC = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "oracle", "keepkv_oracle.py")
 
@@ -57,6 +58,18 @@ MUTANTS = [
      "out.dropped = 0", TL, "test_tiny_loop_conserves_votes", (0.8,)),
     ("merged values averaged without weights", "out.v[r] = wn @ v[g]", "out.v[r] = v[g].mean(axis=0)", TC,
      "test_theorem2_single_step_lossless", (0,)),
+    ("prefill: a slot may match itself or later keys", "row = U[i, :i]", "row = U[i, :i + 1]", TP,
+     "test_nearest_earlier_key_brute_force", (0,)),
+    ("prefill: threshold not strict", "if row[j] > threshold:", "if row[j] >= threshold:", TP,
+     "test_nearest_earlier_key_brute_force", (0,)),
+    ("prefill: last maximiser instead of the first", "j = int(row.argmax())                              # first maximiser",
+     "j = int(row.shape[0] - 1 - row[::-1].argmax())", TP, "test_nearest_earlier_key_brute_force", (0,)),
+    ("prefill: chains collapse transitively", "absorbed[i] = j >= 0 and not absorbed[j]", "absorbed[i] = j >= 0", TP,
+     "test_groups_on_hand_made_forests", ()),
+    ("prefill: absorbed slots point at the wrong receiver", "return root_idx, absorbed_idx, pos[near[absorbed_idx]]",
+     "return root_idx, absorbed_idx, np.zeros_like(absorbed_idx)", TP, "test_groups_on_hand_made_forests", ()),
+    ("prefill: survivors not compacted to the new length", "            cache.len[b, h] = nk\n            trace.append((near, roots))",
+     "            trace.append((near, roots))", TP, "test_exact_duplicates_collapse_with_zero_error_at_any_query", ()),
 ]
 
 
