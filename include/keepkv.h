@@ -228,6 +228,30 @@ keepkv_status keepkv_merge(const keepkv_layout *layout, const keepkv_cache *src,
                            const int32_t *match, float alpha, int64_t *dropped_votes,
                            void *workspace, size_t workspace_bytes, void *stream);
 
+/* Merge-first prefill policy, first half (Sec. 3.3.2, last sentence; App. B.4 "Prefill's Merge Policy":
+ * during prefill, merge by key similarity first and apply the eviction strategy afterwards).  For every
+ * live slot i > 0 of every (b, h): the EARLIER slot j < i of highest key cosine similarity
+ * U[i,j] = k_i.k_j/(|k_i||k_j|), the lowest j winning ties; near[b,h,i] (DEVICE int32
+ * [B, Hkv, capacity]) is that j if U > threshold (strict) and -1 otherwise; near[b,h,0] = -1.  Entries at or
+ * beyond len are not written.  sim_out (DEVICE f32, same shape, may be NULL) receives the best similarity
+ * (-inf for slot 0).  bf16 caches use bf16 MFMA with f32 accumulation and re-evaluate rows within rounding
+ * of a tie or of the threshold in f64, as keepkv_match does, so the indices equal an f64 evaluation. */
+keepkv_status keepkv_prefill_match(const keepkv_layout *layout, const keepkv_cache *cache,
+                                   float threshold, int32_t *near, float *sim_out, void *workspace,
+                                   size_t workspace_bytes, void *stream);
+
+/* Merge-first prefill policy, second half: the links near[] (from keepkv_prefill_match) form a forest; a slot
+ * is absorbed by the slot it links to unless that slot is itself absorbed (slots at odd depth of their tree
+ * are absorbed by their parent, slots at even depth stay and receive their children), so every group is one
+ * receiving slot plus slots whose best earlier key it is.  Each group is merged in one multi-way ZIP merge
+ * with the EMA scores (exactly the arithmetic of keepkv_merge: Eq. 7 in its App. A.3 / A.4 form); nothing is
+ * dropped.  The receiving slots are written to dst in ascending slot order and dst.len = their number;
+ * the usual event (keepkv_select / keepkv_match / keepkv_merge) then brings dst to the budget.  src and dst
+ * must not overlap; dst.capacity >= src.capacity; src.capacity <= 16384. */
+keepkv_status keepkv_prefill_merge(const keepkv_layout *layout, const keepkv_cache *src,
+                                   keepkv_cache *dst, const int32_t *near, float alpha,
+                                   void *workspace, size_t workspace_bytes, void *stream);
+
 /* Measurement probes (not part of the method): what the GPU sustains, to set next to the
  * published peaks.  keepkv_probe_read: `n_workgroups` workgroups stream `bytes` (a multiple of
  * 16) of DEVICE memory at `src` once with coalesced 16-byte loads; nothing is written except

@@ -59,18 +59,22 @@ _lib.keepkv_match.argtypes = [C.POINTER(_Layout), C.POINTER(_Cache), C.c_int32, 
                               _P, _P, _P, C.c_size_t, _P]
 _lib.keepkv_merge.argtypes = [C.POINTER(_Layout), C.POINTER(_Cache), C.POINTER(_Cache), C.c_int32, _P, _P, _P,
                               _P, C.c_float, _P, _P, C.c_size_t, _P]
+_lib.keepkv_prefill_match.argtypes = [C.POINTER(_Layout), C.POINTER(_Cache), C.c_float, _P, _P, _P, C.c_size_t, _P]
+_lib.keepkv_prefill_merge.argtypes = [C.POINTER(_Layout), C.POINTER(_Cache), C.POINTER(_Cache), _P, C.c_float, _P,
+                                      C.c_size_t, _P]
 _lib.keepkv_probe_read.argtypes = [_P, C.c_size_t, C.c_int32, _P, _P]
 _lib.keepkv_probe_mfma.argtypes = [C.c_int32, C.c_int32, C.c_int32, _P, C.POINTER(C.c_double), _P]
 _lib.keepkv_decode_plan.argtypes = [C.POINTER(_Layout), C.c_int32, C.POINTER(C.c_int32), C.POINTER(C.c_int32),
                                     C.POINTER(C.c_int32)]
-for _f in ("decode_step_static", "decode_plan", "probe_read", "probe_mfma", "append", "decode_attn", "decode_step", "workspace_init", "score", "score_window", "select",
+for _f in ("prefill_match", "prefill_merge", "decode_step_static", "decode_plan", "probe_read", "probe_mfma", "append", "decode_attn", "decode_step", "workspace_init", "score", "score_window", "select",
            "select_by_key", "match",
            "merge"):
     getattr(_lib, "keepkv_" + _f).restype = C.c_int
 
 EXPORTS = ["keepkv_strerror", "keepkv_version", "keepkv_workspace_bytes", "keepkv_workspace_init", "keepkv_decode_plan",
            "keepkv_append", "keepkv_decode_attn", "keepkv_decode_step", "keepkv_decode_step_static", "keepkv_score", "keepkv_score_window", "keepkv_select",
-           "keepkv_select_by_key", "keepkv_match", "keepkv_merge", "keepkv_probe_read", "keepkv_probe_mfma"]
+           "keepkv_select_by_key", "keepkv_match", "keepkv_merge", "keepkv_prefill_match", "keepkv_prefill_merge",
+           "keepkv_probe_read", "keepkv_probe_mfma"]
 
 
 class KeepKVError(RuntimeError):
@@ -228,6 +232,16 @@ def match(layout: Layout, cache: Cache, budget: int, keep_idx, evict_idx, n_evic
                              _ptr(n_evict), threshold, _ptr(match_out), _ptr(sim_out), _ptr(workspace),
                              0 if workspace is None else workspace.numel() * workspace.element_size(),
                              _stream()), "keepkv_match")
+
+
+def prefill_match(layout: Layout, cache: Cache, threshold: float, near, sim_out, workspace) -> None:
+    _check(_lib.keepkv_prefill_match(C.byref(layout.c()), C.byref(cache.c()), threshold, _ptr(near), _ptr(sim_out),
+                                     _ptr(workspace), _nbytes(workspace), _stream()), "keepkv_prefill_match")
+
+
+def prefill_merge(layout: Layout, src: Cache, dst: Cache, near, alpha: float, workspace) -> None:
+    _check(_lib.keepkv_prefill_merge(C.byref(layout.c()), C.byref(src.c()), C.byref(dst.c()), _ptr(near), alpha,
+                                     _ptr(workspace), _nbytes(workspace), _stream()), "keepkv_prefill_merge")
 
 
 def merge(layout: Layout, src: Cache, dst: Cache, budget: int, keep_idx, evict_idx, n_evict, match_in,

@@ -52,5 +52,9 @@ extern "C" size_t keepkv_workspace_bytes(const keepkv_layout* layout, int32_t ca
   need = need > s ? need : s;
   need = need > m ? need : m;
   need = need > g ? need : g;
+  const size_t pm = plan_prefill_match(layout, capacity).bytes;
+  const size_t pg = plan_prefill_merge(layout, capacity).bytes;
+  need = need > pm ? need : pm;
+  need = need > pg ? need : pg;
   return need;
 }

@@ -125,6 +125,22 @@ struct MatchPlan {
 };
 MatchPlan plan_match(const keepkv_layout* L, int capacity, int budget);
 
+struct PrefillMatchPlan {
+  size_t rnorm_off;   // float [B*Hkv, capacity]      1/|k_i| of every live slot
+  size_t flag_off;    // int32 [1 + B*Hkv*capacity]   queue of rows for the f64 kernel
+  size_t partial_off; // per-share results of the f64 kernel
+  size_t bytes;
+};
+PrefillMatchPlan plan_prefill_match(const keepkv_layout* L, int capacity);
+
+struct PrefillMergePlan {
+  size_t keep_off;    // int32 [B*Hkv, capacity]      receiving slots, ascending, -1 behind them
+  size_t start_off;   // int32 [B*Hkv, capacity + 1]  CSR row starts
+  size_t member_off;  // int32 [B*Hkv, capacity]      absorbed slots grouped by receiver
+  size_t bytes;
+};
+PrefillMergePlan plan_prefill_merge(const keepkv_layout* L, int capacity);
+
 struct MergePlan {
   size_t start_off;   // int32 [B*Hkv, budget + 1]   CSR row starts
   size_t member_off;  // int32 [B*Hkv, capacity]     evicted slots grouped by target

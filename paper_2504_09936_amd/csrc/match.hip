@@ -115,6 +115,8 @@ struct MatchParams {
   int capacity, budget, max_evict, rn_pitch;
   float threshold, delta;
   int per_unit, n_units;   // first event's kernel: workgroups per head, heads
+  int causal;              // prefill pass: row j is slot j and its columns are the slots before it (no lists)
+  const int32_t* len;      // prefill pass: live slots per head
   int small_parts;         // steady-state kernel: workgroups that share the retained list of one 64-row block
   int32_t* small_partial;  // [row blocks * small_parts][64][3] their per-row results
 };
@@ -720,15 +722,17 @@ __global__ __launch_bounds__(256) void match_exact_kernel(MatchParams p) {
     const int room = imin((int)gridDim.x, kExactResident);
     while (parts < kExactMaxParts && (long)n_flag * (parts * 2) <= (long)room) parts *= 2;
   }
-  const int share = (p.budget + parts - 1) / parts;
   for (int w = blockIdx.x; w < n_flag * parts; w += gridDim.x) {
     const int f = w / parts, part = w % parts;
-    const int c_lo = part * share, c_hi = imin(p.budget, c_lo + share);
     const int o = p.flag_rows[f];
     const int unit = o / p.max_evict, j = o % p.max_evict;
     const T* kunit = kall + (size_t)unit * p.capacity * D;
-    const int32_t* keep = p.keep_idx + (size_t)unit * p.budget;
-    const int e = p.evict_idx[(size_t)unit * p.max_evict + j];
+    // causal (the prefill pass): the row is slot j itself and its columns are the slots 0 .. j - 1
+    const int32_t* keep = p.causal ? nullptr : p.keep_idx + (size_t)unit * p.budget;
+    const int e = p.causal ? j : p.evict_idx[(size_t)unit * p.max_evict + j];
+    const int n_cols = p.causal ? j : p.budget;
+    const int share = (n_cols + parts - 1) / parts;
+    const int c_lo = part * share, c_hi = imin(n_cols, c_lo + share);
     __syncthreads();                      // previous row's shared values are no longer read
     for (int d = tid; d < D; d += 256) {
       if constexpr (sizeof(T) == 2) s_e[d] = (double)bf16_to_f32(reinterpret_cast<const uint16_t*>(kunit)[(size_t)e * D + d]);
@@ -741,7 +745,7 @@ __global__ __launch_bounds__(256) void match_exact_kernel(MatchParams p) {
     double best = -INFINITY;
     int best_c = 0x7FFFFFFF;
     for (int c = c_lo + tid; c < c_hi; c += 256) {
-      const int slot = keep[c];
+      const int slot = p.causal ? c : keep[c];
       if (slot < 0) continue;
       const T* kc = kunit + (size_t)slot * D;
       uint4 rowv[NV];
@@ -842,6 +846,182 @@ __global__ __launch_bounds__(256) void match_exact_kernel(MatchParams p) {
   }
 }
 
+// ---------------------------------------------------------------------------------------------------
+// Merge-first prefill pass (App. B.4): for every live slot its most similar EARLIER key.  The same dense
+// contraction as above with rows = columns = the head's own keys and a causal mask, so the keys need no
+// gathering: a workgroup of 4 wavefronts takes 128 consecutive slots as rows (32 per wavefront, resident in
+// registers as B operands) and streams the slots before them through LDS in 64-key stages, copied straight
+// from the cache with the row swizzle applied on the address side.  A lane holds one row; per value it keeps
+// (best, column, runner-up) with strict comparisons in ascending column order, so the first maximiser wins.
+// Column blocks wholly behind a wavefront's rows are skipped, the one block on the diagonal is masked.
+// Rows that the f32 arithmetic cannot decide are queued for the f64 kernel (causal mode).
+constexpr int kPfWaves = 4;
+constexpr int kPfRowsPerWave = 32;
+constexpr int kPfRows = kPfWaves * kPfRowsPerWave;      // 128 rows per workgroup
+constexpr int kPfStage = 64;                            // keys per LDS stage
+
+// 1/|k_i| (f32) of every live slot; 0 for zero keys and beyond len
+template <typename T, int D>
+__global__ __launch_bounds__(256) void slot_rnorm_kernel(const T* __restrict__ k, const int32_t* __restrict__ len,
+                                                         float* __restrict__ rn, int capacity) {
+  constexpr int EPL = 16 / (int)sizeof(T), LPS = D / EPL, RPB = 256 / LPS;
+  const int unit = blockIdx.y, sub = threadIdx.x % LPS;
+  const int r = blockIdx.x * RPB + threadIdx.x / LPS;
+  const int n = len[unit];
+  if (r >= capacity) return;
+  float ss = 0.f;
+  if (r < n) {
+    const uint4 x = reinterpret_cast<const uint4*>(k)[((size_t)unit * capacity + r) * LPS + sub];
+    if constexpr (sizeof(T) == 2) {
+      const uint32_t w[4] = {x.x, x.y, x.z, x.w};
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const float a = bf16_lo(w[e]), b = bf16_hi(w[e]);
+        ss = fmaf(a, a, ss);
+        ss = fmaf(b, b, ss);
+      }
+    } else {
+      const float w[4] = {__builtin_bit_cast(float, x.x), __builtin_bit_cast(float, x.y),
+                          __builtin_bit_cast(float, x.z), __builtin_bit_cast(float, x.w)};
+#pragma unroll
+      for (int e = 0; e < 4; ++e) ss = fmaf(w[e], w[e], ss);
+    }
+  }
+  ss = group_sum<LPS>(ss);
+  if (sub == 0) rn[(size_t)unit * capacity + r] = ss > 0.f ? 1.0f / sqrtf(ss) : 0.f;
+}
+
+template <int D>
+__global__ __launch_bounds__(kPfWaves* kWave) void prefill_near_kernel(MatchParams p) {
+  constexpr int KS = D / 16, ROWB = D * 2, CHUNKS = ROWB / 16;
+  constexpr int STAGE_BYTES = kPfStage * ROWB;
+  constexpr int LOADS = kPfStage * CHUNKS / (kPfWaves * kWave);
+  __shared__ __align__(16) unsigned char s_stage[2 * STAGE_BYTES];
+  __shared__ __align__(16) float s_rn[2][kPfStage];
+
+  const int unit = blockIdx.y;
+  const int n = p.len[unit];
+  const int r0 = ((int)gridDim.x - 1 - (int)blockIdx.x) * kPfRows;   // the long rows first
+  if (r0 >= n) return;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int l32 = lane & 31, half = lane >> 5;
+  const unsigned char* kbytes = reinterpret_cast<const unsigned char*>(p.k) + (size_t)unit * p.capacity * ROWB;
+  const float* rn_all = p.rnorm + (size_t)unit * p.capacity;
+  const int row_lo = r0 + wave * kPfRowsPerWave;         // this wavefront's rows: row_lo .. row_lo + 31
+  const int row = row_lo + l32;                          // this lane's row (both halves)
+  const int n_cols = min(n, r0 + kPfRows) - 1;           // columns 0 .. n_cols - 1 are needed by some row here
+  const int n_stage = (n_cols + kPfStage - 1) / kPfStage;
+
+  auto issue_stage = [&](int s, int buf) {
+    const int col0 = s * kPfStage;
+#pragma unroll
+    for (int i = 0; i < LOADS; ++i) {
+      const int c = tid + i * (kPfWaves * kWave);
+      const int r = c / CHUNKS, phys = c % CHUNKS;
+      const size_t off = (size_t)min(col0 + r, n - 1) * ROWB + ((phys ^ (r & (CHUNKS - 1))) * 16);
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(kbytes + off),
+                                       (__attribute__((address_space(3))) void*)(s_stage + buf * STAGE_BYTES +
+                                                                               (i * (kPfWaves * kWave) + wave * 64) * 16),
+                                       16, 0, 0);
+    }
+    if (wave == 0)
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(rn_all + min(col0 + lane, n - 1)),
+                                       (__attribute__((address_space(3))) void*)(&s_rn[buf][0]), 4, 0, 0);
+  };
+  if (n_stage > 0) issue_stage(0, 0);
+
+  // B operands: this lane's row, its 8 channels of every k-step
+  bf16x8_t e[KS];
+  {
+    const unsigned char* rp = kbytes + (size_t)min(row, n - 1) * ROWB + half * 16;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) e[ks] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4*>(rp + ks * 32));
+  }
+  const float rn_row = rn_all[min(row, n - 1)];
+
+  float best = -INFINITY, second = -INFINITY;
+  int bcol = 0;
+  int par = 0;
+  for (int s = 0; s < n_stage; ++s) {
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();                                     // stage s has landed; everyone is done with stage s - 1
+    if (s + 1 < n_stage) issue_stage(s + 1, par ^ 1);
+    const int col0 = s * kPfStage;
+#pragma unroll
+    for (int cbl = 0; cbl < kPfStage / 32; ++cbl) {
+      const int cb0 = col0 + 32 * cbl;                   // first column of the block
+      if (cb0 >= row_lo + kPfRowsPerWave || cb0 >= n_cols) continue;   // uniform over the wavefront: nothing before a row
+      f32x16_t acc = {0};
+      const unsigned char* frag = s_stage + par * STAGE_BYTES + (32 * cbl + l32) * ROWB;
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) {
+        const bf16x8_t a = *reinterpret_cast<const bf16x8_t*>(frag + (((2 * ks + half) ^ (l32 & (CHUNKS - 1))) * 16));
+        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, e[ks], acc, 0, 0, 0);
+      }
+      const bool diagonal = cb0 + 32 > row_lo;           // uniform: the block holds columns at or behind some row
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const f32x4_t rn4 = *reinterpret_cast<const f32x4_t*>(&s_rn[par][32 * cbl + 8 * g + 4 * half]);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const int col = cb0 + 8 * g + 4 * half + i;
+          float v = acc[4 * g + i] * rn4[i];
+          if (diagonal) v = (col < row) ? v : -INFINITY;
+          if (col >= n_cols) v = -INFINITY;             // (clamped loads beyond the last needed column)
+          const bool gt = v > best;
+          second = gt ? best : fmaxf(second, v);
+          bcol = gt ? col : bcol;
+          best = gt ? v : best;
+        }
+      }
+    }
+    par ^= 1;
+  }
+  // the two lanes of a row (the halves) meet; equal values: the lower column, and the margin is zero
+  {
+    const float ob = __shfl_xor(best, 32), os = __shfl_xor(second, 32);
+    const int oc = __shfl_xor(bcol, 32);
+    const float hi = fmaxf(best, ob), lo = fminf(best, ob);
+    const int c = (best > ob) ? bcol : ((ob > best) ? oc : min(bcol, oc));
+    second = fmaxf(lo, fmaxf(second, os));
+    best = hi;
+    bcol = c;
+  }
+  if (half != 0 || row >= n) return;
+  const size_t o = (size_t)unit * p.max_evict + row;
+  if (row == 0) {                                        // no earlier key
+    p.match[o] = -1;
+    if (p.sim_out != nullptr) p.sim_out[o] = -INFINITY;
+    return;
+  }
+  const float cos1 = best * rn_row;
+  const bool fragile = !(best > 0.f) || !(rn_row > 0.f) || !(rn_row < INFINITY) || !((best - second) * rn_row > p.delta) ||
+                       !(fabsf(cos1 - p.threshold) > p.delta);
+  p.match[o] = (cos1 > p.threshold) ? bcol : -1;
+  if (p.sim_out != nullptr) p.sim_out[o] = cos1;
+  if (fragile) {
+    const int at = atomicAdd(p.flag_count, 1);
+    p.flag_rows[at] = (int)o;
+  }
+}
+
+// queue every live row but the first (f32 caches: the f64 kernel decides all rows)
+__global__ void flag_all_causal_kernel(const int32_t* __restrict__ len, int32_t* flag_count, int32_t* flag_rows,
+                                       int32_t* near, float* sim_out, int capacity) {
+  const int unit = blockIdx.y;
+  const int n = len[unit];
+  for (int j = blockIdx.x * blockDim.x + threadIdx.x; j < n; j += gridDim.x * blockDim.x) {
+    if (j == 0) {
+      near[(size_t)unit * capacity] = -1;
+      if (sim_out != nullptr) sim_out[(size_t)unit * capacity] = -INFINITY;
+      continue;
+    }
+    const int at = atomicAdd(flag_count, 1);
+    flag_rows[at] = unit * capacity + j;
+  }
+}
+
 template <int D>
 constexpr size_t mfma_smem_bytes() {
   return 2 * (size_t)kStageCols * (D * 2) + 2 * kStageCols * sizeof(float);
@@ -910,7 +1090,74 @@ MatchPlan plan_match(const keepkv_layout* L, int capacity, int budget) {
   return pl;
 }
 
+PrefillMatchPlan plan_prefill_match(const keepkv_layout* L, int capacity) {
+  PrefillMatchPlan pl;
+  const size_t units = (size_t)L->batch * L->n_kv_heads;
+  pl.rnorm_off = kWorkspaceHead;
+  pl.flag_off = pl.rnorm_off + align_up(units * capacity * sizeof(float), 256);
+  pl.partial_off = pl.flag_off + align_up((1 + units * (size_t)capacity) * sizeof(int32_t) + 256, 256);
+  pl.bytes = pl.partial_off + (size_t)kExactResident * 16;
+  return pl;
+}
+
 }  // namespace kk
+
+extern "C" keepkv_status keepkv_prefill_match(const keepkv_layout* layout, const keepkv_cache* cache, float threshold,
+                                              int32_t* near, float* sim_out, void* workspace, size_t workspace_bytes,
+                                              void* stream) {
+  using namespace kk;
+  if (!layout_ok(layout) || !cache_ok(cache) || !near) return KEEPKV_ERR_INVALID_ARG;
+  if (!units_supported(layout)) return KEEPKV_ERR_UNSUPPORTED;
+  if (!(threshold == threshold) || !aligned16(cache->k)) return KEEPKV_ERR_INVALID_ARG;
+  if (layout->head_dim != 64 && layout->head_dim != 128) return KEEPKV_ERR_UNSUPPORTED;
+  const size_t units = (size_t)layout->batch * layout->n_kv_heads;
+  const int cap = cache->capacity;
+  if (units * (size_t)cap >= (size_t)1 << 31) return KEEPKV_ERR_UNSUPPORTED;
+  const PrefillMatchPlan pl = plan_prefill_match(layout, cap);
+  if (!workspace || workspace_bytes < pl.bytes || !aligned16(workspace)) return KEEPKV_ERR_WORKSPACE;
+  hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+
+  MatchParams p;
+  p.k = cache->k; p.keep_idx = nullptr; p.evict_idx = nullptr; p.n_evict = nullptr;
+  p.rnorm = reinterpret_cast<float*>(reinterpret_cast<char*>(workspace) + pl.rnorm_off);
+  p.panel = nullptr;
+  p.flag_count = reinterpret_cast<int32_t*>(reinterpret_cast<char*>(workspace) + kMatchCountersOff);
+  p.exact_done = p.flag_count + 1;
+  p.flag_rows = reinterpret_cast<int32_t*>(reinterpret_cast<char*>(workspace) + pl.flag_off);
+  p.exact_partial = reinterpret_cast<ExactPartial*>(reinterpret_cast<char*>(workspace) + pl.partial_off);
+  p.exact_ticket = reinterpret_cast<int32_t*>(workspace);
+  p.match = near; p.sim_out = sim_out;
+  p.capacity = cap; p.budget = 0; p.max_evict = cap; p.rn_pitch = cap;
+  p.threshold = threshold; p.delta = 1.6e-5f;
+  p.per_unit = 0; p.n_units = 0; p.small_parts = 1; p.small_partial = nullptr;
+  p.causal = 1; p.len = cache->len;
+
+  long eb = (long)units * cap / 16;
+  const int exact_blocks = (int)(eb < 64 ? 64 : (eb > 512 ? 512 : eb));
+  if (layout->dtype == KEEPKV_BF16) {
+    const int lps = layout->head_dim * 2 / 16, rpb = 256 / lps;
+    const dim3 ngrid((cap + rpb - 1) / rpb, (unsigned)units);
+    const dim3 pgrid((cap + kPfRows - 1) / kPfRows, (unsigned)units);
+    if (layout->head_dim == 128) {
+      slot_rnorm_kernel<uint16_t, 128><<<ngrid, 256, 0, st>>>((const uint16_t*)cache->k, cache->len,
+                                                            const_cast<float*>(p.rnorm), cap);
+      prefill_near_kernel<128><<<pgrid, kPfWaves * kWave, 0, st>>>(p);
+      match_exact_kernel<uint16_t, 128><<<exact_blocks, 256, 0, st>>>(p);
+    } else {
+      slot_rnorm_kernel<uint16_t, 64><<<ngrid, 256, 0, st>>>((const uint16_t*)cache->k, cache->len,
+                                                           const_cast<float*>(p.rnorm), cap);
+      prefill_near_kernel<64><<<pgrid, kPfWaves * kWave, 0, st>>>(p);
+      match_exact_kernel<uint16_t, 64><<<exact_blocks, 256, 0, st>>>(p);
+    }
+  } else {
+    int bx = (cap + 255) / 256;
+    if (bx > 64) bx = 64;
+    flag_all_causal_kernel<<<dim3(bx, (unsigned)units), 256, 0, st>>>(cache->len, p.flag_count, p.flag_rows, near, sim_out, cap);
+    if (layout->head_dim == 128) match_exact_kernel<float, 128><<<exact_blocks, 256, 0, st>>>(p);
+    else match_exact_kernel<float, 64><<<exact_blocks, 256, 0, st>>>(p);
+  }
+  return launch_status();
+}
 
 extern "C" keepkv_status keepkv_match(const keepkv_layout* layout, const keepkv_cache* cache, int32_t budget,
                                       const int32_t* keep_idx, const int32_t* evict_idx, const int32_t* n_evict,
@@ -943,6 +1190,7 @@ extern "C" keepkv_status keepkv_match(const keepkv_layout* layout, const keepkv_
   p.panel = reinterpret_cast<const unsigned char*>(workspace) + pl.panel_off;
   p.exact_partial = reinterpret_cast<ExactPartial*>(reinterpret_cast<char*>(workspace) + pl.partial_off);
   p.exact_ticket = reinterpret_cast<int32_t*>(workspace);
+  p.causal = 0; p.len = cache->len;
   p.small_parts = 1;
   p.small_partial = reinterpret_cast<int32_t*>(reinterpret_cast<char*>(workspace) + pl.small_partial_off);
   p.match = match; p.sim_out = sim_out;

@@ -239,6 +239,7 @@ struct MergeParams {
   const int32_t* evict_idx;
   int64_t* dropped_votes;
   int scap, dcap, budget, max_evict;
+  int write_len;               // 0: the caller's grouping kernel has set dst.len (prefill pass)
   double ln_alpha;
 };
 
@@ -280,7 +281,7 @@ __global__ __launch_bounds__(256) void merge_apply_kernel(MergeParams p) {
   const int sub = threadIdx.x % LPS;
   const int lane = threadIdx.x & 63;
   const int gbase = lane - sub;                 // first lane of this group within the wavefront
-  if (blockIdx.x == 0 && threadIdx.x == 0) {
+  if (blockIdx.x == 0 && threadIdx.x == 0 && p.write_len) {
     const int n = p.slen[unit];
     p.dlen[unit] = n < p.budget ? n : p.budget;
   }
@@ -466,7 +467,160 @@ __global__ __launch_bounds__(256) void merge_apply_kernel(MergeParams p) {
   }
 }
 
+// ---------------------------------------------------------------------------------------------------
+// Merge-first prefill pass (App. B.4), grouping.  near[i] is slot i's most similar earlier key above the
+// threshold, or -1: the links form a forest.  A slot is absorbed by the slot it links to unless that slot is
+// itself absorbed, i.e. slots at odd depth of their tree are absorbed by their parent and slots at even depth
+// stay and receive their children.  Depth parity comes from pointer jumping in LDS (links point to lower
+// slot numbers; ceil(log2 len) rounds); the receiving slots are numbered in ascending order by a block scan,
+// the absorbed slots grouped by receiver (histogram, scan, scatter) and put in ascending slot order inside
+// each group by counting, so the merge sums in a fixed order.  Output in the form merge_apply_kernel reads:
+// keep_idx (receivers, -1 behind them), CSR starts and members, all with pitch `capacity`; dst.len = receivers.
+constexpr int kPrefillMaxSlots = 16384;          // two int arrays of that many words in LDS
+constexpr int kPfItems = kPrefillMaxSlots / kGroupThreads;
+
+__global__ __launch_bounds__(kGroupThreads) void prefill_group_kernel(
+    const int32_t* __restrict__ near, const int32_t* __restrict__ slen, int32_t* __restrict__ keep_idx,
+    int32_t* __restrict__ start, int32_t* __restrict__ members, int32_t* __restrict__ dlen, int capacity) {
+  extern __shared__ int s_pf[];                   // [2][n_pad]
+  __shared__ int s_wave[kGroupThreads / 64];
+  const int unit = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int n = min(slen[unit], capacity);
+  const int per = (capacity + kGroupThreads - 1) / kGroupThreads;     // slots per thread, a contiguous run (<= kPfItems)
+  const int i0 = tid * per;
+  const int32_t* nr = near + (size_t)unit * capacity;
+  int* A = s_pf;
+  int* B = s_pf + per * kGroupThreads;
+
+  // (ancestor << 1) | parity of the distance to it; a slot without a link is its own ancestor
+  int link[kPfItems];
+#pragma unroll
+  for (int u = 0; u < kPfItems; ++u) {
+    const int i = i0 + u;
+    link[u] = -1;
+    if (u < per && i < n) {
+      const int l = nr[i];
+      link[u] = (l >= 0 && l < i) ? l : -1;       // (a link that does not point to an earlier slot is ignored)
+      A[i] = link[u] >= 0 ? ((link[u] << 1) | 1) : (i << 1);
+    }
+  }
+  __syncthreads();
+  int rounds = 0;
+  while ((1 << rounds) < n) ++rounds;
+  int* cur = A;
+  int* nxt = B;
+  for (int r = 0; r < rounds; ++r) {              // uniform trip count
+#pragma unroll
+    for (int u = 0; u < kPfItems; ++u) {
+      const int i = i0 + u;
+      if (u < per && i < n) {
+        const int x = cur[i];
+        const int y = cur[x >> 1];
+        nxt[i] = (y & ~1) | ((x ^ y) & 1);
+      }
+    }
+    __syncthreads();
+    int* t = cur; cur = nxt; nxt = t;
+  }
+  // absorbed = odd depth; receivers numbered in slot order
+  bool absorbed[kPfItems];
+  int n_recv_mine = 0;
+#pragma unroll
+  for (int u = 0; u < kPfItems; ++u) {
+    const int i = i0 + u;
+    absorbed[u] = (u < per && i < n) ? (cur[i] & 1) != 0 : false;
+    if (u < per && i < n && !absorbed[u]) ++n_recv_mine;
+  }
+  auto block_exclusive = [&](int mine, int& total) {   // exclusive prefix of `mine` over the threads, and the sum
+    int incl = mine;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+      const int v = __shfl_up(incl, off);
+      if (lane >= off) incl += v;
+    }
+    __syncthreads();                              // previous use of s_wave is over
+    if (lane == 63) s_wave[wave] = incl;
+    __syncthreads();
+    int before = 0, all = 0;
+    for (int w = 0; w < kGroupThreads / 64; ++w) {
+      const int v = s_wave[w];
+      if (w < wave) before += v;
+      all += v;
+    }
+    total = all;
+    return before + incl - mine;
+  };
+  int n_recv = 0;
+  int rpos = block_exclusive(n_recv_mine, n_recv);
+  // nxt: receiver number of every receiving slot; then cur is free
+  int my_rpos[kPfItems];
+#pragma unroll
+  for (int u = 0; u < kPfItems; ++u) {
+    const int i = i0 + u;
+    my_rpos[u] = -1;
+    if (u < per && i < n && !absorbed[u]) {
+      my_rpos[u] = rpos;
+      nxt[i] = rpos;
+      keep_idx[(size_t)unit * capacity + rpos] = i;
+      ++rpos;
+    }
+  }
+  for (int r = n_recv + tid; r < capacity; r += kGroupThreads) keep_idx[(size_t)unit * capacity + r] = -1;
+  __syncthreads();
+  int* cnt = cur;                                 // histogram over receiver numbers, then cursors
+  for (int r = tid; r < n_recv; r += kGroupThreads) cnt[r] = 0;
+  int pos[kPfItems];                              // receiver number of this thread's absorbed slots
+#pragma unroll
+  for (int u = 0; u < kPfItems; ++u) pos[u] = absorbed[u] ? nxt[link[u]] : -1;
+  __syncthreads();
+#pragma unroll
+  for (int u = 0; u < kPfItems; ++u)
+    if (absorbed[u]) atomicAdd(&cnt[pos[u]], 1);
+  __syncthreads();
+  // exclusive scan of cnt[0 .. n_recv): thread t owns a contiguous run of receiver numbers
+  const int rper = (n_recv + kGroupThreads - 1) / kGroupThreads;
+  const int q0 = min(n_recv, tid * rper), q1 = min(n_recv, q0 + rper);
+  int mine = 0;
+  for (int r = q0; r < q1; ++r) mine += cnt[r];
+  int n_abs = 0;
+  int run = block_exclusive(mine, n_abs);
+  int32_t* st = start + (size_t)unit * (capacity + 1);
+  for (int r = q0; r < q1; ++r) {
+    const int c = cnt[r];
+    st[r] = run;
+    cnt[r] = run;                                 // where the group's next member goes
+    run += c;
+  }
+  for (int r = n_recv + tid; r <= capacity; r += kGroupThreads) st[r] = n_abs;
+  if (tid == 0) dlen[unit] = n_recv;
+  __syncthreads();
+  int* tmp = nxt;                                 // the receiver numbers are in registers now: members in arrival order
+#pragma unroll
+  for (int u = 0; u < kPfItems; ++u)
+    if (absorbed[u]) tmp[atomicAdd(&cnt[pos[u]], 1)] = i0 + u;
+  __syncthreads();                                // cnt[r] is now the end of group r
+  int32_t* mem = members + (size_t)unit * capacity;
+#pragma unroll
+  for (int u = 0; u < kPfItems; ++u) {
+    if (!absorbed[u]) continue;
+    const int g0 = pos[u] > 0 ? cnt[pos[u] - 1] : 0, g1 = cnt[pos[u]];
+    int rank = 0;
+    for (int m = g0; m < g1; ++m) rank += tmp[m] < i0 + u;
+    mem[g0 + rank] = i0 + u;
+  }
+}
+
 }  // namespace
+
+PrefillMergePlan plan_prefill_merge(const keepkv_layout* L, int capacity) {
+  PrefillMergePlan pl;
+  const size_t units = (size_t)L->batch * L->n_kv_heads;
+  pl.keep_off = kWorkspaceHead;
+  pl.start_off = pl.keep_off + align_up(units * capacity * sizeof(int32_t), 256);
+  pl.member_off = pl.start_off + align_up(units * ((size_t)capacity + 1) * sizeof(int32_t), 256);
+  pl.bytes = pl.member_off + align_up(units * capacity * sizeof(int32_t), 256);
+  return pl;
+}
 
 MergePlan plan_merge(const keepkv_layout* L, int capacity, int budget) {
   MergePlan pl;
@@ -522,6 +676,7 @@ extern "C" keepkv_status keepkv_merge(const keepkv_layout* layout, const keepkv_
   p.keep_idx = keep_idx; p.n_evict = n_evict; p.start = start; p.members = members;
   p.match = match; p.evict_idx = evict_idx; p.dropped_votes = dropped_votes;
   p.scap = src->capacity; p.dcap = dst->capacity; p.budget = budget; p.max_evict = max_evict;
+  p.write_len = 1;
   p.ln_alpha = alpha > 0.f ? log((double)alpha) : -INFINITY;
   const int esz = layout->dtype == KEEPKV_BF16 ? 2 : 4;
   const int lps = layout->head_dim * esz / 16, gpb = 256 / lps;
@@ -542,6 +697,57 @@ extern "C" keepkv_status keepkv_merge(const keepkv_layout* layout, const keepkv_
       if (direct) merge_apply_kernel<float, 64, true><<<grid, 256, 0, st>>>(p);
       else merge_apply_kernel<float, 64, false><<<grid, 256, 0, st>>>(p);
     }
+  }
+  return launch_status();
+}
+
+extern "C" keepkv_status keepkv_prefill_merge(const keepkv_layout* layout, const keepkv_cache* src, keepkv_cache* dst,
+                                              const int32_t* near, float alpha, void* workspace,
+                                              size_t workspace_bytes, void* stream) {
+  using namespace kk;
+  if (!layout_ok(layout) || !cache_ok(src) || !cache_ok(dst) || !near) return KEEPKV_ERR_INVALID_ARG;
+  if (!units_supported(layout)) return KEEPKV_ERR_UNSUPPORTED;
+  if (dst->capacity < src->capacity || !(alpha >= 0.f && alpha < 1.f)) return KEEPKV_ERR_INVALID_ARG;
+  if (src->k == dst->k || src->v == dst->v || src->votes == dst->votes || src->log_s == dst->log_s ||
+      src->n_obs == dst->n_obs || src->len == dst->len)
+    return KEEPKV_ERR_INVALID_ARG;
+  if (!aligned16(src->k) || !aligned16(src->v) || !aligned16(dst->k) || !aligned16(dst->v)) return KEEPKV_ERR_INVALID_ARG;
+  if (layout->head_dim != 64 && layout->head_dim != 128) return KEEPKV_ERR_UNSUPPORTED;
+  const int cap = src->capacity;
+  if (cap > kPrefillMaxSlots) return KEEPKV_ERR_UNSUPPORTED;
+  const PrefillMergePlan pl = plan_prefill_merge(layout, cap);
+  if (!workspace || workspace_bytes < pl.bytes || !aligned16(workspace)) return KEEPKV_ERR_WORKSPACE;
+  const unsigned units = (unsigned)(layout->batch * layout->n_kv_heads);
+  hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+  int32_t* keep = reinterpret_cast<int32_t*>(reinterpret_cast<char*>(workspace) + pl.keep_off);
+  int32_t* start = reinterpret_cast<int32_t*>(reinterpret_cast<char*>(workspace) + pl.start_off);
+  int32_t* members = reinterpret_cast<int32_t*>(reinterpret_cast<char*>(workspace) + pl.member_off);
+
+  const int per = (cap + kGroupThreads - 1) / kGroupThreads;
+  const size_t lds = (size_t)2 * per * kGroupThreads * sizeof(int);
+  static const hipError_t attr = hipFuncSetAttribute((const void*)prefill_group_kernel,
+                                                     hipFuncAttributeMaxDynamicSharedMemorySize,
+                                                     2 * kPrefillMaxSlots * (int)sizeof(int));
+  if (attr != hipSuccess) return KEEPKV_ERR_DEVICE;
+  prefill_group_kernel<<<units, kGroupThreads, lds, st>>>(near, src->len, keep, start, members, dst->len, cap);
+
+  MergeParams p;
+  p.sk = src->k; p.sv = src->v; p.svotes = src->votes; p.slog_s = src->log_s; p.sn_obs = src->n_obs; p.slen = src->len;
+  p.dk = dst->k; p.dv = dst->v; p.dvotes = dst->votes; p.dlog_s = dst->log_s; p.dn_obs = dst->n_obs; p.dlen = dst->len;
+  p.keep_idx = keep; p.n_evict = nullptr; p.start = start; p.members = members;
+  p.match = nullptr; p.evict_idx = nullptr; p.dropped_votes = nullptr;
+  p.scap = cap; p.dcap = dst->capacity; p.budget = cap; p.max_evict = 0;
+  p.write_len = 0;
+  p.ln_alpha = alpha > 0.f ? log((double)alpha) : -INFINITY;
+  const int esz = layout->dtype == KEEPKV_BF16 ? 2 : 4;
+  const int lps = layout->head_dim * esz / 16, gpb = 256 / lps;
+  const dim3 grid((cap + gpb - 1) / gpb, units);
+  if (layout->dtype == KEEPKV_BF16) {
+    if (layout->head_dim == 128) merge_apply_kernel<uint16_t, 128, false><<<grid, 256, 0, st>>>(p);
+    else merge_apply_kernel<uint16_t, 64, false><<<grid, 256, 0, st>>>(p);
+  } else {
+    if (layout->head_dim == 128) merge_apply_kernel<float, 128, false><<<grid, 256, 0, st>>>(p);
+    else merge_apply_kernel<float, 64, false><<<grid, 256, 0, st>>>(p);
   }
   return launch_status();
 }
