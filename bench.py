@@ -154,6 +154,9 @@ def parse():
     ap.add_argument("--unfused", action="store_true",
                     help="use keepkv_append + keepkv_decode_attn + keepkv_score instead of keepkv_decode_step")
     ap.add_argument("--window", type=int, default=None, help="observation passes before the first event")
+    ap.add_argument("--decode-wavefronts", type=int, default=0, choices=(0, 4, 8, -1),
+                    help="launch override of the decode kernel (keepkv_cache.plan_wavefronts): 4 or 8 wavefronts per "
+                         "workgroup of the matrix-core kernel, -1 = the vector-ALU kernel on a bf16 cache; 0 = the plan's")
     ap.add_argument("--copy-probe", action="store_true",
                     help="only run a plain device copy of known size (calibrates rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     return ap.parse_args()
@@ -221,6 +224,9 @@ def main():
     logits = torch.zeros(B, H, N, dtype=torch.float32, device=dev)
     out = torch.zeros(B, Hq, D, dtype=lay.torch_dtype, device=dev)
     caches = [[kk.Cache(lay, cap), kk.Cache(lay, cap)] for _ in range(R)]
+    for pair in caches:
+        for c in pair:
+            c.plan_wavefronts = args.decode_wavefronts
     cur = [0] * R
 
     ev = lambda: torch.cuda.Event(enable_timing=True)
@@ -231,6 +237,7 @@ def main():
     K0d, V0d = to_dev(K0), to_dev(V0)
     del K0, V0
     first = {"score_window": [], "select": [], "match": [], "merge": []}
+    merge_first = {"match": [], "merge": [], "receivers": None}
     win_chunk = max(1, 128 // (Hq // H))          # queries per keepkv_score_window call
     for layer in range(R):
         # layers are token/batch rotations of the seeded prefill tensors: same statistics, distinct bytes
@@ -246,6 +253,24 @@ def main():
             j1 = min(w.window, j0 + win_chunk)
             kk.score_window(lay, big, q_win[:, :, j0:j1].contiguous() if (j0, j1) != (0, w.window) else q_win,
                             j1 - j0, alpha, -1)
+        if layer < 2 and N <= 16384:
+            # the merge-first prefill pass (App. B.4), timed on the same prefill cache; its output is not used
+            # further: the timed decode loop continues from the usual (evict-first) event below
+            if layer == 0:
+                mf_near = torch.zeros(B, H, N, dtype=torch.int32, device=dev)
+                mf_dst = kk.Cache(lay, N)
+            p = [ev() for _ in range(3)]
+            p[0].record()
+            kk.prefill_match(lay, big, T, mf_near, None, ws)
+            p[1].record()
+            kk.prefill_merge(lay, big, mf_dst, mf_near, alpha, ws)
+            p[2].record()
+            torch.cuda.synchronize()
+            merge_first["match"].append(p[0].elapsed_time(p[1]) * 1e3)
+            merge_first["merge"].append(p[1].elapsed_time(p[2]) * 1e3)
+            merge_first["receivers"] = float(mf_dst.len.float().mean().item())
+            if layer == 1:
+                del mf_near, mf_dst
         e[0].record()
         kk.select(lay, big, Bud, w.n_sink, w.n_recent, alpha, keep, evict_big, n_ev, ws)
         e[1].record()
@@ -547,7 +572,11 @@ def main():
                 "mfma_bf16_TFLOPs": round(flops_box[-1] / mfma_us / 1e6, 1),
                 "mfma_bf16_random_operands_TFLOPs": round(flops_box[-1] / mfma_rand_us / 1e6, 1)}
     ns_, per_, wv_ = kk.decode_plan(lay, cap)
-    if bf16:
+    if args.decode_wavefronts in (4, 8):
+        wv_ = args.decode_wavefronts
+    if bf16 and args.decode_wavefronts == -1:
+        kernel_instance = "decode_attn_kernel (vector ALU, bf16)"
+    elif bf16:
         kernel_instance = (f"decode_mfma_kernel<{D},{Hq // H},{'false' if args.unfused else 'true'},"
                            f"{'true' if per_ <= wv_ * 32 else 'false'},{wv_}>")
     else:
@@ -599,6 +628,11 @@ def main():
                               "frac_of_measured_mfma": round(match_first_tflops / measured["mfma_bf16_TFLOPs"], 4),
                               "frac_of_measured_mfma_random_operands":
                                   round(match_first_tflops / measured["mfma_bf16_random_operands_TFLOPs"], 4)},
+        "prefill_merge_first_pass": (None if not merge_first["match"] else {
+            "match_us": round(float(np.median(merge_first["match"])), 1),
+            "merge_us": round(float(np.median(merge_first["merge"])), 1),
+            "match_TFLOPs": round(B * H * N * (N - 1) * D / (float(np.median(merge_first["match"])) * 1e-6) / 1e12, 1),
+            "slots_left_per_head": round(merge_first["receivers"], 1), "threshold": T}),
         "measured_rates": measured,
         "score_window_prefill": {"bound": "hbm", "achieved": round(win_gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                                  "frac": round(win_gbs / HBM_PEAK_GBS, 4)},

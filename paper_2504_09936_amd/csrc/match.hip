@@ -1022,6 +1022,174 @@ __global__ void flag_all_causal_kernel(const int32_t* __restrict__ len, int32_t*
   }
 }
 
+// The f64 kernel for bf16 caches.  Products of bf16 values are exact in f64 and so are their sums over the head
+// dimension (for any ordinary exponent spread), whatever the order, so a key's channels may be split over lanes:
+// four lanes share a key, each holding a quarter of the channels of the evicted row in registers (as f64) and
+// loading the same quarter of the key, 64 keys per workgroup at a time and kExactBatch such rounds in flight.
+// One workgroup per queued row, or per share of a row's columns when the queue is short (joined by a ticket, as
+// in the generic kernel below).  The first event reads the retained keys from the gathered panel (no slot
+// list to wait for); otherwise the slot numbers of a whole batch are requested first, then their rows.
+constexpr int kExactBatch = 4;
+template <int D>
+__global__ __launch_bounds__(256) void match_exact_bf16_kernel(MatchParams p) {
+  constexpr int ROWB = D * 2, CHUNKS = ROWB / 16, CPL = CHUNKS / 4, EPL = CPL * 8;   // chunks / channels per lane
+  __shared__ double s_best[4];
+  __shared__ int s_bestc[4];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int quad = tid >> 2, sub = tid & 3;
+  const int n_flag = *p.flag_count;
+  const unsigned char* kall = reinterpret_cast<const unsigned char*>(p.k);
+  int parts = 1;
+  {
+    const int room = imin((int)gridDim.x, kExactResident);
+    while (parts < kExactMaxParts && (long)n_flag * (parts * 2) <= (long)room) parts *= 2;
+  }
+  for (int w = blockIdx.x; w < n_flag * parts; w += gridDim.x) {
+    const int f = w / parts, part = w % parts;
+    const int o = p.flag_rows[f];
+    const int unit = o / p.max_evict, j = o % p.max_evict;
+    const unsigned char* kunit = kall + (size_t)unit * p.capacity * ROWB;
+    const int32_t* keep = p.causal ? nullptr : p.keep_idx + (size_t)unit * p.budget;
+    const unsigned char* panel = (p.panel != nullptr && !p.causal) ? p.panel + (size_t)unit * p.rn_pitch * ROWB : nullptr;
+    const int n_cols = p.causal ? j : p.budget;
+    const int share = (n_cols + parts - 1) / parts;
+    const int c_lo = part * share, c_hi = imin(n_cols, c_lo + share);
+    // this lane's quarter of the evicted row (its slot number is one more round trip; the keys below do not wait for it)
+    const int e = p.causal ? j : p.evict_idx[(size_t)unit * p.max_evict + j];
+    uint4 ev[CPL];
+#pragma unroll
+    for (int q = 0; q < CPL; ++q) ev[q] = *reinterpret_cast<const uint4*>(kunit + (size_t)e * ROWB + (sub * CPL + q) * 16);
+    double ed[EPL];
+    double ss_e = 0.0;
+#pragma unroll
+    for (int q = 0; q < CPL; ++q) {
+      const uint32_t wv[4] = {ev[q].x, ev[q].y, ev[q].z, ev[q].w};
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        ed[q * 8 + 2 * i] = (double)bf16_lo(wv[i]);
+        ed[q * 8 + 2 * i + 1] = (double)bf16_hi(wv[i]);
+        ss_e = fma(ed[q * 8 + 2 * i], ed[q * 8 + 2 * i], ss_e);
+        ss_e = fma(ed[q * 8 + 2 * i + 1], ed[q * 8 + 2 * i + 1], ss_e);
+      }
+    }
+    ss_e += __shfl_xor(ss_e, 1);
+    ss_e += __shfl_xor(ss_e, 2);
+    const double rn_e = 1.0 / sqrt(ss_e);
+    double best = -INFINITY;
+    int best_c = 0x7FFFFFFF;
+    for (int c0 = c_lo; c0 < c_hi; c0 += 64 * kExactBatch) {
+      int slot[kExactBatch];
+      uint4 row[kExactBatch][CPL];
+      if (panel == nullptr) {
+#pragma unroll
+        for (int b = 0; b < kExactBatch; ++b) {
+          const int c = c0 + b * 64 + quad;
+          slot[b] = (c < c_hi) ? (p.causal ? c : keep[c]) : -1;
+        }
+      }
+#pragma unroll
+      for (int b = 0; b < kExactBatch; ++b) {
+        const int c = c0 + b * 64 + quad;
+        if (panel != nullptr) {                  // key c of the list, its chunk ch stored at position ch ^ (c mod CHUNKS)
+          slot[b] = c < c_hi ? c : -1;
+          const unsigned char* rp = panel + (size_t)imin(c, n_cols - 1) * ROWB;
+#pragma unroll
+          for (int q = 0; q < CPL; ++q)
+            row[b][q] = *reinterpret_cast<const uint4*>(rp + (((sub * CPL + q) ^ (imin(c, n_cols - 1) & (CHUNKS - 1))) * 16));
+        } else {
+          const unsigned char* rp = kunit + (size_t)imax(slot[b], 0) * ROWB + sub * CPL * 16;
+#pragma unroll
+          for (int q = 0; q < CPL; ++q) row[b][q] = *reinterpret_cast<const uint4*>(rp + q * 16);
+        }
+      }
+#pragma unroll
+      for (int b = 0; b < kExactBatch; ++b) {
+        double dot = 0.0, ss_c = 0.0;
+#pragma unroll
+        for (int q = 0; q < CPL; ++q) {
+          const uint32_t wv[4] = {row[b][q].x, row[b][q].y, row[b][q].z, row[b][q].w};
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            const double lo = (double)bf16_lo(wv[i]), hi = (double)bf16_hi(wv[i]);
+            dot = fma(ed[q * 8 + 2 * i], lo, dot);
+            ss_c = fma(lo, lo, ss_c);
+            dot = fma(ed[q * 8 + 2 * i + 1], hi, dot);
+            ss_c = fma(hi, hi, ss_c);
+          }
+        }
+        dot += __shfl_xor(dot, 1);
+        ss_c += __shfl_xor(ss_c, 1);
+        dot += __shfl_xor(dot, 2);
+        ss_c += __shfl_xor(ss_c, 2);
+        const double rn_c = 1.0 / sqrt(ss_c);
+        double u = (dot * rn_e) * rn_c;
+        if (!(fabs(u) <= 1.79e308)) u = -INFINITY;   // zero-norm keys (nan / inf) match nothing
+        const int c = c0 + b * 64 + quad;
+        if (slot[b] >= 0 && u > best) {              // ascending c per lane and strict: the first maximiser stays
+          best = u;
+          best_c = c;
+        }
+      }
+    }
+#pragma unroll
+    for (int off = 4; off < 64; off <<= 1) {         // (the four lanes of a quad hold the same pair)
+      const double ob = __shfl_xor(best, off);
+      const int oc = __shfl_xor(best_c, off);
+      if (ob > best || (ob == best && oc < best_c)) {
+        best = ob;
+        best_c = oc;
+      }
+    }
+    __syncthreads();                                 // the previous row's shared values are no longer read
+    if (lane == 0) {
+      s_best[wave] = best;
+      s_bestc[wave] = best_c;
+    }
+    __syncthreads();
+    if (tid == 0) {
+      for (int ww = 1; ww < 4; ++ww)
+        if (s_best[ww] > best || (s_best[ww] == best && s_bestc[ww] < best_c)) {
+          best = s_best[ww];
+          best_c = s_bestc[ww];
+        }
+      bool finish = parts == 1;
+      if (!finish) {
+        ExactPartial* mine = p.exact_partial + w;    // with parts > 1 every workgroup has at most one work item
+        __hip_atomic_store(&mine->best_bits, __builtin_bit_cast(unsigned long long, best), __ATOMIC_RELAXED,
+                           __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_store(&mine->best_c, best_c, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");                // the two write-through stores have completed
+        finish = __hip_atomic_fetch_add(&p.exact_ticket[f], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == parts - 1;
+        if (finish) {                                // the last share of this row: join them, in list order
+          best = -INFINITY;
+          best_c = 0x7FFFFFFF;
+          for (int q = 0; q < parts; ++q) {
+            const ExactPartial* r = p.exact_partial + f * parts + q;
+            const double rb = __builtin_bit_cast(double, __hip_atomic_load(&r->best_bits, __ATOMIC_RELAXED,
+                                                                           __HIP_MEMORY_SCOPE_AGENT));
+            const int rc = __hip_atomic_load(&r->best_c, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (rb > best) {
+              best = rb;
+              best_c = rc;
+            }
+          }
+          __hip_atomic_store(&p.exact_ticket[f], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // ready for the next call
+        }
+      }
+      if (finish) {
+        p.match[o] = (best > (double)p.threshold) ? best_c : -1;
+        if (p.sim_out != nullptr) p.sim_out[o] = (float)best;
+      }
+    }
+  }
+  __syncthreads();
+  if (tid == 0 &&
+      __hip_atomic_fetch_add(p.exact_done, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == (int)gridDim.x - 1) {
+    __hip_atomic_store(p.flag_count, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __hip_atomic_store(p.exact_done, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  }
+}
+
 template <int D>
 constexpr size_t mfma_smem_bytes() {
   return 2 * (size_t)kStageCols * (D * 2) + 2 * kStageCols * sizeof(float);
@@ -1142,12 +1310,12 @@ extern "C" keepkv_status keepkv_prefill_match(const keepkv_layout* layout, const
       slot_rnorm_kernel<uint16_t, 128><<<ngrid, 256, 0, st>>>((const uint16_t*)cache->k, cache->len,
                                                             const_cast<float*>(p.rnorm), cap);
       prefill_near_kernel<128><<<pgrid, kPfWaves * kWave, 0, st>>>(p);
-      match_exact_kernel<uint16_t, 128><<<exact_blocks, 256, 0, st>>>(p);
+      match_exact_bf16_kernel<128><<<exact_blocks, 256, 0, st>>>(p);
     } else {
       slot_rnorm_kernel<uint16_t, 64><<<ngrid, 256, 0, st>>>((const uint16_t*)cache->k, cache->len,
                                                            const_cast<float*>(p.rnorm), cap);
       prefill_near_kernel<64><<<pgrid, kPfWaves * kWave, 0, st>>>(p);
-      match_exact_kernel<uint16_t, 64><<<exact_blocks, 256, 0, st>>>(p);
+      match_exact_bf16_kernel<64><<<exact_blocks, 256, 0, st>>>(p);
     }
   } else {
     int bx = (cap + 255) / 256;
@@ -1205,16 +1373,17 @@ extern "C" keepkv_status keepkv_match(const keepkv_layout* layout, const keepkv_
   p.rn_pitch = rn_pitch_of(budget);
   long eb = (long)units * max_evict / 16;      // queued rows are a small fraction of all rows
   const int exact_blocks = (int)(eb < 64 ? 64 : (eb > 512 ? 512 : eb));   // every workgroup ends with one add to a shared counter
+  if (max_evict <= kSmallMaxEvict || layout->dtype != KEEPKV_BF16) p.panel = nullptr;   // only the first event's path gathers it
   if (layout->dtype == KEEPKV_BF16) {
     keepkv_status rc;
     if (layout->head_dim == 128) {
       rc = launch_bf16<128>(p, cache->k, (unsigned)units, st);
       if (rc != KEEPKV_OK) return rc;
-      match_exact_kernel<uint16_t, 128><<<exact_blocks, 256, 0, st>>>(p);
+      match_exact_bf16_kernel<128><<<exact_blocks, 256, 0, st>>>(p);
     } else {
       rc = launch_bf16<64>(p, cache->k, (unsigned)units, st);
       if (rc != KEEPKV_OK) return rc;
-      match_exact_kernel<uint16_t, 64><<<exact_blocks, 256, 0, st>>>(p);
+      match_exact_bf16_kernel<64><<<exact_blocks, 256, 0, st>>>(p);
     }
   } else {
     int bx = (max_evict + 255) / 256;
