@@ -245,7 +245,7 @@ def main():
         big.v.copy_(torch.roll(V0d, shifts=(layer, 257 * layer), dims=(0, 2)))
         if w.query_model == "mean":
             big.k[:, :, 0] = K0d[:, :, 0]
-        big.votes.fill_(1); big.log_s.fill_(float("-inf")); big.n_obs.zero_(); big.len.fill_(N)
+        big.votes.fill_(1); big.log_s.fill_(float("-inf")); big.born.zero_(); big.t_obs.zero_(); big.len.fill_(N)
         # observation window (Eq. 8, t = L): all window queries in one pass over the keys
         q_win = to_dev(np.stack([W.make_query(w, layer, t - w.window) for t in range(w.window)], axis=2))
         e = [ev() for _ in range(4)]
@@ -414,7 +414,7 @@ def main():
         # Every replay must run the K steps (and events) that were captured, on the state they were captured
         # for: appending the same tokens to a cache that already holds them would feed the events exact
         # duplicates.  The caches of all layers are put back before each replay (outside the timed region).
-        fields = ("k", "v", "votes", "log_s", "n_obs", "len")
+        fields = ("k", "v", "votes", "log_s", "born", "t_obs", "len")
         state_at_capture = [[{f_: getattr(c, f_).clone() for f_ in fields} for c in pair] for pair in caches]
         dropped_at_capture = dropped.clone()
         graph = torch.cuda.CUDAGraph()
@@ -529,9 +529,13 @@ def main():
     slots = B * H * live_mean
 
     # algorithmic bytes of one launch.  Per live slot: K and V rows and votes (4 B); the unfused attention
-    # call also writes the logit that feeds the EMA (4 B), the fused step instead reads and writes the EMA
-    # state in place (ln S and n: 16 B) and keeps the logit on chip.  Plus Q in and O out.
+    # call also writes the logit that feeds the EMA (4 B), the fused step instead updates the EMA state in
+    # place and keeps the logit on chip: ln S read and written (8 B) and the slot's observation count read and
+    # written (8 B).  Plus Q in and O out.  This library keeps the count as (head's step counter - slot's
+    # origin) and so moves no per-slot count in a decode step: `bytes_moved_per_launch` is the same sum without
+    # those 8 B; `frac` stays on the algorithmic figure, `frac_of_moved_bytes` is the other one.
     dec_bytes = slots * (2 * D * esz + 4 + (4 if args.unfused else 16)) + 2 * B * Hq * D * esz
+    dec_bytes_moved = slots * (2 * D * esz + 4 + (4 if args.unfused else 8)) + 2 * B * Hq * D * esz
     achieved = dec_bytes / (dec_us * 1e-6) / 1e9
 
     # what the GPU sustains on plain work of the same size (one launch reading a buffer as large as the decode
@@ -584,13 +588,14 @@ def main():
     traffic = traffic_from_profile(w.name, kernel_instance)
     roofline = {"bound": "hbm", "kernel": kernel_instance, "achieved": round(achieved, 1),
                 "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
-                "traffic": traffic, "bytes_per_launch": int(dec_bytes),
+                "traffic": traffic, "bytes_per_launch": int(dec_bytes), "bytes_moved_per_launch": int(dec_bytes_moved),
+                "frac_of_moved_bytes": round(dec_bytes_moved / (dec_us * 1e-6) / 1e9 / HBM_PEAK_GBS, 4),
                 "avg_launch_us": round(dec_us, 2),
                 "frac_of_measured_read": round(achieved / measured["read_decode_working_set_GBps"], 4)}
 
     M1 = N - Bud
     match_first_us = float(np.median(first["match"]))
-    # window pass: keys read once, (log_s, n_obs) read and written, per slot of the uncompressed cache
+    # window pass: keys read once, log_s read and written, per slot of the uncompressed cache
     win_bytes = B * H * N * (D * (2 if w.dtype == "bf16" else 4) + 16) * len(range(0, w.window, win_chunk))
     win_gbs = win_bytes / (float(np.median(first["score_window"])) * 1e-6) / 1e9
     match_first_tflops = 2.0 * M1 * Bud * D * B * H / (match_first_us * 1e-6) / 1e12

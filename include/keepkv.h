@@ -21,8 +21,9 @@
  *  - Storage dtype of Q, K, V, O is f32 or bf16; all accumulation is f32 (f64 where an
  *    integer decision or a merge weight depends on it).
  *  - Scores are natural logarithms: log_s holds ln S_i of Eq. 8 (uncorrected EMA of the
- *    unnormalised score s_i = exp(q.k_i/sqrt(d)) of Eq. 3), -inf while n_obs == 0.
- *    The bias-corrected score is ln s_hat_i = log_s_i - ln(1 - alpha^n_obs_i).
+ *    unnormalised score s_i = exp(q.k_i/sqrt(d)) of Eq. 3), -inf while the slot has no observation.
+ *    The bias-corrected score is ln s_hat_i = log_s_i - ln(1 - alpha^n_i), n_i the slot's
+ *    observation count (keepkv_cache.born / t_obs).
  */
 #ifndef KEEPKV_H
 #define KEEPKV_H
@@ -59,7 +60,15 @@ typedef struct {
   void    *k, *v;       /* [B, Hkv, capacity, D] storage dtype                        */
   int32_t *votes;       /* [B, Hkv, capacity]  p_i >= 1 on live slots (Sec. 3.3.1)     */
   float   *log_s;       /* [B, Hkv, capacity]  ln S_i (Eq. 8), -inf if never observed  */
-  int32_t *n_obs;       /* [B, Hkv, capacity]  observations folded into S_i           */
+  int32_t *born;        /* [B, Hkv, capacity]  origin of the slot's score history: the  */
+                        /* number of observations folded into S_i (the count of Eq. 8's  */
+                        /* bias correction) is n_i = t_obs[b,h] - born[b,h,i]            */
+  int32_t *t_obs;       /* [B, Hkv]            observation steps this head has seen: +1  */
+                        /* per keepkv_score / keepkv_decode_step, +window per             */
+                        /* keepkv_score_window.  Every live slot is observed at every     */
+                        /* step, so a step advances all counts through this one word and  */
+                        /* the per-slot array is written only when a slot is created,     */
+                        /* merged, or seen by part of a causal window                     */
   int32_t *len;         /* [B, Hkv]            live slots, 0 <= len <= capacity        */
   int32_t  capacity;    /* slots allocated per (b, h); 1 <= capacity <= 2^20           */
   int32_t  len_hint;    /* optional: an upper bound on every len[b,h] known to the host */
@@ -104,7 +113,7 @@ keepkv_status keepkv_decode_plan(const keepkv_layout *layout, int32_t capacity, 
 keepkv_status keepkv_workspace_init(void *workspace, size_t workspace_bytes, void *stream);
 
 /* Append one token per (b, h): k_t, v_t [B, Hkv, D] DEVICE are written to slot len[b,h],
- * with votes = 1, log_s = -inf, n_obs = 0, then len[b,h] += 1 (Sec. 3.1 cache update;
+ * with votes = 1, log_s = -inf, born = t_obs[b,h] (no observation yet), then len[b,h] += 1 (Sec. 3.1 cache update;
  * votes initialised to 1, Sec. 3.3.1).  A head already at capacity is left unchanged and
  * `overflow` (DEVICE int32, may be NULL) is set to 1. */
 keepkv_status keepkv_append(const keepkv_layout *layout, keepkv_cache *cache,
@@ -151,7 +160,7 @@ keepkv_status keepkv_decode_step_static(const keepkv_layout *layout, keepkv_cach
                                         void *stream);
 
 /* EMA score update (Eq. 8, t > L branch; Alg. 1 line 6) on the live slots:
- *     S_i <- alpha S_i + (1 - alpha) exp(logits[i]),  n_obs_i += 1
+ *     S_i <- alpha S_i + (1 - alpha) exp(logits[i]),  n_i += 1  (t_obs[b,h] += 1)
  * held as log_s_i = ln S_i.  logits: DEVICE f32 [B, Hkv, capacity] as written by
  * keepkv_decode_attn.  0 <= alpha < 1.  Running it w+1 times from the empty state over the
  * prefill cache yields the t = L window sum of Eq. 8. */
@@ -164,9 +173,9 @@ keepkv_status keepkv_score(const keepkv_layout *layout, keepkv_cache *cache,
  * slot i (as in keepkv_decode_attn), every live slot seen by the last n_i queries of the window
  * gets
  *     S_i <- alpha^{n_i} S_i + sum_{j >= window - n_i} (1 - alpha) alpha^{window-1-j} s_{j,i},
- *     n_obs_i += n_i
+ *     the slot's count += n_i  (t_obs[b,h] += window; born_i += window - n_i where n_i < window)
  * i.e. the result of `window` consecutive keepkv_score calls; on a fresh cache (log_s = -inf,
- * n_obs = 0) this is the window sum of Eq. 8.  first_pos < 0: every query sees every live
+ * no observation) this is the window sum of Eq. 8.  first_pos < 0: every query sees every live
  * slot (n_i = window).  first_pos >= 0: query j sits at sequence position first_pos + j and
  * sees only slots i <= first_pos + j (causal prefill; first_pos = len - window for the last
  * `window` prompt tokens).  bf16 caches use bf16 MFMA with f32 accumulation.  Requires
@@ -216,7 +225,7 @@ keepkv_status keepkv_match(const keepkv_layout *layout, const keepkv_cache *cach
  * A.4 form; Alg. 1 lines 7-11).  For retained position r with group g = {keep_idx[r]} +
  * {evict_idx[j] : match[j] = r}, w_i = p_i s_hat_i, W = sum w, P = sum p:
  *     v_r = sum w_i v_i / W,   k_r = (sum w_i k_i / W) * ln(W/P) / (sum w_i ln s_hat_i / W),
- *     p_r = P,   ln s_hat_r = ln(W/P),   n_r = max(n_obs of the retained slot, 1).
+ *     p_r = P,   ln s_hat_r = ln(W/P),   n_r = max(count of the retained slot, 1);  dst.t_obs = src.t_obs.
  * When |sum w_i ln s_hat_i / W| < 1e-3 the key scale is taken as 1.  Unmatched evicted
  * slots are dropped and their votes added to dropped_votes[b,h] (DEVICE int64, accumulated,
  * may be NULL).  Results are written to dst slots 0..budget-1 in keep_idx order and

@@ -33,7 +33,7 @@ class _Layout(C.Structure):
 
 class _Cache(C.Structure):
     _fields_ = [("k", C.c_void_p), ("v", C.c_void_p), ("votes", C.c_void_p), ("log_s", C.c_void_p),
-                ("n_obs", C.c_void_p), ("len", C.c_void_p), ("capacity", C.c_int32), ("len_hint", C.c_int32),
+                ("born", C.c_void_p), ("t_obs", C.c_void_p), ("len", C.c_void_p), ("capacity", C.c_int32), ("len_hint", C.c_int32),
                 ("plan_slots_per_split", C.c_int32), ("plan_wavefronts", C.c_int32)]
 
 
@@ -126,12 +126,13 @@ class Cache:
         self.v = torch.zeros(B, H, capacity, D, dtype=layout.torch_dtype, device=device)
         self.votes = torch.zeros(B, H, capacity, dtype=torch.int32, device=device)
         self.log_s = torch.full((B, H, capacity), float("-inf"), dtype=torch.float32, device=device)
-        self.n_obs = torch.zeros(B, H, capacity, dtype=torch.int32, device=device)
+        self.born = torch.zeros(B, H, capacity, dtype=torch.int32, device=device)
+        self.t_obs = torch.zeros(B, H, dtype=torch.int32, device=device)
         self.len = torch.zeros(B, H, dtype=torch.int32, device=device)
 
     def c(self) -> _Cache:
         return _Cache(self.k.data_ptr(), self.v.data_ptr(), self.votes.data_ptr(), self.log_s.data_ptr(),
-                      self.n_obs.data_ptr(), self.len.data_ptr(), self.capacity, int(self.len_hint),
+                      self.born.data_ptr(), self.t_obs.data_ptr(), self.len.data_ptr(), self.capacity, int(self.len_hint),
                       int(self.plan_slots_per_split), int(self.plan_wavefronts))
 
 

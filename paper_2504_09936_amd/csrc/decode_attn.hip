@@ -37,7 +37,8 @@ struct DecodeParams {
   void* v;
   int32_t* votes;
   float* log_s;       // step mode / score fusion
-  int32_t* n_obs;
+  int32_t* born;      // step mode: the new slot's origin (a slot's observation count is t_obs - born)
+  int32_t* t_obs;     // step mode: [B * Hkv] steps observed by the head, += 1 per step
   int32_t* len;
   const void* k_t;    // step mode: [B, Hkv, D] new token, else null
   const void* v_t;
@@ -76,7 +77,7 @@ __device__ __forceinline__ float ld_agent(const float* p) {
 template <typename T, int D, int G, int kParts, bool STEP, int WAVES>
 __device__ __forceinline__ void combine_and_finish(const DecodeParams& p, const float* s_m, const float* s_l,
                                                    const float* s_acc, int* s_last_p, int unit, int split, bool grow,
-                                                   int len) {
+                                                   int len, int t_old) {
   constexpr bool kBf16 = sizeof(T) == 2;
   int& s_last = *s_last_p;
   auto finish = [&](size_t row, int d, float M, float L, float A) {
@@ -116,6 +117,7 @@ __device__ __forceinline__ void combine_and_finish(const DecodeParams& p, const 
   }
 
   if (p.nsplit == 1) {
+    if (STEP && threadIdx.x == 0) p.t_obs[unit] = t_old + 1;   // one more observation of every slot of the head
     if (STEP && threadIdx.x == 0 && grow) p.len[unit] = len;   // every wavefront read len before the barrier above
     if (STEP && threadIdx.x == 0 && !grow && p.overflow != nullptr) *p.overflow = 1;
     return;
@@ -193,6 +195,7 @@ __device__ __forceinline__ void combine_and_finish(const DecodeParams& p, const 
   KK_TS(5);
   if (threadIdx.x == 0) {
     __hip_atomic_store(&p.ticket[unit], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // ready for the next launch
+    if (STEP) p.t_obs[unit] = t_old + 1;             // (every workgroup of the head read it before taking its ticket)
     if (STEP && grow) p.len[unit] = len;
     if (STEP && !grow && p.overflow != nullptr) *p.overflow = 1;
   }
@@ -223,6 +226,7 @@ __global__ __launch_bounds__(kWavesPerBlock* kWave) void decode_attn_kernel(Deco
   const int grp = lane / LPS, sub = lane % LPS;
   KK_TS(0);
   const int len_old = p.len[unit];          // needed only once the row loads are in flight (see `bound`)
+  const int t_old = STEP ? p.t_obs[unit] : 0;   // used at the very end only
   // step mode: the new token becomes slot len_old (unless the head is full); it is attended as one
   // extra slot after the cache slots, so the streaming loop below never depends on it
   const int start = split * p.per;
@@ -294,12 +298,7 @@ __global__ __launch_bounds__(kWavesPerBlock* kWave) void decode_attn_kernel(Deco
     // EMA state of the slot this lane will update (lane `sub` < kUnroll owns slot s0 + sub)
     const int s_mine = s0 + (extra ? 0 : sub);
     float ls_old = -INFINITY;
-    int no_old = 0;
-    if (STEP && !extra) {
-      const int sc = min(s_mine, bound - 1);
-      ls_old = p.log_s[ubase + sc];
-      no_old = p.n_obs[ubase + sc];
-    }
+    if (STEP && !extra) ls_old = p.log_s[ubase + min(s_mine, bound - 1)];
     // ---- first use of len: everything above was issued without waiting for it
     const int live_end = min(len_old, start + p.per);
 #pragma unroll
@@ -356,14 +355,11 @@ __global__ __launch_bounds__(kWavesPerBlock* kWave) void decode_attn_kernel(Deco
       const bool mine = extra ? (grp == 0 && sub == 0) : (sub < kUnroll && s_mine < live_end);
       if (p.logits_out != nullptr && mine) p.logits_out[ubase + s_mine] = x;
       if constexpr (STEP) {
-        // log_s <- ln(alpha S + (1 - alpha) e^x), n_obs += 1  (Eq. 8)
+        // log_s <- ln(alpha S + (1 - alpha) e^x)  (Eq. 8); the count advances with the head's t_obs
         const float a = p.ln_alpha + ls_old, b = p.ln_1m_alpha + x;
         const float hi = fmaxf(a, b), lo = fminf(a, b);
         const float r = (lo == -INFINITY) ? hi : hi + log1pf(expf(lo - hi));
-        if (mine) {
-          p.log_s[ubase + s_mine] = r;
-          p.n_obs[ubase + s_mine] = no_old + 1;
-        }
+        if (mine) p.log_s[ubase + s_mine] = r;
       }
     }
     if (STEP && extra && grp == 0) {
@@ -373,7 +369,10 @@ __global__ __launch_bounds__(kWavesPerBlock* kWave) void decode_attn_kernel(Deco
         kbase[(size_t)len_old * RV + v * LPS] = kk_[0][v];
         vbase[(size_t)len_old * RV + v * LPS] = vv_[0][v];
       }
-      if (sub == 0) p.votes[ubase + len_old] = 1;
+      if (sub == 0) {
+        p.votes[ubase + len_old] = 1;
+        p.born[ubase + len_old] = t_old;          // first observed in this step
+      }
     }
 
     // online softmax update for this group's kUnroll slots
@@ -480,7 +479,7 @@ __global__ __launch_bounds__(kWavesPerBlock* kWave) void decode_attn_kernel(Deco
   __syncthreads();
   KK_TS(2);
 
-  combine_and_finish<T, D, G, kParts, STEP, kWavesPerBlock>(p, s_m, s_l, s_acc, &s_last, unit, split, grow, len);
+  combine_and_finish<T, D, G, kParts, STEP, kWavesPerBlock>(p, s_m, s_l, s_acc, &s_last, unit, split, grow, len, t_old);
 }
 
 // ---------------------------------------------------------------------------------------------------
@@ -503,7 +502,8 @@ constexpr int kMTile = 32;
 // beside it cost 1 us instead of 12).
 constexpr int kStreamOnce = 2;
 // Per wavefront, behind the tile buffers: the head group's query rows (whole 1 KB pieces, one asynchronous
-// 16-byte copy per lane each) and the tile's votes, ln S and observation counts (4 bytes per lane each).
+// 16-byte copy per lane each) and the tile's votes and ln S (4 bytes per lane each); the tile loop stages its
+// updated ln S here instead.
 constexpr int mfma_stage_bytes(int D, int G) { return (G * D * 2 + 1023) / 1024 * 1024 + 3 * 256; }
 
 // LDS reads that the compiler does not see as such.  It orders an LDS read that it cannot tell apart from an
@@ -556,6 +556,7 @@ __global__ __launch_bounds__(kMfmaWaves* kWave, 2) void decode_mfma_kernel(Decod
   const int l16 = lane & 15, q = lane >> 4;
   KK_TS(0);
   const int len_old = p.len[unit];
+  const int t_old = STEP ? p.t_obs[unit] : 0;   // used at the very end only
   const int start = split * p.per;
   const bool takes_new = STEP && split == p.nsplit - 1 && wave == kMfmaWaves - 1;
   if (takes_new && lane < 2 * CHUNKS) {        // asynchronous copy of (k_t, v_t) into LDS, awaited after the loop
@@ -581,7 +582,7 @@ __global__ __launch_bounds__(kMfmaWaves* kWave, 2) void decode_mfma_kernel(Decod
   // compiler wait for everything at their first use.)
   constexpr int Q_PIECES = (G * ROWB + 1023) / 1024;
   unsigned char* s_q = smem_raw + kMfmaWaves * 2 * TILE_BYTES + wave * mfma_stage_bytes(D, G);
-  unsigned char* s_sc = s_q + Q_PIECES * 1024;                  // [votes | ln S | n_obs][64] 4-byte words
+  unsigned char* s_sc = s_q + Q_PIECES * 1024;                  // [votes | ln S][64] 4-byte words
   if constexpr (ONE) {
     const unsigned char* qbase = reinterpret_cast<const unsigned char*>(p.q) + (size_t)unit * G * ROWB;
 #pragma unroll
@@ -624,12 +625,9 @@ __global__ __launch_bounds__(kMfmaWaves* kWave, 2) void decode_mfma_kernel(Decod
       const size_t at = ubase + min(base + lane, bound - 1);
       __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(p.votes + at),
                                        (__attribute__((address_space(3))) void*)s_sc, 4, 0, 0);
-      if constexpr (STEP) {
+      if constexpr (STEP)
         __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(p.log_s + at),
                                          (__attribute__((address_space(3))) void*)(s_sc + 256), 4, 0, 0);
-        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(p.n_obs + at),
-                                         (__attribute__((address_space(3))) void*)(s_sc + 512), 4, 0, 0);
-      }
     }
     issue_rows(vbytes, Vb, base);
   }
@@ -637,14 +635,9 @@ __global__ __launch_bounds__(kMfmaWaves* kWave, 2) void decode_mfma_kernel(Decod
   // are first used behind the loop's full wait)
   int pv_next = 1;      // votes of slot tbase + lane mod 32; log2 is taken once per slot and handed round by lane shuffles
   float ls_next = -INFINITY;
-  int no_next = 0;
   auto request_scalars = [&](int tbase) {
     pv_next = p.votes[ubase + min(tbase + (lane & 31), bound - 1)];
-    if constexpr (STEP) {
-      const size_t at = ubase + min(tbase + 16 * (l16 >> 2) + 4 * q + (l16 & 3), bound - 1);
-      ls_next = p.log_s[at];
-      no_next = p.n_obs[at];
-    }
+    if constexpr (STEP) ls_next = p.log_s[ubase + min(tbase + 16 * (l16 >> 2) + 4 * q + (l16 & 3), bound - 1)];
   };
   if constexpr (!ONE) {
     if (base < lim) request_scalars(base);
@@ -668,7 +661,7 @@ __global__ __launch_bounds__(kMfmaWaves* kWave, 2) void decode_mfma_kernel(Decod
   // are done, when it fits: many small stores spread over the streaming phase slow the row stream down more
   // than their bytes account for, one burst per workgroup less so.
   unsigned char* const s_stage = smem_raw + kMfmaWaves * 2 * TILE_BYTES;
-  const bool staged = !ONE && STEP && (size_t)p.per * 8 <= (size_t)kMfmaWaves * mfma_stage_bytes(D, G);
+  const bool staged = !ONE && STEP && (size_t)p.per * 4 <= (size_t)kMfmaWaves * mfma_stage_bytes(D, G);
   const float sl2 = p.scale * kLog2e;
   float m_run = -INFINITY, l_run = 0.f;
   f32x4_t O[NTILE];
@@ -681,7 +674,7 @@ __global__ __launch_bounds__(kMfmaWaves* kWave, 2) void decode_mfma_kernel(Decod
   // `next`: the wavefront's next tile (or -1); its K rows are requested as soon as the score product has
   // consumed the K buffer, its V rows after the second product, so both travel during the arithmetic.
   // `v_in_flight`: the V rows are still outstanding when the call starts (ONE, the wavefront's own tile).
-  auto compute = [&](int tbase, bool extra, int next, const float (&lp)[2][4], float ls_old, int no_old,
+  auto compute = [&](int tbase, bool extra, int next, const float (&lp)[2][4], float ls_old,
                      bool v_in_flight) {
     const int n_live = extra ? 1 : max(0, min(kMTile, live_end - tbase));
     auto clear_masked_v = [&]() {
@@ -880,12 +873,10 @@ __global__ __launch_bounds__(kMfmaWaves* kWave, 2) void decode_mfma_kernel(Decod
             // (a statement the compiler does not see as an LDS store: it would order one behind the next
             // tile's outstanding copies into LDS)
             const uint32_t sa = (uint32_t)(uintptr_t)(const __attribute__((address_space(3))) void*)(
-                s_stage + (size_t)(tbase - start + row_mine) * 8);
-            const float2 rn = make_float2(r, __builtin_bit_cast(float, no_old + 1));
-            asm volatile("ds_write_b64 %0, %1" : : "v"(sa), "v"(rn) : "memory");
+                s_stage + (size_t)(tbase - start + row_mine) * 4);
+            asm volatile("ds_write_b32 %0, %1" : : "v"(sa), "v"(r) : "memory");
           } else {
             p.log_s[at] = r;
-            p.n_obs[at] = no_old + 1;
           }
         }
       }
@@ -895,7 +886,6 @@ __global__ __launch_bounds__(kMfmaWaves* kWave, 2) void decode_mfma_kernel(Decod
   while (base < lim) {                           // a single pass with ONE
     float lp[2][4];                                // log2(votes) of the slots whose logits this lane holds
     float ls_old = -INFINITY;
-    int no_old = 0;
     if constexpr (ONE) {
       // all copies but the youngest LOADS (the V rows) have landed: query rows, K rows, votes and EMA state
       asm volatile("s_waitcnt vmcnt(%0)" ::"n"(LOADS) : "memory");
@@ -909,9 +899,8 @@ __global__ __launch_bounds__(kMfmaWaves* kWave, 2) void decode_mfma_kernel(Decod
       if constexpr (STEP) {
         const int mine = 16 * (l16 >> 2) + 4 * q + (l16 & 3);
         ls_old = __builtin_bit_cast(float, lds_read_b32_awaited(s_sc + 256 + mine * 4));
-        no_old = lds_read_b32_awaited(s_sc + 512 + mine * 4);
       }
-      compute(base, false, -1, lp, ls_old, no_old, true);
+      compute(base, false, -1, lp, ls_old, true);
       base = lim;
     } else {
       // the tile's K rows (registers), V rows (LDS) and scalars have landed; the K registers pass through the
@@ -937,9 +926,8 @@ __global__ __launch_bounds__(kMfmaWaves* kWave, 2) void decode_mfma_kernel(Decod
           for (int i = 0; i < 4; ++i) lp[st][i] = __shfl(lp_lane, 16 * st + 4 * q + i);
       }
       ls_old = ls_next;
-      no_old = no_next;
       const int next = base + kMfmaWaves * kMTile;
-      compute(base, false, next < lim ? next : -1, lp, ls_old, no_old, false);
+      compute(base, false, next < lim ? next : -1, lp, ls_old, false);
       Vb = Tb + (Vb == Tb ? TILE_BYTES : 0);
       base = next;
     }
@@ -968,11 +956,14 @@ __global__ __launch_bounds__(kMfmaWaves* kWave, 2) void decode_mfma_kernel(Decod
         unsigned char* dst = reinterpret_cast<unsigned char*>(lane < CHUNKS ? p.k : p.v) + (ubase + len_old) * ROWB;
         *reinterpret_cast<uint4*>(dst + (lane % CHUNKS) * 16) = x;
       }
-      if (lane == 0) p.votes[ubase + len_old] = 1;
+      if (lane == 0) {
+        p.votes[ubase + len_old] = 1;
+        p.born[ubase + len_old] = t_old;          // first observed in this step
+      }
       __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
       __builtin_amdgcn_wave_barrier();
       const float one[2][4] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};   // one vote: log2 = 0
-      compute(0, true, -1, one, -INFINITY, 0, false);
+      compute(0, true, -1, one, -INFINITY, false);
     }
   }
 
@@ -984,11 +975,9 @@ __global__ __launch_bounds__(kMfmaWaves* kWave, 2) void decode_mfma_kernel(Decod
   if constexpr (!ONE && STEP) {
     if (staged) {                                // the split's updated EMA state, slot by slot
       for (int j = threadIdx.x; j < live_end - start; j += kMfmaWaves * kWave) {
-        const float2 rn = *reinterpret_cast<const float2*>(s_stage + (size_t)j * 8);
-        // (write-through: measured 1.3 us faster at batch 128 than leaving 7 MB of dirty lines to the caches)
-        __hip_atomic_store(&p.log_s[ubase + start + j], rn.x, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        __hip_atomic_store(&p.n_obs[ubase + start + j], __builtin_bit_cast(int, rn.y), __ATOMIC_RELAXED,
-                           __HIP_MEMORY_SCOPE_AGENT);
+        // (write-through: measured faster at batch 128 than leaving megabytes of dirty lines to the caches)
+        __hip_atomic_store(&p.log_s[ubase + start + j], *reinterpret_cast<const float*>(s_stage + (size_t)j * 4),
+                           __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       }
     }
   }
@@ -1009,7 +998,7 @@ __global__ __launch_bounds__(kMfmaWaves* kWave, 2) void decode_mfma_kernel(Decod
   }
   __syncthreads();
   KK_TS(2);
-  combine_and_finish<T, D, G, kParts, STEP, kMfmaWaves>(p, s_m, s_l, s_acc, &s_last, unit, split, grow, len);
+  combine_and_finish<T, D, G, kParts, STEP, kMfmaWaves>(p, s_m, s_l, s_acc, &s_last, unit, split, grow, len, t_old);
 }
 
 template <typename T, int D, int G>
@@ -1090,7 +1079,7 @@ keepkv_status run_decode(const keepkv_layout* layout, const keepkv_cache* cache,
   if (pl.nsplit > 1 && (!workspace || workspace_bytes < pl.bytes || !aligned16(workspace))) return KEEPKV_ERR_WORKSPACE;
 
   DecodeParams p;
-  p.q = q; p.k = cache->k; p.v = cache->v; p.votes = cache->votes; p.log_s = cache->log_s; p.n_obs = cache->n_obs;
+  p.q = q; p.k = cache->k; p.v = cache->v; p.votes = cache->votes; p.log_s = cache->log_s; p.born = cache->born; p.t_obs = cache->t_obs;
   p.len = cache->len; p.k_t = k_t; p.v_t = v_t; p.overflow = overflow;
   p.out = out; p.logits_out = logits_out; p.lse_out = lse_out;
   p.partial = reinterpret_cast<float*>(reinterpret_cast<char*>(workspace) + pl.partial_off);

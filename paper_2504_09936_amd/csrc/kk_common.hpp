@@ -79,7 +79,7 @@ inline bool layout_supported(const keepkv_layout* L) {
   return g == 1 || g == 2 || g == 4 || g == 8;
 }
 inline bool cache_ok(const keepkv_cache* c) {
-  return c && c->k && c->v && c->votes && c->log_s && c->n_obs && c->len && c->capacity >= 1 &&
+  return c && c->k && c->v && c->votes && c->log_s && c->born && c->t_obs && c->len && c->capacity >= 1 &&
          c->capacity <= (1 << 20);
 }
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }

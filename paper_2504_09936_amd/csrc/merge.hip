@@ -224,12 +224,14 @@ struct MergeParams {
   const void *sk, *sv;
   const int32_t* svotes;
   const float* slog_s;
-  const int32_t* sn_obs;
+  const int32_t* sborn;        // a slot's observation count is t_obs - born
+  const int32_t* st_obs;       // [units]
   const int32_t* slen;
   void *dk, *dv;
   int32_t* dvotes;
   float* dlog_s;
-  int32_t* dn_obs;
+  int32_t* dborn;
+  int32_t* dt_obs;             // receives st_obs
   int32_t* dlen;
   const int32_t* keep_idx;
   const int32_t* n_evict;
@@ -281,9 +283,13 @@ __global__ __launch_bounds__(256) void merge_apply_kernel(MergeParams p) {
   const int sub = threadIdx.x % LPS;
   const int lane = threadIdx.x & 63;
   const int gbase = lane - sub;                 // first lane of this group within the wavefront
-  if (blockIdx.x == 0 && threadIdx.x == 0 && p.write_len) {
-    const int n = p.slen[unit];
-    p.dlen[unit] = n < p.budget ? n : p.budget;
+  const int t_head = p.st_obs[unit];            // the head's step counter: unchanged by a merge
+  if (blockIdx.x == 0 && threadIdx.x == 0) {
+    p.dt_obs[unit] = t_head;
+    if (p.write_len) {
+      const int n = p.slen[unit];
+      p.dlen[unit] = n < p.budget ? n : p.budget;
+    }
   }
   const size_t sbase = (size_t)unit * p.scap, dbase = (size_t)unit * p.dcap;
   const uint4* sk = reinterpret_cast<const uint4*>(p.sk);
@@ -302,7 +308,7 @@ __global__ __launch_bounds__(256) void merge_apply_kernel(MergeParams p) {
     vc = sv[at * LPS + sub];
     p_c = p.svotes[at];
     ls_c = p.slog_s[at];
-    n_c = p.sn_obs[at];
+    n_c = t_head - p.sborn[at];
   };
   if constexpr (DIRECT) {
     n_ev = min(p.n_evict[unit], kDirectMaxEvict);
@@ -362,7 +368,7 @@ __global__ __launch_bounds__(256) void merge_apply_kernel(MergeParams p) {
     if (sub == 0) {
       p.dvotes[dbase + r] = p_c;
       p.dlog_s[dbase + r] = ls_c;
-      p.dn_obs[dbase + r] = n_c;
+      p.dborn[dbase + r] = t_head - n_c;
     }
     return;
   }
@@ -380,7 +386,7 @@ __global__ __launch_bounds__(256) void merge_apply_kernel(MergeParams p) {
     if (i < nm) {
       const int s = mem[i];
       pv = p.svotes[sbase + s];
-      E = log_s_hat(p.slog_s[sbase + s], p.sn_obs[sbase + s], p.ln_alpha);
+      E = log_s_hat(p.slog_s[sbase + s], t_head - p.sborn[sbase + s], p.ln_alpha);
     }
     mx = fmax(mx, group_max_f64<LPS>(E));
     P += (long long)group_sum_f64<LPS>((double)pv);
@@ -416,7 +422,7 @@ __global__ __launch_bounds__(256) void merge_apply_kernel(MergeParams p) {
     if (i < nm) {
       s = mem[i];
       const int pv = p.svotes[sbase + s];
-      E = log_s_hat(p.slog_s[sbase + s], p.sn_obs[sbase + s], p.ln_alpha);
+      E = log_s_hat(p.slog_s[sbase + s], t_head - p.sborn[sbase + s], p.ln_alpha);
       w = none_seen ? (double)pv : (E > -INFINITY ? (double)pv * exp(E - mx) : 0.0);
     }
     W += group_sum_f64<LPS>(w);
@@ -463,7 +469,7 @@ __global__ __launch_bounds__(256) void merge_apply_kernel(MergeParams p) {
   if (sub == 0) {
     p.dvotes[dbase + r] = (int32_t)P;
     p.dlog_s[dbase + r] = out_log_s;
-    p.dn_obs[dbase + r] = n_r;
+    p.dborn[dbase + r] = t_head - n_r;
   }
 }
 
@@ -645,7 +651,7 @@ extern "C" keepkv_status keepkv_merge(const keepkv_layout* layout, const keepkv_
   if (max_evict > 0 && (!evict_idx || !match)) return KEEPKV_ERR_INVALID_ARG;
   if (!(alpha >= 0.f && alpha < 1.f)) return KEEPKV_ERR_INVALID_ARG;
   if (src->k == dst->k || src->v == dst->v || src->votes == dst->votes || src->log_s == dst->log_s ||
-      src->n_obs == dst->n_obs)
+      src->born == dst->born || src->t_obs == dst->t_obs)
     return KEEPKV_ERR_INVALID_ARG;
   if (!aligned16(src->k) || !aligned16(src->v) || !aligned16(dst->k) || !aligned16(dst->v)) return KEEPKV_ERR_INVALID_ARG;
   if (layout->head_dim != 64 && layout->head_dim != 128) return KEEPKV_ERR_UNSUPPORTED;
@@ -671,8 +677,8 @@ extern "C" keepkv_status keepkv_merge(const keepkv_layout* layout, const keepkv_
                                                                 dropped_votes, src->capacity, budget, max_evict,
                                                                 (int)(key_bytes / 4));
   MergeParams p;
-  p.sk = src->k; p.sv = src->v; p.svotes = src->votes; p.slog_s = src->log_s; p.sn_obs = src->n_obs; p.slen = src->len;
-  p.dk = dst->k; p.dv = dst->v; p.dvotes = dst->votes; p.dlog_s = dst->log_s; p.dn_obs = dst->n_obs; p.dlen = dst->len;
+  p.sk = src->k; p.sv = src->v; p.svotes = src->votes; p.slog_s = src->log_s; p.sborn = src->born; p.st_obs = src->t_obs; p.slen = src->len;
+  p.dk = dst->k; p.dv = dst->v; p.dvotes = dst->votes; p.dlog_s = dst->log_s; p.dborn = dst->born; p.dt_obs = dst->t_obs; p.dlen = dst->len;
   p.keep_idx = keep_idx; p.n_evict = n_evict; p.start = start; p.members = members;
   p.match = match; p.evict_idx = evict_idx; p.dropped_votes = dropped_votes;
   p.scap = src->capacity; p.dcap = dst->capacity; p.budget = budget; p.max_evict = max_evict;
@@ -709,7 +715,7 @@ extern "C" keepkv_status keepkv_prefill_merge(const keepkv_layout* layout, const
   if (!units_supported(layout)) return KEEPKV_ERR_UNSUPPORTED;
   if (dst->capacity < src->capacity || !(alpha >= 0.f && alpha < 1.f)) return KEEPKV_ERR_INVALID_ARG;
   if (src->k == dst->k || src->v == dst->v || src->votes == dst->votes || src->log_s == dst->log_s ||
-      src->n_obs == dst->n_obs || src->len == dst->len)
+      src->born == dst->born || src->t_obs == dst->t_obs || src->len == dst->len)
     return KEEPKV_ERR_INVALID_ARG;
   if (!aligned16(src->k) || !aligned16(src->v) || !aligned16(dst->k) || !aligned16(dst->v)) return KEEPKV_ERR_INVALID_ARG;
   if (layout->head_dim != 64 && layout->head_dim != 128) return KEEPKV_ERR_UNSUPPORTED;
@@ -732,8 +738,8 @@ extern "C" keepkv_status keepkv_prefill_merge(const keepkv_layout* layout, const
   prefill_group_kernel<<<units, kGroupThreads, lds, st>>>(near, src->len, keep, start, members, dst->len, cap);
 
   MergeParams p;
-  p.sk = src->k; p.sv = src->v; p.svotes = src->votes; p.slog_s = src->log_s; p.sn_obs = src->n_obs; p.slen = src->len;
-  p.dk = dst->k; p.dv = dst->v; p.dvotes = dst->votes; p.dlog_s = dst->log_s; p.dn_obs = dst->n_obs; p.dlen = dst->len;
+  p.sk = src->k; p.sv = src->v; p.svotes = src->votes; p.slog_s = src->log_s; p.sborn = src->born; p.st_obs = src->t_obs; p.slen = src->len;
+  p.dk = dst->k; p.dv = dst->v; p.dvotes = dst->votes; p.dlog_s = dst->log_s; p.dborn = dst->born; p.dt_obs = dst->t_obs; p.dlen = dst->len;
   p.keep_idx = keep; p.n_evict = nullptr; p.start = start; p.members = members;
   p.match = nullptr; p.evict_idx = nullptr; p.dropped_votes = nullptr;
   p.scap = cap; p.dcap = dst->capacity; p.budget = cap; p.max_evict = 0;

@@ -5,8 +5,9 @@
 namespace kk {
 namespace {
 
-// log_s <- ln(alpha * S + (1 - alpha) * exp(logit)),  n_obs += 1   on slots < len[unit]
-__global__ __launch_bounds__(256) void score_kernel(float* __restrict__ log_s, int32_t* __restrict__ n_obs,
+// log_s <- ln(alpha * S + (1 - alpha) * exp(logit)) on slots < len[unit]; the head's step counter t_obs += 1, which
+// is one more observation for every slot (a slot's count is t_obs - born)
+__global__ __launch_bounds__(256) void score_kernel(float* __restrict__ log_s, int32_t* __restrict__ t_obs,
                                                     const float* __restrict__ logits, const int32_t* __restrict__ len,
                                                     int capacity, float ln_alpha, float ln_1m_alpha) {
   const int unit = blockIdx.y;
@@ -19,14 +20,14 @@ __global__ __launch_bounds__(256) void score_kernel(float* __restrict__ log_s, i
     // ln(e^hi + e^lo) = hi + log1p(e^(lo - hi)); lo = -inf gives hi
     const float r = (lo == -INFINITY) ? hi : hi + log1pf(expf(lo - hi));
     log_s[base + i] = r;
-    n_obs[base + i] += 1;
   }
+  if (blockIdx.x == 0 && threadIdx.x == 0) t_obs[unit] += 1;
 }
 
 template <typename T>
 __global__ __launch_bounds__(128) void append_kernel(T* __restrict__ k, T* __restrict__ v, int32_t* __restrict__ votes,
-                                                     float* __restrict__ log_s, int32_t* __restrict__ n_obs,
-                                                     int32_t* __restrict__ len, const T* __restrict__ k_t,
+                                                     float* __restrict__ log_s, int32_t* __restrict__ born,
+                                                     const int32_t* __restrict__ t_obs, int32_t* __restrict__ len, const T* __restrict__ k_t,
                                                      const T* __restrict__ v_t, int32_t* overflow, int capacity, int D) {
   const int unit = blockIdx.x;
   const int i = len[unit];
@@ -43,7 +44,7 @@ __global__ __launch_bounds__(128) void append_kernel(T* __restrict__ k, T* __res
   if (threadIdx.x == 0) {
     votes[(size_t)unit * capacity + i] = 1;
     log_s[(size_t)unit * capacity + i] = -INFINITY;
-    n_obs[(size_t)unit * capacity + i] = 0;
+    born[(size_t)unit * capacity + i] = t_obs[unit];       // no observation yet
     len[unit] = i + 1;
   }
 }
@@ -62,7 +63,7 @@ extern "C" keepkv_status keepkv_score(const keepkv_layout* layout, keepkv_cache*
   if (bx > 64) bx = 64;
   const float la = alpha > 0.f ? logf(alpha) : -INFINITY;
   score_kernel<<<dim3(bx, units), 256, 0, reinterpret_cast<hipStream_t>(stream)>>>(
-      cache->log_s, cache->n_obs, logits, cache->len, cache->capacity, la, log1pf(-alpha));
+      cache->log_s, cache->t_obs, logits, cache->len, cache->capacity, la, log1pf(-alpha));
   return launch_status();
 }
 
@@ -76,11 +77,11 @@ extern "C" keepkv_status keepkv_append(const keepkv_layout* layout, keepkv_cache
   hipStream_t st = reinterpret_cast<hipStream_t>(stream);
   if (layout->dtype == KEEPKV_BF16)
     append_kernel<uint16_t><<<units, 128, 0, st>>>((uint16_t*)cache->k, (uint16_t*)cache->v, cache->votes, cache->log_s,
-                                                   cache->n_obs, cache->len, (const uint16_t*)k_t, (const uint16_t*)v_t,
+                                                   cache->born, cache->t_obs, cache->len, (const uint16_t*)k_t, (const uint16_t*)v_t,
                                                    overflow, cache->capacity, layout->head_dim);
   else
     append_kernel<float><<<units, 128, 0, st>>>((float*)cache->k, (float*)cache->v, cache->votes, cache->log_s,
-                                                cache->n_obs, cache->len, (const float*)k_t, (const float*)v_t, overflow,
+                                                cache->born, cache->t_obs, cache->len, (const float*)k_t, (const float*)v_t, overflow,
                                                 cache->capacity, layout->head_dim);
   return launch_status();
 }

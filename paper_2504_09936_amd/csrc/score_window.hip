@@ -24,7 +24,8 @@ struct WinParams {
   const void* k;
   const void* q;             // [B, Hq, W, D]
   float* log_s;
-  int32_t* n_obs;
+  int32_t* born;             // a slot's observation count is t_obs - born
+  int32_t* t_obs;            // [B, Hkv] steps observed by the head: += W here
   const int32_t* len;
   int capacity, W, G, n_q_heads, n_kv_heads, first_pos, slots_per_wg;
   int alpha_zero;            // alpha == 0: only the last query of the window counts
@@ -42,13 +43,14 @@ __device__ __forceinline__ int win_first_query(int slot, int first_pos) {
   return first_pos < 0 ? 0 : max(0, slot - first_pos);
 }
 
-// log_s <- ln(alpha^n_vis S + fresh), n_obs += n_vis;  fresh = ln of the window's weighted sum
+// log_s <- ln(alpha^n_vis S + fresh), observation count += n_vis;  fresh = ln of the window's weighted sum.
+// The head's step counter advances by W, so a slot seen by fewer than W queries moves its origin by the rest.
 __device__ __forceinline__ void win_store(const WinParams& p, size_t at, int n_vis, float fresh) {
+  if (n_vis < p.W) p.born[at] += p.W - n_vis;
   if (n_vis <= 0) return;
   const float old = p.alpha_zero ? -INFINITY : p.log_s[at] + (float)n_vis * p.ln_alpha;   // -inf: nothing observed
   const float hi = fmaxf(old, fresh), lo = fminf(old, fresh);
   p.log_s[at] = (lo == -INFINITY) ? hi : hi + log1pf(expf(lo - hi));
-  p.n_obs[at] += n_vis;
 }
 
 template <int D, int G>
@@ -62,6 +64,7 @@ __global__ __launch_bounds__(kWinWaves* kWave, 2) void score_window_mfma_kernel(
 
   const int unit = blockIdx.y;
   const int n = p.len[unit];
+  if (blockIdx.x == 0 && threadIdx.x == 0) p.t_obs[unit] += p.W;   // (no workgroup of this launch reads it)
   const int slot_begin = blockIdx.x * p.slots_per_wg;
   if (slot_begin >= n) return;               // uniform over the workgroup
   const int slot_end = min(n, slot_begin + p.slots_per_wg);
@@ -124,19 +127,21 @@ __global__ __launch_bounds__(kWinWaves* kWave, 2) void score_window_mfma_kernel(
   const float c0 = (p.ln_1m_alpha + (float)(p.W - 1) * p.ln_alpha) * kLog2e;
   const bool every_query = p.first_pos < 0 && !p.alpha_zero;      // uniform: no visibility mask needed
 
-  // The read-modify-write of (log_s, n_obs) trails the tiles by one iteration: the old values are
+  // The read-modify-write of log_s (and, under a causal window, of born) trails the tiles by one iteration: the old values are
   // requested when a tile's arithmetic starts and consumed after the next tile's arrival has been
   // awaited, so neither their latency nor the stores' sit on the critical path.
   size_t pend_at = 0;
-  int pend_nvis = 0, pend_n = 0;
+  int pend_nvis = 0, pend_born = 0;
+  bool pend_writer = false;
   float pend_fresh = 0.f, pend_ls = 0.f;
+  const bool causal = p.first_pos >= 0;       // uniform: only then can a live slot be seen by fewer than W queries
   auto finish = [&]() {
+    if (causal && pend_writer && pend_nvis < p.W) p.born[pend_at] = pend_born + (p.W - pend_nvis);
     if (pend_nvis > 0) {
       const float old2 = p.alpha_zero ? -INFINITY : (pend_ls + (float)pend_nvis * p.ln_alpha) * kLog2e;
       const float hi = fmaxf(old2, pend_fresh), lo = fminf(old2, pend_fresh);      // base-2 logarithms
       const float r = (lo == -INFINITY) ? hi : hi + fast_log2(1.f + fast_exp2(lo - hi));
       p.log_s[pend_at] = r * kLn2;
-      p.n_obs[pend_at] = pend_n + pend_nvis;
     }
   };
 
@@ -151,7 +156,7 @@ __global__ __launch_bounds__(kWinWaves* kWave, 2) void score_window_mfma_kernel(
     const bool writer = half == 0 && slot < slot_end;
     const size_t at = (size_t)unit * p.capacity + min(slot, slot_end - 1);
     const float old_ls = p.log_s[at];
-    const int old_n = p.n_obs[at];
+    const int old_born = causal ? p.born[at] : 0;
     const unsigned char* src = s_buf + ((it & 1) * kWinWaves + wave) * TILE_BYTES;
     bf16x8_t bk[KS];
 #pragma unroll
@@ -204,7 +209,8 @@ __global__ __launch_bounds__(kWinWaves* kWave, 2) void score_window_mfma_kernel(
     pend_nvis = writer ? p.W - min(p.W, j_first) : 0;
     pend_fresh = m + fast_log2(sum);         // base-2 logarithm of the window's weighted sum
     pend_ls = old_ls;
-    pend_n = old_n;
+    pend_born = old_born;
+    pend_writer = writer;
   }
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   finish();
@@ -219,6 +225,7 @@ __global__ __launch_bounds__(128) void score_window_f32_kernel(WinParams p) {
   const int n = p.len[unit];
   const int G = p.G, R = p.W * G;
   const int b = unit / p.n_kv_heads, kvh = unit % p.n_kv_heads;
+  if (blockIdx.x == 0 && threadIdx.x == 0) p.t_obs[unit] += p.W;   // (no workgroup of this launch reads it)
   if ((int)(blockIdx.x * blockDim.x) >= n) return;
   const float* q = reinterpret_cast<const float*>(p.q);
   for (int e = threadIdx.x; e < R * D; e += blockDim.x) {
@@ -291,7 +298,7 @@ extern "C" keepkv_status keepkv_score_window(const keepkv_layout* layout, keepkv
   hipStream_t st = reinterpret_cast<hipStream_t>(stream);
 
   WinParams p;
-  p.k = cache->k, p.q = q_win, p.log_s = cache->log_s, p.n_obs = cache->n_obs, p.len = cache->len;
+  p.k = cache->k, p.q = q_win, p.log_s = cache->log_s, p.born = cache->born, p.t_obs = cache->t_obs, p.len = cache->len;
   p.capacity = cache->capacity, p.W = window, p.G = G;
   p.n_q_heads = layout->n_q_heads, p.n_kv_heads = layout->n_kv_heads;
   p.first_pos = first_pos < 0 ? -1 : first_pos;

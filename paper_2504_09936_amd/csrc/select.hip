@@ -64,14 +64,14 @@ __device__ __forceinline__ int rank_in_wave(uint64_t mask) {
   return (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
 }
 
-// EXT: the ranking value is read from a caller-supplied array (passed as log_s; n_obs and votes
+// EXT: the ranking value is read from a caller-supplied array (passed as log_s; born, t_obs and votes
 // unused) instead of being formed from the cache's votes and EMA scores.
 // LDSKEYS: the sortable keys of the head live in LDS (capacity * 8 bytes fit) instead of the workspace, so
 // the radix passes and the compaction never leave the CU.
 template <bool EXT, bool LDSKEYS>
 __global__ __launch_bounds__(kSelThreads) void select_kernel(
-    const float* __restrict__ log_s, const int32_t* __restrict__ n_obs, const int32_t* __restrict__ votes,
-    const int32_t* __restrict__ len, uint64_t* __restrict__ keys, int32_t* __restrict__ keep_idx,
+    const float* __restrict__ log_s, const int32_t* __restrict__ born, const int32_t* __restrict__ t_obs,
+    const int32_t* __restrict__ votes, const int32_t* __restrict__ len, uint64_t* __restrict__ keys, int32_t* __restrict__ keep_idx,
     int32_t* __restrict__ evict_idx, int32_t* __restrict__ n_evict, int capacity, int budget, int n_sink,
     int n_recent, double ln_alpha, int n_table) {
   constexpr int kWaves = kSelThreads / 64;
@@ -96,12 +96,13 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
       const int i = min(i0 + u * kSelThreads, capacity - 1);
-      nn[u] = EXT ? 1 : n_obs[base + i];
+      nn[u] = EXT ? 0 : born[base + i];          // turned into the observation count t_obs - born at its use
       pv[u] = EXT ? 1 : votes[base + i];
       ls[u] = log_s[base + i];
     }
   };
   request(lo + tid);
+  const int t_head = EXT ? 1 : t_obs[unit];
   const int n = len[unit];
   int32_t* keep_out = keep_idx + (size_t)unit * budget;
   int32_t* evict_out = evict_idx + (size_t)unit * (capacity - budget);
@@ -138,6 +139,8 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(
     } else {
       // ln p + ln S - ln(1 - alpha^n), the two logarithms from the tables; a wavefront evaluates them itself
       // only where one of its lanes has a count beyond a table.
+#pragma unroll
+      for (int u = 0; u < 4; ++u) nn[u] = t_head - nn[u];
 #pragma unroll
       for (int u = 0; u < 4; ++u) {
         const bool valid = i0 + u * kSelThreads < hi;
@@ -332,8 +335,8 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(
 constexpr int kSelLdsKeys = 16384;     // up to this capacity the keys of a head are kept in LDS (128 KB)
 
 template <bool EXT>
-void launch_select(int units, hipStream_t st, const float* log_s, const int32_t* n_obs, const int32_t* votes,
-                   const int32_t* len, uint64_t* keys, int32_t* keep_idx, int32_t* evict_idx, int32_t* n_evict,
+void launch_select(int units, hipStream_t st, const float* log_s, const int32_t* born, const int32_t* t_obs,
+                   const int32_t* votes, const int32_t* len, uint64_t* keys, int32_t* keep_idx, int32_t* evict_idx, int32_t* n_evict,
                    int capacity, int budget, int n_sink, int n_recent, double ln_alpha) {
   // counts from which alpha^n is below half an ulp of 1 (n ln alpha <= -40) need no table entry
   int n_table = 0;
@@ -346,11 +349,11 @@ void launch_select(int units, hipStream_t st, const float* log_s, const int32_t*
                                                        hipFuncAttributeMaxDynamicSharedMemorySize, kSelLdsKeys * 8);
     (void)attr;                              // a refusal shows up as a launch error
     select_kernel<EXT, true><<<units, kSelThreads, (size_t)capacity * 8, st>>>(
-        log_s, n_obs, votes, len, keys, keep_idx, evict_idx, n_evict, capacity, budget, n_sink, n_recent, ln_alpha,
+        log_s, born, t_obs, votes, len, keys, keep_idx, evict_idx, n_evict, capacity, budget, n_sink, n_recent, ln_alpha,
         n_table);
   } else {
     select_kernel<EXT, false><<<units, kSelThreads, 0, st>>>(
-        log_s, n_obs, votes, len, keys, keep_idx, evict_idx, n_evict, capacity, budget, n_sink, n_recent, ln_alpha,
+        log_s, born, t_obs, votes, len, keys, keep_idx, evict_idx, n_evict, capacity, budget, n_sink, n_recent, ln_alpha,
         n_table);
   }
 }
@@ -380,7 +383,7 @@ extern "C" keepkv_status keepkv_select(const keepkv_layout* layout, const keepkv
   const int units = layout->batch * layout->n_kv_heads;
   const double la = alpha > 0.f ? log((double)alpha) : -INFINITY;
   launch_select<false>(units, reinterpret_cast<hipStream_t>(stream),
-      cache->log_s, cache->n_obs, cache->votes, cache->len,
+      cache->log_s, cache->born, cache->t_obs, cache->votes, cache->len,
       reinterpret_cast<uint64_t*>(reinterpret_cast<char*>(workspace) + pl.keys_off), keep_idx, evict_idx, n_evict,
       cache->capacity, budget, n_sink, n_recent, la);
   return launch_status();
@@ -401,7 +404,7 @@ extern "C" keepkv_status keepkv_select_by_key(const keepkv_layout* layout, const
   if (!workspace || workspace_bytes < pl.bytes || !aligned16(workspace)) return KEEPKV_ERR_WORKSPACE;
   const int units = layout->batch * layout->n_kv_heads;
   launch_select<true>(units, reinterpret_cast<hipStream_t>(stream),
-      rank, nullptr, nullptr, cache->len,
+      rank, nullptr, nullptr, nullptr, cache->len,
       reinterpret_cast<uint64_t*>(reinterpret_cast<char*>(workspace) + pl.keys_off), keep_idx, evict_idx, n_evict,
       cache->capacity, budget, n_sink, n_recent, 0.0);
   return launch_status();

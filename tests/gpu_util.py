@@ -50,9 +50,26 @@ def download(c):
     o.v[:] = to_host(c.v)
     o.votes[:] = c.votes.cpu().numpy()
     o.log_S[:] = c.log_s.cpu().numpy().astype(np.float64)
-    o.n_obs[:] = c.n_obs.cpu().numpy()
+    o.n_obs[:] = n_obs(c).cpu().numpy()
     o.len[:] = c.len.cpu().numpy()
     return o
+
+
+def n_obs(c):
+    """Observation count of every slot of a GPU cache (the library stores its origin: count = t_obs - born)."""
+    return c.t_obs.unsqueeze(-1) - c.born
+
+
+def set_n_obs(c, n, index=None):
+    """Give the slots `index` (default: all) of a GPU cache the observation counts `n` (scalar, array or tensor):
+    born = t_obs - n with the heads' current step counters."""
+    if not torch.is_tensor(n):
+        n = torch.as_tensor(np.asarray(n, dtype=np.int32)).cuda()
+    t = c.t_obs.unsqueeze(-1).expand_as(c.born)
+    if index is None:
+        c.born[:] = t - n
+    else:
+        c.born[index] = t[index] - n
 
 
 def workspace(lay, capacity, budget):

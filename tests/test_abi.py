@@ -49,7 +49,7 @@ def test_workspace_and_argument_validation_without_device():
     # null pointers are rejected on the host; nothing is launched
     assert lib.keepkv_score(None, None, None, C.c_float(0.9), None) == kk.ERR_INVALID_ARG
     assert lib.keepkv_decode_attn(C.byref(lay.c()), None, None, None, None, None, None, 0, None) == kk.ERR_INVALID_ARG
-    cache = kk._Cache(16, 16, 16, 16, 16, 16, 884, 0)     # non-null dummies; never dereferenced on these paths
+    cache = kk._Cache(16, 16, 16, 16, 16, 16, 16, 884, 0)     # non-null dummies; never dereferenced on these paths
     assert lib.keepkv_score(C.byref(lay.c()), C.byref(cache), C.c_void_p(16), C.c_float(1.5), None) == kk.ERR_INVALID_ARG
     lay3 = kk.Layout(8, 24, 8, 128, kk.BF16, 0.1)       # group size 3 is not built
     assert lib.keepkv_decode_attn(C.byref(lay3.c()), C.byref(cache), C.c_void_p(16), C.c_void_p(16), None, None,
@@ -65,7 +65,7 @@ def test_too_many_heads_is_refused_by_every_call():
     from paper_2504_09936_amd import binding as kk
     lib = kk._lib
     lay = kk.Layout(4097, 16, 4, 128, kk.BF16, 0.1)       # 16388 (batch, kv head) pairs
-    cache = kk._Cache(16, 16, 16, 16, 16, 16, 884, 0)     # non-null dummies; never dereferenced on these paths
+    cache = kk._Cache(16, 16, 16, 16, 16, 16, 16, 884, 0)     # non-null dummies; never dereferenced on these paths
     P = C.c_void_p(16)
     L, K = C.byref(lay.c()), C.byref(cache)
     assert lib.keepkv_score(L, K, P, C.c_float(0.9), None) == kk.ERR_UNSUPPORTED

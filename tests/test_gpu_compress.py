@@ -96,7 +96,7 @@ def _run_compress_stagewise(w, lay, c, ws, alpha, threshold, check_merge=True):
             nk = len(rk)
             assert d.len[b, h].item() == nk
             np.testing.assert_array_equal(d.votes[b, h, :nk].cpu().numpy(), res.votes)
-            np.testing.assert_array_equal(d.n_obs[b, h, :nk].cpu().numpy(), res.n_obs)
+            np.testing.assert_array_equal(U.n_obs(d)[b, h, :nk].cpu().numpy(), res.n_obs)
             assert dropped[b, h].item() == res.dropped
             np.testing.assert_allclose(d.log_s[b, h, :nk].cpu().numpy(), res.log_S, rtol=2e-6, atol=2e-6)
             ev = U.storage_err_rows(dv[b, h, :nk], res.v, w.dtype)
@@ -167,7 +167,7 @@ def test_select_exact_ties_keep_lowest_index():
     g = np.random.default_rng(0)
     # coarse scores: thousands of exact ties across the selection boundary
     c.log_s[:] = torch.from_numpy(np.round(g.standard_normal((1, 8, 900)), 1).astype(np.float32)).cuda()
-    c.n_obs[:] = 5
+    U.set_n_obs(c, 5)
     c.votes[:] = torch.from_numpy(g.integers(1, 3, size=(1, 8, 900)).astype(np.int32)).cuda()
     _run_compress_stagewise(w, lay, c, ws, alpha, U.f32(0.8), check_merge=False)
 
@@ -266,11 +266,11 @@ def test_degenerate_inputs(alpha):
     c.k[:, :, zero] = 0                                        # zero-norm keys on retained and evicted slots
     unobs = g.choice(N, 120, replace=False)
     c.log_s[:, :, unobs] = float("-inf")
-    c.n_obs[:, :, unobs] = 0
+    U.set_n_obs(c, 0, (slice(None), slice(None), unobs))
     c.log_s[0, 0] = torch.from_numpy((g.standard_normal(N) * 1e-3).astype(np.float32)).cuda()   # ln s_hat ~ 0: guarded
-    c.n_obs[0, 0] = 50
+    U.set_n_obs(c, 50, (0, 0))
     c.log_s[0, 1, :] = float("-inf")                           # a head in which nothing was ever observed
-    c.n_obs[0, 1, :] = 0
+    U.set_n_obs(c, 0, (0, 1))
     c.k[0, 2, 100:400] = c.k[0, 2, 100:101]                    # a run of identical keys
     c.votes[0, 3] = torch.from_numpy(g.integers(1, 1000, N).astype(np.int32)).cuda()
     _run_compress_stagewise(w, lay, c, ws, alpha, U.f32(-2.0))
@@ -357,7 +357,7 @@ def test_select_skips_only_logarithms_that_are_zero(alpha):
     votes = np.ones((B, H, n), dtype=np.int32)
     votes[:, :, 64:128] = g.integers(1, 9, size=(B, H, 64))            # one wavefront's worth with votes
     votes[1, :, ::5] = g.integers(2, 50, size=(H, 600))
-    c.n_obs[:] = torch.from_numpy(n_obs).cuda()
+    U.set_n_obs(c, n_obs)
     c.votes[:] = torch.from_numpy(votes).cuda()
     c.log_s[:] = torch.from_numpy((g.standard_normal((B, H, n)) * 3 - 8).astype(np.float32)).cuda()
     c.len[:] = n
@@ -383,7 +383,7 @@ def test_merge_groups_short_long_and_mixed():
     lay, c = U.new_cache(w, capacity=n, K=K, V=V)
     ws = U.workspace(lay, c.capacity, w.budget)
     c.log_s[:] = torch.from_numpy(log_s).cuda()
-    c.n_obs[:] = 7
+    U.set_n_obs(c, 7)
     c.votes[:] = torch.from_numpy(g.integers(1, 4, size=(B, H, n)).astype(np.int32)).cuda()
     n_matched = _run_compress_stagewise(w, lay, c, ws, alpha, U.f32(0.8))
     assert n_matched >= sum(copies.values())

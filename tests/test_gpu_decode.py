@@ -115,7 +115,7 @@ def test_score_and_append_match_oracle(alpha):
         O.observe(oc, logits.cpu().numpy().astype(np.float64), alpha)
         n = w.context + t + 1
         assert (c.len.cpu().numpy() == n).all() and (oc.len == n).all()
-        np.testing.assert_array_equal(c.n_obs.cpu().numpy()[:, :, :n], oc.n_obs[:, :, :n])
+        np.testing.assert_array_equal(U.n_obs(c).cpu().numpy()[:, :, :n], oc.n_obs[:, :, :n])
         np.testing.assert_allclose(c.log_s.cpu().numpy()[:, :, :n], oc.log_S[:, :, :n], rtol=1e-5, atol=1e-5)
         np.testing.assert_array_equal(U.to_host(c.k)[:, :, :n], oc.k[:, :, :n].astype(np.float32))
         np.testing.assert_array_equal(c.votes.cpu().numpy()[:, :, :n], oc.votes[:, :, :n])
@@ -148,7 +148,7 @@ def test_decode_step_equals_append_attend_score(name, w, hint):
     votes = g.integers(1, 5, size=(B, H, cap)).astype(np.int32)
     lay, c = U.new_cache(w, capacity=cap, K=Kp, V=Vp, votes=votes, lens=lens)
     c.log_s[:] = torch.from_numpy(g.standard_normal((B, H, cap)).astype(np.float32)).cuda()
-    c.n_obs[:] = torch.from_numpy(g.integers(1, 9, size=(B, H, cap)).astype(np.int32)).cuda()
+    U.set_n_obs(c, g.integers(1, 9, size=(B, H, cap)).astype(np.int32))
     ws = U.workspace(lay, cap, max(1, N // 10))
     out = torch.zeros(B, w.n_q_heads, w.head_dim, dtype=lay.torch_dtype, device="cuda")
     logits = torch.zeros(B, H, cap, dtype=torch.float32, device="cuda")
@@ -181,7 +181,7 @@ def test_decode_step_equals_append_attend_score(name, w, hint):
         for b in range(B):
             for h in range(H):
                 n = int(oc.len[b, h])
-                np.testing.assert_array_equal(c.n_obs[b, h, :n].cpu().numpy(), oc.n_obs[b, h, :n])
+                np.testing.assert_array_equal(U.n_obs(c)[b, h, :n].cpu().numpy(), oc.n_obs[b, h, :n])
                 np.testing.assert_array_equal(c.votes[b, h, :n].cpu().numpy(), oc.votes[b, h, :n])
                 np.testing.assert_allclose(c.log_s[b, h, :n].cpu().numpy(), oc.log_S[b, h, :n], rtol=2e-3, atol=2e-3)
                 np.testing.assert_array_equal(U.to_host(c.k)[b, h, :n], oc.k[b, h, :n].astype(np.float32))

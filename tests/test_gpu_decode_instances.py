@@ -43,7 +43,7 @@ def _steady_state(w, cap, seed, lens):
     lay, c = U.new_cache(w, capacity=cap, K=K, V=V, votes=votes, lens=lens)
     del K, V
     c.log_s[:] = torch.from_numpy(g.standard_normal((B, H, cap)).astype(np.float32)).cuda()
-    c.n_obs[:] = torch.from_numpy(g.integers(1, 40, size=(B, H, cap)).astype(np.int32)).cuda()
+    U.set_n_obs(c, g.integers(1, 40, size=(B, H, cap)).astype(np.int32))
     return lay, c
 
 
@@ -72,7 +72,7 @@ def _check_steps(w, lay, c, ws, sample, n_steps, seed, hint, tag):
 
     def snapshot():
         return dict(k=U.to_host(c.k[bs, hs]), v=U.to_host(c.v[bs, hs]), votes=c.votes[bs, hs].cpu().numpy(),
-                    log_s=c.log_s[bs, hs].cpu().numpy(), n_obs=c.n_obs[bs, hs].cpu().numpy(),
+                    log_s=c.log_s[bs, hs].cpu().numpy(), n_obs=U.n_obs(c)[bs, hs].cpu().numpy(), born=c.born[bs, hs].cpu().numpy(),
                     len=c.len[bs, hs].cpu().numpy())
 
     lens_max = int(c.len.max().item())
@@ -107,7 +107,7 @@ def _check_steps(w, lay, c, ws, sample, n_steps, seed, hint, tag):
             np.testing.assert_array_equal(post["v"][i][:n], v[:n].astype(np.float32), err_msg=str(where))
             # slots beyond the live prefix are untouched
             np.testing.assert_array_equal(post["log_s"][i][n:], pre["log_s"][i][n:], err_msg=str(where))
-            np.testing.assert_array_equal(post["n_obs"][i][n:], pre["n_obs"][i][n:], err_msg=str(where))
+            np.testing.assert_array_equal(post["born"][i][n:], pre["born"][i][n:], err_msg=str(where))
     return overflow.item()
 
 
@@ -178,10 +178,11 @@ def test_every_d128_instance_attention_only(base, waves, per):
     out = torch.full_like(qd, 7.0)
     logits = torch.full((B, H, cap), -123.0, dtype=torch.float32, device="cuda")
     lse = torch.zeros(B, w.n_q_heads, dtype=torch.float32, device="cuda")
-    before = (c.log_s.clone(), c.n_obs.clone(), c.len.clone())
+    before = (c.log_s.clone(), c.born.clone(), c.len.clone(), c.t_obs.clone())
     kk.decode_attn(lay, c, qd, out, logits, lse, ws)
     torch.cuda.synchronize()
-    assert torch.equal(before[0], c.log_s) and torch.equal(before[1], c.n_obs) and torch.equal(before[2], c.len)
+    assert torch.equal(before[0], c.log_s) and torch.equal(before[1], c.born) and torch.equal(before[2], c.len)
+    assert torch.equal(before[3], c.t_obs)
     oc = U.download(c)
     oc.k[np.isnan(oc.k)] = 0.0
     oc.v[np.isnan(oc.v)] = 0.0

@@ -142,7 +142,7 @@ def _free_run(w, seed, threshold):
     n = int(oc.len[0, 0])
     assert np.array_equal(c.len.cpu().numpy(), oc.len)
     assert np.array_equal(c.votes[:, :, :n].cpu().numpy(), oc.votes[:, :, :n])
-    assert np.array_equal(c.n_obs[:, :, :n].cpu().numpy(), oc.n_obs[:, :, :n])
+    assert np.array_equal(U.n_obs(c)[:, :, :n].cpu().numpy(), oc.n_obs[:, :, :n])
     assert np.array_equal(dropped.cpu().numpy(), oc.dropped)
     ok = np.ones((B, H), dtype=bool)
     for u in ill:

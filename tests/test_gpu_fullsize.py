@@ -19,7 +19,7 @@ def _unit_cache(c, b, h):
     cap, D = c.capacity, c.k.shape[-1]
     o = O.Cache(1, 1, cap, D)
     o.k[0, 0], o.v[0, 0] = U.to_host(c.k[b, h]), U.to_host(c.v[b, h])
-    o.votes[0, 0], o.n_obs[0, 0] = c.votes[b, h].cpu().numpy(), c.n_obs[b, h].cpu().numpy()
+    o.votes[0, 0], o.n_obs[0, 0] = c.votes[b, h].cpu().numpy(), U.n_obs(c)[b, h].cpu().numpy()
     o.log_S[0, 0] = c.log_s[b, h].cpu().numpy().astype(np.float64)
     o.len[0, 0] = int(c.len[b, h].item())
     return o
@@ -108,7 +108,7 @@ def _run(w, seed, n_window, n_steps, threshold, sample):
         assert err.max() <= TOL, ("decode step", b, h, err.max())
         n = Bud + n_steps
         np.testing.assert_allclose(small.log_s[b, h, :n].cpu().numpy(), oc.log_S[0, 0, :n], rtol=2e-3, atol=2e-3)
-        np.testing.assert_array_equal(small.n_obs[b, h, :n].cpu().numpy(), oc.n_obs[0, 0, :n])
+        np.testing.assert_array_equal(U.n_obs(small)[b, h, :n].cpu().numpy(), oc.n_obs[0, 0, :n])
 
 
 def test_llama3_8b_full_size_first_event_and_decode():
@@ -163,7 +163,7 @@ def test_window_scores_full_size(cfg, kw, window, causal):
     first_pos = N - window if causal else -1
     kk.score_window(lay, c, U.to_device(q, w.dtype), window, alpha, first_pos)
     torch.cuda.synchronize()
-    n_obs = c.n_obs.cpu().numpy()
+    n_obs = U.n_obs(c).cpu().numpy()
     want_n = np.full(N, window) if not causal else window - np.maximum(0, np.arange(N) - first_pos)
     assert (n_obs == want_n[None, None, :]).all()
     empty_S, empty_n = np.full(N, -np.inf), np.zeros(N, dtype=np.int64)

@@ -14,11 +14,11 @@ pytestmark = pytest.mark.gpu
 
 def _state(c):
     n = c.capacity
-    return [c.k.clone(), c.v.clone(), c.votes.clone(), c.log_s.clone(), c.n_obs.clone(), c.len.clone()]
+    return [c.k.clone(), c.v.clone(), c.votes.clone(), c.log_s.clone(), c.born.clone(), c.t_obs.clone(), c.len.clone()]
 
 
 def _restore(c, st):
-    for dst, src in zip((c.k, c.v, c.votes, c.log_s, c.n_obs, c.len), st):
+    for dst, src in zip((c.k, c.v, c.votes, c.log_s, c.born, c.t_obs, c.len), st):
         dst.copy_(src)
 
 
@@ -115,7 +115,7 @@ def test_graph_replay_matches_eager():
         got = [_bits(x) for x in (out, *_state(small), *_state(other), *sbufs[:4])]
         n = w.budget
         for i, (a, b) in enumerate(zip(got, ref)):
-            if 7 <= i <= 11:                           # destination cache: compare the live prefix only
+            if 8 <= i <= 12:                           # destination cache (k, v, votes, log_s, born): the live prefix only
                 a, b = a[:, :, :n], b[:, :, :n]
             assert torch.equal(a, b), (rep, i)
 

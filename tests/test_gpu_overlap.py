@@ -21,7 +21,7 @@ def _state(caches, cur, dropped):
     for c2, cu in zip(caches, cur):
         c = c2[cu]
         n = int(c.len.max().item())
-        out.append([c.len.clone(), c.votes[:, :, :n].clone(), c.n_obs[:, :, :n].clone(), c.log_s[:, :, :n].clone(),
+        out.append([c.len.clone(), c.votes[:, :, :n].clone(), U.n_obs(c)[:, :, :n].clone(), c.log_s[:, :, :n].clone(),
                     c.k[:, :, :n].clone().view(torch.int16), c.v[:, :, :n].clone().view(torch.int16)])
     out.append([dropped.clone()])
     return out
@@ -53,7 +53,7 @@ def test_graph_equals_eager_single_stream(period, layers, overlap):
             c.v[:, :, :Bud] = V0[layer]
             c.votes[:, :, :Bud] = 1
             c.log_s[:, :, :Bud] = -1.0
-            c.n_obs[:, :, :Bud] = 2
+            U.set_n_obs(c, 2, (slice(None), slice(None), slice(0, Bud)))
             c.len.fill_(Bud)
             caches.append(pair)
         return caches
@@ -123,7 +123,7 @@ def test_graph_equals_eager_single_stream(period, layers, overlap):
 
     # one graph, events on a side stream or in line; replayed three times from the same starting state
     caches_b, dropped_b = fresh(), torch.zeros(R, B, H, dtype=torch.int64, device="cuda")
-    start = [[[t.clone() for t in (c.k, c.v, c.votes, c.log_s, c.n_obs, c.len)] for c in pair] for pair in caches_b]
+    start = [[[t.clone() for t in (c.k, c.v, c.votes, c.log_s, c.born, c.t_obs, c.len)] for c in pair] for pair in caches_b]
     stream, side = torch.cuda.Stream(), torch.cuda.Stream()
     graph = torch.cuda.CUDAGraph()
     torch.cuda.synchronize()
@@ -133,7 +133,7 @@ def test_graph_equals_eager_single_stream(period, layers, overlap):
     for replay in range(3):
         for pair, saved in zip(caches_b, start):          # eager work between the replays: restore the state
             for c, s in zip(pair, saved):
-                for t, s_t in zip((c.k, c.v, c.votes, c.log_s, c.n_obs, c.len), s):
+                for t, s_t in zip((c.k, c.v, c.votes, c.log_s, c.born, c.t_obs, c.len), s):
                     t.copy_(s_t)
         dropped_b.zero_()
         torch.cuda.synchronize()

@@ -47,7 +47,7 @@ def _setup(w, seed, ragged=True):
     q_win = np.stack([W.make_query(w, seed, t - 4) for t in range(4)], axis=2)
     kk.score_window(lay, c, U.to_device(np.ascontiguousarray(q_win), w.dtype), 4, alpha, -1)
     c.log_s[0, 0, 41] = float("-inf")
-    c.n_obs[0, 0, 41] = 0
+    U.set_n_obs(c, 0, (0, 0, 41))
     torch.cuda.synchronize()
     return lay, c, lens, alpha
 
@@ -96,7 +96,7 @@ def test_prefill_match_and_merge_match_oracle(name, w, T):
             nk = roots.shape[0]
             assert got_len[b, h] == nk, (name, b, h)
             np.testing.assert_array_equal(d.votes[b, h, :nk].cpu().numpy(), r.votes)
-            np.testing.assert_array_equal(d.n_obs[b, h, :nk].cpu().numpy(), r.n_obs)
+            np.testing.assert_array_equal(U.n_obs(d)[b, h, :nk].cpu().numpy(), r.n_obs)
             assert int(r.votes.sum()) == int(oc.votes[b, h, :n].sum())                        # nothing dropped
             ls = d.log_s[b, h, :nk].cpu().numpy()
             fin = np.isfinite(r.log_S)
@@ -190,7 +190,7 @@ def test_prefill_pass_full_size_sampled_units():
         roots, absorbed, tgt = O.prefill_groups(ref_near)
         assert dl[b, h] == roots.shape[0]
         r = O.merge(k, U.to_host(c.v[b, h]).astype(np.float64), c.votes[b, h].cpu().numpy(),
-                    c.log_s[b, h].cpu().numpy().astype(np.float64), c.n_obs[b, h].cpu().numpy(), roots, absorbed, tgt, alpha)
+                    c.log_s[b, h].cpu().numpy().astype(np.float64), U.n_obs(c)[b, h].cpu().numpy(), roots, absorbed, tgt, alpha)
         nk = roots.shape[0]
         np.testing.assert_array_equal(votes[b, h, :nk], r.votes)
         err_v = U.storage_err_rows(U.to_host(d.v[b, h, :nk]), r.v, w.dtype)

@@ -28,13 +28,13 @@ def _state(w, cap, seed):
     def make():
         lay, c = U.new_cache(w, capacity=cap, K=K, V=V, votes=votes, lens=lens)
         c.log_s[:] = torch.from_numpy(log_s).cuda()
-        c.n_obs[:] = torch.from_numpy(n_obs).cuda()
+        U.set_n_obs(c, n_obs)
         return lay, c
     return make
 
 
 def _same(a, b):
-    for name in ("k", "v", "votes", "log_s", "n_obs", "len"):
+    for name in ("k", "v", "votes", "log_s", "born", "t_obs", "len"):
         x, y = getattr(a, name), getattr(b, name)
         if x.dtype == torch.bfloat16:
             x, y = x.view(torch.int16), y.view(torch.int16)
