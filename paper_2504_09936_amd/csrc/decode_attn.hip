@@ -618,7 +618,9 @@ __global__ __launch_bounds__(kMfmaWaves* kWave, 2) void decode_mfma_kernel(Decod
     }
   };
   int base = start + wave * kMTile;
-  if (base < lim) {
+  const int wave_lim = lim;
+  constexpr int kTileStep = kMfmaWaves * kMTile;
+  if (base < wave_lim) {
     if constexpr (ONE) issue_rows(kbytes, Kb, base);
     else issue_k(base);
     if constexpr (ONE) {                         // slot base + lane of the tile (lanes beyond the tile repeat a slot)
@@ -640,7 +642,7 @@ __global__ __launch_bounds__(kMfmaWaves* kWave, 2) void decode_mfma_kernel(Decod
     if constexpr (STEP) ls_next = p.log_s[ubase + min(tbase + 16 * (l16 >> 2) + 4 * q + (l16 & 3), bound - 1)];
   };
   if constexpr (!ONE) {
-    if (base < lim) request_scalars(base);
+    if (base < wave_lim) request_scalars(base);
   }
 
   // B operand of the score product: column l16 is head l16 mod G, this lane's 8 channels of every k-step
@@ -883,7 +885,7 @@ __global__ __launch_bounds__(kMfmaWaves* kWave, 2) void decode_mfma_kernel(Decod
     }
   };
 
-  while (base < lim) {                           // a single pass with ONE
+  while (base < wave_lim) {                      // a single pass with ONE
     float lp[2][4];                                // log2(votes) of the slots whose logits this lane holds
     float ls_old = -INFINITY;
     if constexpr (ONE) {
@@ -926,8 +928,8 @@ __global__ __launch_bounds__(kMfmaWaves* kWave, 2) void decode_mfma_kernel(Decod
           for (int i = 0; i < 4; ++i) lp[st][i] = __shfl(lp_lane, 16 * st + 4 * q + i);
       }
       ls_old = ls_next;
-      const int next = base + kMfmaWaves * kMTile;
-      compute(base, false, next < lim ? next : -1, lp, ls_old, false);
+      const int next = base + kTileStep;
+      compute(base, false, next < wave_lim ? next : -1, lp, ls_old, false);
       Vb = Tb + (Vb == Tb ? TILE_BYTES : 0);
       base = next;
     }
