@@ -110,7 +110,7 @@ struct MatchParams {
   struct ExactPartial* exact_partial;   // [kExactResident] per-share results of the f64 kernel
   int32_t* exact_ticket;                // control words at the head of the workspace
   int32_t* flag_count;   // [1] rows queued for the f64 kernel; zero between calls (the f64 kernel clears it)
-  int32_t* exact_done;   // [1] workgroups of the f64 kernel that have finished; zero between calls
+  int32_t* exact_done;   // [1] queued rows that the f64 kernel has finished; zero between calls
   int32_t* flag_rows;    // [units * max_evict]: unit * max_evict + j
   int capacity, budget, max_evict, rn_pitch;
   float threshold, delta;
@@ -126,6 +126,14 @@ __device__ __forceinline__ int imin(int a, int b) { return a < b ? a : b; }
 // median of three; the backend folds this into v_med3_i32
 __device__ __forceinline__ int imed3(int a, int b, int c) { return imax(imin(a, b), imin(imax(a, b), c)); }
 
+// A row whose best cosine lies below the threshold by more than the f32 arithmetic's error has no target
+// whichever column holds that best value, so neither a small margin to the runner-up nor a best value that
+// is not positive (`upper` is then 0: every value of the row is at most 0) makes it undecided, as long as
+// the caller does not ask for the similarity itself.  A NaN in `upper` compares false and keeps the row queued.
+__device__ __forceinline__ bool surely_below(const MatchParams& p, float upper, float ss, float rn_e) {
+  return p.sim_out == nullptr && ss > 0.f && rn_e < INFINITY && upper + p.delta < p.threshold;
+}
+
 // Decision of one row from the integer images of its best value v1 (column c1) and of an upper bound v2 of
 // every other column's value, both still lacking the factor 1/|k_e| (ss = |k_e|^2); a row that the f32
 // arithmetic cannot decide is queued for the f64 kernel.
@@ -133,8 +141,9 @@ __device__ __forceinline__ void decide_row(const MatchParams& p, int unit, int j
   const float rn_e = 1.0f / sqrtf(ss);
   const float y1 = __builtin_bit_cast(float, v1), y2 = (v2 > 0) ? __builtin_bit_cast(float, v2) : 0.f;
   const float cos1 = y1 * rn_e;
-  const bool fragile = !(v1 > 0) || !(ss > 0.f) || !(rn_e < INFINITY) || (y1 - y2) * rn_e <= p.delta ||
-                       fabsf(cos1 - p.threshold) <= p.delta || c1 >= p.budget;
+  bool fragile = !(v1 > 0) || !(ss > 0.f) || !(rn_e < INFINITY) || (y1 - y2) * rn_e <= p.delta ||
+                 fabsf(cos1 - p.threshold) <= p.delta || c1 >= p.budget;
+  if (surely_below(p, (v1 > 0) ? cos1 : 0.f, ss, rn_e)) fragile = false;
   const size_t o = (size_t)unit * p.max_evict + j;
   p.match[o] = (cos1 > p.threshold) ? c1 : -1;
   if (p.sim_out != nullptr) p.sim_out[o] = cos1;
@@ -150,8 +159,9 @@ __device__ __forceinline__ void decide_row_f32(const MatchParams& p, int unit, i
                                                float ss) {
   const float rn_e = 1.0f / sqrtf(ss);
   const float cos1 = y1 * rn_e;
-  const bool fragile = !(y1 > 0.f) || !(ss > 0.f) || !(rn_e < INFINITY) || !((y1 - y2) * rn_e > p.delta) ||
-                       !(fabsf(cos1 - p.threshold) > p.delta) || c1 >= p.budget;
+  bool fragile = !(y1 > 0.f) || !(ss > 0.f) || !(rn_e < INFINITY) || !((y1 - y2) * rn_e > p.delta) ||
+                 !(fabsf(cos1 - p.threshold) > p.delta) || c1 >= p.budget;
+  if (surely_below(p, (y1 <= 0.f) ? 0.f : cos1, ss, rn_e)) fragile = false;
   const size_t o = (size_t)unit * p.max_evict + j;
   p.match[o] = (cos1 > p.threshold) ? c1 : -1;
   if (p.sim_out != nullptr) p.sim_out[o] = cos1;
@@ -702,11 +712,25 @@ __global__ void flag_all_kernel(const int32_t* __restrict__ n_evict, int32_t* fl
 // meet the way the decode splits do: device-scope stores, a ticket, the last one to arrive combines and
 // clears the ticket (the tickets are control words at the head of the workspace, zero between calls).
 constexpr int kExactMaxParts = 8;
-constexpr int kExactResident = 256;     // workgroups of this kernel that run at once (its registers allow one per compute unit)
+constexpr int kExactResident = 512;     // workgroups of the bf16 f64 kernel that run at once (two per compute unit); size of the partial array
+constexpr int kExactResidentGeneric = 256;   // the generic kernel's registers allow one per compute unit
 struct ExactPartial {
   unsigned long long best_bits;
   int best_c, pad;
 };
+
+// The queue counter is a control word that must be zero when the next call starts.  A workgroup adds the
+// number of queued rows it has finished to the exit counter (nothing if it finished none: with an empty queue
+// no workgroup touches either word), and the workgroup whose addition completes the queue clears both.
+// Every workgroup that had work read the queue counter before it started, and the others do nothing whatever
+// value they read, so clearing it then is safe.
+__device__ __forceinline__ void exact_exit(const MatchParams& p, int n_flag, int rows_finished) {
+  if (threadIdx.x == 0 && rows_finished > 0 &&
+      __hip_atomic_fetch_add(p.exact_done, rows_finished, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) + rows_finished == n_flag) {
+    __hip_atomic_store(p.flag_count, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __hip_atomic_store(p.exact_done, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  }
+}
 
 template <typename T, int D>
 __global__ __launch_bounds__(256) void match_exact_kernel(MatchParams p) {
@@ -715,11 +739,12 @@ __global__ __launch_bounds__(256) void match_exact_kernel(MatchParams p) {
   __shared__ int s_bestc[4];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int n_flag = *p.flag_count;
+  int rows_finished = 0;                 // (thread 0) queued rows whose result this workgroup has written
   const T* kall = reinterpret_cast<const T*>(p.k);
   constexpr int EPV = 16 / (int)sizeof(T), NV = D / EPV;
   int parts = 1;
   {
-    const int room = imin((int)gridDim.x, kExactResident);
+    const int room = imin((int)gridDim.x, kExactResidentGeneric);
     while (parts < kExactMaxParts && (long)n_flag * (parts * 2) <= (long)room) parts *= 2;
   }
   for (int w = blockIdx.x; w < n_flag * parts; w += gridDim.x) {
@@ -832,18 +857,11 @@ __global__ __launch_bounds__(256) void match_exact_kernel(MatchParams p) {
       if (finish) {
         p.match[o] = (best > (double)p.threshold) ? best_c : -1;
         if (p.sim_out != nullptr) p.sim_out[o] = (float)best;
+        ++rows_finished;
       }
     }
   }
-  // The queue counter is a control word that must be zero when the next call starts.  Every workgroup has
-  // read it by now (the barrier: also the threads that had no work); the last workgroup to get here clears
-  // it, and the exit counter with it.
-  __syncthreads();
-  if (tid == 0 &&
-      __hip_atomic_fetch_add(p.exact_done, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == (int)gridDim.x - 1) {
-    __hip_atomic_store(p.flag_count, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    __hip_atomic_store(p.exact_done, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-  }
+  exact_exit(p, n_flag, rows_finished);
 }
 
 // ---------------------------------------------------------------------------------------------------
@@ -996,8 +1014,9 @@ __global__ __launch_bounds__(kPfWaves* kWave) void prefill_near_kernel(MatchPara
     return;
   }
   const float cos1 = best * rn_row;
-  const bool fragile = !(best > 0.f) || !(rn_row > 0.f) || !(rn_row < INFINITY) || !((best - second) * rn_row > p.delta) ||
-                       !(fabsf(cos1 - p.threshold) > p.delta);
+  bool fragile = !(best > 0.f) || !(rn_row > 0.f) || !(rn_row < INFINITY) || !((best - second) * rn_row > p.delta) ||
+                 !(fabsf(cos1 - p.threshold) > p.delta);
+  if (surely_below(p, (best <= 0.f) ? 0.f : cos1, rn_row, rn_row)) fragile = false;
   p.match[o] = (cos1 > p.threshold) ? bcol : -1;
   if (p.sim_out != nullptr) p.sim_out[o] = cos1;
   if (fragile) {
@@ -1038,6 +1057,7 @@ __global__ __launch_bounds__(256) void match_exact_bf16_kernel(MatchParams p) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int quad = tid >> 2, sub = tid & 3;
   const int n_flag = *p.flag_count;
+  int rows_finished = 0;                 // (thread 0) queued rows whose result this workgroup has written
   const unsigned char* kall = reinterpret_cast<const unsigned char*>(p.k);
   int parts = 1;
   {
@@ -1179,15 +1199,11 @@ __global__ __launch_bounds__(256) void match_exact_bf16_kernel(MatchParams p) {
       if (finish) {
         p.match[o] = (best > (double)p.threshold) ? best_c : -1;
         if (p.sim_out != nullptr) p.sim_out[o] = (float)best;
+        ++rows_finished;
       }
     }
   }
-  __syncthreads();
-  if (tid == 0 &&
-      __hip_atomic_fetch_add(p.exact_done, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == (int)gridDim.x - 1) {
-    __hip_atomic_store(p.flag_count, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    __hip_atomic_store(p.exact_done, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-  }
+  exact_exit(p, n_flag, rows_finished);
 }
 
 template <int D>
@@ -1372,7 +1388,7 @@ extern "C" keepkv_status keepkv_match(const keepkv_layout* layout, const keepkv_
 
   p.rn_pitch = rn_pitch_of(budget);
   long eb = (long)units * max_evict / 16;      // queued rows are a small fraction of all rows
-  const int exact_blocks = (int)(eb < 64 ? 64 : (eb > 512 ? 512 : eb));   // every workgroup ends with one add to a shared counter
+  const int exact_blocks = (int)(eb < 64 ? 64 : (eb > 512 ? 512 : eb));
   if (max_evict <= kSmallMaxEvict || layout->dtype != KEEPKV_BF16) p.panel = nullptr;   // only the first event's path gathers it
   if (layout->dtype == KEEPKV_BF16) {
     keepkv_status rc;
