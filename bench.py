@@ -253,7 +253,7 @@ def main():
             j1 = min(w.window, j0 + win_chunk)
             kk.score_window(lay, big, q_win[:, :, j0:j1].contiguous() if (j0, j1) != (0, w.window) else q_win,
                             j1 - j0, alpha, -1)
-        if layer < 2 and N <= 16384:
+        if layer < 2 and N <= 32768:
             # the merge-first prefill pass (App. B.4), timed on the same prefill cache; its output is not used
             # further: the timed decode loop continues from the usual (evict-first) event below
             if layer == 0:

@@ -256,7 +256,8 @@ keepkv_status keepkv_prefill_match(const keepkv_layout *layout, const keepkv_cac
  * with the EMA scores (exactly the arithmetic of keepkv_merge: Eq. 7 in its App. A.3 / A.4 form); nothing is
  * dropped.  The receiving slots are written to dst in ascending slot order and dst.len = their number;
  * the usual event (keepkv_select / keepkv_match / keepkv_merge) then brings dst to the budget.  src and dst
- * must not overlap; dst.capacity >= src.capacity; src.capacity <= 16384. */
+ * must not overlap; dst.capacity >= src.capacity; src.capacity <= 32768 (KEEPKV_ERR_UNSUPPORTED beyond; up to
+ * 16384 slots per head the grouping works in LDS, above that in the workspace). */
 keepkv_status keepkv_prefill_merge(const keepkv_layout *layout, const keepkv_cache *src,
                                    keepkv_cache *dst, const int32_t *near, float alpha,
                                    void *workspace, size_t workspace_bytes, void *stream);

@@ -137,6 +137,7 @@ struct PrefillMergePlan {
   size_t keep_off;    // int32 [B*Hkv, capacity]      receiving slots, ascending, -1 behind them
   size_t start_off;   // int32 [B*Hkv, capacity + 1]  CSR row starts
   size_t member_off;  // int32 [B*Hkv, capacity]      absorbed slots grouped by receiver
+  size_t work_off;    // int32 [B*Hkv, 2, capacity padded to 1024]  per-slot work arrays, only above 16384 slots per head
   size_t bytes;
 };
 PrefillMergePlan plan_prefill_merge(const keepkv_layout* L, int capacity);

@@ -482,21 +482,38 @@ __global__ __launch_bounds__(256) void merge_apply_kernel(MergeParams p) {
 // the absorbed slots grouped by receiver (histogram, scan, scatter) and put in ascending slot order inside
 // each group by counting, so the merge sums in a fixed order.  Output in the form merge_apply_kernel reads:
 // keep_idx (receivers, -1 behind them), CSR starts and members, all with pitch `capacity`; dst.len = receivers.
-constexpr int kPrefillMaxSlots = 16384;          // two int arrays of that many words in LDS
-constexpr int kPfItems = kPrefillMaxSlots / kGroupThreads;
+// The two per-slot work arrays live in LDS up to kPrefillLdsSlots slots per head; beyond that (GLOBAL) they are
+// in the workspace and are read and written with device-scope accesses: the same steps, an L2 round trip each.
+constexpr int kPrefillLdsSlots = 16384;          // two int arrays of that many words fit in LDS
+constexpr int kPrefillMaxSlots = 32768;
 
+template <int kPfItems, bool GLOBAL>
 __global__ __launch_bounds__(kGroupThreads) void prefill_group_kernel(
     const int32_t* __restrict__ near, const int32_t* __restrict__ slen, int32_t* __restrict__ keep_idx,
-    int32_t* __restrict__ start, int32_t* __restrict__ members, int32_t* __restrict__ dlen, int capacity) {
-  extern __shared__ int s_pf[];                   // [2][n_pad]
+    int32_t* __restrict__ start, int32_t* __restrict__ members, int32_t* __restrict__ dlen, int capacity,
+    int32_t* __restrict__ gwork) {
+  extern __shared__ int s_pf[];                   // [2][n_pad] (unused when GLOBAL)
   __shared__ int s_wave[kGroupThreads / 64];
+  // (device-scope stores of this workgroup are awaited before a barrier that publishes them to its other threads)
+  auto sync = [] {
+    if constexpr (GLOBAL) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+  };
+  auto ld = [](const int* q, int i) -> int {
+    if constexpr (GLOBAL) return __hip_atomic_load(q + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    else return q[i];
+  };
+  auto st_ = [](int* q, int i, int v) {
+    if constexpr (GLOBAL) __hip_atomic_store(q + i, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    else q[i] = v;
+  };
   const int unit = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int n = min(slen[unit], capacity);
   const int per = (capacity + kGroupThreads - 1) / kGroupThreads;     // slots per thread, a contiguous run (<= kPfItems)
   const int i0 = tid * per;
   const int32_t* nr = near + (size_t)unit * capacity;
-  int* A = s_pf;
-  int* B = s_pf + per * kGroupThreads;
+  int* A = GLOBAL ? gwork + (size_t)unit * 2 * per * kGroupThreads : s_pf;
+  int* B = A + per * kGroupThreads;
 
   // (ancestor << 1) | parity of the distance to it; a slot without a link is its own ancestor
   int link[kPfItems];
@@ -507,10 +524,10 @@ __global__ __launch_bounds__(kGroupThreads) void prefill_group_kernel(
     if (u < per && i < n) {
       const int l = nr[i];
       link[u] = (l >= 0 && l < i) ? l : -1;       // (a link that does not point to an earlier slot is ignored)
-      A[i] = link[u] >= 0 ? ((link[u] << 1) | 1) : (i << 1);
+      st_(A, i, link[u] >= 0 ? ((link[u] << 1) | 1) : (i << 1));
     }
   }
-  __syncthreads();
+  sync();
   int rounds = 0;
   while ((1 << rounds) < n) ++rounds;
   int* cur = A;
@@ -520,12 +537,12 @@ __global__ __launch_bounds__(kGroupThreads) void prefill_group_kernel(
     for (int u = 0; u < kPfItems; ++u) {
       const int i = i0 + u;
       if (u < per && i < n) {
-        const int x = cur[i];
-        const int y = cur[x >> 1];
-        nxt[i] = (y & ~1) | ((x ^ y) & 1);
+        const int x = ld(cur, i);
+        const int y = ld(cur, x >> 1);
+        st_(nxt, i, (y & ~1) | ((x ^ y) & 1));
       }
     }
-    __syncthreads();
+    sync();
     int* t = cur; cur = nxt; nxt = t;
   }
   // absorbed = odd depth; receivers numbered in slot order
@@ -534,7 +551,7 @@ __global__ __launch_bounds__(kGroupThreads) void prefill_group_kernel(
 #pragma unroll
   for (int u = 0; u < kPfItems; ++u) {
     const int i = i0 + u;
-    absorbed[u] = (u < per && i < n) ? (cur[i] & 1) != 0 : false;
+    absorbed[u] = (u < per && i < n) ? (ld(cur, i) & 1) != 0 : false;
     if (u < per && i < n && !absorbed[u]) ++n_recv_mine;
   }
   auto block_exclusive = [&](int mine, int& total) {   // exclusive prefix of `mine` over the threads, and the sum
@@ -559,59 +576,56 @@ __global__ __launch_bounds__(kGroupThreads) void prefill_group_kernel(
   int n_recv = 0;
   int rpos = block_exclusive(n_recv_mine, n_recv);
   // nxt: receiver number of every receiving slot; then cur is free
-  int my_rpos[kPfItems];
 #pragma unroll
   for (int u = 0; u < kPfItems; ++u) {
     const int i = i0 + u;
-    my_rpos[u] = -1;
     if (u < per && i < n && !absorbed[u]) {
-      my_rpos[u] = rpos;
-      nxt[i] = rpos;
+      st_(nxt, i, rpos);
       keep_idx[(size_t)unit * capacity + rpos] = i;
       ++rpos;
     }
   }
   for (int r = n_recv + tid; r < capacity; r += kGroupThreads) keep_idx[(size_t)unit * capacity + r] = -1;
-  __syncthreads();
+  sync();
   int* cnt = cur;                                 // histogram over receiver numbers, then cursors
-  for (int r = tid; r < n_recv; r += kGroupThreads) cnt[r] = 0;
+  for (int r = tid; r < n_recv; r += kGroupThreads) st_(cnt, r, 0);
   int pos[kPfItems];                              // receiver number of this thread's absorbed slots
 #pragma unroll
-  for (int u = 0; u < kPfItems; ++u) pos[u] = absorbed[u] ? nxt[link[u]] : -1;
-  __syncthreads();
+  for (int u = 0; u < kPfItems; ++u) pos[u] = absorbed[u] ? ld(nxt, link[u]) : -1;
+  sync();
 #pragma unroll
   for (int u = 0; u < kPfItems; ++u)
     if (absorbed[u]) atomicAdd(&cnt[pos[u]], 1);
-  __syncthreads();
+  sync();
   // exclusive scan of cnt[0 .. n_recv): thread t owns a contiguous run of receiver numbers
   const int rper = (n_recv + kGroupThreads - 1) / kGroupThreads;
   const int q0 = min(n_recv, tid * rper), q1 = min(n_recv, q0 + rper);
   int mine = 0;
-  for (int r = q0; r < q1; ++r) mine += cnt[r];
+  for (int r = q0; r < q1; ++r) mine += ld(cnt, r);
   int n_abs = 0;
   int run = block_exclusive(mine, n_abs);
   int32_t* st = start + (size_t)unit * (capacity + 1);
   for (int r = q0; r < q1; ++r) {
-    const int c = cnt[r];
+    const int c = ld(cnt, r);
     st[r] = run;
-    cnt[r] = run;                                 // where the group's next member goes
+    st_(cnt, r, run);                             // where the group's next member goes
     run += c;
   }
   for (int r = n_recv + tid; r <= capacity; r += kGroupThreads) st[r] = n_abs;
   if (tid == 0) dlen[unit] = n_recv;
-  __syncthreads();
+  sync();
   int* tmp = nxt;                                 // the receiver numbers are in registers now: members in arrival order
 #pragma unroll
   for (int u = 0; u < kPfItems; ++u)
-    if (absorbed[u]) tmp[atomicAdd(&cnt[pos[u]], 1)] = i0 + u;
-  __syncthreads();                                // cnt[r] is now the end of group r
+    if (absorbed[u]) st_(tmp, atomicAdd(&cnt[pos[u]], 1), i0 + u);
+  sync();                                // cnt[r] is now the end of group r
   int32_t* mem = members + (size_t)unit * capacity;
 #pragma unroll
   for (int u = 0; u < kPfItems; ++u) {
     if (!absorbed[u]) continue;
-    const int g0 = pos[u] > 0 ? cnt[pos[u] - 1] : 0, g1 = cnt[pos[u]];
+    const int g0 = pos[u] > 0 ? ld(cnt, pos[u] - 1) : 0, g1 = ld(cnt, pos[u]);
     int rank = 0;
-    for (int m = g0; m < g1; ++m) rank += tmp[m] < i0 + u;
+    for (int m = g0; m < g1; ++m) rank += ld(tmp, m) < i0 + u;
     mem[g0 + rank] = i0 + u;
   }
 }
@@ -624,7 +638,9 @@ PrefillMergePlan plan_prefill_merge(const keepkv_layout* L, int capacity) {
   pl.keep_off = kWorkspaceHead;
   pl.start_off = pl.keep_off + align_up(units * capacity * sizeof(int32_t), 256);
   pl.member_off = pl.start_off + align_up(units * ((size_t)capacity + 1) * sizeof(int32_t), 256);
-  pl.bytes = pl.member_off + align_up(units * capacity * sizeof(int32_t), 256);
+  pl.work_off = pl.member_off + align_up(units * capacity * sizeof(int32_t), 256);
+  const size_t pad = (size_t)((capacity + kGroupThreads - 1) / kGroupThreads) * kGroupThreads;
+  pl.bytes = pl.work_off + (capacity > kPrefillLdsSlots ? align_up(units * 2 * pad * sizeof(int32_t), 256) : 0);
   return pl;
 }
 
@@ -730,12 +746,19 @@ extern "C" keepkv_status keepkv_prefill_merge(const keepkv_layout* layout, const
   int32_t* members = reinterpret_cast<int32_t*>(reinterpret_cast<char*>(workspace) + pl.member_off);
 
   const int per = (cap + kGroupThreads - 1) / kGroupThreads;
-  const size_t lds = (size_t)2 * per * kGroupThreads * sizeof(int);
-  static const hipError_t attr = hipFuncSetAttribute((const void*)prefill_group_kernel,
-                                                     hipFuncAttributeMaxDynamicSharedMemorySize,
-                                                     2 * kPrefillMaxSlots * (int)sizeof(int));
-  if (attr != hipSuccess) return KEEPKV_ERR_DEVICE;
-  prefill_group_kernel<<<units, kGroupThreads, lds, st>>>(near, src->len, keep, start, members, dst->len, cap);
+  if (cap <= kPrefillLdsSlots) {
+    const size_t lds = (size_t)2 * per * kGroupThreads * sizeof(int);
+    static const hipError_t attr = hipFuncSetAttribute((const void*)prefill_group_kernel<kPrefillLdsSlots / kGroupThreads, false>,
+                                                       hipFuncAttributeMaxDynamicSharedMemorySize,
+                                                       2 * kPrefillLdsSlots * (int)sizeof(int));
+    if (attr != hipSuccess) return KEEPKV_ERR_DEVICE;
+    prefill_group_kernel<kPrefillLdsSlots / kGroupThreads, false><<<units, kGroupThreads, lds, st>>>(
+        near, src->len, keep, start, members, dst->len, cap, nullptr);
+  } else {
+    int32_t* work = reinterpret_cast<int32_t*>(reinterpret_cast<char*>(workspace) + pl.work_off);
+    prefill_group_kernel<kPrefillMaxSlots / kGroupThreads, true><<<units, kGroupThreads, 0, st>>>(
+        near, src->len, keep, start, members, dst->len, cap, work);
+  }
 
   MergeParams p;
   p.sk = src->k; p.sv = src->v; p.svotes = src->votes; p.slog_s = src->log_s; p.sborn = src->born; p.st_obs = src->t_obs; p.slen = src->len;

@@ -204,3 +204,60 @@ def test_prefill_pass_full_size_sampled_units():
     torch.cuda.synchronize()
     print(f"\n[prefill pass, {B} x {H} heads x {N} slots] match {e0.elapsed_time(e1) * 1e3:.0f} us, merge {e1.elapsed_time(e2) * 1e3:.0f} us, "
           f"receivers per head {dl.min()}..{dl.max()}")
+
+
+def test_prefill_pass_at_32768_slots():
+    """The long-context configuration at full size (one sequence, 8 heads, 32768 slots per head; mixture keys
+    with near-duplicates, so most slots have a link): the grouping works in the workspace above 16384 slots.
+    Links of one head against the oracle's full f64 evaluation, of the others on sampled rows; groups and the
+    merged cache of every head against the oracle on the GPU's links."""
+    kk = U.kk()
+    w = W.CONFIGS["long_32k"]
+    T, alpha = U.f32(w.threshold), U.f32(w.alpha)
+    B, H, N = w.batch, w.n_kv_heads, w.context
+    assert N == 32768
+    K, V = W.make_cache(w, 2)
+    lay, c = U.new_cache(w, capacity=N, K=K, V=V)
+    del K, V
+    q_win = np.stack([W.make_query(w, 2, t - 4) for t in range(4)], axis=2)
+    kk.score_window(lay, c, U.to_device(np.ascontiguousarray(q_win), w.dtype), 4, alpha, -1)
+    ws = U.workspace(lay, N, w.budget)
+    near = torch.zeros(B, H, N, dtype=torch.int32, device="cuda")
+    lay2, d = U.new_cache(w, capacity=N)
+    kk.prefill_match(lay, c, T, near, None, ws)
+    kk.prefill_merge(lay, c, d, near, alpha, ws)
+    torch.cuda.synchronize()
+    near_h = near.cpu().numpy()
+    assert (near_h[:, :, 0] == -1).all() and (near_h < np.arange(N)[None, None]).all() and (near_h >= -1).all()
+    assert (near_h >= 0).mean() > 0.5, "the mixture keys should link most slots"
+    oc = U.download(c)
+    dl = d.len.cpu().numpy()
+    rng = np.random.default_rng(5)
+    for h in range(H):
+        k = oc.k[0, h]
+        if h == 0:                                           # every row of one head
+            ref_near, _ = O.prefill_nearest_earlier(k, N, T, True)
+            np.testing.assert_array_equal(near_h[0, h], ref_near)
+        else:                                                # sampled rows: the defining argmax, row by row
+            rn = 1.0 / np.sqrt((k * k).sum(axis=1))
+            for i in rng.integers(1, N, size=64):
+                u = ((k[:i] @ k[i]) * rn[i]) * rn[:i]
+                j = int(u.argmax())
+                assert near_h[0, h, i] == (j if u[j] > T else -1), (h, i)
+        roots, absorbed, tgt = O.prefill_groups(near_h[0, h])
+        nk = roots.shape[0]
+        assert dl[0, h] == nk
+        r = O.merge(k, oc.v[0, h], oc.votes[0, h], oc.log_S[0, h], oc.n_obs[0, h], roots, absorbed, tgt, alpha)
+        np.testing.assert_array_equal(d.votes[0, h, :nk].cpu().numpy(), r.votes)
+        np.testing.assert_array_equal(U.n_obs(d)[0, h, :nk].cpu().numpy(), r.n_obs)
+        assert int(r.votes.sum()) == N
+        ls = d.log_s[0, h, :nk].cpu().numpy()
+        fin = np.isfinite(r.log_S)
+        np.testing.assert_array_equal(np.isfinite(ls), fin)
+        np.testing.assert_allclose(ls[fin], r.log_S[fin], rtol=2e-6, atol=2e-6)
+        err_v = U.storage_err_rows(U.to_host(d.v[0, h, :nk]), r.v, w.dtype)
+        assert err_v.max() <= TOL
+        well = r.guarded | ~np.isfinite(r.ell_bar) | (np.abs(r.ell_bar) >= 4e-3)
+        err_k = U.storage_err_rows(U.to_host(d.k[0, h, :nk]), r.k, w.dtype)
+        assert err_k[well].max() <= TOL
+    print(f"\n[prefill pass, 8 heads x 32768 slots] receivers per head {dl.min()}..{dl.max()}")
