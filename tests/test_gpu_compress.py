@@ -66,7 +66,12 @@ def _run_compress_stagewise(w, lay, c, ws, alpha, threshold, check_merge=True):
     match = torch.full((B, H, cap - w.budget), -9, dtype=torch.int32, device="cuda")
     sim = torch.full((B, H, cap - w.budget), -9.0, dtype=torch.float32, device="cuda")
     kk.match(lay, c, w.budget, keep, evict, n_ev, threshold, match, sim, ws)
+    # without the similarity output, rows whose best value is safely below the threshold skip the f64 re-check:
+    # the targets must not depend on it
+    match_nosim = torch.full_like(match, -9)
+    kk.match(lay, c, w.budget, keep, evict, n_ev, threshold, match_nosim, None, ws)
     torch.cuda.synchronize()
+    assert torch.equal(match, match_nosim)
     match_h, sim_h = match.cpu().numpy(), sim.cpu().numpy()
     n_matched = 0
     for b in range(B):

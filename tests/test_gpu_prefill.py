@@ -62,7 +62,10 @@ def test_prefill_match_and_merge_match_oracle(name, w, T):
     near = torch.full((B, H, N), -7, dtype=torch.int32, device="cuda")
     sim = torch.full((B, H, N), -9.0, dtype=torch.float32, device="cuda")
     kk.prefill_match(lay, c, T, near, sim, ws)
+    near_nosim = torch.full_like(near, -7)               # (rows safely below the threshold skip the f64 re-check then)
+    kk.prefill_match(lay, c, T, near_nosim, None, ws)
     torch.cuda.synchronize()
+    assert torch.equal(near, near_nosim)
     oc = U.download(c)
     near_h, sim_h = near.cpu().numpy(), sim.cpu().numpy()
     exact = w.dtype == "bf16"
