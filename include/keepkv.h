@@ -237,6 +237,33 @@ keepkv_status keepkv_merge(const keepkv_layout *layout, const keepkv_cache *src,
                            const int32_t *match, float alpha, int64_t *dropped_votes,
                            void *workspace, size_t workspace_bytes, void *stream);
 
+/* The steady-state event without rewriting the cache (Alg. 1, same selection, matching and merging as the
+ * calls above; only where the results are stored differs).  The cache is used in place: its live slots are
+ * not in age order.  order (DEVICE int32 [B, Hkv, budget], in/out, owned by the caller) lists the slots below
+ * `budget` from the oldest token to the newest; the slots from `budget` to len-1 (appended since the last
+ * event) follow in slot order.  It starts as 0..budget-1 for a cache that keepkv_merge has just written.
+ *
+ * keepkv_select_aged is keepkv_select on that age order: the first n_sink and the last n_recent tokens by
+ * age are protected, and keep_idx / evict_idx receive SLOT numbers listed from oldest to newest (so that
+ * "lowest position wins ties" in keepkv_match and the summation order of the merge are those of a cache kept
+ * in age order).  keepkv_match is then called as usual.
+ *
+ * keepkv_merge_inplace applies the merge of keepkv_merge to the cache itself: a retained slot that absorbs
+ * evicted slots is overwritten with the merged token, all other retained slots below `budget` are not touched,
+ * the retained tokens at or beyond `budget` are moved into the slots that evicted tokens leave below `budget`
+ * (exactly as many), `order` is rewritten accordingly and len = number of retained slots (= budget); decode
+ * steps then append behind them as before.  Votes of unmatched evicted slots go to dropped_votes (may be NULL).
+ * Heads with n_evict == 0 are left as they are.  capacity - budget <= 256 (KEEPKV_ERR_UNSUPPORTED beyond:
+ * use keepkv_merge).  The merged values are bit for bit those keepkv_merge would write. */
+keepkv_status keepkv_select_aged(const keepkv_layout *layout, const keepkv_cache *cache,
+                                 const int32_t *order, int32_t budget, int32_t n_sink, int32_t n_recent,
+                                 float alpha, int32_t *keep_idx, int32_t *evict_idx, int32_t *n_evict,
+                                 void *workspace, size_t workspace_bytes, void *stream);
+keepkv_status keepkv_merge_inplace(const keepkv_layout *layout, keepkv_cache *cache, int32_t *order,
+                                   int32_t budget, const int32_t *keep_idx, const int32_t *evict_idx,
+                                   const int32_t *n_evict, const int32_t *match, float alpha,
+                                   int64_t *dropped_votes, void *stream);
+
 /* Merge-first prefill policy, first half (Sec. 3.3.2, last sentence; App. B.4 "Prefill's Merge Policy":
  * during prefill, merge by key similarity first and apply the eviction strategy afterwards).  For every
  * live slot i > 0 of every (b, h): the EARLIER slot j < i of highest key cosine similarity

@@ -59,6 +59,10 @@ _lib.keepkv_match.argtypes = [C.POINTER(_Layout), C.POINTER(_Cache), C.c_int32, 
                               _P, _P, _P, C.c_size_t, _P]
 _lib.keepkv_merge.argtypes = [C.POINTER(_Layout), C.POINTER(_Cache), C.POINTER(_Cache), C.c_int32, _P, _P, _P,
                               _P, C.c_float, _P, _P, C.c_size_t, _P]
+_lib.keepkv_select_aged.argtypes = [C.POINTER(_Layout), C.POINTER(_Cache), _P, C.c_int32, C.c_int32, C.c_int32, C.c_float,
+                                    _P, _P, _P, _P, C.c_size_t, _P]
+_lib.keepkv_merge_inplace.argtypes = [C.POINTER(_Layout), C.POINTER(_Cache), _P, C.c_int32, _P, _P, _P, _P, C.c_float,
+                                      _P, _P]
 _lib.keepkv_prefill_match.argtypes = [C.POINTER(_Layout), C.POINTER(_Cache), C.c_float, _P, _P, _P, C.c_size_t, _P]
 _lib.keepkv_prefill_merge.argtypes = [C.POINTER(_Layout), C.POINTER(_Cache), C.POINTER(_Cache), _P, C.c_float, _P,
                                       C.c_size_t, _P]
@@ -66,14 +70,14 @@ _lib.keepkv_probe_read.argtypes = [_P, C.c_size_t, C.c_int32, _P, _P]
 _lib.keepkv_probe_mfma.argtypes = [C.c_int32, C.c_int32, C.c_int32, _P, C.POINTER(C.c_double), _P]
 _lib.keepkv_decode_plan.argtypes = [C.POINTER(_Layout), C.c_int32, C.POINTER(C.c_int32), C.POINTER(C.c_int32),
                                     C.POINTER(C.c_int32)]
-for _f in ("prefill_match", "prefill_merge", "decode_step_static", "decode_plan", "probe_read", "probe_mfma", "append", "decode_attn", "decode_step", "workspace_init", "score", "score_window", "select",
+for _f in ("select_aged", "merge_inplace", "prefill_match", "prefill_merge", "decode_step_static", "decode_plan", "probe_read", "probe_mfma", "append", "decode_attn", "decode_step", "workspace_init", "score", "score_window", "select",
            "select_by_key", "match",
            "merge"):
     getattr(_lib, "keepkv_" + _f).restype = C.c_int
 
 EXPORTS = ["keepkv_strerror", "keepkv_version", "keepkv_workspace_bytes", "keepkv_workspace_init", "keepkv_decode_plan",
            "keepkv_append", "keepkv_decode_attn", "keepkv_decode_step", "keepkv_decode_step_static", "keepkv_score", "keepkv_score_window", "keepkv_select",
-           "keepkv_select_by_key", "keepkv_match", "keepkv_merge", "keepkv_prefill_match", "keepkv_prefill_merge",
+           "keepkv_select_by_key", "keepkv_select_aged", "keepkv_match", "keepkv_merge", "keepkv_merge_inplace", "keepkv_prefill_match", "keepkv_prefill_merge",
            "keepkv_probe_read", "keepkv_probe_mfma"]
 
 
@@ -233,6 +237,20 @@ def match(layout: Layout, cache: Cache, budget: int, keep_idx, evict_idx, n_evic
                              _ptr(n_evict), threshold, _ptr(match_out), _ptr(sim_out), _ptr(workspace),
                              0 if workspace is None else workspace.numel() * workspace.element_size(),
                              _stream()), "keepkv_match")
+
+
+def select_aged(layout: Layout, cache: Cache, order, budget: int, n_sink: int, n_recent: int, alpha: float,
+                keep_idx, evict_idx, n_evict, workspace) -> None:
+    _check(_lib.keepkv_select_aged(C.byref(layout.c()), C.byref(cache.c()), _ptr(order), budget, n_sink, n_recent, alpha,
+                                   _ptr(keep_idx), _ptr(evict_idx), _ptr(n_evict), _ptr(workspace), _nbytes(workspace),
+                                   _stream()), "keepkv_select_aged")
+
+
+def merge_inplace(layout: Layout, cache: Cache, order, budget: int, keep_idx, evict_idx, n_evict, match_in,
+                  alpha: float, dropped_votes) -> None:
+    _check(_lib.keepkv_merge_inplace(C.byref(layout.c()), C.byref(cache.c()), _ptr(order), budget, _ptr(keep_idx),
+                                     _ptr(evict_idx), _ptr(n_evict), _ptr(match_in), alpha, _ptr(dropped_votes), _stream()),
+           "keepkv_merge_inplace")
 
 
 def prefill_match(layout: Layout, cache: Cache, threshold: float, near, sim_out, workspace) -> None:

@@ -268,6 +268,119 @@ __device__ __forceinline__ double group_sum_f64(double x) {
   return x;
 }
 
+// One retained slot c (row kc / vc, votes p_c, ln S ls_c, observation count n_c) absorbs the nm evicted slots
+// listed in mem, in list order: the multi-way merge of App. A.3 / A.4 with weights p * s_hat formed in f64
+// relative to the group's largest ln s_hat, rows accumulated in f32 and scaled once.  Called by all LPS lanes
+// of the position's lane group (lane `sub` holds 16 bytes of each row; gbase = the group's first lane in the
+// wavefront).  Shared by the compacting and the in-place kernels, so both produce the same bits.
+struct MergedRow {
+  uint4 k, v;
+  int32_t votes;
+  float log_s;
+  int32_t n_r;       // observation count of the merged slot
+};
+template <typename T, int D>
+__device__ __forceinline__ MergedRow merge_position(const MergeParams& p, size_t sbase, int t_head, int c, const uint4& kc,
+                                                    const uint4& vc, int p_c, float ls_c, int n_c, const int32_t* mem,
+                                                    int nm, int sub, int gbase) {
+  constexpr int EPL = 16 / (int)sizeof(T), LPS = D / EPL;
+  const uint4* sk = reinterpret_cast<const uint4*>(p.sk);
+  const uint4* sv = reinterpret_cast<const uint4*>(p.sv);
+  const double E_c = log_s_hat(ls_c, n_c, p.ln_alpha);
+
+  // pass 1 over the scalars: largest ln s_hat and total votes of the group
+  double mx = E_c;
+  long long P = p_c;
+  for (int i0 = 0; i0 < nm; i0 += LPS) {
+    const int i = i0 + sub;
+    double E = -INFINITY;
+    int pv = 0;
+    if (i < nm) {
+      const int s = mem[i];
+      pv = p.svotes[sbase + s];
+      E = log_s_hat(p.slog_s[sbase + s], t_head - p.sborn[sbase + s], p.ln_alpha);
+    }
+    mx = fmax(mx, group_max_f64<LPS>(E));
+    P += (long long)group_sum_f64<LPS>((double)pv);
+  }
+  const bool none_seen = !(mx > -INFINITY);
+
+  // pass 2: weights, weighted sums of rows
+  float ak[EPL], av[EPL];
+  auto fma_row = [&](const uint4& x, float w, float* a) {
+    if constexpr (sizeof(T) == 2) {
+      const uint32_t u[4] = {x.x, x.y, x.z, x.w};
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        a[2 * q] = fmaf(w, bf16_lo(u[q]), a[2 * q]);
+        a[2 * q + 1] = fmaf(w, bf16_hi(u[q]), a[2 * q + 1]);
+      }
+    } else {
+      const uint32_t u[4] = {x.x, x.y, x.z, x.w};
+#pragma unroll
+      for (int q = 0; q < 4; ++q) a[q] = fmaf(w, __builtin_bit_cast(float, u[q]), a[q]);
+    }
+  };
+#pragma unroll
+  for (int e = 0; e < EPL; ++e) ak[e] = av[e] = 0.f;
+  const double w_c = none_seen ? (double)p_c : (E_c > -INFINITY ? (double)p_c * exp(E_c - mx) : 0.0);
+  double W = w_c, WE = (w_c > 0.0 && !none_seen) ? w_c * E_c : 0.0;
+  fma_row(kc, (float)w_c, ak);
+  fma_row(vc, (float)w_c, av);
+  for (int i0 = 0; i0 < nm; i0 += LPS) {
+    const int i = i0 + sub;
+    double w = 0.0, E = 0.0;
+    int s = c;
+    if (i < nm) {
+      s = mem[i];
+      const int pv = p.svotes[sbase + s];
+      E = log_s_hat(p.slog_s[sbase + s], t_head - p.sborn[sbase + s], p.ln_alpha);
+      w = none_seen ? (double)pv : (E > -INFINITY ? (double)pv * exp(E - mx) : 0.0);
+    }
+    W += group_sum_f64<LPS>(w);
+    WE += group_sum_f64<LPS>((w > 0.0 && !none_seen) ? w * E : 0.0);
+    const float wf = (float)w;
+    const int cnt = min(LPS, nm - i0);
+    for (int q = 0; q < cnt; ++q) {
+      const int sq = __shfl(s, gbase + q);
+      const float wq = __shfl(wf, gbase + q);
+      fma_row(sk[(sbase + sq) * LPS + sub], wq, ak);
+      fma_row(sv[(sbase + sq) * LPS + sub], wq, av);
+    }
+  }
+
+  double kscale, L = -INFINITY;
+  int n_r = 0;
+  float out_log_s = -INFINITY;
+  if (none_seen) {
+    kscale = 1.0 / W;                            // W = P: vote-weighted mean, stays unobserved
+  } else {
+    L = mx + log(W / (double)P);                 // ln(sum p s_hat / sum p)
+    const double ell_bar = WE / W;               // sum w ln s_hat / W
+    kscale = (fabs(ell_bar) < kEllGuard) ? 1.0 / W : (L / ell_bar) / W;
+    n_r = n_c > 1 ? n_c : 1;
+    double ls = L;
+    if (p.ln_alpha > -INFINITY) ls += log(-expm1((double)n_r * p.ln_alpha));
+    out_log_s = (float)ls;
+  }
+  const float fk = (float)kscale, fv = (float)(1.0 / W);
+  uint4 ok, ov;
+  if constexpr (sizeof(T) == 2) {
+    ok.x = pack_bf16x2(ak[0] * fk, ak[1] * fk); ok.y = pack_bf16x2(ak[2] * fk, ak[3] * fk);
+    ok.z = pack_bf16x2(ak[4] * fk, ak[5] * fk); ok.w = pack_bf16x2(ak[6] * fk, ak[7] * fk);
+    ov.x = pack_bf16x2(av[0] * fv, av[1] * fv); ov.y = pack_bf16x2(av[2] * fv, av[3] * fv);
+    ov.z = pack_bf16x2(av[4] * fv, av[5] * fv); ov.w = pack_bf16x2(av[6] * fv, av[7] * fv);
+  } else {
+    ok.x = __builtin_bit_cast(uint32_t, ak[0] * fk); ok.y = __builtin_bit_cast(uint32_t, ak[1] * fk);
+    ok.z = __builtin_bit_cast(uint32_t, ak[2] * fk); ok.w = __builtin_bit_cast(uint32_t, ak[3] * fk);
+    ov.x = __builtin_bit_cast(uint32_t, av[0] * fv); ov.y = __builtin_bit_cast(uint32_t, av[1] * fv);
+    ov.z = __builtin_bit_cast(uint32_t, av[2] * fv); ov.w = __builtin_bit_cast(uint32_t, av[3] * fv);
+  }
+  MergedRow out;
+  out.k = ok; out.v = ov; out.votes = (int32_t)P; out.log_s = out_log_s; out.n_r = n_r;
+  return out;
+}
+
 // DIRECT (few evictable slots per head, the steady state): no CSR list has been built; the workgroup reads
 // the head's match and evict lists into LDS and every lane group picks its own members out of them, in list
 // (= ascending slot) order, so the summation order is the CSR variant's.  The first workgroup of a head
@@ -374,102 +487,13 @@ __global__ __launch_bounds__(256) void merge_apply_kernel(MergeParams p) {
   }
 
   const int32_t* mem = DIRECT ? s_mem[threadIdx.x / LPS] : p.members + sbase + m0;
-  const double E_c = log_s_hat(ls_c, n_c, p.ln_alpha);
-
-  // pass 1 over the scalars: largest ln s_hat and total votes of the group
-  double mx = E_c;
-  long long P = p_c;
-  for (int i0 = 0; i0 < nm; i0 += LPS) {
-    const int i = i0 + sub;
-    double E = -INFINITY;
-    int pv = 0;
-    if (i < nm) {
-      const int s = mem[i];
-      pv = p.svotes[sbase + s];
-      E = log_s_hat(p.slog_s[sbase + s], t_head - p.sborn[sbase + s], p.ln_alpha);
-    }
-    mx = fmax(mx, group_max_f64<LPS>(E));
-    P += (long long)group_sum_f64<LPS>((double)pv);
-  }
-  const bool none_seen = !(mx > -INFINITY);
-
-  // pass 2: weights, weighted sums of rows
-  float ak[EPL], av[EPL];
-  auto fma_row = [&](const uint4& x, float w, float* a) {
-    if constexpr (sizeof(T) == 2) {
-      const uint32_t u[4] = {x.x, x.y, x.z, x.w};
-#pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        a[2 * q] = fmaf(w, bf16_lo(u[q]), a[2 * q]);
-        a[2 * q + 1] = fmaf(w, bf16_hi(u[q]), a[2 * q + 1]);
-      }
-    } else {
-      const uint32_t u[4] = {x.x, x.y, x.z, x.w};
-#pragma unroll
-      for (int q = 0; q < 4; ++q) a[q] = fmaf(w, __builtin_bit_cast(float, u[q]), a[q]);
-    }
-  };
-#pragma unroll
-  for (int e = 0; e < EPL; ++e) ak[e] = av[e] = 0.f;
-  const double w_c = none_seen ? (double)p_c : (E_c > -INFINITY ? (double)p_c * exp(E_c - mx) : 0.0);
-  double W = w_c, WE = (w_c > 0.0 && !none_seen) ? w_c * E_c : 0.0;
-  fma_row(kc, (float)w_c, ak);
-  fma_row(vc, (float)w_c, av);
-  for (int i0 = 0; i0 < nm; i0 += LPS) {
-    const int i = i0 + sub;
-    double w = 0.0, E = 0.0;
-    int s = c;
-    if (i < nm) {
-      s = mem[i];
-      const int pv = p.svotes[sbase + s];
-      E = log_s_hat(p.slog_s[sbase + s], t_head - p.sborn[sbase + s], p.ln_alpha);
-      w = none_seen ? (double)pv : (E > -INFINITY ? (double)pv * exp(E - mx) : 0.0);
-    }
-    W += group_sum_f64<LPS>(w);
-    WE += group_sum_f64<LPS>((w > 0.0 && !none_seen) ? w * E : 0.0);
-    const float wf = (float)w;
-    const int cnt = min(LPS, nm - i0);
-    for (int q = 0; q < cnt; ++q) {
-      const int sq = __shfl(s, gbase + q);
-      const float wq = __shfl(wf, gbase + q);
-      fma_row(sk[(sbase + sq) * LPS + sub], wq, ak);
-      fma_row(sv[(sbase + sq) * LPS + sub], wq, av);
-    }
-  }
-
-  double kscale, L = -INFINITY;
-  int n_r = 0;
-  float out_log_s = -INFINITY;
-  if (none_seen) {
-    kscale = 1.0 / W;                            // W = P: vote-weighted mean, stays unobserved
-  } else {
-    L = mx + log(W / (double)P);                 // ln(sum p s_hat / sum p)
-    const double ell_bar = WE / W;               // sum w ln s_hat / W
-    kscale = (fabs(ell_bar) < kEllGuard) ? 1.0 / W : (L / ell_bar) / W;
-    n_r = n_c > 1 ? n_c : 1;
-    double ls = L;
-    if (p.ln_alpha > -INFINITY) ls += log(-expm1((double)n_r * p.ln_alpha));
-    out_log_s = (float)ls;
-  }
-  const float fk = (float)kscale, fv = (float)(1.0 / W);
-  uint4 ok, ov;
-  if constexpr (sizeof(T) == 2) {
-    ok.x = pack_bf16x2(ak[0] * fk, ak[1] * fk); ok.y = pack_bf16x2(ak[2] * fk, ak[3] * fk);
-    ok.z = pack_bf16x2(ak[4] * fk, ak[5] * fk); ok.w = pack_bf16x2(ak[6] * fk, ak[7] * fk);
-    ov.x = pack_bf16x2(av[0] * fv, av[1] * fv); ov.y = pack_bf16x2(av[2] * fv, av[3] * fv);
-    ov.z = pack_bf16x2(av[4] * fv, av[5] * fv); ov.w = pack_bf16x2(av[6] * fv, av[7] * fv);
-  } else {
-    ok.x = __builtin_bit_cast(uint32_t, ak[0] * fk); ok.y = __builtin_bit_cast(uint32_t, ak[1] * fk);
-    ok.z = __builtin_bit_cast(uint32_t, ak[2] * fk); ok.w = __builtin_bit_cast(uint32_t, ak[3] * fk);
-    ov.x = __builtin_bit_cast(uint32_t, av[0] * fv); ov.y = __builtin_bit_cast(uint32_t, av[1] * fv);
-    ov.z = __builtin_bit_cast(uint32_t, av[2] * fv); ov.w = __builtin_bit_cast(uint32_t, av[3] * fv);
-  }
-  dk[(dbase + r) * LPS + sub] = ok;
-  dv[(dbase + r) * LPS + sub] = ov;
+  const MergedRow mr = merge_position<T, D>(p, sbase, t_head, c, kc, vc, p_c, ls_c, n_c, mem, nm, sub, gbase);
+  dk[(dbase + r) * LPS + sub] = mr.k;
+  dv[(dbase + r) * LPS + sub] = mr.v;
   if (sub == 0) {
-    p.dvotes[dbase + r] = (int32_t)P;
-    p.dlog_s[dbase + r] = out_log_s;
-    p.dborn[dbase + r] = t_head - n_r;
+    p.dvotes[dbase + r] = mr.votes;
+    p.dlog_s[dbase + r] = mr.log_s;
+    p.dborn[dbase + r] = t_head - mr.n_r;
   }
 }
 
@@ -630,6 +654,175 @@ __global__ __launch_bounds__(kGroupThreads) void prefill_group_kernel(
   }
 }
 
+
+// ---------------------------------------------------------------------------------------------------
+// In-place event (the steady state without rewriting the cache).  The live slots are not kept in age order:
+// the caller's `order` lists the slots below `budget` from oldest to newest and the slots from `budget` on
+// (appended since the last event) follow in slot order.  The merged slots are rewritten where they are, the
+// retained slots that absorb nothing are not touched at all, and the retained tokens of the append region move
+// into the slots that evicted tokens leave below `budget` (there are exactly as many), so that afterwards the
+// slots below `budget` are all live, len = budget, and decode steps append behind them as before.
+//
+// merge_inplace_kernel, one workgroup per head: the distinct targets of the head's match list (the first
+// occurrence of each, found by comparing list entries pairwise: at most kDirectMaxEvict of them) are dealt to
+// the lane groups; a group collects its members from the lists in list order, as the compacting kernel does,
+// and writes the merged row over the retained slot.  Nothing that any group reads (its own retained row, evicted
+// rows) is written by another group.
+template <typename T, int D>
+__global__ __launch_bounds__(256) void merge_inplace_kernel(MergeParams p) {
+  constexpr int EPL = 16 / (int)sizeof(T), LPS = D / EPL, GPB = 256 / LPS;
+  __shared__ int s_match[kDirectMaxEvict], s_evict[kDirectMaxEvict], s_tgt[kDirectMaxEvict];
+  __shared__ int s_mem[GPB][kDirectMaxEvict];
+  __shared__ int s_wcnt[4];
+  __shared__ long long s_drop;
+  const int unit = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int sub = tid % LPS, grp = tid / LPS, gbase = lane - sub;
+  const int t_head = p.st_obs[unit];
+  const int n_ev = min(p.n_evict[unit], kDirectMaxEvict);
+  if (n_ev <= 0) return;                              // uniform over the workgroup
+  const size_t sbase = (size_t)unit * p.scap;
+  int mt = -1, ev = 0;
+  if (tid < n_ev) {
+    mt = p.match[(size_t)unit * p.max_evict + tid];
+    ev = p.evict_idx[(size_t)unit * p.max_evict + tid];
+    s_match[tid] = mt;
+    s_evict[tid] = ev;
+  }
+  if (tid == 0) s_drop = 0;
+  __syncthreads();
+  if (p.dropped_votes != nullptr && tid < n_ev && mt < 0) {
+    const long long drop = p.svotes[sbase + ev];
+    if (drop != 0) atomicAdd((unsigned long long*)&s_drop, (unsigned long long)drop);
+  }
+  bool leader = tid < n_ev && mt >= 0 && mt < p.budget;
+  if (leader)
+    for (int j = 0; j < tid; ++j)
+      if (s_match[j] == mt) {
+        leader = false;
+        break;
+      }
+  const unsigned long long lm = __ballot(leader);
+  if (lane == 0) s_wcnt[wave] = __popcll(lm);
+  __syncthreads();
+  int before = 0, nt = 0;
+  for (int w = 0; w < 4; ++w) {
+    if (w < wave) before += s_wcnt[w];
+    nt += s_wcnt[w];
+  }
+  if (leader) s_tgt[before + __popcll(lm & ((1ull << lane) - 1ull))] = mt;
+  __syncthreads();
+  if (tid == 0 && p.dropped_votes != nullptr && s_drop != 0) p.dropped_votes[unit] += s_drop;
+
+  const uint4* sk = reinterpret_cast<const uint4*>(p.sk);
+  const uint4* sv = reinterpret_cast<const uint4*>(p.sv);
+  uint4* dk = reinterpret_cast<uint4*>(p.dk);
+  uint4* dv = reinterpret_cast<uint4*>(p.dv);
+  for (int t0 = 0; t0 < nt; t0 += GPB) {              // uniform trip count: a group without a target repeats the first one and writes nothing
+    const bool active = t0 + grp < nt;
+    const int r = s_tgt[active ? t0 + grp : 0];
+    const int c = p.keep_idx[(size_t)unit * p.budget + r];
+    const size_t at = sbase + max(c, 0);
+    const uint4 kc = sk[at * LPS + sub], vc = sv[at * LPS + sub];
+    const int p_c = p.svotes[at];
+    const float ls_c = p.slog_s[at];
+    const int n_c = t_head - p.sborn[at];
+    int* mine = s_mem[grp];
+    int m1 = 0;
+    for (int i0 = 0; i0 < n_ev; i0 += LPS) {
+      const bool hit = i0 + sub < n_ev && s_match[i0 + sub] == r;
+      const unsigned long long wave_hits = __ballot(hit);
+      const unsigned int hits = (unsigned int)(wave_hits >> gbase) & (unsigned int)((1ull << LPS) - 1ull);   // LPS <= 32
+      if (hit) mine[m1 + __popc(hits & ((1u << sub) - 1u))] = s_evict[i0 + sub];
+      m1 += __popc(hits);
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");   // the list is read back by this group's own lanes
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    const MergedRow mr = merge_position<T, D>(p, sbase, t_head, c, kc, vc, p_c, ls_c, n_c, mine, m1, sub, gbase);
+    if (active && c >= 0) {
+      dk[at * LPS + sub] = mr.k;
+      dv[at * LPS + sub] = mr.v;
+      if (sub == 0) {
+        p.dvotes[at] = mr.votes;
+        p.dlog_s[at] = mr.log_s;
+        p.dborn[at] = t_head - mr.n_r;
+      }
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");   // the member list is rewritten in the next round
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+  }
+}
+
+// move_retained_kernel, one workgroup per head, after merge_inplace_kernel has completed: the k-th retained
+// token that lives at or beyond `budget` (in keep-list order) is copied into the k-th evicted slot below
+// `budget` (in evict-list order), `order` is rewritten to the keep list with the moved tokens at their new
+// slots, and len becomes the number of retained tokens.  Sources and destinations are disjoint.
+template <typename T, int D>
+__global__ __launch_bounds__(256) void move_retained_kernel(MergeParams p, int32_t* __restrict__ order) {
+  constexpr int EPL = 16 / (int)sizeof(T), LPS = D / EPL, GPB = 256 / LPS;
+  __shared__ int s_hole[kDirectMaxEvict], s_mover[kDirectMaxEvict];
+  __shared__ int s_wcnt[4];
+  const int unit = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int sub = tid % LPS, grp = tid / LPS;
+  const int n_ev = min(p.n_evict[unit], kDirectMaxEvict);
+  if (n_ev <= 0) return;                              // nothing was evicted: slots, order and len stay
+  const size_t sbase = (size_t)unit * p.scap;
+  int32_t* ord = order + (size_t)unit * p.budget;
+  const int32_t* keep = p.keep_idx + (size_t)unit * p.budget;
+  // counts below the calling thread and in total, over the workgroup (two barriers)
+  auto compact = [&](bool flag, int& total) -> int {
+    const unsigned long long m = __ballot(flag);
+    __syncthreads();                                  // the previous use of s_wcnt is over
+    if (lane == 0) s_wcnt[wave] = __popcll(m);
+    __syncthreads();
+    int before = 0;
+    total = 0;
+    for (int w = 0; w < 4; ++w) {
+      if (w < wave) before += s_wcnt[w];
+      total += s_wcnt[w];
+    }
+    return before + __popcll(m & ((1ull << lane) - 1ull));
+  };
+  int n_hole = 0;
+  {
+    const int ev = tid < n_ev ? p.evict_idx[(size_t)unit * p.max_evict + tid] : p.budget;
+    const bool hole = tid < n_ev && ev >= 0 && ev < p.budget;
+    const int at = compact(hole, n_hole);
+    if (hole) s_hole[at] = ev;
+  }
+  int n_mover = 0;
+  for (int r0 = 0; r0 < p.budget; r0 += 256) {        // uniform trip count
+    const int r = r0 + tid;
+    const int c = r < p.budget ? keep[r] : -1;
+    const bool mover = c >= p.budget;
+    int cnt = 0;
+    const int at = n_mover + compact(mover, cnt);
+    if (mover && at < kDirectMaxEvict) s_mover[at] = r;
+    if (r < p.budget && !mover && c >= 0) ord[r] = c;
+    n_mover += cnt;
+  }
+  __syncthreads();
+  const int n_move = min(min(n_mover, n_hole), kDirectMaxEvict);
+  const uint4* sk = reinterpret_cast<const uint4*>(p.sk);
+  const uint4* sv = reinterpret_cast<const uint4*>(p.sv);
+  uint4* dk = reinterpret_cast<uint4*>(p.dk);
+  uint4* dv = reinterpret_cast<uint4*>(p.dv);
+  for (int k = grp; k < n_move; k += GPB) {
+    const int r = s_mover[k];
+    const size_t src = sbase + keep[r], dst = sbase + s_hole[k];
+    dk[dst * LPS + sub] = sk[src * LPS + sub];
+    dv[dst * LPS + sub] = sv[src * LPS + sub];
+    if (sub == 0) {
+      p.dvotes[dst] = p.svotes[src];
+      p.dlog_s[dst] = p.slog_s[src];
+      p.dborn[dst] = p.sborn[src];
+      ord[r] = s_hole[k];
+    }
+  }
+  if (tid == 0) p.dlen[unit] = p.slen[unit] - n_ev;
+}
+
 }  // namespace
 
 PrefillMergePlan plan_prefill_merge(const keepkv_layout* L, int capacity) {
@@ -718,6 +911,51 @@ extern "C" keepkv_status keepkv_merge(const keepkv_layout* layout, const keepkv_
     } else {
       if (direct) merge_apply_kernel<float, 64, true><<<grid, 256, 0, st>>>(p);
       else merge_apply_kernel<float, 64, false><<<grid, 256, 0, st>>>(p);
+    }
+  }
+  return launch_status();
+}
+
+extern "C" keepkv_status keepkv_merge_inplace(const keepkv_layout* layout, keepkv_cache* cache, int32_t* order,
+                                              int32_t budget, const int32_t* keep_idx, const int32_t* evict_idx,
+                                              const int32_t* n_evict, const int32_t* match, float alpha,
+                                              int64_t* dropped_votes, void* stream) {
+  using namespace kk;
+  if (!layout_ok(layout) || !cache_ok(cache) || !order || !keep_idx || !n_evict) return KEEPKV_ERR_INVALID_ARG;
+  if (!units_supported(layout)) return KEEPKV_ERR_UNSUPPORTED;
+  if (budget < 1 || budget > cache->capacity) return KEEPKV_ERR_INVALID_ARG;
+  const int max_evict = cache->capacity - budget;
+  if (max_evict > 0 && (!evict_idx || !match)) return KEEPKV_ERR_INVALID_ARG;
+  if (!(alpha >= 0.f && alpha < 1.f)) return KEEPKV_ERR_INVALID_ARG;
+  if (!aligned16(cache->k) || !aligned16(cache->v)) return KEEPKV_ERR_INVALID_ARG;
+  if (layout->head_dim != 64 && layout->head_dim != 128) return KEEPKV_ERR_UNSUPPORTED;
+  if (budget > kMaxBudget || max_evict > kDirectMaxEvict) return KEEPKV_ERR_UNSUPPORTED;
+  if (max_evict == 0) return KEEPKV_OK;                // nothing can have been evicted
+  const unsigned units = (unsigned)(layout->batch * layout->n_kv_heads);
+  hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+  MergeParams p;
+  p.sk = cache->k; p.sv = cache->v; p.svotes = cache->votes; p.slog_s = cache->log_s; p.sborn = cache->born; p.st_obs = cache->t_obs; p.slen = cache->len;
+  p.dk = cache->k; p.dv = cache->v; p.dvotes = cache->votes; p.dlog_s = cache->log_s; p.dborn = cache->born; p.dt_obs = cache->t_obs; p.dlen = cache->len;
+  p.keep_idx = keep_idx; p.n_evict = n_evict; p.start = nullptr; p.members = nullptr;
+  p.match = match; p.evict_idx = evict_idx; p.dropped_votes = dropped_votes;
+  p.scap = cache->capacity; p.dcap = cache->capacity; p.budget = budget; p.max_evict = max_evict;
+  p.write_len = 0;
+  p.ln_alpha = alpha > 0.f ? log((double)alpha) : -INFINITY;
+  if (layout->dtype == KEEPKV_BF16) {
+    if (layout->head_dim == 128) {
+      merge_inplace_kernel<uint16_t, 128><<<units, 256, 0, st>>>(p);
+      move_retained_kernel<uint16_t, 128><<<units, 256, 0, st>>>(p, order);
+    } else {
+      merge_inplace_kernel<uint16_t, 64><<<units, 256, 0, st>>>(p);
+      move_retained_kernel<uint16_t, 64><<<units, 256, 0, st>>>(p, order);
+    }
+  } else {
+    if (layout->head_dim == 128) {
+      merge_inplace_kernel<float, 128><<<units, 256, 0, st>>>(p);
+      move_retained_kernel<float, 128><<<units, 256, 0, st>>>(p, order);
+    } else {
+      merge_inplace_kernel<float, 64><<<units, 256, 0, st>>>(p);
+      move_retained_kernel<float, 64><<<units, 256, 0, st>>>(p, order);
     }
   }
   return launch_status();

@@ -68,12 +68,15 @@ __device__ __forceinline__ int rank_in_wave(uint64_t mask) {
 // unused) instead of being formed from the cache's votes and EMA scores.
 // LDSKEYS: the sortable keys of the head live in LDS (capacity * 8 bytes fit) instead of the workspace, so
 // the radix passes and the compaction never leave the CU.
-template <bool EXT, bool LDSKEYS>
+// AGED: the live slots are not in age order.  `order` lists the slots below `budget` from oldest to newest and
+// the slots from `budget` on follow in slot order (tokens appended since the last in-place event); the whole
+// selection runs on the age rank i and reads and reports slot(i), so the lists come out in age order.
+template <bool EXT, bool LDSKEYS, bool AGED>
 __global__ __launch_bounds__(kSelThreads) void select_kernel(
     const float* __restrict__ log_s, const int32_t* __restrict__ born, const int32_t* __restrict__ t_obs,
     const int32_t* __restrict__ votes, const int32_t* __restrict__ len, uint64_t* __restrict__ keys, int32_t* __restrict__ keep_idx,
     int32_t* __restrict__ evict_idx, int32_t* __restrict__ n_evict, int capacity, int budget, int n_sink,
-    int n_recent, double ln_alpha, int n_table) {
+    int n_recent, double ln_alpha, int n_table, const int32_t* __restrict__ order) {
   constexpr int kWaves = kSelThreads / 64;
   __shared__ double s_lnterm[EXT ? 1 : kTermTable];
   __shared__ double s_lnvotes[EXT ? 1 : kVotesTable];
@@ -87,15 +90,23 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   KS_TS(0);
   const size_t base = (size_t)unit * capacity;
+  const int32_t* ord = AGED ? order + (size_t)unit * budget : nullptr;
+  auto slot_of = [&](int i) -> int {              // age rank -> slot
+    if constexpr (AGED) return i < budget ? min(max(ord[i], 0), capacity - 1) : i;   // (clamped: never out of bounds)
+    else return i;
+  };
   const int lo = n_sink;
   // the first four candidate slots of every thread are requested together with the head's length
   int nn[4], pv[4];
   float ls[4];
   uint64_t k_or = 0, k_nand = 0;              // OR of this thread's keys and of their complements
   auto request = [&](int i0) {
+    int sl[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) sl[u] = slot_of(min(i0 + u * kSelThreads, capacity - 1));
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
-      const int i = min(i0 + u * kSelThreads, capacity - 1);
+      const int i = sl[u];
       nn[u] = EXT ? 0 : born[base + i];          // turned into the observation count t_obs - born at its use
       pv[u] = EXT ? 1 : votes[base + i];
       ls[u] = log_s[base + i];
@@ -108,7 +119,7 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(
   int32_t* evict_out = evict_idx + (size_t)unit * (capacity - budget);
 
   if (n <= budget) {
-    for (int i = tid; i < budget; i += kSelThreads) keep_out[i] = (i < n) ? i : -1;
+    for (int i = tid; i < budget; i += kSelThreads) keep_out[i] = (i < n) ? slot_of(i) : -1;
     if (tid == 0) n_evict[unit] = 0;
     return;
   }
@@ -321,8 +332,9 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(
     const uint64_t m = kept_mask(c, eq);
     const int at = kpos + rank_in_wave(m);
     if (i < n) {
-      if ((m >> lane) & 1) keep_out[at] = i;
-      else evict_out[i - at] = i;
+      const int s = slot_of(i);
+      if ((m >> lane) & 1) keep_out[at] = s;
+      else evict_out[i - at] = s;
     }
     kpos += __popcll(m);
   }
@@ -334,10 +346,10 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(
 
 constexpr int kSelLdsKeys = 16384;     // up to this capacity the keys of a head are kept in LDS (128 KB)
 
-template <bool EXT>
+template <bool EXT, bool AGED = false>
 void launch_select(int units, hipStream_t st, const float* log_s, const int32_t* born, const int32_t* t_obs,
                    const int32_t* votes, const int32_t* len, uint64_t* keys, int32_t* keep_idx, int32_t* evict_idx, int32_t* n_evict,
-                   int capacity, int budget, int n_sink, int n_recent, double ln_alpha) {
+                   int capacity, int budget, int n_sink, int n_recent, double ln_alpha, const int32_t* order = nullptr) {
   // counts from which alpha^n is below half an ulp of 1 (n ln alpha <= -40) need no table entry
   int n_table = 0;
   if (!EXT && ln_alpha > -INFINITY && ln_alpha < 0.0) {
@@ -345,16 +357,16 @@ void launch_select(int units, hipStream_t st, const float* log_s, const int32_t*
     n_table = n_zero < (double)kTermTable ? (int)n_zero : kTermTable;
   }
   if (capacity <= kSelLdsKeys) {
-    static const hipError_t attr = hipFuncSetAttribute((const void*)select_kernel<EXT, true>,
+    static const hipError_t attr = hipFuncSetAttribute((const void*)select_kernel<EXT, true, AGED>,
                                                        hipFuncAttributeMaxDynamicSharedMemorySize, kSelLdsKeys * 8);
     (void)attr;                              // a refusal shows up as a launch error
-    select_kernel<EXT, true><<<units, kSelThreads, (size_t)capacity * 8, st>>>(
+    select_kernel<EXT, true, AGED><<<units, kSelThreads, (size_t)capacity * 8, st>>>(
         log_s, born, t_obs, votes, len, keys, keep_idx, evict_idx, n_evict, capacity, budget, n_sink, n_recent, ln_alpha,
-        n_table);
+        n_table, order);
   } else {
-    select_kernel<EXT, false><<<units, kSelThreads, 0, st>>>(
+    select_kernel<EXT, false, AGED><<<units, kSelThreads, 0, st>>>(
         log_s, born, t_obs, votes, len, keys, keep_idx, evict_idx, n_evict, capacity, budget, n_sink, n_recent, ln_alpha,
-        n_table);
+        n_table, order);
   }
 }
 
@@ -386,6 +398,28 @@ extern "C" keepkv_status keepkv_select(const keepkv_layout* layout, const keepkv
       cache->log_s, cache->born, cache->t_obs, cache->votes, cache->len,
       reinterpret_cast<uint64_t*>(reinterpret_cast<char*>(workspace) + pl.keys_off), keep_idx, evict_idx, n_evict,
       cache->capacity, budget, n_sink, n_recent, la);
+  return launch_status();
+}
+
+extern "C" keepkv_status keepkv_select_aged(const keepkv_layout* layout, const keepkv_cache* cache,
+                                            const int32_t* order, int32_t budget, int32_t n_sink, int32_t n_recent,
+                                            float alpha, int32_t* keep_idx, int32_t* evict_idx, int32_t* n_evict,
+                                            void* workspace, size_t workspace_bytes, void* stream) {
+  using namespace kk;
+  if (!layout_ok(layout) || !cache_ok(cache) || !order || !keep_idx || !n_evict) return KEEPKV_ERR_INVALID_ARG;
+  if (!units_supported(layout)) return KEEPKV_ERR_UNSUPPORTED;
+  if (budget < 1 || budget > cache->capacity || n_sink < 0 || n_recent < 0 || n_sink + n_recent > budget)
+    return KEEPKV_ERR_INVALID_ARG;
+  if (budget < cache->capacity && !evict_idx) return KEEPKV_ERR_INVALID_ARG;
+  if (!(alpha >= 0.f && alpha < 1.f)) return KEEPKV_ERR_INVALID_ARG;
+  const SelectPlan pl = plan_select(layout, cache->capacity);
+  if (!workspace || workspace_bytes < pl.bytes || !aligned16(workspace)) return KEEPKV_ERR_WORKSPACE;
+  const int units = layout->batch * layout->n_kv_heads;
+  const double la = alpha > 0.f ? log((double)alpha) : -INFINITY;
+  launch_select<false, true>(units, reinterpret_cast<hipStream_t>(stream),
+      cache->log_s, cache->born, cache->t_obs, cache->votes, cache->len,
+      reinterpret_cast<uint64_t*>(reinterpret_cast<char*>(workspace) + pl.keys_off), keep_idx, evict_idx, n_evict,
+      cache->capacity, budget, n_sink, n_recent, la, order);
   return launch_status();
 }
 
