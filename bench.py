@@ -151,6 +151,10 @@ def parse():
                          "A branch to a second queue costs the decode stream 20-35 us per event whatever its length, "
                          "an event on the decode stream its own 50-60 us: auto overlaps when events are frequent "
                          "(period <= 32), where the side stream also has to hide several events at once")
+    ap.add_argument("--events", choices=("auto", "inplace", "compact"), default="auto",
+                    help="steady-state compression events: rewrite the cache into the layer's other buffer (compact) or "
+                         "update it where it is (inplace: keepkv_select_aged / keepkv_merge_inplace).  auto = inplace "
+                         "from 128 (batch, kv head) units on when a period has at most 256 steps")
     ap.add_argument("--unfused", action="store_true",
                     help="use keepkv_append + keepkv_decode_attn + keepkv_score instead of keepkv_decode_step")
     ap.add_argument("--window", type=int, default=None, help="observation passes before the first event")
@@ -339,10 +343,22 @@ def main():
             c.len_hint = Bud + since          # host-known bound on len before this step's append
             kk.decode_step(lay, c, q_all[layer, t], k_all[layer, t], v_all[layer, t], out, None, alpha, None, ws)
 
+    # In-place events: the cache keeps its buffer; `orders[layer]` lists the slots below the budget by age (the
+    # first event wrote them in age order).
+    # (auto: from 128 heads on, where rewriting the cache costs more than the in-place kernel's longer chain of
+    # dependent loads; measured 44 against 39 us per event at 64 heads, 316 against 525 us at 1024)
+    inplace = args.events == "inplace" or (args.events == "auto" and P <= 256 and B * H >= 128)
+    orders = [torch.arange(Bud, dtype=torch.int32, device=dev).repeat(B, H, 1).contiguous() for _ in range(R)] if inplace else []
+
     def compress(c, d, layer, wsp):
-        kk.select(lay, c, Bud, w.n_sink, w.n_recent, alpha, keep, evict_s, n_ev, wsp)
-        kk.match(lay, c, Bud, keep, evict_s, n_ev, T, match_s, None, wsp)
-        kk.merge(lay, c, d, Bud, keep, evict_s, n_ev, match_s, alpha, dropped[layer], wsp)
+        if inplace:
+            kk.select_aged(lay, c, orders[layer], Bud, w.n_sink, w.n_recent, alpha, keep, evict_s, n_ev, wsp)
+            kk.match(lay, c, Bud, keep, evict_s, n_ev, T, match_s, None, wsp)
+            kk.merge_inplace(lay, c, orders[layer], Bud, keep, evict_s, n_ev, match_s, alpha, dropped[layer])
+        else:
+            kk.select(lay, c, Bud, w.n_sink, w.n_recent, alpha, keep, evict_s, n_ev, wsp)
+            kk.match(lay, c, Bud, keep, evict_s, n_ev, T, match_s, None, wsp)
+            kk.merge(lay, c, d, Bud, keep, evict_s, n_ev, match_s, alpha, dropped[layer], wsp)
 
     deferred = []                                # events whose side-stream work is still to be enqueued
 
@@ -382,7 +398,8 @@ def main():
                 fork = torch.cuda.Event()
                 fork.record()                    # on the main stream, right after this layer's step
                 deferred.append((c, d, layer, fork))
-            cur[layer] = 1 - cur[layer]
+            if not inplace:
+                cur[layer] = 1 - cur[layer]
             since[layer] = 0
             n_events += 1
 
@@ -417,6 +434,7 @@ def main():
         fields = ("k", "v", "votes", "log_s", "born", "t_obs", "len")
         state_at_capture = [[{f_: getattr(c, f_).clone() for f_ in fields} for c in pair] for pair in caches]
         dropped_at_capture = dropped.clone()
+        orders_at_capture = [o.clone() for o in orders]
         graph = torch.cuda.CUDAGraph()
         with torch.cuda.graph(graph, stream=stream):
             for i in range(Wm, Wm + K):
@@ -430,6 +448,8 @@ def main():
                     for f_ in fields:
                         getattr(c, f_).copy_(st[f_])
             dropped.copy_(dropped_at_capture)
+            for o, so in zip(orders, orders_at_capture):
+                o.copy_(so)
 
         replay_ms = []
         for rep in range(1 + N_REPLAY):           # one untimed replay first
@@ -464,8 +484,19 @@ def main():
     #     First the whole event of every layer, back to back inside one graph (the way the timed region launches
     #     them; an event reads its layer's cache and writes the other buffer, so replaying it changes nothing
     #     that the eager events below depend on): elapsed / layers = one event without host launch gaps.
+    #     (an in-place event changes its cache: the caches and slot lists are put back before every replay)
     torch.cuda.synchronize()
     dropped_saved = dropped.clone()
+    ev_fields = ("k", "v", "votes", "log_s", "born", "t_obs", "len")
+    ev_saved = [{f_: getattr(caches[layer][cur[layer]], f_).clone() for f_ in ev_fields} for layer in range(R)] if inplace else []
+    ev_orders = [o.clone() for o in orders]
+
+    def ev_restore():
+        for layer in range(len(ev_saved)):
+            for f_ in ev_fields:
+                getattr(caches[layer][cur[layer]], f_).copy_(ev_saved[layer][f_])
+            orders[layer].copy_(ev_orders[layer])
+
     egraph = torch.cuda.CUDAGraph()
     with torch.cuda.graph(egraph, stream=stream):
         for layer in range(R):
@@ -473,6 +504,8 @@ def main():
     torch.cuda.synchronize()
     eg_runs = []
     for rep in range(1 + N_REPLAY):
+        ev_restore()
+        torch.cuda.synchronize()
         g0, g1 = ev(), ev()
         with torch.cuda.stream(stream):
             g0.record()
@@ -483,22 +516,31 @@ def main():
             eg_runs.append(g0.elapsed_time(g1) * 1e3 / R)
     event_graph_us = float(np.median(eg_runs))
     dropped.copy_(dropped_saved)
+    ev_restore()
+    del ev_saved
     for layer in range(R):
         c = caches[layer][cur[layer]]
         since[layer] = 0
         d = caches[layer][1 - cur[layer]]
         e = [ev() for _ in range(4)]
         e[0].record()
-        kk.select(lay, c, Bud, w.n_sink, w.n_recent, alpha, keep, evict_s, n_ev, ws)
+        if inplace:
+            kk.select_aged(lay, c, orders[layer], Bud, w.n_sink, w.n_recent, alpha, keep, evict_s, n_ev, ws)
+        else:
+            kk.select(lay, c, Bud, w.n_sink, w.n_recent, alpha, keep, evict_s, n_ev, ws)
         e[1].record()
         kk.match(lay, c, Bud, keep, evict_s, n_ev, T, match_s, None, ws)
         e[2].record()
-        kk.merge(lay, c, d, Bud, keep, evict_s, n_ev, match_s, alpha, dropped[layer], ws)
+        if inplace:
+            kk.merge_inplace(lay, c, orders[layer], Bud, keep, evict_s, n_ev, match_s, alpha, dropped[layer])
+        else:
+            kk.merge(lay, c, d, Bud, keep, evict_s, n_ev, match_s, alpha, dropped[layer], ws)
         e[3].record()
         torch.cuda.synchronize()
         for j, name in enumerate(("select", "match", "merge")):
             comp[name].append(e[j].elapsed_time(e[j + 1]) * 1e3)
-        cur[layer] = 1 - cur[layer]
+        if not inplace:
+            cur[layer] = 1 - cur[layer]
     # (2) the decode kernel: a graph of decode steps only (every layer now sits at len = budget, so
     #     P/2 steps per layer stay inside the period), HIP events around the replay on the stream the
     #     kernels run on; average duration = elapsed / launches (back-to-back launches, no host gaps).
@@ -614,7 +656,7 @@ def main():
         "config": {"workload": f"{w.name}: B={B} Hq={Hq} Hkv={H} D={D} {w.dtype}, context {N} -> budget {Bud} "
                                f"({w.ratio:.0%}), period {P}, T={T:g}, alpha={alpha:g}",
                    "layers_rotated": R, "graph": not args.no_graph, "fused_step": not args.unfused, "compress_events_timed": timed_events,
-                   "compress_overlapped": args.overlap},
+                   "compress_overlapped": args.overlap, "steady_events": "in place" if inplace else "compacting"},
         "roofline": roofline,
         "cpu_baseline": cpu,
         "decode_tokens_per_s": round(B / (dec_us * 1e-6), 1),

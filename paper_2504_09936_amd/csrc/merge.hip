@@ -667,11 +667,12 @@ __global__ __launch_bounds__(kGroupThreads) void prefill_group_kernel(
 // occurrence of each, found by comparing list entries pairwise: at most kDirectMaxEvict of them) are dealt to
 // the lane groups; a group collects its members from the lists in list order, as the compacting kernel does,
 // and writes the merged row over the retained slot.  Nothing that any group reads (its own retained row, evicted
-// rows) is written by another group.
+// rows) is written by another group.  The same workgroup then moves the append region's retained tokens.
 template <typename T, int D>
-__global__ __launch_bounds__(256) void merge_inplace_kernel(MergeParams p) {
+__global__ __launch_bounds__(256) void merge_inplace_kernel(MergeParams p, int32_t* __restrict__ order) {
   constexpr int EPL = 16 / (int)sizeof(T), LPS = D / EPL, GPB = 256 / LPS;
   __shared__ int s_match[kDirectMaxEvict], s_evict[kDirectMaxEvict], s_tgt[kDirectMaxEvict];
+  __shared__ int s_hole[kDirectMaxEvict], s_mover[kDirectMaxEvict];
   __shared__ int s_mem[GPB][kDirectMaxEvict];
   __shared__ int s_wcnt[4];
   __shared__ long long s_drop;
@@ -752,41 +753,30 @@ __global__ __launch_bounds__(256) void merge_inplace_kernel(MergeParams p) {
     __builtin_amdgcn_wave_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
   }
-}
 
-// move_retained_kernel, one workgroup per head, after merge_inplace_kernel has completed: the k-th retained
-// token that lives at or beyond `budget` (in keep-list order) is copied into the k-th evicted slot below
-// `budget` (in evict-list order), `order` is rewritten to the keep list with the moved tokens at their new
-// slots, and len becomes the number of retained tokens.  Sources and destinations are disjoint.
-template <typename T, int D>
-__global__ __launch_bounds__(256) void move_retained_kernel(MergeParams p, int32_t* __restrict__ order) {
-  constexpr int EPL = 16 / (int)sizeof(T), LPS = D / EPL, GPB = 256 / LPS;
-  __shared__ int s_hole[kDirectMaxEvict], s_mover[kDirectMaxEvict];
-  __shared__ int s_wcnt[4];
-  const int unit = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int sub = tid % LPS, grp = tid / LPS;
-  const int n_ev = min(p.n_evict[unit], kDirectMaxEvict);
-  if (n_ev <= 0) return;                              // nothing was evicted: slots, order and len stay
-  const size_t sbase = (size_t)unit * p.scap;
+  // ---- move the retained tokens of the append region into the evicted slots below `budget`.  Every read of an
+  // evicted row of this head happened above, in this workgroup: the barriers inside compact() order them before
+  // the writes below.  The k-th retained token at or beyond `budget` (in keep-list order) goes to the k-th
+  // evicted slot below `budget` (in evict-list order); `order` becomes the keep list with the moved tokens at
+  // their new slots; len becomes the number of retained tokens.  Sources and destinations are disjoint.
   int32_t* ord = order + (size_t)unit * p.budget;
   const int32_t* keep = p.keep_idx + (size_t)unit * p.budget;
-  // counts below the calling thread and in total, over the workgroup (two barriers)
-  auto compact = [&](bool flag, int& total) -> int {
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");    // this wavefront's merged rows are written (a mover may be one of them)
+  auto compact = [&](bool flag, int& total) -> int {   // flagged threads below the caller, and in total
     const unsigned long long m = __ballot(flag);
     __syncthreads();                                  // the previous use of s_wcnt is over
     if (lane == 0) s_wcnt[wave] = __popcll(m);
     __syncthreads();
-    int before = 0;
+    int below = 0;
     total = 0;
     for (int w = 0; w < 4; ++w) {
-      if (w < wave) before += s_wcnt[w];
+      if (w < wave) below += s_wcnt[w];
       total += s_wcnt[w];
     }
-    return before + __popcll(m & ((1ull << lane) - 1ull));
+    return below + __popcll(m & ((1ull << lane) - 1ull));
   };
   int n_hole = 0;
   {
-    const int ev = tid < n_ev ? p.evict_idx[(size_t)unit * p.max_evict + tid] : p.budget;
     const bool hole = tid < n_ev && ev >= 0 && ev < p.budget;
     const int at = compact(hole, n_hole);
     if (hole) s_hole[at] = ev;
@@ -804,10 +794,6 @@ __global__ __launch_bounds__(256) void move_retained_kernel(MergeParams p, int32
   }
   __syncthreads();
   const int n_move = min(min(n_mover, n_hole), kDirectMaxEvict);
-  const uint4* sk = reinterpret_cast<const uint4*>(p.sk);
-  const uint4* sv = reinterpret_cast<const uint4*>(p.sv);
-  uint4* dk = reinterpret_cast<uint4*>(p.dk);
-  uint4* dv = reinterpret_cast<uint4*>(p.dv);
   for (int k = grp; k < n_move; k += GPB) {
     const int r = s_mover[k];
     const size_t src = sbase + keep[r], dst = sbase + s_hole[k];
@@ -943,19 +929,15 @@ extern "C" keepkv_status keepkv_merge_inplace(const keepkv_layout* layout, keepk
   p.ln_alpha = alpha > 0.f ? log((double)alpha) : -INFINITY;
   if (layout->dtype == KEEPKV_BF16) {
     if (layout->head_dim == 128) {
-      merge_inplace_kernel<uint16_t, 128><<<units, 256, 0, st>>>(p);
-      move_retained_kernel<uint16_t, 128><<<units, 256, 0, st>>>(p, order);
+      merge_inplace_kernel<uint16_t, 128><<<units, 256, 0, st>>>(p, order);
     } else {
-      merge_inplace_kernel<uint16_t, 64><<<units, 256, 0, st>>>(p);
-      move_retained_kernel<uint16_t, 64><<<units, 256, 0, st>>>(p, order);
+      merge_inplace_kernel<uint16_t, 64><<<units, 256, 0, st>>>(p, order);
     }
   } else {
     if (layout->head_dim == 128) {
-      merge_inplace_kernel<float, 128><<<units, 256, 0, st>>>(p);
-      move_retained_kernel<float, 128><<<units, 256, 0, st>>>(p, order);
+      merge_inplace_kernel<float, 128><<<units, 256, 0, st>>>(p, order);
     } else {
-      merge_inplace_kernel<float, 64><<<units, 256, 0, st>>>(p);
-      move_retained_kernel<float, 64><<<units, 256, 0, st>>>(p, order);
+      merge_inplace_kernel<float, 64><<<units, 256, 0, st>>>(p, order);
     }
   }
   return launch_status();

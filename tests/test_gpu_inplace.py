@@ -188,3 +188,60 @@ def test_inplace_refusals():
         kk.merge_inplace(lay, c, None, w.budget, keep, ev, nev, ev, 0.9, None)
     assert e.value.status == kk.ERR_INVALID_ARG
     torch.cuda.synchronize()
+
+
+def test_inplace_event_in_a_graph_replays_like_eager():
+    """A decode step and an in-place event captured in one HIP graph and replayed several times, with eager work
+    and synchronisation between the replays, leave the cache, the slot list and the index lists as the eager
+    sequence does, every time."""
+    kk = U.kk()
+    w = W.CONFIGS["llama3_8b"].scaled(batch=2, context=300 + 64, ratio=299.5 / 364, period=64)
+    T = U.f32(0.4)
+    B, H, Bud, P = w.batch, w.n_kv_heads, w.budget, w.period
+    lay, c, ws, alpha = _setup(w, 5, True)
+    c.len.fill_(Bud + P - 1)                              # the step below fills the cache
+    order = torch.arange(Bud, dtype=torch.int32, device="cuda").flip(0).repeat(B, H, 1).contiguous()   # (any permutation)
+    keep = torch.zeros(B, H, Bud, dtype=torch.int32, device="cuda")
+    evict, match = (torch.zeros(B, H, P, dtype=torch.int32, device="cuda") for _ in range(2))
+    nev = torch.zeros(B, H, dtype=torch.int32, device="cuda")
+    drop = torch.zeros(B, H, dtype=torch.int64, device="cuda")
+    out = torch.zeros(B, w.n_q_heads, w.head_dim, dtype=lay.torch_dtype, device="cuda")
+    q = U.to_device(W.make_query(w, 5, 0), w.dtype)
+    kt, vt = (U.to_device(x, w.dtype) for x in W.make_token(w, 5, 0))
+    fields = ("k", "v", "votes", "log_s", "born", "t_obs", "len")
+    start = {f: getattr(c, f).clone() for f in fields}
+    order0 = order.clone()
+
+    def restore():
+        for f in fields:
+            getattr(c, f).copy_(start[f])
+        order.copy_(order0)
+        drop.zero_()
+
+    def body():
+        kk.decode_step(lay, c, q, kt, vt, out, None, alpha, None, ws)
+        kk.select_aged(lay, c, order, Bud, w.n_sink, w.n_recent, alpha, keep, evict, nev, ws)
+        kk.match(lay, c, Bud, keep, evict, nev, T, match, None, ws)
+        kk.merge_inplace(lay, c, order, Bud, keep, evict, nev, match, alpha, drop)
+
+    def snapshot():
+        live = [getattr(c, f)[:, :, :Bud] if getattr(c, f).dim() >= 3 else getattr(c, f) for f in fields]
+        return [_bits(x).clone() for x in (out, order, keep, evict, match, nev, drop, *live)]
+
+    body()
+    torch.cuda.synchronize()
+    ref = snapshot()
+    assert (c.len == Bud).all() and int((match >= 0).sum()) > 0
+    restore()
+    torch.cuda.synchronize()
+    graph, stream = torch.cuda.CUDAGraph(), torch.cuda.Stream()
+    with torch.cuda.graph(graph, stream=stream):
+        body()
+    for rep in range(3):
+        restore()
+        keep.fill_(-3); match.fill_(-3); out.zero_()       # eager work between the replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for i, (a, b) in enumerate(zip(snapshot(), ref)):
+            assert torch.equal(a, b), (rep, i)
