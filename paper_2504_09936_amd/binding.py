@@ -134,6 +134,30 @@ class Cache:
         self.t_obs = torch.zeros(B, H, dtype=torch.int32, device=device)
         self.len = torch.zeros(B, H, dtype=torch.int32, device=device)
 
+    FIELDS = ("k", "v", "votes", "log_s", "born", "t_obs", "len")
+
+    def state(self) -> dict:
+        """Host copies of every array of the cache (for dumps and replays of a failing step; plain copies)."""
+        torch.cuda.synchronize()
+        d = {f: getattr(self, f).detach().cpu().clone() for f in self.FIELDS}
+        d["capacity"] = torch.tensor(self.capacity)
+        return d
+
+    def load_state(self, d: dict) -> None:
+        if int(d["capacity"]) != self.capacity:
+            raise ValueError("cache state of another capacity")
+        for f in self.FIELDS:
+            t = getattr(self, f)
+            if tuple(d[f].shape) != tuple(t.shape) or d[f].dtype != t.dtype:
+                raise ValueError(f"cache state field {f} does not fit this cache")
+            t.copy_(d[f])
+
+    def save(self, path: str) -> None:
+        torch.save(self.state(), path)
+
+    def load(self, path: str) -> None:
+        self.load_state(torch.load(path, map_location="cpu", weights_only=True))
+
     def c(self) -> _Cache:
         return _Cache(self.k.data_ptr(), self.v.data_ptr(), self.votes.data_ptr(), self.log_s.data_ptr(),
                       self.born.data_ptr(), self.t_obs.data_ptr(), self.len.data_ptr(), self.capacity, int(self.len_hint),

@@ -164,3 +164,23 @@ def test_measurement_probes_run_and_validate_arguments():
         with pytest.raises(kk.KeepKVError) as e:
             bad()
         assert e.value.status == kk.ERR_INVALID_ARG
+
+
+def test_cache_state_dump_and_reload(tmp_path):
+    """A cache dumped to a file and loaded into a fresh one gives the same decode step, bit for bit."""
+    kk, w, alpha, lay, big, ws, out, logits = _setup(seed=3, batch=1, context=500)
+    path = str(tmp_path / "cache.pt")
+    big.save(path)
+    other = kk.Cache(lay, big.capacity)
+    other.load(path)
+    q = U.to_device(W.make_query(w, 3, 9), w.dtype)
+    res = []
+    for c in (big, other):
+        kk.decode_attn(lay, c, q, out, logits, None, ws)
+        torch.cuda.synchronize()
+        res.append((_bits(out).clone(), logits.clone(), [_bits(x).clone() for x in _state(c)]))
+    assert torch.equal(res[0][0], res[1][0]) and torch.equal(res[0][1], res[1][1])
+    for a, b in zip(res[0][2], res[1][2]):
+        assert torch.equal(a, b)
+    with pytest.raises(ValueError):
+        kk.Cache(lay, big.capacity + 1).load(path)
