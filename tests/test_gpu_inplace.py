@@ -245,3 +245,78 @@ def test_inplace_event_in_a_graph_replays_like_eager():
         torch.cuda.synchronize()
         for i, (a, b) in enumerate(zip(snapshot(), ref)):
             assert torch.equal(a, b), (rep, i)
+
+
+def test_inplace_event_at_full_batch_128():
+    """The batch-128 share of the Llama-3-70B shape (1024 heads, 820 + 64 slots): the configuration in which bench.py
+    runs its events in place.  Two events with a period of decode steps between them; after each, every head of
+    the in-place cache read through its slot list equals the compacting path's cache bit for bit, and sampled
+    heads are compared with the oracle stage by stage."""
+    from types import SimpleNamespace
+    kk = U.kk()
+    w = W.CONFIGS["llama3_70b"].scaled(context=820 + 64, ratio=819.5 / 884)
+    T = U.f32(w.threshold)
+    B, H, Bud, P = w.batch, w.n_kv_heads, w.budget, w.period
+    assert (B, H, Bud, P) == (128, 8, 820, 64)
+    cap = Bud + P
+    lay, cb, ws, alpha = _setup(w, 2, False)
+    ca = _clone_cache(lay, cb)
+    lay2, ca2 = U.new_cache(w, capacity=cap)
+    order = torch.arange(Bud, dtype=torch.int32, device="cuda").repeat(B, H, 1).contiguous()
+    z = lambda *s, dt=torch.int32, fill=-7: torch.full(s, fill, dtype=dt, device="cuda")
+    out = torch.zeros(B, w.n_q_heads, w.head_dim, dtype=lay.torch_dtype, device="cuda")
+    sample = [(0, 0), (37, 5), (127, 7)]
+    step = 0
+    for event in range(2):
+        keep_a, evict_a, nev_a, match_a = z(B, H, Bud), z(B, H, P), z(B, H), z(B, H, P, fill=-9)
+        keep_b, evict_b, nev_b, match_b = z(B, H, Bud), z(B, H, P), z(B, H), z(B, H, P, fill=-9)
+        drop_a, drop_b = z(B, H, dt=torch.int64, fill=0), z(B, H, dt=torch.int64, fill=0)
+        torch.cuda.synchronize()
+        before = {}
+        for (b, h) in sample:                               # the sampled heads' state before the event, for the oracle
+            view = SimpleNamespace(**{f: getattr(cb, f)[b:b + 1, h:h + 1].clone() for f in ("k", "v", "votes", "log_s", "born", "t_obs", "len")})
+            before[b, h] = (U.download(view), order[b, h].cpu().numpy().astype(np.int64))
+        kk.select_aged(lay, cb, order, Bud, w.n_sink, w.n_recent, alpha, keep_b, evict_b, nev_b, ws)
+        kk.match(lay, cb, Bud, keep_b, evict_b, nev_b, T, match_b, None, ws)
+        kk.merge_inplace(lay, cb, order, Bud, keep_b, evict_b, nev_b, match_b, alpha, drop_b)
+        kk.select(lay, ca, Bud, w.n_sink, w.n_recent, alpha, keep_a, evict_a, nev_a, ws)
+        kk.match(lay, ca, Bud, keep_a, evict_a, nev_a, T, match_a, None, ws)
+        kk.merge(lay, ca, ca2, Bud, keep_a, evict_a, nev_a, match_a, alpha, drop_a, ws)
+        torch.cuda.synchronize()
+        assert torch.equal(match_a, match_b) and torch.equal(nev_a, nev_b) and torch.equal(drop_a, drop_b)
+        assert (cb.len == Bud).all() and torch.equal(ca2.len, cb.len) and torch.equal(ca2.t_obs, cb.t_obs)
+        assert torch.equal(order.sort(dim=-1).values, torch.arange(Bud, dtype=torch.int32, device="cuda").expand(B, H, Bud))
+        g = order.long()
+        for f in ("k", "v", "votes", "log_s", "born"):
+            a, bb = getattr(ca2, f)[:, :, :Bud], getattr(cb, f)
+            gi = g if bb.dim() == 3 else g.unsqueeze(-1).expand(-1, -1, -1, bb.shape[-1])
+            assert torch.equal(_bits(a), _bits(torch.gather(bb, 2, gi))), (event, f)
+        n_merged = 0
+        for (b, h) in sample:
+            oc, ordr = before[b, h]
+            idx = np.concatenate([ordr, np.arange(Bud, cap)])
+            k_, v_, p_, ls_, n_ = oc.k[0, 0, idx], oc.v[0, 0, idx], oc.votes[0, 0, idx], oc.log_S[0, 0, idx], oc.n_obs[0, 0, idx]
+            rk, re = O.select(ls_, n_, p_, cap, Bud, w.n_sink, w.n_recent, alpha)
+            np.testing.assert_array_equal(keep_b[b, h].cpu().numpy(), idx[rk])
+            np.testing.assert_array_equal(evict_b[b, h].cpu().numpy(), idx[re])
+            tgt, _ = O.match(k_, rk, re, T, exact_any_order=True)
+            np.testing.assert_array_equal(match_b[b, h].cpu().numpy(), tgt)
+            res = O.merge(k_, v_, p_, ls_, n_, rk, re, tgt, alpha)
+            s = order[b, h].cpu().numpy().astype(np.int64)
+            np.testing.assert_array_equal(cb.votes[b, h].cpu().numpy()[s], res.votes)
+            np.testing.assert_array_equal(U.n_obs(cb)[b, h].cpu().numpy()[s], res.n_obs)
+            assert drop_b[b, h].item() == res.dropped
+            np.testing.assert_allclose(cb.log_s[b, h].cpu().numpy()[s], res.log_S, rtol=2e-6, atol=2e-6)
+            ev = U.storage_err_rows(U.to_host(cb.v[b, h])[s], res.v, w.dtype)
+            ek = U.storage_err_rows(U.to_host(cb.k[b, h])[s], res.k, w.dtype)
+            well = ~(np.abs(res.ell_bar) < 4 * O.ELL_GUARD)
+            assert ev.max(initial=0) <= TOL and ek[well].max(initial=0) <= TOL, (event, b, h)
+            n_merged += int((tgt >= 0).sum())
+        assert n_merged > 0
+        ca, ca2 = ca2, ca
+        for _ in range(P):
+            q = U.to_device(W.make_query(w, 2, step), w.dtype)
+            kt, vt = (U.to_device(x, w.dtype) for x in W.make_token(w, 2, step))
+            kk.decode_step(lay, cb, q, kt, vt, out, None, alpha, None, ws)
+            kk.decode_step(lay, ca, q, kt, vt, out, None, alpha, None, ws)
+            step += 1
