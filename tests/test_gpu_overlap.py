@@ -27,8 +27,9 @@ def _state(caches, cur, dropped):
     return out
 
 
-@pytest.mark.parametrize("period,layers,overlap", [(8, 4, True), (5, 3, True), (8, 4, False)])
-def test_graph_equals_eager_single_stream(period, layers, overlap):
+@pytest.mark.parametrize("period,layers,overlap,inplace", [(8, 4, True, False), (5, 3, True, False), (8, 4, False, False),
+                                                          (8, 4, True, True), (5, 3, False, True)])
+def test_graph_equals_eager_single_stream(period, layers, overlap, inplace):
     kk = U.kk()
     w = W.CONFIGS["llama3_8b"].scaled(batch=2, context=400, ratio=0.25, period=period)
     B, H, Hq, D, Bud, P, R = w.batch, w.n_kv_heads, w.n_q_heads, w.head_dim, w.budget, period, layers
@@ -65,12 +66,20 @@ def test_graph_equals_eager_single_stream(period, layers, overlap):
     match = torch.zeros(B, H, cap - Bud, dtype=torch.int32, device="cuda")
     ws, ws_side = kk.new_workspace(lay, cap, Bud), kk.new_workspace(lay, cap, Bud)
 
-    def compress(c, d, dropped, layer, wsp):
-        kk.select(lay, c, Bud, w.n_sink, w.n_recent, alpha, keep, evict, n_ev, wsp)
-        kk.match(lay, c, Bud, keep, evict, n_ev, T, match, None, wsp)
-        kk.merge(lay, c, d, Bud, keep, evict, n_ev, match, alpha, dropped[layer], wsp)
+    def compress(c, d, dropped, layer, wsp, orders):
+        if inplace:                                      # the event updates the cache where it is; `orders` = its slots by age
+            kk.select_aged(lay, c, orders[layer], Bud, w.n_sink, w.n_recent, alpha, keep, evict, n_ev, wsp)
+            kk.match(lay, c, Bud, keep, evict, n_ev, T, match, None, wsp)
+            kk.merge_inplace(lay, c, orders[layer], Bud, keep, evict, n_ev, match, alpha, dropped[layer])
+        else:
+            kk.select(lay, c, Bud, w.n_sink, w.n_recent, alpha, keep, evict, n_ev, wsp)
+            kk.match(lay, c, Bud, keep, evict, n_ev, T, match, None, wsp)
+            kk.merge(lay, c, d, Bud, keep, evict, n_ev, match, alpha, dropped[layer], wsp)
 
-    def run(caches, dropped, overlapped, side):
+    def new_orders():
+        return torch.arange(Bud, dtype=torch.int32, device="cuda").repeat(R, B, H, 1).contiguous()
+
+    def run(caches, dropped, overlapped, side, orders):
         cur = [0] * R
         since = [(layer * P) // R for layer in range(R)]
         pending = [None] * R
@@ -81,7 +90,7 @@ def test_graph_equals_eager_single_stream(period, layers, overlap):
                 c, d, layer, fork = deferred.pop(0)
                 side.wait_event(fork)
                 with torch.cuda.stream(side):
-                    compress(c, d, dropped, layer, ws_side)
+                    compress(c, d, dropped, layer, ws_side, orders)
                     pending[layer] = torch.cuda.Event()
                     pending[layer].record()
 
@@ -106,8 +115,9 @@ def test_graph_equals_eager_single_stream(period, layers, overlap):
                     fork.record()
                     deferred.append((c, d, layer, fork))
                 else:
-                    compress(c, d, dropped, layer, ws)
-                cur[layer] = 1 - cur[layer]
+                    compress(c, d, dropped, layer, ws, orders)
+                if not inplace:
+                    cur[layer] = 1 - cur[layer]
                 since[layer] = 0
         if overlapped:
             launch_deferred()
@@ -116,7 +126,8 @@ def test_graph_equals_eager_single_stream(period, layers, overlap):
 
     # eager, single stream
     caches_a, dropped_a = fresh(), torch.zeros(R, B, H, dtype=torch.int64, device="cuda")
-    cur_a = run(caches_a, dropped_a, False, None)
+    orders_a = new_orders()
+    cur_a = run(caches_a, dropped_a, False, None, orders_a)
     torch.cuda.synchronize()
     ref = _state(caches_a, cur_a, dropped_a)
     assert int(dropped_a.sum().item()) >= 0 and all(int(c[cu].len.max().item()) <= cap for c, cu in zip(caches_a, cur_a))
@@ -127,8 +138,9 @@ def test_graph_equals_eager_single_stream(period, layers, overlap):
     stream, side = torch.cuda.Stream(), torch.cuda.Stream()
     graph = torch.cuda.CUDAGraph()
     torch.cuda.synchronize()
+    orders_b = new_orders()
     with torch.cuda.graph(graph, stream=stream):
-        cur_b = run(caches_b, dropped_b, overlap, side)
+        cur_b = run(caches_b, dropped_b, overlap, side, orders_b)
     assert cur_b == cur_a
     for replay in range(3):
         for pair, saved in zip(caches_b, start):          # eager work between the replays: restore the state
@@ -136,10 +148,12 @@ def test_graph_equals_eager_single_stream(period, layers, overlap):
                 for t, s_t in zip((c.k, c.v, c.votes, c.log_s, c.born, c.t_obs, c.len), s):
                     t.copy_(s_t)
         dropped_b.zero_()
+        orders_b.copy_(new_orders())
         torch.cuda.synchronize()
         with torch.cuda.stream(stream):
             graph.replay()
         torch.cuda.synchronize()
+        assert torch.equal(orders_a, orders_b)
         got = _state(caches_b, cur_b, dropped_b)
         for layer, (r_, g_) in enumerate(zip(ref, got)):
             for j, (x, y) in enumerate(zip(r_, g_)):
