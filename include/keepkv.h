@@ -4,7 +4,7 @@
  * KeepKV (arXiv 2504.09936) keeps a compressed per-layer KV cache in which every slot i
  * carries an integer Electoral Votes count p_i (Sec. 3.3.1).  Decoding attends with the
  * vote-weighted softmax of Eq. 6; every `period` steps the cache is compressed back to
- * `budget` slots by scoring (Eq. 8), selecting, matching (Alg. 1 l.4-5) and ZIP-Merging
+ * `budget` slots by scoring (Eq. 8), selecting, matching (Alg. 1, matching step) and ZIP-Merging
  * (Eq. 7 / App. A.3).  This library exposes exactly those steps.
  *
  * Conventions common to all calls
@@ -159,7 +159,7 @@ keepkv_status keepkv_decode_step_static(const keepkv_layout *layout, keepkv_cach
                                         float *logits_out, float alpha, int32_t *overflow,
                                         void *stream);
 
-/* EMA score update (Eq. 8, t > L branch; Alg. 1 line 6) on the live slots:
+/* EMA score update (Eq. 8, t > L branch; Alg. 1, score update) on the live slots:
  *     S_i <- alpha S_i + (1 - alpha) exp(logits[i]),  n_i += 1  (t_obs[b,h] += 1)
  * held as log_s_i = ln S_i.  logits: DEVICE f32 [B, Hkv, capacity] as written by
  * keepkv_decode_attn.  0 <= alpha < 1.  Running it w+1 times from the empty state over the
@@ -184,7 +184,7 @@ keepkv_status keepkv_score_window(const keepkv_layout *layout, keepkv_cache *cac
                                   const void *q_win, int32_t window, float alpha,
                                   int32_t first_pos, void *stream);
 
-/* Token selection (Alg. 1 lines 2-3; fixed-budget policy with sink tokens, a recent
+/* Token selection (Alg. 1, selection step; fixed-budget policy with sink tokens, a recent
  * window and heavy hitters, App. B.3).  Per (b, h) with len > budget: slots [0, n_sink)
  * and [len - n_recent, len) are kept; of the others the budget - n_sink - n_recent with the
  * largest ln p_i + ln s_hat_i are kept, equal values resolved in favour of the lower
@@ -209,7 +209,7 @@ keepkv_status keepkv_select_by_key(const keepkv_layout *layout, const keepkv_cac
                                    int32_t *n_evict, void *workspace, size_t workspace_bytes,
                                    void *stream);
 
-/* Merge-candidate matching (Alg. 1 lines 4-5): for every to-be-evicted slot e the
+/* Merge-candidate matching (Alg. 1, matching step): for every to-be-evicted slot e the
  * retained slot of highest key cosine similarity U[e,c] = k_e.k_c/(|k_e||k_c|), lowest
  * position winning ties; match[b,h,j] (DEVICE int32 [B, Hkv, capacity - budget]) is that
  * position in keep_idx if U > threshold (strict) and -1 otherwise.  sim_out (DEVICE f32,
@@ -222,7 +222,7 @@ keepkv_status keepkv_match(const keepkv_layout *layout, const keepkv_cache *cach
                            float *sim_out, void *workspace, size_t workspace_bytes, void *stream);
 
 /* Multi-way Zero Inference-Perturbation Merging with EMA scores (Eq. 7 in its App. A.3 /
- * A.4 form; Alg. 1 lines 7-11).  For retained position r with group g = {keep_idx[r]} +
+ * A.4 form; Alg. 1, merging step).  For retained position r with group g = {keep_idx[r]} +
  * {evict_idx[j] : match[j] = r}, w_i = p_i s_hat_i, W = sum w, P = sum p:
  *     v_r = sum w_i v_i / W,   k_r = (sum w_i k_i / W) * ln(W/P) / (sum w_i ln s_hat_i / W),
  *     p_r = P,   ln s_hat_r = ln(W/P),   n_r = max(count of the retained slot, 1);  dst.t_obs = src.t_obs.

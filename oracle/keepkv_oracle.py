@@ -146,7 +146,7 @@ def log_s_hat(log_S, n_obs, alpha):
     return out
 
 
-# --------------------------------------------------------------------------- selection (Alg. 1 l.2-3)
+# --------------------------------------------------------------------------- selection (Alg. 1, selection step)
 def select_by_key(rank, length, budget, n_sink, n_recent):
     """Split the live slots into retained and to-be-evicted sets under any ranking value.
 
@@ -174,7 +174,7 @@ def select_by_key(rank, length, budget, n_sink, n_recent):
 
 
 def select(log_S, n_obs, votes, length, budget, n_sink, n_recent, alpha):
-    """Split the live slots into retained K_c and to-be-evicted K_e (Alg. 1 lines 2-3).
+    """Split the live slots into retained K_c and to-be-evicted K_e (Alg. 1, selection step).
 
     Policy (fixed budget, sink tokens, recent window, heavy hitters -- App. B.3) with the
     vote-weighted EMA mass ln p_i + ln s_hat_i as the ranking value of select_by_key.
@@ -185,7 +185,7 @@ def select(log_S, n_obs, votes, length, budget, n_sink, n_recent, alpha):
     return select_by_key(key, length, budget, n_sink, n_recent)
 
 
-# --------------------------------------------------------------------------- matching (Alg. 1 l.4-5)
+# --------------------------------------------------------------------------- matching (Alg. 1, matching step)
 def _dots(a, b, exact_any_order):
     """a [m, d] . b [n, d] -> [m, n] in float64.
 
@@ -203,7 +203,7 @@ def _dots(a, b, exact_any_order):
 
 
 def match(k, keep_idx, evict_idx, threshold, exact_any_order=False):
-    """Merge target of every to-be-evicted key (Alg. 1 lines 4-5).
+    """Merge target of every to-be-evicted key (Alg. 1, matching step).
 
     U[e, c] = cos(k_e, k_c) = (k_e . k_c) * (1/|k_e|) * (1/|k_c|); the target of e is the
     first maximiser of U[e, :] over the retained keys; it is used only if U > threshold
@@ -247,7 +247,7 @@ class MergeResult:
 
 def merge(k, v, votes, log_S, n_obs, keep_idx, evict_idx, target, alpha):
     """Multi-way Zero Inference-Perturbation Merging with EMA scores (App. A.3 / A.4 form
-    of Eq. 7; Alg. 1 lines 7-11).
+    of Eq. 7; Alg. 1, merging step).
 
     For retained slot c with group g = {c} + {e : target[e] = c}, E_i = ln s_hat_i,
     w_i = p_i s_hat_i, W = sum w, P = sum p:

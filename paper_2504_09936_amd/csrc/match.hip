@@ -1,5 +1,5 @@
 // keepkv_match: nearest retained key by cosine similarity for every to-be-evicted key
-// (Alg. 1 lines 4-5), the one dense contraction of the method.
+// (Alg. 1, matching step), the one dense contraction of the method.
 //
 // bf16 caches, first event (thousands of evicted rows per head): the retained keys of a head are first
 // gathered into a panel in list order; one workgroup of 8 wavefronts per compute unit then walks blocks of

@@ -1,5 +1,5 @@
 // keepkv_merge: multi-way Zero Inference-Perturbation Merging (Eq. 7 in the many-to-one form of
-// App. A.3, with the EMA scores of App. A.4; Alg. 1 lines 7-11) and compaction into the
+// App. A.3, with the EMA scores of App. A.4; Alg. 1, merging step) and compaction into the
 // destination cache.
 //
 // Two kernels.  (1) Per head, the evicted slots are grouped by merge target into a CSR list: an LDS

@@ -1,5 +1,5 @@
 // keepkv_select: per (batch, kv head) choose the retained set K_c and the to-be-evicted set K_e
-// (Alg. 1 lines 2-3) under the fixed-budget sink / recent / heavy-hitter policy (App. B.3).
+// (Alg. 1, selection step) under the fixed-budget sink / recent / heavy-hitter policy (App. B.3).
 //
 // One 1024-thread workgroup per head.  The ranking value ln p + ln s_hat is formed in f64 and
 // mapped to an order-preserving u64, the (budget - n_sink - n_recent)-th largest is found by an
