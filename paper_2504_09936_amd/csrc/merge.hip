@@ -663,18 +663,23 @@ __global__ __launch_bounds__(kGroupThreads) void prefill_group_kernel(
 // into the slots that evicted tokens leave below `budget` (there are exactly as many), so that afterwards the
 // slots below `budget` are all live, len = budget, and decode steps append behind them as before.
 //
-// merge_inplace_kernel, one workgroup per head: the distinct targets of the head's match list (the first
-// occurrence of each, found by comparing list entries pairwise: at most kDirectMaxEvict of them) are dealt to
-// the lane groups; a group collects its members from the lists in list order, as the compacting kernel does,
-// and writes the merged row over the retained slot.  Nothing that any group reads (its own retained row, evicted
-// rows) is written by another group.  The same workgroup then moves the append region's retained tokens.
+// merge_inplace_kernel, one workgroup per head.  The head's match list (at most kDirectMaxEvict entries) is
+// grouped by target in LDS: every entry counts the earlier entries with its target (its place in the group,
+// so members keep list order, the compacting kernel's summation order) and all of them (the group's size); the
+// first entry of each target is its leader, the leaders are numbered by a ballot compaction and a scan over
+// their sizes gives each group its range of the member array.  The targets are then dealt to the lane groups,
+// which write the merged row over the retained slot.  Nothing that any group reads (its own retained row,
+// evicted rows) is written by another group.  The same workgroup then moves the append region's retained tokens.
+constexpr int kInplaceThreads = 512;
 template <typename T, int D>
-__global__ __launch_bounds__(256) void merge_inplace_kernel(MergeParams p, int32_t* __restrict__ order) {
-  constexpr int EPL = 16 / (int)sizeof(T), LPS = D / EPL, GPB = 256 / LPS;
-  __shared__ int s_match[kDirectMaxEvict], s_evict[kDirectMaxEvict], s_tgt[kDirectMaxEvict];
+__global__ __launch_bounds__(kInplaceThreads) void merge_inplace_kernel(MergeParams p, int32_t* __restrict__ order) {
+  constexpr int EPL = 16 / (int)sizeof(T), LPS = D / EPL, GPB = kInplaceThreads / LPS, kWaves = kInplaceThreads / 64;
+  static_assert(kInplaceThreads >= kDirectMaxEvict, "one list entry per thread");
+  __shared__ int s_match[kDirectMaxEvict], s_evict[kDirectMaxEvict];
+  __shared__ int s_tgt[kDirectMaxEvict], s_cnt[kDirectMaxEvict], s_start[kDirectMaxEvict], s_tidx[kDirectMaxEvict];
+  __shared__ int s_members[kDirectMaxEvict];
   __shared__ int s_hole[kDirectMaxEvict], s_mover[kDirectMaxEvict];
-  __shared__ int s_mem[GPB][kDirectMaxEvict];
-  __shared__ int s_wcnt[4];
+  __shared__ int s_wcnt[kWaves];
   __shared__ long long s_drop;
   const int unit = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int sub = tid % LPS, grp = tid / LPS, gbase = lane - sub;
@@ -695,22 +700,45 @@ __global__ __launch_bounds__(256) void merge_inplace_kernel(MergeParams p, int32
     const long long drop = p.svotes[sbase + ev];
     if (drop != 0) atomicAdd((unsigned long long*)&s_drop, (unsigned long long)drop);
   }
-  bool leader = tid < n_ev && mt >= 0 && mt < p.budget;
-  if (leader)
-    for (int j = 0; j < tid; ++j)
-      if (s_match[j] == mt) {
-        leader = false;
-        break;
-      }
-  const unsigned long long lm = __ballot(leader);
-  if (lane == 0) s_wcnt[wave] = __popcll(lm);
-  __syncthreads();
-  int before = 0, nt = 0;
-  for (int w = 0; w < 4; ++w) {
-    if (w < wave) before += s_wcnt[w];
-    nt += s_wcnt[w];
+  const bool matched = tid < n_ev && mt >= 0 && mt < p.budget;
+  int place = 0, size = 0, first = tid;               // among the entries with this entry's target
+  if (matched)
+    for (int j = 0; j < n_ev; ++j) {
+      const bool same = s_match[j] == mt;
+      size += same;
+      place += same && j < tid;
+      if (same && j < first) first = j;
+    }
+  const bool leader = matched && place == 0;
+  // uniform helper: flagged threads below the caller, and in total (two barriers)
+  auto compact = [&](bool flag, int& total) -> int {
+    const unsigned long long m = __ballot(flag);
+    __syncthreads();                                  // the previous use of s_wcnt is over
+    if (lane == 0) s_wcnt[wave] = __popcll(m);
+    __syncthreads();
+    int below = 0;
+    total = 0;
+    for (int w = 0; w < kWaves; ++w) {
+      if (w < wave) below += s_wcnt[w];
+      total += s_wcnt[w];
+    }
+    return below + __popcll(m & ((1ull << lane) - 1ull));
+  };
+  int nt = 0;
+  const int my_t = compact(leader, nt);               // the leader's group number (list order of first entries)
+  if (leader) {
+    s_tgt[my_t] = mt;
+    s_cnt[my_t] = size;
+    s_tidx[tid] = my_t;
   }
-  if (leader) s_tgt[before + __popcll(lm & ((1ull << lane) - 1ull))] = mt;
+  __syncthreads();
+  if (tid < nt) {                                     // start of each group's range: a scan over at most 256 sizes
+    int run = 0;
+    for (int t = 0; t < tid; ++t) run += s_cnt[t];
+    s_start[tid] = run;
+  }
+  __syncthreads();
+  if (matched) s_members[s_start[s_tidx[first]] + place] = ev;
   __syncthreads();
   if (tid == 0 && p.dropped_votes != nullptr && s_drop != 0) p.dropped_votes[unit] += s_drop;
 
@@ -720,26 +748,16 @@ __global__ __launch_bounds__(256) void merge_inplace_kernel(MergeParams p, int32
   uint4* dv = reinterpret_cast<uint4*>(p.dv);
   for (int t0 = 0; t0 < nt; t0 += GPB) {              // uniform trip count: a group without a target repeats the first one and writes nothing
     const bool active = t0 + grp < nt;
-    const int r = s_tgt[active ? t0 + grp : 0];
+    const int ti = active ? t0 + grp : 0;
+    const int r = s_tgt[ti];
     const int c = p.keep_idx[(size_t)unit * p.budget + r];
     const size_t at = sbase + max(c, 0);
     const uint4 kc = sk[at * LPS + sub], vc = sv[at * LPS + sub];
     const int p_c = p.svotes[at];
     const float ls_c = p.slog_s[at];
     const int n_c = t_head - p.sborn[at];
-    int* mine = s_mem[grp];
-    int m1 = 0;
-    for (int i0 = 0; i0 < n_ev; i0 += LPS) {
-      const bool hit = i0 + sub < n_ev && s_match[i0 + sub] == r;
-      const unsigned long long wave_hits = __ballot(hit);
-      const unsigned int hits = (unsigned int)(wave_hits >> gbase) & (unsigned int)((1ull << LPS) - 1ull);   // LPS <= 32
-      if (hit) mine[m1 + __popc(hits & ((1u << sub) - 1u))] = s_evict[i0 + sub];
-      m1 += __popc(hits);
-    }
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");   // the list is read back by this group's own lanes
-    __builtin_amdgcn_wave_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-    const MergedRow mr = merge_position<T, D>(p, sbase, t_head, c, kc, vc, p_c, ls_c, n_c, mine, m1, sub, gbase);
+    const MergedRow mr = merge_position<T, D>(p, sbase, t_head, c, kc, vc, p_c, ls_c, n_c, s_members + s_start[ti], s_cnt[ti],
+                                              sub, gbase);
     if (active && c >= 0) {
       dk[at * LPS + sub] = mr.k;
       dv[at * LPS + sub] = mr.v;
@@ -749,9 +767,6 @@ __global__ __launch_bounds__(256) void merge_inplace_kernel(MergeParams p, int32
         p.dborn[at] = t_head - mr.n_r;
       }
     }
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");   // the member list is rewritten in the next round
-    __builtin_amdgcn_wave_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
   }
 
   // ---- move the retained tokens of the append region into the evicted slots below `budget`.  Every read of an
@@ -762,19 +777,6 @@ __global__ __launch_bounds__(256) void merge_inplace_kernel(MergeParams p, int32
   int32_t* ord = order + (size_t)unit * p.budget;
   const int32_t* keep = p.keep_idx + (size_t)unit * p.budget;
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");    // this wavefront's merged rows are written (a mover may be one of them)
-  auto compact = [&](bool flag, int& total) -> int {   // flagged threads below the caller, and in total
-    const unsigned long long m = __ballot(flag);
-    __syncthreads();                                  // the previous use of s_wcnt is over
-    if (lane == 0) s_wcnt[wave] = __popcll(m);
-    __syncthreads();
-    int below = 0;
-    total = 0;
-    for (int w = 0; w < 4; ++w) {
-      if (w < wave) below += s_wcnt[w];
-      total += s_wcnt[w];
-    }
-    return below + __popcll(m & ((1ull << lane) - 1ull));
-  };
   int n_hole = 0;
   {
     const bool hole = tid < n_ev && ev >= 0 && ev < p.budget;
@@ -782,7 +784,7 @@ __global__ __launch_bounds__(256) void merge_inplace_kernel(MergeParams p, int32
     if (hole) s_hole[at] = ev;
   }
   int n_mover = 0;
-  for (int r0 = 0; r0 < p.budget; r0 += 256) {        // uniform trip count
+  for (int r0 = 0; r0 < p.budget; r0 += kInplaceThreads) {   // uniform trip count
     const int r = r0 + tid;
     const int c = r < p.budget ? keep[r] : -1;
     const bool mover = c >= p.budget;
@@ -929,15 +931,15 @@ extern "C" keepkv_status keepkv_merge_inplace(const keepkv_layout* layout, keepk
   p.ln_alpha = alpha > 0.f ? log((double)alpha) : -INFINITY;
   if (layout->dtype == KEEPKV_BF16) {
     if (layout->head_dim == 128) {
-      merge_inplace_kernel<uint16_t, 128><<<units, 256, 0, st>>>(p, order);
+      merge_inplace_kernel<uint16_t, 128><<<units, kInplaceThreads, 0, st>>>(p, order);
     } else {
-      merge_inplace_kernel<uint16_t, 64><<<units, 256, 0, st>>>(p, order);
+      merge_inplace_kernel<uint16_t, 64><<<units, kInplaceThreads, 0, st>>>(p, order);
     }
   } else {
     if (layout->head_dim == 128) {
-      merge_inplace_kernel<float, 128><<<units, 256, 0, st>>>(p, order);
+      merge_inplace_kernel<float, 128><<<units, kInplaceThreads, 0, st>>>(p, order);
     } else {
-      merge_inplace_kernel<float, 64><<<units, 256, 0, st>>>(p, order);
+      merge_inplace_kernel<float, 64><<<units, kInplaceThreads, 0, st>>>(p, order);
     }
   }
   return launch_status();
