@@ -58,6 +58,19 @@ def test_workspace_and_argument_validation_without_device():
                                   None, 0, None) == kk.ERR_WORKSPACE
     assert lib.keepkv_select(C.byref(lay.c()), C.byref(cache), 820, 500, 500, C.c_float(0.9), C.c_void_p(16),
                              C.c_void_p(16), C.c_void_p(16), C.c_void_p(16), 1 << 30, None) == kk.ERR_INVALID_ARG
+    # the in-place event: a missing slot list, a workspace that is too small, more evictable slots than it handles
+    P16 = C.c_void_p(16)
+    assert lib.keepkv_select_aged(C.byref(lay.c()), C.byref(cache), None, 820, 4, 652, C.c_float(0.9), P16, P16, P16,
+                                  P16, 1 << 30, None) == kk.ERR_INVALID_ARG
+    assert lib.keepkv_select_aged(C.byref(lay.c()), C.byref(cache), P16, 820, 4, 652, C.c_float(0.9), P16, P16, P16,
+                                  P16, 1024, None) == kk.ERR_WORKSPACE
+    assert lib.keepkv_merge_inplace(C.byref(lay.c()), C.byref(cache), None, 820, P16, P16, P16, P16, C.c_float(0.9),
+                                    None, None) == kk.ERR_INVALID_ARG
+    wide = kk._Cache(16, 16, 16, 16, 16, 16, 16, 820 + 257, 0)
+    assert lib.keepkv_merge_inplace(C.byref(lay.c()), C.byref(wide), P16, 820, P16, P16, P16, P16, C.c_float(0.9),
+                                    None, None) == kk.ERR_UNSUPPORTED
+    assert lib.keepkv_merge_inplace(C.byref(lay.c()), C.byref(cache), P16, 820, P16, P16, P16, P16, C.c_float(1.0),
+                                    None, None) == kk.ERR_INVALID_ARG
 
 
 def test_too_many_heads_is_refused_by_every_call():
