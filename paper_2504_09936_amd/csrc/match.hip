@@ -958,8 +958,16 @@ __global__ __launch_bounds__(kPfWaves* kWave) void prefill_near_kernel(MatchPara
   }
   const float rn_row = rn_all[min(row, n - 1)];
 
-  float best = -INFINITY, second = -INFINITY;
-  int bcol = 0;
+  // Running state per lane (its row, its 16 columns of every 32-column block), as in the first event's kernel:
+  // the best value of each column class i, and (best, second best, block) over the blocks' maxima, all as integer
+  // images (the order of positive floats; a masked or negative value loses to the initial 0, and a row without
+  // a positive similarity is queued for the f64 kernel or has no target anyway).  No column number travels
+  // with the values: at the end the winning class is the one whose best equals the overall best and the
+  // winning block is the triple's; every other column is bounded by the second-best block or another class.
+  int cls[16];
+#pragma unroll
+  for (int i = 0; i < 16; ++i) cls[i] = 0;
+  int b1 = 0, b2 = 0, g1 = 0;
   int par = 0;
   for (int s = 0; s < n_stage; ++s) {
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
@@ -978,33 +986,48 @@ __global__ __launch_bounds__(kPfWaves* kWave) void prefill_near_kernel(MatchPara
         acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, e[ks], acc, 0, 0, 0);
       }
       const bool diagonal = cb0 + 32 > row_lo;           // uniform: the block holds columns at or behind some row
+      int gm = 0;
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
         const f32x4_t rn4 = *reinterpret_cast<const f32x4_t*>(&s_rn[par][32 * cbl + 8 * g + 4 * half]);
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-          const int col = cb0 + 8 * g + 4 * half + i;
-          float v = acc[4 * g + i] * rn4[i];
-          if (diagonal) v = (col < row) ? v : -INFINITY;
-          if (col >= n_cols) v = -INFINITY;             // (clamped loads beyond the last needed column)
-          const bool gt = v > best;
-          second = gt ? best : fmaxf(second, v);
-          bcol = gt ? col : bcol;
-          best = gt ? v : best;
+          int k = __builtin_bit_cast(int, acc[4 * g + i] * rn4[i]);
+          if (diagonal) {                                // only earlier columns count (and none beyond the last one needed)
+            const int col = cb0 + 8 * g + 4 * half + i;
+            k = (col < row && col < n_cols) ? k : 0;
+          }
+          cls[4 * g + i] = imax(cls[4 * g + i], k);
+          gm = imax(gm, k);
         }
       }
+      const int cb = cb0 >> 5;
+      g1 = (gm > b1) ? cb : g1;                          // strict: the first of equal blocks stays
+      b2 = imed3(b1, b2, gm);
+      b1 = imax(b1, gm);
     }
     par ^= 1;
   }
-  // the two lanes of a row (the halves) meet; equal values: the lower column, and the margin is zero
+  // winning class of this lane's half of the row, then the two lanes of a row (the halves) meet; equal values:
+  // the lower column, and the margin is zero
+  float best, second;
+  int bcol;
   {
-    const float ob = __shfl_xor(best, 32), os = __shfl_xor(second, 32);
-    const int oc = __shfl_xor(bcol, 32);
-    const float hi = fmaxf(best, ob), lo = fminf(best, ob);
-    const int c = (best > ob) ? bcol : ((ob > best) ? oc : min(bcol, oc));
-    second = fmaxf(lo, fmaxf(second, os));
-    best = hi;
-    bcol = c;
+    int s1 = cls[0], s2 = 0, ci = 0;
+#pragma unroll
+    for (int i = 1; i < 16; ++i) {
+      const int x = cls[i];
+      const bool up = x > s1;
+      s2 = up ? s1 : imax(s2, x);
+      ci = up ? i : ci;
+      s1 = up ? x : s1;
+    }
+    const int col = 32 * g1 + 8 * (ci / 4) + 4 * half + (ci % 4);
+    const int rest = imax(b2, s2);                       // bounds every other column of this half
+    const int o1 = __shfl_xor(s1, 32), orest = __shfl_xor(rest, 32), ocol = __shfl_xor(col, 32);
+    best = __builtin_bit_cast(float, imax(s1, o1));
+    bcol = (s1 > o1) ? col : ((o1 > s1) ? ocol : min(col, ocol));
+    second = __builtin_bit_cast(float, imax(imax(rest, orest), imin(s1, o1)));
   }
   if (half != 0 || row >= n) return;
   const size_t o = (size_t)unit * p.max_evict + row;
