@@ -869,8 +869,8 @@ __global__ __launch_bounds__(256) void match_exact_kernel(MatchParams p) {
 // contraction as above with rows = columns = the head's own keys and a causal mask, so the keys need no
 // gathering: a workgroup of 4 wavefronts takes 128 consecutive slots as rows (32 per wavefront, resident in
 // registers as B operands) and streams the slots before them through LDS in 64-key stages, copied straight
-// from the cache with the row swizzle applied on the address side.  A lane holds one row; per value it keeps
-// (best, column, runner-up) with strict comparisons in ascending column order, so the first maximiser wins.
+// from the cache with the row swizzle applied on the address side.  A lane holds one row; the products are
+// folded as in the first event's kernel (class maxima and a triple over block maxima; ties go to the f64 kernel).
 // Column blocks wholly behind a wavefront's rows are skipped, the one block on the diagonal is masked.
 // Rows that the f32 arithmetic cannot decide are queued for the f64 kernel (causal mode).
 constexpr int kPfWaves = 4;
