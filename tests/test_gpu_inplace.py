@@ -58,6 +58,8 @@ CASES = [
     ("f32_tiny", W.CONFIGS["tiny"].scaled(batch=2, context=52 + 32, ratio=51.5 / 84, period=32), 0.2, None),
     ("bf16_ragged", W.CONFIGS["llama3_8b"].scaled(batch=1, context=200 + 48, ratio=199.5 / 248, period=48), 0.4,
      [[248, 200, 201, 150, 0, 247, 1, 248]]),
+    # no evicted slot finds a target: every one is dropped, the retained tokens of the append region still move
+    ("bf16_nomatch", W.CONFIGS["llama3_8b"].scaled(batch=1, context=120 + 40, ratio=119.5 / 160, period=40), 2.0, None),
 ]
 
 
@@ -170,7 +172,7 @@ def test_inplace_event_matches_oracle_and_compacting_event(name, w, threshold, l
             kk.decode_step(lay, cb, q, kt, vt, out, None, alpha, None, ws)
             kk.decode_step(lay, ca, q, kt, vt, out, None, alpha, None, ws)
             step += 1
-    assert n_merged_total > 0 and n_moved_total > 0, "the case exercises no merge or no move"
+    assert (n_merged_total > 0 or threshold > 1.0) and n_moved_total > 0, "the case exercises no merge or no move"
 
 
 def test_inplace_refusals():
